@@ -1,0 +1,9 @@
+"""CPU oracle for the fused optimizer step + weight prediction.
+
+Test infrastructure only: imported by ``tests/``, by ``__graft_entry__.smoke()``
+and by the ``cpu_baseline`` leg of ``bench.py``.  Nothing in the GPU package
+imports it and it imports nothing from the GPU package.
+"""
+from .po_oracle import (  # noqa: F401
+    SGDM, ADAM, ADAMW, build, step_predict, bf16_from_f32, version_difference,
+)
