@@ -1,0 +1,174 @@
+#!/usr/bin/env python3
+"""Benchmark of the fused optimizer step + weight prediction on one MI355X.
+
+A "step" is one pass of the whole hot path over one stage of synthetic input that
+is already resident in HBM: the version difference s = D - rank - 1 (paper Eq. 4),
+the host-side coefficient derivation, and the single fused kernel launch that
+updates W, m, v in place and writes the predicted weights What (paper Table 1,
+Eq. 1, Eq. 5).  The chunk table is built once per stage, before the timed region.
+
+Prints ONE JSON line.  `value` is parameters per second over the timed steps;
+`roofline.achieved` is algorithmic HBM bytes per launch divided by the kernel's
+average launch duration, measured with HIP events on the stream the kernel runs
+on; `cpu_baseline` is the CPU oracle timed on a bounded sample of the same
+workload on this machine's host cores (a reported baseline, not a target).
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+HBM_PEAK_GBPS = 8000.0            # MI355X published HBM3E bandwidth
+
+# HBM traffic per launch measured with rocprofv3 --pmc (FETCH_SIZE, WRITE_SIZE), scaled by the
+# same counters on the plain copy kernel; see the summary under profiles/.  bytes per launch.
+MEASURED_TRAFFIC = {}
+
+
+def parse_args():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--config", type=int, default=5, help="workload 1..5 (default: the 0.74B-parameter stage)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-copy-probe", action="store_true")
+    ap.add_argument("--launch", default="", help="comma separated po_launch overrides, e.g. vec=8,unroll=2,chunk_elems=8192")
+    ap.add_argument("--pipeline-depth", type=int, default=0, help="D of Eq. 4; default: s_max + 1 so that rank 0 gets the config's s")
+    return ap.parse_args()
+
+
+def cpu_baseline(wl, s):
+    """The oracle, as it stands, on a bounded sample of the workload (about 10-30 s of CPU work)."""
+    import numpy as np
+    import oracle
+    from paper_2312_00839_amd.workloads import make_inputs
+
+    oracle.build()
+    budget = 112_500_000                       # parameters; ~14 s of single-core oracle time
+    idx, total = [], 0
+    for i, n in enumerate(wl.numels):
+        if total + n > budget and idx:
+            break
+        idx.append(i)
+        total += n
+    inp = make_inputs(wl, "cpu", tensors=idx)
+    threads = min(16, os.cpu_count() or 1)
+    code = {"sgdm": oracle.SGDM, "adam": oracle.ADAM, "adamw": oracle.ADAMW}[wl.optimizer]
+    arrays = [{k: inp[k][j].numpy() for k in ("W", "g", "m", "v") if inp[k] is not None} for j in range(len(idx))]
+    t0 = time.perf_counter()
+    for a in arrays:
+        oracle.step_predict(code, a["W"], a["g"], a["m"], a.get("v"), lr=wl.hyper["lr"], beta1=wl.hyper["beta1"],
+                            beta2=wl.hyper["beta2"], eps=wl.hyper["eps"], weight_decay=wl.hyper["weight_decay"],
+                            t=wl.t, s=s, nthreads=threads)
+    dt = time.perf_counter() - t0
+    return {"value": total / dt, "unit": "params/s", "cores": threads, "kind": "oracle",
+            "sample": "tensors %d..%d of the stage (%d params), one oracle pass, %.2f s wall" % (idx[0], idx[-1], total, dt)}
+
+
+def main():
+    args = parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build measures one GPU's stage on one GPU; --gpus %d is not supported "
+              "(the path has no cross-GPU communication: each stage runs this same call)" % args.gpus, file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_2312_00839_amd import binding
+    from paper_2312_00839_amd.stage import Stage
+    from paper_2312_00839_amd.workloads import make_inputs, workload
+
+    binding.lib()                                  # fail loudly if the HIP library is missing
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(1)
+    dev = "cuda:0"
+    torch.cuda.set_device(0)
+
+    wl = workload(args.config)
+    s_cfg = wl.s_values[-1]
+    D = args.pipeline_depth or (s_cfg + 1)
+    rank = D - 1 - s_cfg
+    tensors = make_inputs(wl, dev)
+    stage = Stage(tensors["W"], tensors["g"], tensors["m"], tensors["v"], wl.what_dtype)
+    if args.launch:
+        stage.plan.set_launch(**{k: int(v) for k, v in (kv.split("=") for kv in args.launch.split(","))})
+    L = stage.plan.get_launch()
+    hyper = binding.make_hyper(wl.optimizer, wl.hyper["lr"], wl.hyper["beta1"], wl.hyper["beta2"], wl.hyper["eps"],
+                               wl.hyper["weight_decay"], True)
+    N = stage.n_params
+    bytes_per_launch = wl.bytes_per_param * N
+
+    def one_step(i):
+        s = binding.pipeoptim_version_difference(D, rank)         # Eq. 4
+        stage.step_predict(hyper, wl.t + i, s)                    # coefficients + the fused launch
+
+    for i in range(args.warmup):
+        one_step(i)
+    torch.cuda.synchronize()
+
+    K = args.steps
+    stream = torch.cuda.current_stream()
+    events = [torch.cuda.Event(enable_timing=True) for _ in range(K + 1)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    events[0].record(stream)
+    for i in range(K):
+        one_step(args.warmup + i)
+        events[i + 1].record(stream)
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    per_launch_ms = sorted(events[i].elapsed_time(events[i + 1]) for i in range(K))
+    avg_ms = sum(per_launch_ms) / K
+    med_ms = per_launch_ms[K // 2]
+    achieved = bytes_per_launch / (avg_ms * 1e-3) / 1e9
+
+    out = {
+        "metric": "params/sec, fused optimizer step + weight prediction, 1 GPU",
+        "value": N * K / wall,
+        "unit": "params/s",
+        "n_gpus": 1, "steps": K, "warmup": args.warmup,
+        "ms_per_step": wall / K * 1e3,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32", "data": "synthetic",
+        "config": {"workload": "config %d: %s, %s, t=%d.., s=%d, %s What" % (wl.config, wl.name, wl.optimizer, wl.t, s_cfg, wl.what_dtype),
+                   "n_params": N, "n_tensors": len(wl.shapes), "bytes_per_param": wl.bytes_per_param,
+                   "launch": {f: getattr(L, f) for f, _ in L._fields_}, "n_chunks": stage.plan.info()["n_chunks"]},
+        "kernel_ms": {"avg": avg_ms, "median": med_ms, "min": per_launch_ms[0], "max": per_launch_ms[-1]},
+        "achieved_hbm_GBps": achieved,
+        "pct_of_hbm_peak": 100.0 * achieved / HBM_PEAK_GBPS,
+        "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                     "frac": achieved / HBM_PEAK_GBPS, "traffic": MEASURED_TRAFFIC.get(wl.config)},
+    }
+
+    if not args.no_copy_probe:
+        nbytes = 4 << 30
+        src = torch.empty(nbytes, dtype=torch.uint8, device=dev).fill_(1)
+        dst = torch.empty(nbytes, dtype=torch.uint8, device=dev)
+        for _ in range(3):
+            binding.pipeoptim_probe_copy(dst.data_ptr(), src.data_ptr(), nbytes, stream.cuda_stream)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        reps = 20
+        e0.record(stream)
+        for _ in range(reps):
+            binding.pipeoptim_probe_copy(dst.data_ptr(), src.data_ptr(), nbytes, stream.cuda_stream)
+        e1.record(stream)
+        torch.cuda.synchronize()
+        copy_gbps = 2.0 * nbytes * reps / (e0.elapsed_time(e1) * 1e-3) / 1e9
+        out["copy_kernel_GBps"] = copy_gbps
+        out["frac_of_copy_kernel"] = achieved / copy_gbps
+        del src, dst
+
+    stage.close()
+    del stage, tensors
+    torch.cuda.empty_cache()
+
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(wl, s_cfg)
+
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -1,0 +1,177 @@
+/*
+ * pipeoptim.h -- C ABI of libpipeoptim: PipeOptim's optimizer-dependent weight
+ * prediction fused with the optimizer step, for one pipeline stage's ragged
+ * list of fp32 parameter tensors, on one AMD MI355X (gfx950).
+ *
+ * One call of pipeoptim_step_predict() makes one coalesced pass over the stage:
+ * it reads W_t, g_t and the cached optimizer state once, and writes the updated
+ * state, the stepped weights W_{t+1} (paper Eq. 1, first line) and the predicted
+ * weights What_{t+s} = W_t - lr*s*dW_t (paper Eq. 3 / Eq. 5) that the next
+ * forward pass uses, with dW_t from the optimizer's update rule (paper Table 1).
+ *
+ * Conventions for every function
+ *   - extern "C"; returns PO_OK (0) or a negative po_status; never throws.
+ *   - Tensor pointers are DEVICE pointers owned by the caller.  The library
+ *     never allocates, frees or keeps tensor memory; a plan owns only its own
+ *     small device tables (tensor descriptors + chunk table).
+ *   - `hip_stream` is a hipStream_t passed as void* (NULL = the null stream).
+ *     Work is enqueued and not waited for, except where a function says it
+ *     synchronises.
+ *   - On failure nothing is launched and pipeoptim_last_error() describes it.
+ */
+#ifndef PIPEOPTIM_H
+#define PIPEOPTIM_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    PO_OK = 0,
+    PO_EINVAL = -1,  /* bad argument: NULL where a pointer is required, t < 1, s < 0, negative size,
+                        beta outside [0,1), non-finite hyper-parameter, Adam/AdamW on a plan without v,
+                        launch shape outside the documented limits */
+    PO_EALIGN = -2,  /* a tensor base pointer is not aligned to its element size */
+    PO_EHIP   = -3,  /* a HIP call failed; the HIP error string is in pipeoptim_last_error() */
+    PO_ENOMEM = -4   /* host or device allocation of the plan's tables failed */
+} po_status;
+
+typedef enum { PO_SGDM = 0, PO_ADAM = 1, PO_ADAMW = 2 } po_optimizer;   /* rows of paper Table 1 */
+typedef enum { PO_WHAT_F32 = 0, PO_WHAT_BF16 = 1 } po_what_dtype;       /* element type of What */
+
+/*
+ * Hyper-parameters, in double; the library derives the fp32 kernel coefficients
+ * (including the bias corrections 1-beta1^t and 1-beta2^t of Table 1) itself.
+ */
+typedef struct po_hyper {
+    int32_t opt;                  /* po_optimizer */
+    int32_t decay_in_prediction;  /* AdamW only.  1: dW_t = r + wd*W, the whole per-step increment over lr,
+                                     so that Eq. 1 holds and s = 1 predicts the optimizer's own step.
+                                     0: the prediction uses Table 1's AdamW row alone (r); the step still decays. */
+    double lr;
+    double beta1;                 /* Adam/AdamW beta1;  SGDM: momentum factor u          */
+    double beta2;                 /* Adam/AdamW beta2;  SGDM: dampening tau              */
+    double eps;                   /* Adam/AdamW epsilon (added after the root); SGDM: ignored */
+    double weight_decay;          /* SGDM and Adam: coupled L2, g + wd*W enters the state update.
+                                     AdamW: decoupled, W shrinks by lr*wd*W.              */
+} po_hyper;
+
+/* fp32 coefficients one launch runs with (what the host derives from po_hyper, t and s). */
+typedef struct po_coeffs {
+    float beta1;          /* u or beta1                                   */
+    float grad_scale;     /* 1 - tau or 1 - beta1                         */
+    float beta2;          /* beta2 (0 for SGDM)                           */
+    float one_m_beta2;    /* 1 - beta2 (0 for SGDM)                       */
+    float inv_bc1;        /* 1 / (1 - beta1^t)          (1 for SGDM)      */
+    float inv_sqrt_bc2;   /* 1 / sqrt(1 - beta2^t)      (1 for SGDM)      */
+    float eps;
+    float lr;             /* step:       W' = W - lr   * dW               */
+    float s_lr;           /* prediction: What = W - s_lr * dW,  s_lr = s*lr */
+    float wd_coupled;     /* wd for SGDM/Adam, else 0                     */
+    float wd_step;        /* wd for AdamW, else 0 (decay inside the step's dW) */
+    float wd_pred;        /* wd for AdamW with decay_in_prediction, else 0 */
+    int32_t s_is_zero;    /* 1: What is a copy of W (last pipeline stage, paper Algorithm 1 else-branch) */
+} po_coeffs;
+
+/* One entry of the chunk table: elements [chunk * chunk_elems, min(numel, (chunk+1) * chunk_elems)) of `tensor`. */
+typedef struct po_chunk {
+    uint32_t tensor;
+    uint32_t chunk;
+} po_chunk;
+
+/*
+ * Launch shape of the fused kernel.  Limits: block in {64,128,256}; vec in {4,8}
+ * (fp32 elements per lane per access group; 8 makes the bf16 What store a
+ * dwordx4); unroll in {1,2,4} with vec*unroll <= 16; chunk_elems a positive
+ * multiple of block*vec*unroll, at most 2^30; max_grid >= 0 (0: one workgroup
+ * per chunk; otherwise at most that many workgroups walk the table with a
+ * stride); nontemporal in {0,1,2,3}: bit 0 = loads, bit 1 = stores; xcd_remap in {0,1}:
+ * 1 hands each of the chip's 8 XCDs (workgroup id mod 8) a contiguous eighth of the chunk table
+ * instead of every eighth chunk.
+ */
+typedef struct po_launch {
+    int32_t block;
+    int32_t vec;
+    int32_t unroll;
+    int32_t nontemporal;
+    int64_t chunk_elems;
+    int32_t max_grid;
+    int32_t xcd_remap;
+} po_launch;
+
+typedef struct po_plan po_plan;   /* opaque */
+
+/*
+ * Build a plan for a stage: n_tensors tensors, tensor i having numel[i] fp32
+ * elements at W[i], g[i], m[i], v[i] (device) and a What[i] buffer of numel[i]
+ * elements of what_dtype.  numel, W, g, m, v, What are HOST arrays of length
+ * n_tensors.  v may be NULL (SGDM-only plan).  numel[i] == 0 and n_tensors == 0
+ * are legal.  What[i] must not overlap any other buffer; g is only read;
+ * W, m, v are updated in place.  Buffers aligned to 16 bytes take the vector
+ * path; 4-byte (What bf16: 2-byte) alignment is accepted and takes a scalar
+ * path for that tensor.  Uploads the tables with a blocking copy (this call
+ * synchronises with its own copy, not with `hip_stream`'s other work).
+ * The caller keeps all buffers alive and at the same addresses while the plan lives.
+ */
+int pipeoptim_plan_create(po_plan** out, int64_t n_tensors, const int64_t* numel,
+                          float* const* W, const float* const* g, float* const* m, float* const* v,
+                          void* const* What, int32_t what_dtype, void* hip_stream);
+
+/* Frees the plan's tables.  Synchronises the device first so no launch still reads them.  NULL is a no-op. */
+int pipeoptim_plan_destroy(po_plan* plan);
+
+/* Replace one pointer column (which: 0 W, 1 g, 2 m, 3 v, 4 What) with n_tensors new device pointers
+ * (host array), e.g. when gradient buffers are re-allocated between steps.  Blocking upload. */
+int pipeoptim_plan_set_pointers(po_plan* plan, int32_t which, void* const* ptrs);
+
+/* Get / set the launch shape (set rebuilds and re-uploads the chunk table if chunk_elems changes; blocking). */
+int pipeoptim_plan_get_launch(const po_plan* plan, po_launch* out);
+int pipeoptim_plan_set_launch(po_plan* plan, const po_launch* launch);
+
+/* Totals of a plan: parameters, chunk-table entries, tensors on the scalar (unaligned) path. */
+int pipeoptim_plan_info(const po_plan* plan, int64_t* n_params, int64_t* n_chunks, int64_t* n_unaligned);
+
+/*
+ * The hot path.  For every element of every tensor of the plan, with dW_t from
+ * paper Table 1 (built from the new gradient and the cached state):
+ *     SGDM : g~ = g + wd*W;  m' = u*m + (1-tau)*g~;  dW = m'
+ *     Adam : g~ = g + wd*W;  m' = b1*m + (1-b1)*g~;  v' = b2*v + (1-b2)*g~^2
+ *            dW = (m'/(1-b1^t)) / (sqrt(v'/(1-b2^t)) + eps)
+ *     AdamW: as Adam with g~ = g;  dW = r + wd*W  (prediction: r alone if !decay_in_prediction)
+ *     W'   = W - lr*dW                      (paper Eq. 1)
+ *     What = W - lr*s*dW                    (paper Eq. 5);  s == 0: What = W
+ * in fp32 arithmetic.  W, m, v are overwritten with W', m', v'; What receives
+ * the prediction (bf16: round-to-nearest-even).  t >= 1 is the 1-based step
+ * index of the bias corrections; s >= 0 is the version difference of paper
+ * Eq. 4.  Enqueues exactly one kernel on hip_stream and returns.
+ */
+int pipeoptim_step_predict(const po_plan* plan, const po_hyper* hyper, int64_t t, int32_t s,
+                           void* hip_stream);
+
+/* Paper Eq. 4: s = D - rank - 1 for stage `rank` (0-based) of a depth-D pipeline.  PO_EINVAL unless 0 <= rank < D. */
+int pipeoptim_version_difference(int32_t D, int32_t rank, int32_t* s_out);
+
+/* Host only: the fp32 coefficients pipeoptim_step_predict would launch with (validates hyper, t, s). */
+int pipeoptim_coefficients(const po_hyper* hyper, int64_t t, int32_t s, po_coeffs* out);
+
+/*
+ * Host only: the chunk table for a ragged list.  Writes up to `capacity` entries to out (may be NULL
+ * with capacity 0 to count) and the total to *n_chunks.  Tensors appear in list order, chunks of a
+ * tensor in ascending order, empty tensors contribute none.
+ */
+int pipeoptim_chunk_table_build(int64_t n_tensors, const int64_t* numel, int64_t chunk_elems,
+                                po_chunk* out, int64_t capacity, int64_t* n_chunks);
+
+/* Measurement aid: dst[0..nbytes) = src[0..nbytes) with a plain dwordx4 copy kernel (device pointers,
+ * 16-byte aligned, nbytes a multiple of 16).  Gives the box's achievable read+write bandwidth. */
+int pipeoptim_probe_copy(void* dst, const void* src, int64_t nbytes, void* hip_stream);
+
+/* Thread-local description of the last failure on this thread ("" if none). */
+const char* pipeoptim_last_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* PIPEOPTIM_H */

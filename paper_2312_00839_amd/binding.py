@@ -1,0 +1,186 @@
+"""ctypes binding of libpipeoptim (argument marshalling only).
+
+Function names mirror the C ABI of ``include/pipeoptim.h``.  Every step of the
+path runs in the HIP library; there is no Python or CPU fallback: if the
+library has not been built, loading raises.
+"""
+import ctypes
+import os
+from typing import Optional, Sequence
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libpipeoptim.so")
+
+PO_OK, PO_EINVAL, PO_EALIGN, PO_EHIP, PO_ENOMEM = 0, -1, -2, -3, -4
+PO_SGDM, PO_ADAM, PO_ADAMW = 0, 1, 2
+PO_WHAT_F32, PO_WHAT_BF16 = 0, 1
+OPTIMIZERS = {"sgdm": PO_SGDM, "adam": PO_ADAM, "adamw": PO_ADAMW}
+WHAT_DTYPES = {"f32": PO_WHAT_F32, "bf16": PO_WHAT_BF16}
+
+
+class PipeOptimError(RuntimeError):
+    def __init__(self, status, message):
+        super().__init__("pipeoptim status %d: %s" % (status, message))
+        self.status = status
+
+
+class po_hyper(ctypes.Structure):
+    _fields_ = [("opt", ctypes.c_int32), ("decay_in_prediction", ctypes.c_int32),
+                ("lr", ctypes.c_double), ("beta1", ctypes.c_double), ("beta2", ctypes.c_double),
+                ("eps", ctypes.c_double), ("weight_decay", ctypes.c_double)]
+
+
+class po_coeffs(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_float) for n in
+                ("beta1", "grad_scale", "beta2", "one_m_beta2", "inv_bc1", "inv_sqrt_bc2", "eps", "lr", "s_lr",
+                 "wd_coupled", "wd_step", "wd_pred")] + [("s_is_zero", ctypes.c_int32)]
+
+
+class po_chunk(ctypes.Structure):
+    _fields_ = [("tensor", ctypes.c_uint32), ("chunk", ctypes.c_uint32)]
+
+
+class po_launch(ctypes.Structure):
+    _fields_ = [("block", ctypes.c_int32), ("vec", ctypes.c_int32), ("unroll", ctypes.c_int32),
+                ("nontemporal", ctypes.c_int32), ("chunk_elems", ctypes.c_int64),
+                ("max_grid", ctypes.c_int32), ("xcd_remap", ctypes.c_int32)]
+
+
+EXPORTS = (
+    "pipeoptim_plan_create", "pipeoptim_plan_destroy", "pipeoptim_plan_set_pointers",
+    "pipeoptim_plan_get_launch", "pipeoptim_plan_set_launch", "pipeoptim_plan_info",
+    "pipeoptim_step_predict", "pipeoptim_version_difference", "pipeoptim_coefficients",
+    "pipeoptim_chunk_table_build", "pipeoptim_probe_copy", "pipeoptim_last_error",
+)
+
+_lib = None
+
+
+def lib():
+    """The loaded library.  Raises if it was not built (``python -m paper_2312_00839_amd.build``)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise ImportError("libpipeoptim.so is not built: run `python -m paper_2312_00839_amd.build` "
+                              "(there is no CPU fallback)")
+        L = ctypes.CDLL(LIB_PATH)
+        vp, i32, i64 = ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64
+        P = ctypes.POINTER
+        L.pipeoptim_plan_create.argtypes = [P(vp), i64, P(i64), P(vp), P(vp), P(vp), P(vp), P(vp), i32, vp]
+        L.pipeoptim_plan_destroy.argtypes = [vp]
+        L.pipeoptim_plan_set_pointers.argtypes = [vp, i32, P(vp)]
+        L.pipeoptim_plan_get_launch.argtypes = [vp, P(po_launch)]
+        L.pipeoptim_plan_set_launch.argtypes = [vp, P(po_launch)]
+        L.pipeoptim_plan_info.argtypes = [vp, P(i64), P(i64), P(i64)]
+        L.pipeoptim_step_predict.argtypes = [vp, P(po_hyper), i64, i32, vp]
+        L.pipeoptim_version_difference.argtypes = [i32, i32, P(i32)]
+        L.pipeoptim_coefficients.argtypes = [P(po_hyper), i64, i32, P(po_coeffs)]
+        L.pipeoptim_chunk_table_build.argtypes = [i64, P(i64), i64, P(po_chunk), i64, P(i64)]
+        L.pipeoptim_probe_copy.argtypes = [vp, vp, i64, vp]
+        for name in EXPORTS:
+            getattr(L, name).restype = ctypes.c_int
+        L.pipeoptim_last_error.restype = ctypes.c_char_p
+        L.pipeoptim_last_error.argtypes = []
+        _lib = L
+    return _lib
+
+
+def pipeoptim_last_error() -> str:
+    return lib().pipeoptim_last_error().decode()
+
+
+def _check(rc):
+    if rc != PO_OK:
+        raise PipeOptimError(rc, pipeoptim_last_error())
+
+
+def make_hyper(opt, lr, beta1, beta2, eps=0.0, weight_decay=0.0, decay_in_prediction=True) -> po_hyper:
+    if isinstance(opt, str):
+        opt = OPTIMIZERS[opt]
+    return po_hyper(int(opt), int(bool(decay_in_prediction)), float(lr), float(beta1), float(beta2),
+                    float(eps), float(weight_decay))
+
+
+def pipeoptim_version_difference(D: int, rank: int) -> int:
+    s = ctypes.c_int32(-1)
+    _check(lib().pipeoptim_version_difference(int(D), int(rank), ctypes.byref(s)))
+    return s.value
+
+
+def pipeoptim_coefficients(hyper: po_hyper, t: int, s: int) -> po_coeffs:
+    c = po_coeffs()
+    _check(lib().pipeoptim_coefficients(ctypes.byref(hyper), int(t), int(s), ctypes.byref(c)))
+    return c
+
+
+def pipeoptim_chunk_table_build(numel: Sequence[int], chunk_elems: int):
+    """Host-only: list of (tensor, chunk) pairs for a ragged list."""
+    n = len(numel)
+    arr = (ctypes.c_int64 * max(n, 1))(*numel)
+    count = ctypes.c_int64(0)
+    _check(lib().pipeoptim_chunk_table_build(n, arr, int(chunk_elems), None, 0, ctypes.byref(count)))
+    buf = (po_chunk * max(count.value, 1))()
+    _check(lib().pipeoptim_chunk_table_build(n, arr, int(chunk_elems), buf, count.value, ctypes.byref(count)))
+    return [(buf[i].tensor, buf[i].chunk) for i in range(count.value)]
+
+
+def _ptr_array(ptrs: Sequence[int]):
+    return (ctypes.c_void_p * max(len(ptrs), 1))(*[ctypes.c_void_p(p) for p in ptrs])
+
+
+class Plan:
+    """Owner of a ``po_plan*``.  Pointers are raw device addresses (ints), e.g. ``tensor.data_ptr()``."""
+
+    def __init__(self, numel: Sequence[int], W: Sequence[int], g: Sequence[int], m: Sequence[int],
+                 v: Optional[Sequence[int]], What: Sequence[int], what_dtype, stream: int = 0):
+        if isinstance(what_dtype, str):
+            what_dtype = WHAT_DTYPES[what_dtype]
+        n = len(numel)
+        self._h = ctypes.c_void_p()
+        self.n_tensors = n
+        self.what_dtype = what_dtype
+        _check(lib().pipeoptim_plan_create(
+            ctypes.byref(self._h), n, (ctypes.c_int64 * max(n, 1))(*numel), _ptr_array(W), _ptr_array(g),
+            _ptr_array(m), _ptr_array(v) if v is not None else None, _ptr_array(What), int(what_dtype),
+            ctypes.c_void_p(stream)))
+
+    def step_predict(self, hyper: po_hyper, t: int, s: int, stream: int = 0) -> None:
+        _check(lib().pipeoptim_step_predict(self._h, ctypes.byref(hyper), int(t), int(s), ctypes.c_void_p(stream)))
+
+    def set_pointers(self, which: int, ptrs: Sequence[int]) -> None:
+        _check(lib().pipeoptim_plan_set_pointers(self._h, int(which), _ptr_array(ptrs)))
+
+    def get_launch(self) -> po_launch:
+        L = po_launch()
+        _check(lib().pipeoptim_plan_get_launch(self._h, ctypes.byref(L)))
+        return L
+
+    def set_launch(self, **kw) -> po_launch:
+        L = self.get_launch()
+        for k, val in kw.items():
+            if not hasattr(L, k):
+                raise TypeError("po_launch has no field %r" % k)
+            setattr(L, k, int(val))
+        _check(lib().pipeoptim_plan_set_launch(self._h, ctypes.byref(L)))
+        return L
+
+    def info(self):
+        a, b, c = ctypes.c_int64(), ctypes.c_int64(), ctypes.c_int64()
+        _check(lib().pipeoptim_plan_info(self._h, ctypes.byref(a), ctypes.byref(b), ctypes.byref(c)))
+        return {"n_params": a.value, "n_chunks": b.value, "n_unaligned": c.value}
+
+    def destroy(self) -> None:
+        if self._h:
+            h, self._h = self._h, ctypes.c_void_p()
+            _check(lib().pipeoptim_plan_destroy(h))
+
+    def __del__(self):
+        try:
+            self.destroy()
+        except Exception:
+            pass
+
+
+def pipeoptim_probe_copy(dst: int, src: int, nbytes: int, stream: int = 0) -> None:
+    _check(lib().pipeoptim_probe_copy(ctypes.c_void_p(dst), ctypes.c_void_p(src), int(nbytes),
+                                      ctypes.c_void_p(stream)))

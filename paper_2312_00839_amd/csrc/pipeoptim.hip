@@ -1,0 +1,378 @@
+// Host side of libpipeoptim: the C ABI declared in include/pipeoptim.h.
+//
+// Holds the plan (tensor descriptors + chunk table, mirrored on the device), the
+// derivation of the fp32 kernel coefficients from the double hyper-parameters
+// (bias corrections of paper Table 1 in fp64), the version-difference rule of
+// paper Eq. 4, and argument validation.  The kernels live in
+// step_predict_kernels.hip.
+#include <cmath>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <new>
+#include <vector>
+
+#include "po_internal.h"
+
+namespace {
+
+thread_local char g_err[512] = "";
+
+int fail(int code, const char* fmt, ...)
+{
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_err, sizeof g_err, fmt, ap);
+    va_end(ap);
+    return code;
+}
+
+int fail_hip(hipError_t e, const char* what)
+{
+    return fail(PO_EHIP, "%s: %s", what, hipGetErrorString(e));
+}
+
+constexpr int64_t kMaxChunkElems = int64_t(1) << 30;
+
+int check_launch(const po_launch& L)
+{
+    if (L.block != 64 && L.block != 128 && L.block != 256) return fail(PO_EINVAL, "launch.block must be 64, 128 or 256");
+    if (L.vec != 4 && L.vec != 8) return fail(PO_EINVAL, "launch.vec must be 4 or 8");
+    if (L.unroll != 1 && L.unroll != 2 && L.unroll != 4) return fail(PO_EINVAL, "launch.unroll must be 1, 2 or 4");
+    if (L.vec * L.unroll > 16) return fail(PO_EINVAL, "launch.vec * launch.unroll must not exceed 16");
+    if (L.nontemporal < 0 || L.nontemporal > 3) return fail(PO_EINVAL, "launch.nontemporal must be 0..3");
+    if (L.xcd_remap != 0 && L.xcd_remap != 1) return fail(PO_EINVAL, "launch.xcd_remap must be 0 or 1");
+    if (L.max_grid < 0) return fail(PO_EINVAL, "launch.max_grid must be >= 0");
+    const int64_t tile = (int64_t)L.block * L.vec * L.unroll;
+    if (L.chunk_elems <= 0 || L.chunk_elems > kMaxChunkElems || L.chunk_elems % tile != 0)
+        return fail(PO_EINVAL, "launch.chunk_elems must be a positive multiple of block*vec*unroll (%lld), at most 2^30",
+                    (long long)tile);
+    return PO_OK;
+}
+
+int build_chunks(int64_t n_tensors, const int64_t* numel, int64_t chunk_elems, po_chunk* out, int64_t capacity,
+                 int64_t* n_chunks)
+{
+    if (n_tensors < 0) return fail(PO_EINVAL, "n_tensors < 0");
+    if (n_tensors > 0 && !numel) return fail(PO_EINVAL, "numel is NULL");
+    if (chunk_elems <= 0 || chunk_elems > kMaxChunkElems) return fail(PO_EINVAL, "chunk_elems out of range");
+    if (n_tensors > (int64_t)UINT32_MAX) return fail(PO_EINVAL, "too many tensors");
+    if (capacity < 0 || (capacity > 0 && !out)) return fail(PO_EINVAL, "bad output buffer");
+    if (!n_chunks) return fail(PO_EINVAL, "n_chunks is NULL");
+    int64_t total = 0;
+    for (int64_t i = 0; i < n_tensors; ++i) {
+        if (numel[i] < 0) return fail(PO_EINVAL, "numel[%lld] < 0", (long long)i);
+        const int64_t k = (numel[i] + chunk_elems - 1) / chunk_elems;
+        if (k > (int64_t)UINT32_MAX) return fail(PO_EINVAL, "tensor %lld needs too many chunks", (long long)i);
+        for (int64_t j = 0; j < k; ++j, ++total)
+            if (total < capacity) out[total] = po_chunk{(uint32_t)i, (uint32_t)j};
+    }
+    if (total > (int64_t)UINT32_MAX) return fail(PO_EINVAL, "chunk table too long; raise chunk_elems");
+    *n_chunks = total;
+    return PO_OK;
+}
+
+bool finite_d(double x) { return std::isfinite(x); }
+
+}  // namespace
+
+struct po_plan {
+    int64_t n_tensors = 0;
+    int64_t n_params = 0;
+    int64_t n_unaligned = 0;
+    int32_t what_dtype = PO_WHAT_F32;
+    bool has_v = false;
+    int device = 0;
+    po_launch launch{};
+    std::vector<int64_t> numel;
+    std::vector<po_tensor_desc> descs;    // host mirror
+    std::vector<po_chunk> chunks;         // host mirror
+    po_tensor_desc* d_descs = nullptr;
+    po_chunk* d_chunks = nullptr;
+    int64_t d_chunks_capacity = 0;
+};
+
+namespace {
+
+int upload_chunks(po_plan* p)
+{
+    int64_t n = 0;
+    int rc = build_chunks(p->n_tensors, p->numel.data(), p->launch.chunk_elems, nullptr, 0, &n);
+    if (rc != PO_OK) return rc;
+    p->chunks.resize((size_t)n);
+    rc = build_chunks(p->n_tensors, p->numel.data(), p->launch.chunk_elems, p->chunks.data(), n, &n);
+    if (rc != PO_OK) return rc;
+    if (n > p->d_chunks_capacity) {
+        if (p->d_chunks) {
+            hipError_t e = hipDeviceSynchronize();   // a launch may still read the old table
+            if (e != hipSuccess) return fail_hip(e, "hipDeviceSynchronize");
+            (void)hipFree(p->d_chunks);
+            p->d_chunks = nullptr;
+            p->d_chunks_capacity = 0;
+        }
+        hipError_t e = hipMalloc(reinterpret_cast<void**>(&p->d_chunks), (size_t)n * sizeof(po_chunk));
+        if (e != hipSuccess) return fail(PO_ENOMEM, "hipMalloc(chunk table, %lld entries): %s", (long long)n,
+                                         hipGetErrorString(e));
+        p->d_chunks_capacity = n;
+    }
+    if (n > 0) {
+        hipError_t e = hipMemcpy(p->d_chunks, p->chunks.data(), (size_t)n * sizeof(po_chunk), hipMemcpyHostToDevice);
+        if (e != hipSuccess) return fail_hip(e, "hipMemcpy(chunk table)");
+    }
+    return PO_OK;
+}
+
+int upload_descs(po_plan* p)
+{
+    if (p->n_tensors == 0) return PO_OK;
+    hipError_t e = hipMemcpy(p->d_descs, p->descs.data(), (size_t)p->n_tensors * sizeof(po_tensor_desc),
+                             hipMemcpyHostToDevice);
+    if (e != hipSuccess) return fail_hip(e, "hipMemcpy(tensor descriptors)");
+    return PO_OK;
+}
+
+void refresh_flags(po_plan* p)
+{
+    p->n_unaligned = 0;
+    for (auto& d : p->descs) {
+        uintptr_t bits = (uintptr_t)d.W | (uintptr_t)d.g | (uintptr_t)d.m | (uintptr_t)d.v | (uintptr_t)d.What;
+        d.flags = (bits & 15u) == 0 ? PO_DESC_VECTOR_OK : 0u;
+        if (!d.flags && d.numel > 0) ++p->n_unaligned;
+    }
+}
+
+// Default launch shape; chunk size shrinks for small stages so that the grid still fills 256 CUs.
+po_launch default_launch(int64_t n_params, int32_t what_dtype)
+{
+    po_launch L{};
+    L.block = 256;
+    L.vec = 4;
+    L.unroll = 4;
+    L.nontemporal = 0;
+    L.max_grid = 0;
+    L.xcd_remap = 0;
+    (void)what_dtype;
+    const int64_t tile = (int64_t)L.block * L.vec * L.unroll;   // 4096 elements
+    L.chunk_elems = n_params >= (int64_t(1) << 27) ? 4 * tile : tile;
+    return L;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* pipeoptim_last_error(void) { return g_err; }
+
+int pipeoptim_version_difference(int32_t D, int32_t rank, int32_t* s_out)
+{
+    if (!s_out) return fail(PO_EINVAL, "s_out is NULL");
+    if (D < 1 || rank < 0 || rank >= D) return fail(PO_EINVAL, "need 0 <= rank < D (D=%d, rank=%d)", D, rank);
+    *s_out = D - rank - 1;   // paper Eq. 4
+    return PO_OK;
+}
+
+int pipeoptim_coefficients(const po_hyper* h, int64_t t, int32_t s, po_coeffs* out)
+{
+    if (!h || !out) return fail(PO_EINVAL, "hyper or out is NULL");
+    if (h->opt != PO_SGDM && h->opt != PO_ADAM && h->opt != PO_ADAMW) return fail(PO_EINVAL, "unknown optimizer %d", h->opt);
+    if (t < 1) return fail(PO_EINVAL, "t must be >= 1 (got %lld): steps are 1-based", (long long)t);
+    if (s < 0) return fail(PO_EINVAL, "s must be >= 0 (got %d)", s);
+    if (!finite_d(h->lr) || !finite_d(h->eps) || !finite_d(h->weight_decay) || !finite_d(h->beta1) || !finite_d(h->beta2))
+        return fail(PO_EINVAL, "non-finite hyper-parameter");
+    if (h->eps < 0) return fail(PO_EINVAL, "eps must be >= 0");
+    po_coeffs c{};
+    if (h->opt == PO_SGDM) {
+        if (h->beta1 < 0 || h->beta1 >= 1) return fail(PO_EINVAL, "momentum must be in [0,1)");
+        if (h->beta2 < 0 || h->beta2 > 1) return fail(PO_EINVAL, "dampening must be in [0,1]");
+        c.beta1 = (float)h->beta1;
+        c.grad_scale = (float)(1.0 - h->beta2);
+        c.beta2 = 0.f;
+        c.one_m_beta2 = 0.f;
+        c.inv_bc1 = 1.f;
+        c.inv_sqrt_bc2 = 1.f;
+        c.eps = 0.f;
+        c.wd_coupled = (float)h->weight_decay;
+    } else {
+        if (h->beta1 < 0 || h->beta1 >= 1 || h->beta2 < 0 || h->beta2 >= 1) return fail(PO_EINVAL, "betas must be in [0,1)");
+        // bias corrections of Table 1, in fp64; t >= 1 and beta < 1 keep both strictly positive
+        const double bc1 = 1.0 - std::pow(h->beta1, (double)t);
+        const double bc2 = 1.0 - std::pow(h->beta2, (double)t);
+        c.beta1 = (float)h->beta1;
+        c.grad_scale = (float)(1.0 - h->beta1);
+        c.beta2 = (float)h->beta2;
+        c.one_m_beta2 = (float)(1.0 - h->beta2);
+        c.inv_bc1 = (float)(1.0 / bc1);
+        c.inv_sqrt_bc2 = (float)(1.0 / std::sqrt(bc2));
+        c.eps = (float)h->eps;
+        if (h->opt == PO_ADAM) {
+            c.wd_coupled = (float)h->weight_decay;
+        } else {
+            c.wd_step = (float)h->weight_decay;
+            c.wd_pred = h->decay_in_prediction ? (float)h->weight_decay : 0.f;
+        }
+    }
+    c.lr = (float)h->lr;
+    c.s_lr = (float)((double)s * h->lr);
+    c.s_is_zero = (s == 0);
+    *out = c;
+    return PO_OK;
+}
+
+int pipeoptim_chunk_table_build(int64_t n_tensors, const int64_t* numel, int64_t chunk_elems, po_chunk* out,
+                                int64_t capacity, int64_t* n_chunks)
+{
+    return build_chunks(n_tensors, numel, chunk_elems, out, capacity, n_chunks);
+}
+
+int pipeoptim_plan_create(po_plan** out, int64_t n_tensors, const int64_t* numel, float* const* W,
+                          const float* const* g, float* const* m, float* const* v, void* const* What,
+                          int32_t what_dtype, void* hip_stream)
+{
+    (void)hip_stream;
+    if (!out) return fail(PO_EINVAL, "out is NULL");
+    *out = nullptr;
+    if (n_tensors < 0) return fail(PO_EINVAL, "n_tensors < 0");
+    if (n_tensors > 0 && (!numel || !W || !g || !m || !What)) return fail(PO_EINVAL, "a required pointer array is NULL");
+    if (what_dtype != PO_WHAT_F32 && what_dtype != PO_WHAT_BF16) return fail(PO_EINVAL, "unknown what_dtype %d", what_dtype);
+    const uintptr_t what_mask = what_dtype == PO_WHAT_BF16 ? 1u : 3u;
+    int64_t total = 0;
+    for (int64_t i = 0; i < n_tensors; ++i) {
+        if (numel[i] < 0) return fail(PO_EINVAL, "numel[%lld] < 0", (long long)i);
+        if (numel[i] == 0) continue;
+        if (!W[i] || !g[i] || !m[i] || !What[i] || (v && !v[i]))
+            return fail(PO_EINVAL, "tensor %lld has a NULL buffer", (long long)i);
+        if (((uintptr_t)W[i] | (uintptr_t)g[i] | (uintptr_t)m[i] | (v ? (uintptr_t)v[i] : 0)) & 3u)
+            return fail(PO_EALIGN, "tensor %lld: fp32 buffer not 4-byte aligned", (long long)i);
+        if ((uintptr_t)What[i] & what_mask) return fail(PO_EALIGN, "tensor %lld: What not aligned to its element", (long long)i);
+        total += numel[i];
+    }
+    po_plan* p = new (std::nothrow) po_plan;
+    if (!p) return fail(PO_ENOMEM, "out of host memory");
+    p->n_tensors = n_tensors;
+    p->n_params = total;
+    p->what_dtype = what_dtype;
+    p->has_v = (v != nullptr);
+    p->numel.assign(numel, numel + n_tensors);
+    p->descs.resize((size_t)n_tensors);
+    for (int64_t i = 0; i < n_tensors; ++i) {
+        po_tensor_desc& d = p->descs[(size_t)i];
+        d.W = W[i]; d.g = g[i]; d.m = m[i]; d.v = v ? v[i] : nullptr; d.What = What[i];
+        d.numel = numel[i]; d.flags = 0; d.pad = 0;
+    }
+    refresh_flags(p);
+    p->launch = default_launch(total, what_dtype);
+
+    hipError_t e = hipGetDevice(&p->device);
+    if (e != hipSuccess) { delete p; return fail_hip(e, "hipGetDevice"); }
+    if (n_tensors > 0) {
+        e = hipMalloc(reinterpret_cast<void**>(&p->d_descs), (size_t)n_tensors * sizeof(po_tensor_desc));
+        if (e != hipSuccess) { delete p; return fail(PO_ENOMEM, "hipMalloc(descriptors): %s", hipGetErrorString(e)); }
+    }
+    int rc = upload_descs(p);
+    if (rc == PO_OK) rc = upload_chunks(p);
+    if (rc != PO_OK) { pipeoptim_plan_destroy(p); return rc; }
+    *out = p;
+    return PO_OK;
+}
+
+int pipeoptim_plan_destroy(po_plan* p)
+{
+    if (!p) return PO_OK;
+    int rc = PO_OK;
+    if (p->d_descs || p->d_chunks) {
+        hipError_t e = hipDeviceSynchronize();
+        if (e != hipSuccess) rc = fail_hip(e, "hipDeviceSynchronize");
+        if (p->d_descs) (void)hipFree(p->d_descs);
+        if (p->d_chunks) (void)hipFree(p->d_chunks);
+    }
+    delete p;
+    return rc;
+}
+
+int pipeoptim_plan_set_pointers(po_plan* p, int32_t which, void* const* ptrs)
+{
+    if (!p) return fail(PO_EINVAL, "plan is NULL");
+    if (which < 0 || which > 4) return fail(PO_EINVAL, "which must be 0..4");
+    if (which == 3 && !p->has_v) return fail(PO_EINVAL, "plan has no v column");
+    if (p->n_tensors > 0 && !ptrs) return fail(PO_EINVAL, "ptrs is NULL");
+    const uintptr_t mask = (which == 4 && p->what_dtype == PO_WHAT_BF16) ? 1u : 3u;
+    for (int64_t i = 0; i < p->n_tensors; ++i) {
+        if (p->numel[(size_t)i] == 0) continue;
+        if (!ptrs[i]) return fail(PO_EINVAL, "tensor %lld: NULL pointer", (long long)i);
+        if ((uintptr_t)ptrs[i] & mask) return fail(PO_EALIGN, "tensor %lld: pointer not aligned to its element", (long long)i);
+    }
+    for (int64_t i = 0; i < p->n_tensors; ++i) {
+        po_tensor_desc& d = p->descs[(size_t)i];
+        switch (which) {
+        case 0: d.W = static_cast<float*>(ptrs[i]); break;
+        case 1: d.g = static_cast<const float*>(ptrs[i]); break;
+        case 2: d.m = static_cast<float*>(ptrs[i]); break;
+        case 3: d.v = static_cast<float*>(ptrs[i]); break;
+        case 4: d.What = ptrs[i]; break;
+        }
+    }
+    refresh_flags(p);
+    hipError_t e = hipDeviceSynchronize();   // a launch may still read the old descriptors
+    if (e != hipSuccess) return fail_hip(e, "hipDeviceSynchronize");
+    return upload_descs(p);
+}
+
+int pipeoptim_plan_get_launch(const po_plan* p, po_launch* out)
+{
+    if (!p || !out) return fail(PO_EINVAL, "plan or out is NULL");
+    *out = p->launch;
+    return PO_OK;
+}
+
+int pipeoptim_plan_set_launch(po_plan* p, const po_launch* L)
+{
+    if (!p || !L) return fail(PO_EINVAL, "plan or launch is NULL");
+    int rc = check_launch(*L);
+    if (rc != PO_OK) return rc;
+    const bool rechunk = L->chunk_elems != p->launch.chunk_elems;
+    const po_launch old = p->launch;
+    p->launch = *L;
+    if (rechunk) {
+        hipError_t e = hipDeviceSynchronize();   // a launch may still read the old table
+        if (e != hipSuccess) { p->launch = old; return fail_hip(e, "hipDeviceSynchronize"); }
+        rc = upload_chunks(p);
+        if (rc != PO_OK) { p->launch = old; (void)upload_chunks(p); return rc; }
+    }
+    return PO_OK;
+}
+
+int pipeoptim_plan_info(const po_plan* p, int64_t* n_params, int64_t* n_chunks, int64_t* n_unaligned)
+{
+    if (!p) return fail(PO_EINVAL, "plan is NULL");
+    if (n_params) *n_params = p->n_params;
+    if (n_chunks) *n_chunks = (int64_t)p->chunks.size();
+    if (n_unaligned) *n_unaligned = p->n_unaligned;
+    return PO_OK;
+}
+
+int pipeoptim_step_predict(const po_plan* p, const po_hyper* h, int64_t t, int32_t s, void* hip_stream)
+{
+    if (!p) return fail(PO_EINVAL, "plan is NULL");
+    po_coeffs c;
+    int rc = pipeoptim_coefficients(h, t, s, &c);
+    if (rc != PO_OK) return rc;
+    if (h->opt != PO_SGDM && !p->has_v) return fail(PO_EINVAL, "Adam/AdamW needs a plan created with v");
+    if (p->chunks.empty()) return PO_OK;
+    hipError_t e = po_launch_step_predict(h->opt, p->what_dtype, p->launch, p->d_descs, p->d_chunks,
+                                          (uint32_t)p->chunks.size(), c, static_cast<hipStream_t>(hip_stream));
+    if (e != hipSuccess) return fail_hip(e, "launch of the fused step+predict kernel");
+    return PO_OK;
+}
+
+int pipeoptim_probe_copy(void* dst, const void* src, int64_t nbytes, void* hip_stream)
+{
+    if (nbytes < 0 || (nbytes & 15)) return fail(PO_EINVAL, "nbytes must be a non-negative multiple of 16");
+    if (nbytes == 0) return PO_OK;
+    if (!dst || !src) return fail(PO_EINVAL, "dst or src is NULL");
+    if (((uintptr_t)dst | (uintptr_t)src) & 15u) return fail(PO_EALIGN, "dst and src must be 16-byte aligned");
+    hipError_t e = po_launch_probe_copy(dst, src, nbytes, static_cast<hipStream_t>(hip_stream));
+    if (e != hipSuccess) return fail_hip(e, "launch of the copy kernel");
+    return PO_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,174 @@
+"""Host-side checks of libpipeoptim that need no GPU: exported symbols, the version-difference
+rule, the coefficient derivation, the chunk table, and argument validation that fails before
+any device call."""
+import ctypes
+import math
+import os
+import re
+
+import numpy as np
+import pytest
+
+from paper_2312_00839_amd import binding
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "pipeoptim.h")
+
+
+def _declared_functions():
+    text = open(HEADER).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(pipeoptim_\w+)\s*\(", text)))
+
+
+def test_library_loads_and_exports_every_declared_symbol():
+    L = binding.lib()
+    declared = _declared_functions()
+    assert len(declared) >= 12
+    for name in declared:
+        assert hasattr(L, name), name
+    assert sorted(binding.EXPORTS) == declared
+
+
+def test_struct_layouts_match_header():
+    assert ctypes.sizeof(binding.po_hyper) == 48
+    assert ctypes.sizeof(binding.po_coeffs) == 52
+    assert ctypes.sizeof(binding.po_chunk) == 8
+    assert ctypes.sizeof(binding.po_launch) == 32
+
+
+def test_version_difference_eq4():
+    # D = 4: stages 0..3 predict 3, 2, 1, 0 versions ahead (the indices of the paper's Fig. 2 discussion)
+    assert [binding.pipeoptim_version_difference(4, r) for r in range(4)] == [3, 2, 1, 0]
+    assert binding.pipeoptim_version_difference(1, 0) == 0
+    for D, rank in [(4, 4), (4, -1), (0, 0)]:
+        with pytest.raises(binding.PipeOptimError) as e:
+            binding.pipeoptim_version_difference(D, rank)
+        assert e.value.status == binding.PO_EINVAL
+
+
+def test_version_difference_agrees_with_oracle(oracle):
+    for D in range(1, 13):
+        for rank in range(D):
+            assert binding.pipeoptim_version_difference(D, rank) == oracle.version_difference(D, rank)
+
+
+def _f32(x):
+    return float(np.float32(x))
+
+
+def test_coefficients_adam_family():
+    h = binding.make_hyper("adamw", 1e-3, 0.9, 0.999, 1e-8, 0.01, True)
+    for t, s in [(1, 0), (2, 1), (100, 3), (5000, 7), (10 ** 7, 2)]:
+        c = binding.pipeoptim_coefficients(h, t, s)
+        assert c.beta1 == _f32(0.9) and c.grad_scale == _f32(1 - 0.9)
+        assert c.beta2 == _f32(0.999) and c.one_m_beta2 == _f32(1 - 0.999)
+        assert c.inv_bc1 == _f32(1 / (1 - 0.9 ** t))
+        assert c.inv_sqrt_bc2 == _f32(1 / math.sqrt(1 - 0.999 ** t))
+        assert c.eps == _f32(1e-8) and c.lr == _f32(1e-3) and c.s_lr == _f32(s * 1e-3)
+        assert c.wd_coupled == 0 and c.wd_step == _f32(0.01) and c.wd_pred == _f32(0.01)
+        assert c.s_is_zero == int(s == 0)
+    h0 = binding.make_hyper("adamw", 1e-3, 0.9, 0.999, 1e-8, 0.01, False)
+    c = binding.pipeoptim_coefficients(h0, 3, 2)
+    assert c.wd_step == _f32(0.01) and c.wd_pred == 0
+    ha = binding.make_hyper("adam", 1e-3, 0.9, 0.999, 1e-8, 0.1)
+    c = binding.pipeoptim_coefficients(ha, 3, 2)
+    assert c.wd_coupled == _f32(0.1) and c.wd_step == 0 and c.wd_pred == 0
+
+
+def test_coefficients_sgdm():
+    h = binding.make_hyper("sgdm", 0.1, 0.9, 0.25, 123.0, 1e-4)
+    c = binding.pipeoptim_coefficients(h, 1, 3)
+    assert c.beta1 == _f32(0.9) and c.grad_scale == _f32(0.75)
+    assert c.inv_bc1 == 1 and c.inv_sqrt_bc2 == 1 and c.eps == 0 and c.beta2 == 0 and c.one_m_beta2 == 0
+    assert c.wd_coupled == _f32(1e-4) and c.wd_step == 0 and c.wd_pred == 0
+    assert c.lr == _f32(0.1) and c.s_lr == _f32(0.3)
+
+
+@pytest.mark.parametrize("kw,t,s", [
+    (dict(lr=float("nan")), 1, 1), (dict(lr=float("inf")), 1, 1), (dict(beta1=1.0), 1, 1), (dict(beta1=-0.1), 1, 1),
+    (dict(beta2=1.0), 1, 1), (dict(eps=-1.0), 1, 1), (dict(weight_decay=float("nan")), 1, 1),
+    (dict(opt=7), 1, 1), ({}, 0, 1), ({}, -5, 1), ({}, 1, -1),
+])
+def test_coefficients_reject_bad_arguments(kw, t, s):
+    base = dict(opt="adam", lr=1e-3, beta1=0.9, beta2=0.999, eps=1e-8, weight_decay=0.0)
+    base.update(kw)
+    h = binding.make_hyper(**base)
+    with pytest.raises(binding.PipeOptimError) as e:
+        binding.pipeoptim_coefficients(h, t, s)
+    assert e.value.status == binding.PO_EINVAL
+    assert binding.pipeoptim_last_error() != ""
+
+
+@pytest.mark.parametrize("chunk", [1, 4096, 8192, 65536, 1 << 30])
+def test_chunk_table_covers_every_element_exactly_once(chunk):
+    numel = [0, 1, 3, 4095, 4096, 4097, 0, 131072000, 12288, 7]
+    if chunk == 1:
+        numel = [0, 1, 3, 0, 17]
+    table = binding.pipeoptim_chunk_table_build(numel, chunk)
+    # order: tensors ascending, chunks ascending inside a tensor, empty tensors absent
+    assert table == sorted(table)
+    covered = {}
+    for tensor, c in table:
+        begin = c * chunk
+        end = min(numel[tensor], begin + chunk)
+        assert begin < end, "empty chunk"
+        assert covered.get(tensor, 0) == begin, "gap or overlap"
+        covered[tensor] = end
+    for i, n in enumerate(numel):
+        assert covered.get(i, 0) == n
+    assert len(table) == sum((n + chunk - 1) // chunk for n in numel)
+
+
+def test_chunk_table_count_only_and_errors():
+    L = binding.lib()
+    numel = (ctypes.c_int64 * 3)(10, 20, 30)
+    n = ctypes.c_int64(-1)
+    assert L.pipeoptim_chunk_table_build(3, numel, 8, None, 0, ctypes.byref(n)) == 0 and n.value == 2 + 3 + 4
+    small = (binding.po_chunk * 2)()
+    assert L.pipeoptim_chunk_table_build(3, numel, 8, small, 2, ctypes.byref(n)) == 0 and n.value == 9
+    assert (small[1].tensor, small[1].chunk) == (0, 1)
+    bad = (ctypes.c_int64 * 1)(-4)
+    assert L.pipeoptim_chunk_table_build(1, bad, 8, None, 0, ctypes.byref(n)) == binding.PO_EINVAL
+    assert L.pipeoptim_chunk_table_build(3, numel, 0, None, 0, ctypes.byref(n)) == binding.PO_EINVAL
+    assert L.pipeoptim_chunk_table_build(3, None, 8, None, 0, ctypes.byref(n)) == binding.PO_EINVAL
+    assert L.pipeoptim_chunk_table_build(-1, numel, 8, None, 0, ctypes.byref(n)) == binding.PO_EINVAL
+    assert L.pipeoptim_chunk_table_build(3, numel, 8, None, 0, None) == binding.PO_EINVAL
+
+
+def test_plan_create_validation_happens_before_any_device_call():
+    L = binding.lib()
+    h = ctypes.c_void_p()
+    one = (ctypes.c_int64 * 1)(8)
+    neg = (ctypes.c_int64 * 1)(-8)
+    p = (ctypes.c_void_p * 1)(ctypes.c_void_p(4096))
+    odd = (ctypes.c_void_p * 1)(ctypes.c_void_p(4098))
+    null = (ctypes.c_void_p * 1)(None)
+    assert L.pipeoptim_plan_create(None, 1, one, p, p, p, p, p, 0, None) == binding.PO_EINVAL
+    assert L.pipeoptim_plan_create(ctypes.byref(h), -1, one, p, p, p, p, p, 0, None) == binding.PO_EINVAL
+    assert L.pipeoptim_plan_create(ctypes.byref(h), 1, neg, p, p, p, p, p, 0, None) == binding.PO_EINVAL
+    assert L.pipeoptim_plan_create(ctypes.byref(h), 1, one, None, p, p, p, p, 0, None) == binding.PO_EINVAL
+    assert L.pipeoptim_plan_create(ctypes.byref(h), 1, one, p, null, p, p, p, 0, None) == binding.PO_EINVAL
+    assert L.pipeoptim_plan_create(ctypes.byref(h), 1, one, p, p, p, p, p, 5, None) == binding.PO_EINVAL
+    assert L.pipeoptim_plan_create(ctypes.byref(h), 1, one, odd, p, p, p, p, 0, None) == binding.PO_EALIGN
+    assert L.pipeoptim_plan_create(ctypes.byref(h), 1, one, p, p, p, p, odd, 0, None) == binding.PO_EALIGN
+    assert not h.value
+    assert "aligned" in binding.pipeoptim_last_error()
+    # NULL plan handles are rejected (or ignored by destroy)
+    hyper = binding.make_hyper("adam", 1e-3, 0.9, 0.999, 1e-8)
+    assert L.pipeoptim_step_predict(None, ctypes.byref(hyper), 1, 1, None) == binding.PO_EINVAL
+    assert L.pipeoptim_plan_destroy(None) == binding.PO_OK
+    assert L.pipeoptim_probe_copy(None, None, 24, None) == binding.PO_EINVAL
+    assert L.pipeoptim_probe_copy(None, None, 0, None) == binding.PO_OK
+
+
+def test_product_path_never_touches_the_oracle():
+    """The GPU package must not import, call or link the oracle (and has no CPU fallback)."""
+    pkg = os.path.join(ROOT, "paper_2312_00839_amd")
+    for dirpath, _, files in os.walk(pkg):
+        for f in files:
+            if f.endswith((".py", ".hip", ".h", ".cpp")):
+                text = open(os.path.join(dirpath, f)).read()
+                assert "oracle" not in text.replace("CPU oracle", ""), os.path.join(dirpath, f)
+    src = open(os.path.join(ROOT, "oracle", "po_oracle.c")).read() + open(os.path.join(ROOT, "oracle", "po_oracle.py")).read()
+    assert "paper_2312_00839_amd" not in src and "pipeoptim.h" not in src

@@ -1,0 +1,376 @@
+"""GPU parity: libpipeoptim (through its C ABI) against the CPU oracle, element by element.
+
+Every test here needs a real MI355X.  Inputs are seeded and synthetic; expected values come
+only from ``oracle/``.  Tolerances are defined in ``parity_util``.
+"""
+import os
+
+import numpy as np
+import pytest
+import torch
+
+pytestmark = pytest.mark.gpu
+
+from parity_util import (compare, make_hyper, run_and_compare_full, run_oracle, what_bits)  # noqa: E402
+
+from paper_2312_00839_amd import binding  # noqa: E402
+from paper_2312_00839_amd.stage import Stage  # noqa: E402
+from paper_2312_00839_amd.workloads import make_inputs, workload  # noqa: E402
+
+DEV = "cuda:0"
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden", "hand_cases.txt")
+
+HP = {
+    "sgdm": dict(lr=0.1, beta1=0.9, beta2=0.0, eps=0.0, weight_decay=1e-4),
+    "adam": dict(lr=1e-3, beta1=0.9, beta2=0.999, eps=1e-8, weight_decay=0.0),
+    "adamw": dict(lr=1e-3, beta1=0.9, beta2=0.999, eps=1e-8, weight_decay=0.01),
+}
+
+
+def _say(msg):
+    print("[gpu-parity] " + msg, flush=True)
+
+
+def _rand_list(sizes, seed, kind, sw=0.02, sg=1e-3, sm=1e-4, sv=1e-3, offset=0):
+    """Device tensors with the given sizes.  offset > 0 makes every tensor a view that starts
+    `offset` elements into its allocation (4-byte but not 16-byte aligned for offset 1..3)."""
+    gen = torch.Generator(device=DEV)
+    gen.manual_seed(seed)
+
+    def draw(n, sigma, square=False):
+        x = torch.randn(n + offset, generator=gen, device=DEV, dtype=torch.float32) * sigma
+        if square:
+            x = x * x
+        return x[offset:]
+
+    out = {"W": [], "g": [], "m": [], "v": None if kind == "sgdm" else []}
+    for n in sizes:
+        out["W"].append(draw(n, sw))
+        out["g"].append(draw(n, sg))
+        out["m"].append(draw(n, sm))
+        if out["v"] is not None:
+            out["v"].append(draw(n, sv, True))
+    return out
+
+
+# --------------------------------------------------------------------------- tiny tensors and hand cases
+def _hand_cases():
+    cases = {}
+    with open(GOLDEN) as f:
+        for line in f:
+            line = line.strip()
+            if not line or line.startswith("#"):
+                continue
+            head, inp, out = [p.split() for p in line.split("|")]
+            cases.setdefault(tuple(head), []).append((inp, out))
+    return list(cases.items())
+
+
+@pytest.mark.parametrize("head,rows", _hand_cases(), ids=lambda x: x[0] if isinstance(x, tuple) else "")
+@pytest.mark.parametrize("what_dtype", ["f32", "bf16"])
+def test_hand_cases_on_gpu(head, rows, what_dtype):
+    name, kind, lr, b1, b2, eps, wd, dip, t, s = head
+    _say("hand case %s %s" % (name, what_dtype))
+    hp = dict(lr=float(lr), beta1=float(b1), beta2=float(b2), eps=float(eps), weight_decay=float(wd))
+    col = lambda j, src: torch.tensor([float(r[src][j]) for r in rows], dtype=torch.float32, device=DEV)
+    tensors = {"W": [col(0, 0)], "g": [col(1, 0)], "m": [col(2, 0)], "v": None if kind == "sgdm" else [col(3, 0)]}
+    expect_W, expect_What = col(0, 1).cpu().numpy(), col(3, 1).cpu().numpy()
+    stage = Stage(tensors["W"], tensors["g"], tensors["m"], tensors["v"], what_dtype)
+    stage.step_predict(make_hyper(kind, hp, bool(int(dip))), int(t), int(s))
+    torch.cuda.synchronize()
+    # dyadic values: fp32 arithmetic is exact apart from sqrt/divide, which are within 1 ulp
+    np.testing.assert_allclose(stage.W[0].cpu().numpy(), expect_W, rtol=3e-7, atol=0)
+    if what_dtype == "f32":
+        np.testing.assert_allclose(stage.What[0].cpu().numpy(), expect_What, rtol=3e-7, atol=1e-7)
+    else:
+        got = what_bits(stage.What[0]).astype(np.int32)
+        want = (expect_What.view(np.uint32) >> 16).astype(np.int32)
+        assert np.abs(got - want).max() <= 1
+    stage.close()
+
+
+@pytest.mark.parametrize("kind", ["sgdm", "adam", "adamw"])
+@pytest.mark.parametrize("what_dtype", ["f32", "bf16"])
+def test_tiny_tensors_all_lengths_up_to_16(kind, what_dtype):
+    _say("tiny %s %s" % (kind, what_dtype))
+    for s in (0, 1, 3, 7):
+        tensors = _rand_list(list(range(0, 17)), seed=100 + s, kind=kind)
+        run_and_compare_full(kind, HP[kind], 5, s, tensors, what_dtype, label="tiny s=%d" % s)
+
+
+# --------------------------------------------------------------------------- ragged lists over several tiles
+RAGGED = [1, 2, 3, 5, 7, 8, 9, 4095, 4096, 4097, 0, 12289, 70001, 16384, 65537]
+
+LAUNCHES = [
+    None,
+    dict(block=256, vec=4, unroll=4, chunk_elems=4096),
+    dict(block=256, vec=4, unroll=2, chunk_elems=2048, nontemporal=3),
+    dict(block=256, vec=4, unroll=1, chunk_elems=1024 * 7, nontemporal=1),
+    dict(block=256, vec=8, unroll=2, chunk_elems=4096, nontemporal=2),
+    dict(block=256, vec=8, unroll=1, chunk_elems=2048 * 3),
+    dict(block=128, vec=8, unroll=2, chunk_elems=2048, max_grid=16),
+    dict(block=64, vec=4, unroll=4, chunk_elems=1024, max_grid=7),
+    dict(block=256, vec=4, unroll=4, chunk_elems=8192, xcd_remap=1),
+    dict(block=256, vec=8, unroll=2, chunk_elems=4096, xcd_remap=1, max_grid=24),
+    dict(block=256, vec=4, unroll=2, chunk_elems=2048, xcd_remap=1, max_grid=13),
+]
+
+
+@pytest.mark.parametrize("kind", ["sgdm", "adam", "adamw"])
+@pytest.mark.parametrize("what_dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("launch", LAUNCHES, ids=lambda L: "default" if L is None else "-".join("%s%d" % (k[0], v) for k, v in L.items()))
+def test_ragged_list_every_launch_shape(kind, what_dtype, launch):
+    _say("ragged %s %s %s" % (kind, what_dtype, launch))
+    tensors = _rand_list(RAGGED, seed=7, kind=kind)
+    run_and_compare_full(kind, HP[kind], 100, 3, tensors, what_dtype, launch=launch, label="ragged")
+
+
+@pytest.mark.parametrize("kind", ["sgdm", "adamw"])
+@pytest.mark.parametrize("what_dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("offset", [1, 2, 3])
+def test_unaligned_tensors_take_scalar_path(kind, what_dtype, offset):
+    _say("unaligned %s %s offset %d" % (kind, what_dtype, offset))
+    sizes = [5, 4096, 9001]
+    tensors = _rand_list(sizes, seed=11, kind=kind, offset=offset)
+    stage = Stage(tensors["W"], tensors["g"], tensors["m"], tensors["v"], what_dtype)
+    assert stage.plan.info()["n_unaligned"] == len(sizes)
+    stage.close()
+    run_and_compare_full(kind, HP[kind], 9, 2, tensors, what_dtype, label="unaligned")
+
+
+def test_adamw_prediction_without_decay_reading():
+    _say("adamw decay_in_prediction=0")
+    tensors = _rand_list([10000, 33], seed=12, kind="adamw")
+    run_and_compare_full("adamw", HP["adamw"], 10, 5, tensors, "f32", decay_in_prediction=False, label="adamw-A")
+    tensors = _rand_list([10000, 33], seed=12, kind="adamw")
+    run_and_compare_full("adamw", HP["adamw"], 10, 5, tensors, "bf16", decay_in_prediction=False, label="adamw-A")
+
+
+def test_adam_with_coupled_decay_and_sgdm_dampening():
+    _say("coupled decay / dampening")
+    hp = dict(lr=3e-4, beta1=0.8, beta2=0.99, eps=1e-6, weight_decay=0.1)
+    run_and_compare_full("adam", hp, 3, 4, _rand_list([5000], 13, "adam"), "f32", label="adam-l2")
+    hp = dict(lr=0.01, beta1=0.9, beta2=0.3, eps=0.0, weight_decay=5e-4)
+    run_and_compare_full("sgdm", hp, 1, 4, _rand_list([5000], 14, "sgdm"), "f32", label="sgdm-damp")
+
+
+def test_step_extremes():
+    _say("t and s extremes")
+    for t, s in [(1, 1), (1, 0), (2, 64), (10 ** 6, 1000), (2 ** 40, 3)]:
+        run_and_compare_full("adam", HP["adam"], t, s, _rand_list([3001], 15, "adam"), "f32", label="t=%d s=%d" % (t, s))
+
+
+def test_zero_state_and_zero_gradient_no_nan():
+    _say("zero state")
+    n = 2048
+    z = lambda: torch.zeros(n, device=DEV)
+    W = torch.linspace(-1, 1, n, device=DEV)
+    st = Stage([W.clone()], [z()], [z()], [z()], "f32")
+    st.step_predict(make_hyper("adam", HP["adam"]), 1, 3)
+    torch.cuda.synchronize()
+    assert torch.equal(st.W[0], W) and torch.equal(st.What[0], W)      # dW = 0/(0+eps) = 0
+    assert torch.isfinite(st.m[0]).all() and torch.isfinite(st.v[0]).all()
+    st.close()
+
+
+def test_nonfinite_values_propagate():
+    _say("nan/inf propagation")
+    t = _rand_list([64], 16, "adam")
+    t["g"][0][3] = float("nan")
+    t["g"][0][5] = float("inf")
+    t["W"][0][7] = float("inf")
+    host = {k: t[k][0].cpu().numpy().copy() for k in ("W", "g", "m", "v")}
+    st = Stage(t["W"], t["g"], t["m"], t["v"], "f32")
+    st.step_predict(make_hyper("adam", HP["adam"]), 4, 2)
+    torch.cuda.synchronize()
+    ref = run_oracle("adam", HP["adam"], 4, 2, host)
+    for name, gpu in (("W", st.W[0]), ("m", st.m[0]), ("v", st.v[0]), ("What", st.What[0])):
+        a, b = gpu.cpu().numpy(), ref[name]
+        assert np.array_equal(np.isnan(a), np.isnan(b)), name
+        assert np.array_equal(np.isinf(a), np.isinf(b)), name
+    st.close()
+
+
+def test_two_steps_in_place_chain():
+    # the state a call leaves in place is the next call's input: check the second of two chained calls
+    # against the oracle started from the state the first call left on the device
+    _say("two chained steps")
+    kind, hp = "adamw", HP["adamw"]
+    t = _rand_list([20000, 17], 17, kind)
+    g2 = [torch.randn_like(x) * 1e-3 for x in t["g"]]
+    st = Stage(t["W"], t["g"], t["m"], t["v"], "bf16")
+    st.step_predict(make_hyper(kind, hp), 7, 3)
+    for i in range(2):
+        st.g[i].copy_(g2[i])
+    torch.cuda.synchronize()
+    mid = [{k: getattr(st, k)[i].cpu().numpy().copy() for k in ("W", "g", "m", "v")} for i in range(2)]
+    st.step_predict(make_hyper(kind, hp), 8, 3)
+    torch.cuda.synchronize()
+    for i in range(2):
+        ref = run_oracle(kind, hp, 8, 3, mid[i])
+        got = {"W": st.W[i].cpu().numpy(), "m": st.m[i].cpu().numpy(), "v": st.v[i].cpu().numpy(),
+               "What": what_bits(st.What[i])}
+        compare(kind, hp, 3, mid[i], ref, got, "bf16", "chain tensor %d" % i)
+    st.close()
+
+
+def test_set_pointers_swaps_gradient_buffers():
+    _say("set_pointers")
+    kind, hp = "adam", HP["adam"]
+    t = _rand_list([5000, 300], 18, kind)
+    new_g = [torch.randn_like(x) * 1e-3 for x in t["g"]]
+    host = [{"W": t["W"][i].cpu().numpy().copy(), "g": new_g[i].cpu().numpy().copy(),
+             "m": t["m"][i].cpu().numpy().copy(), "v": t["v"][i].cpu().numpy().copy()} for i in range(2)]
+    st = Stage(t["W"], t["g"], t["m"], t["v"], "f32")
+    st.plan.set_pointers(1, [x.data_ptr() for x in new_g])
+    st.step_predict(make_hyper(kind, hp), 3, 2)
+    torch.cuda.synchronize()
+    for i in range(2):
+        ref = run_oracle(kind, hp, 3, 2, host[i])
+        got = {"W": st.W[i].cpu().numpy(), "m": st.m[i].cpu().numpy(), "v": st.v[i].cpu().numpy(),
+               "What": st.What[i].cpu().numpy()}
+        compare(kind, hp, 2, host[i], ref, got, "f32", "set_pointers %d" % i)
+    st.close()
+
+
+# --------------------------------------------------------------------------- ABI behaviour on the device
+def test_empty_plans_are_noops():
+    _say("empty plans")
+    p = binding.Plan([], [], [], [], [], [], "f32")
+    p.step_predict(make_hyper("adam", HP["adam"]), 1, 1)
+    assert p.info() == {"n_params": 0, "n_chunks": 0, "n_unaligned": 0}
+    p.destroy()
+    p = binding.Plan([0, 0], [0, 0], [0, 0], [0, 0], [0, 0], [0, 0], "bf16")
+    p.step_predict(make_hyper("adamw", HP["adamw"]), 1, 1)
+    p.destroy()
+    torch.cuda.synchronize()
+
+
+def test_error_paths_launch_nothing():
+    _say("error paths")
+    t = _rand_list([1000], 19, "sgdm")
+    before = t["W"][0].clone()
+    st = Stage(t["W"], t["g"], t["m"], None, "f32")
+    with pytest.raises(binding.PipeOptimError) as e:
+        st.step_predict(make_hyper("adam", HP["adam"]), 1, 1)            # no v in this plan
+    assert e.value.status == binding.PO_EINVAL
+    for bad_t, bad_s in [(0, 1), (-3, 1), (1, -1)]:
+        with pytest.raises(binding.PipeOptimError) as e:
+            st.step_predict(make_hyper("sgdm", HP["sgdm"]), bad_t, bad_s)
+        assert e.value.status == binding.PO_EINVAL
+    for bad in [dict(block=100), dict(vec=3), dict(unroll=3), dict(vec=8, unroll=4), dict(chunk_elems=1000),
+                dict(chunk_elems=0), dict(nontemporal=4), dict(max_grid=-1), dict(xcd_remap=2)]:
+        with pytest.raises(binding.PipeOptimError) as e:
+            st.plan.set_launch(**bad)
+        assert e.value.status == binding.PO_EINVAL, bad
+    torch.cuda.synchronize()
+    assert torch.equal(t["W"][0], before)
+    st.close()
+    x = torch.zeros(64, device=DEV)
+    ok = x.data_ptr()
+    with pytest.raises(binding.PipeOptimError) as e:
+        binding.Plan([8], [ok + 2], [ok], [ok], None, [ok], "f32")
+    assert e.value.status == binding.PO_EALIGN
+    with pytest.raises(binding.PipeOptimError) as e:
+        binding.Plan([8], [ok], [ok], [ok], None, [ok + 1], "bf16")
+    assert e.value.status == binding.PO_EALIGN
+    with pytest.raises(binding.PipeOptimError) as e:
+        binding.Plan([8], [ok], [0], [ok], None, [ok], "f32")
+    assert e.value.status == binding.PO_EINVAL
+
+
+def test_probe_copy_copies():
+    _say("probe copy")
+    src = torch.randn(1 << 20, device=DEV)
+    dst = torch.zeros_like(src)
+    binding.pipeoptim_probe_copy(dst.data_ptr(), src.data_ptr(), src.numel() * 4,
+                                 torch.cuda.current_stream().cuda_stream)
+    torch.cuda.synchronize()
+    assert torch.equal(src, dst)
+
+
+# --------------------------------------------------------------------------- the five configurations
+def _full_config(cfg, s):
+    wl = workload(cfg)
+    _say("config %d (%s) s=%d full compare, N=%d" % (cfg, wl.name, s, wl.n_params))
+    tensors = make_inputs(wl, DEV)
+    reps = run_and_compare_full(wl.optimizer, wl.hyper, wl.t, s, tensors, wl.what_dtype, label="config %d" % cfg)
+    worst = {k: max(r[k] for r in reps if k in r) for k in reps[0]}
+    _say("config %d s=%d worst error ratios (1.0 = 1e-0 of scale): %s" % (cfg, s, worst))
+
+
+def test_config1_flat_adam_full():
+    _full_config(1, 3)
+
+
+@pytest.mark.parametrize("s", [0, 1, 2, 3])
+def test_config2_resnet_sgdm_sweep_full(s):
+    _full_config(2, s)
+
+
+def test_config3_bert_adam_bf16_full():
+    _full_config(3, 2)
+
+
+def _sampled_config(cfg, s, blocks_per_tensor=6, block=8192, seed=0):
+    """Full-size run in the default (benchmarked) launch shape; the oracle recomputes sampled
+    index ranges of every tensor: its head, its ragged tail and random interior ranges."""
+    wl = workload(cfg)
+    _say("config %d (%s) s=%d sampled compare, N=%d" % (cfg, wl.name, s, wl.n_params))
+    tensors = make_inputs(wl, DEV)
+    rng = np.random.default_rng(1234 + cfg * 10 + s + seed)
+    ranges, saved = [], []
+    for i, n in enumerate(wl.numels):
+        r = [(0, min(block, n)), (max(0, n - block - 3), n)]
+        for _ in range(blocks_per_tensor - 2):
+            a = int(rng.integers(0, max(1, n - block)))
+            r.append((a, min(n, a + block + int(rng.integers(0, 9)))))
+        ranges.append(r)
+        idx = torch.cat([torch.arange(a, b, device=DEV) for a, b in r])
+        saved.append((idx, {k: tensors[k][i][idx].cpu().numpy() for k in ("W", "g", "m", "v") if tensors.get(k) is not None}))
+    stage = Stage(tensors["W"], tensors["g"], tensors["m"], tensors.get("v"), wl.what_dtype)
+    stage.step_predict(make_hyper(wl.optimizer, wl.hyper), wl.t, s)
+    torch.cuda.synchronize()
+    worst = {}
+    for i, (idx, inp) in enumerate(saved):
+        ref = run_oracle(wl.optimizer, wl.hyper, wl.t, s, inp)
+        got = {"W": stage.W[i][idx].cpu().numpy(), "m": stage.m[i][idx].cpu().numpy(),
+               "v": stage.v[i][idx].cpu().numpy() if stage.v is not None else None,
+               "What": what_bits(stage.What[i][idx]) if wl.what_dtype == "bf16" else stage.What[i][idx].cpu().numpy()}
+        rep = compare(wl.optimizer, wl.hyper, s, inp, ref, got, wl.what_dtype, "config %d tensor %d" % (cfg, i))
+        for k, val in rep.items():
+            worst[k] = max(worst.get(k, 0), val)
+    # properties that hold at any size, over ALL elements: g untouched is implied by read-only access;
+    # W moved by at most lr*|dW| with |dW| bounded for Adam-family (|r| <= 1/(1-b1) * sqrt(bc2)/bc1 ...): just finiteness
+    for i in range(len(stage.W)):
+        assert torch.isfinite(stage.W[i]).all() and torch.isfinite(stage.m[i]).all()
+        assert torch.isfinite(stage.What[i].float()).all()
+    stage.close()
+    _say("config %d s=%d worst: %s" % (cfg, s, worst))
+
+
+@pytest.mark.parametrize("s", list(range(8)))
+def test_config4_gpt_adamw_bf16_sweep_sampled(s):
+    _sampled_config(4, s)
+
+
+def test_config4_gpt_adamw_bf16_full():
+    _full_config(4, 5)
+
+
+def test_config5_llama_adamw_bf16_sampled():
+    _sampled_config(5, 7, blocks_per_tensor=10)
+
+
+def test_config5_s0_prediction_is_rounded_W_everywhere():
+    # a property that holds at any size: s = 0 makes What the bf16 rounding of the INPUT W, for all 738M elements
+    wl = workload(5)
+    _say("config 5 s=0 whole-stage identity")
+    tensors = make_inputs(wl, DEV)
+    expect = [w.to(torch.bfloat16) for w in tensors["W"]]       # plain cast of the input weights
+    stage = Stage(tensors["W"], tensors["g"], tensors["m"], tensors["v"], "bf16")
+    stage.step_predict(make_hyper(wl.optimizer, wl.hyper), wl.t, 0)
+    torch.cuda.synchronize()
+    for i in range(len(expect)):
+        assert torch.equal(stage.What[i].view(torch.int16), expect[i].view(torch.int16)), i
+    stage.close()
