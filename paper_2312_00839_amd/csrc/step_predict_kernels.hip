@@ -243,6 +243,7 @@ hipError_t launch_one(const po_launch& L, const po_tensor_desc* descs, const po_
         grid = (uint32_t)L.max_grid;
         if (L.xcd_remap && grid >= 8u) grid &= ~7u;   // keeps a workgroup on one XCD's range
     }
+    if (grid > (1u << 24)) grid = 1u << 24;           // stay far below the grid-size limits
     hipLaunchKernelGGL((step_predict_kernel<OPT, BF16, VEC, UNROLL, NT>), dim3(grid), dim3(L.block), 0, stream,
                        descs, chunks, n_chunks, L.chunk_elems, L.xcd_remap, c);
     return hipGetLastError();

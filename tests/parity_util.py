@@ -1,13 +1,20 @@
 """Shared helpers of the GPU parity tests: run the HIP path, run the oracle, compare.
 
-Tolerances (the bar the GPU path is held to):
-  fp32 outputs: per element |gpu - ref| <= 1e-6 * scale, where scale is the sum of the
-    magnitudes of the terms the result is built from, so that cancellation does not
-    make the bound meaningless:
-      W'   : |W| + |W - W'_ref|        (= |W| + lr*|dW|)
-      What : |W| + |W - What_ref|      (= |W| + s*lr*|dW|)
-      m'   : b1*|m| + (1-b1)*|g + wd_c*W|      (SGDM: u, 1 - tau)
-      v'   : v'_ref                     (a sum of non-negative terms)
+Tolerances (the bar the GPU path is held to).  "<= 1e-6 relative" needs a reference
+magnitude that survives cancellation: m' = b1*m + (1-b1)*g and W - c*dW are differences of
+terms that can nearly cancel, and an fp32 kernel's rounding error is proportional to the
+TERMS, not to the (possibly tiny) result.  So every fp32 output is held to
+    |gpu - ref| <= 1e-6 * scale
+where scale is the same expression as the result with every term replaced by its
+magnitude (the standard running-error bound; about 8 roundings of 2^-24 = 6e-8 fit in it):
+    g~_abs  = |g| + wd_c*|W|
+    m'      : m_abs  = b1*|m| + (1-b1)*g~_abs                  (SGDM: u, 1 - tau)
+    v'      : v_abs  = b2*v + (1-b2)*g~_abs^2
+    dW_abs  : SGDM m_abs;  Adam m_abs/(1-b1^t)/(sqrt(v'_ref/(1-b2^t)) + eps);  AdamW that + wd*|W|
+    W'      : |W| + lr*dW_abs
+    What    : |W| + s*lr*dW_abs   (AdamW without decay in the prediction: dW_abs without wd*|W|)
+For almost every element scale equals |result| to within a small factor; it differs only
+where terms cancel.
   bf16 What: at most one bf16 unit in the last place (bit patterns compared in
     sign-magnitude order); s = 0 must be exact (What is a copy of W).
   fp32 What at s = 0: bit-exact copy of W.
@@ -34,37 +41,78 @@ def what_bits(t: torch.Tensor) -> np.ndarray:
     return t.view(torch.int16).cpu().numpy().view(np.uint16)
 
 
-def compare(kind, hp, s, inp, ref, got, what_dtype, label=""):
+def scales(kind, hp, t, s, inp, ref, decay_in_prediction=True):
+    """Per-element reference magnitudes (see the module docstring)."""
+    W = np.abs(inp["W"].astype(np.float64))
+    g = np.abs(inp["g"].astype(np.float64))
+    m = np.abs(inp["m"].astype(np.float64))
+    wd = hp["weight_decay"]
+    wd_c = wd if kind in ("sgdm", "adam") else 0.0
+    gs = (1.0 - hp["beta2"]) if kind == "sgdm" else (1.0 - hp["beta1"])
+    g_abs = g + wd_c * W
+    m_abs = hp["beta1"] * m + gs * g_abs
+    out = {"m": m_abs}
+    if kind == "sgdm":
+        d_step = d_pred = m_abs
+    else:
+        v = inp["v"].astype(np.float64)
+        out["v"] = hp["beta2"] * v + (1.0 - hp["beta2"]) * g_abs * g_abs
+        bc1 = 1.0 - hp["beta1"] ** t
+        bc2 = 1.0 - hp["beta2"] ** t
+        r_abs = m_abs / bc1 / (np.sqrt(ref["v"].astype(np.float64) / bc2) + hp["eps"])
+        d_step = r_abs + (wd * W if kind == "adamw" else 0.0)
+        d_pred = d_step if (kind != "adamw" or decay_in_prediction) else r_abs
+    out["W"] = W + hp["lr"] * d_step
+    out["What"] = W + s * hp["lr"] * d_pred
+    return out
+
+
+def compare(kind, hp, t, s, inp, ref, got, what_dtype, label="", decay_in_prediction=True):
     """inp: dict of fp32 numpy W, g, m, v; ref: oracle dict; got: dict of numpy W, m, v, What (bf16 as uint16)."""
-    W64 = inp["W"].astype(np.float64)
-    g64 = inp["g"].astype(np.float64)
-    m64 = inp["m"].astype(np.float64)
+    sc = scales(kind, hp, t, s, inp, ref, decay_in_prediction)
     tiny = 1e-45
     report = {}
 
     def check(name, gpu, reference, scale):
         err = np.abs(gpu.astype(np.float64) - reference.astype(np.float64))
+        ratio = err / (scale + tiny)
+        report[name] = float(ratio.max()) if err.size else 0.0
         bad = err > REL_TOL * scale + tiny
-        report[name] = float((err / (scale + tiny)).max()) if err.size else 0.0
         assert not bad.any(), "%s %s: %d of %d elements beyond 1e-6*scale; worst ratio %.3e at %d" % (
-            label, name, int(bad.sum()), bad.size, report[name], int(np.argmax(err / (scale + tiny))))
+            label, name, int(bad.sum()), bad.size, report[name], int(np.argmax(ratio)))
 
-    check("W", got["W"], ref["W"], np.abs(W64) + np.abs(W64 - ref["W"]))
-    wd_c = hp["weight_decay"] if kind in ("sgdm", "adam") else 0.0
-    gs = (1.0 - hp["beta2"]) if kind == "sgdm" else (1.0 - hp["beta1"])
-    check("m", got["m"], ref["m"], hp["beta1"] * np.abs(m64) + gs * np.abs(g64 + wd_c * W64))
+    check("W", got["W"], ref["W"], sc["W"])
+    check("m", got["m"], ref["m"], sc["m"])
     if kind != "sgdm":
-        check("v", got["v"], ref["v"], ref["v"].astype(np.float64))
+        check("v", got["v"], ref["v"], sc["v"])
     if what_dtype == "f32":
         if s == 0:
             assert np.array_equal(got["What"].view(np.uint32), inp["W"].view(np.uint32)), label + " What(s=0) != W"
-        check("What", got["What"], ref["What"], np.abs(W64) + np.abs(W64 - ref["What"]))
+        check("What", got["What"], ref["What"], sc["What"])
     else:
-        d = np.abs(bf16_order(got["What"]) - bf16_order(ref["What_bf16"]))
+        # The kernel rounds ITS fp32 prediction to bf16, so the code it may produce is the rounding of
+        # any value inside the fp32 tolerance band around the reference.  Away from cancellation the
+        # band is far narrower than a bf16 step and this is "at most one unit in the last place";
+        # where W and s*lr*dW nearly cancel, a result near zero has tiny bf16 steps and the band may
+        # span a few of them.
+        ref32 = ref["What"].astype(np.float64)
+        tol = REL_TOL * sc["What"] + tiny
+        lo = bf16_order(oracle.bf16_from_f32((ref32 - tol).astype(np.float32)))
+        hi = bf16_order(oracle.bf16_from_f32((ref32 + tol).astype(np.float32)))
+        code = bf16_order(got["What"])
+        d = np.abs(code - bf16_order(ref["What_bf16"]))
         report["What_bf16_ulp"] = int(d.max()) if d.size else 0
-        limit = 0 if s == 0 else 1
-        assert report["What_bf16_ulp"] <= limit, "%s bf16 What off by %d ulp (limit %d) at %d" % (
-            label, report["What_bf16_ulp"], limit, int(np.argmax(d)))
+        report["What_bf16_over_1ulp"] = int((d > 1).sum())
+        if s == 0:
+            assert report["What_bf16_ulp"] == 0, "%s bf16 What(s=0) is not the rounding of W" % label
+        outside = (code < np.minimum(lo, hi) - 0) | (code > np.maximum(lo, hi) + 0)
+        assert not outside.any(), "%s bf16 What: %d codes outside the rounding of the fp32 band; first at %d" % (
+            label, int(outside.sum()), int(np.argmax(outside)))
+        # more than one unit apart is only legitimate where the band itself is wider than half a bf16 step
+        wide = d > 1
+        if wide.any():
+            step = np.abs(ref32[wide]) * 2.0 ** -8
+            assert (tol[wide] >= 0.25 * step).all(), "%s bf16 What off by >1 ulp away from cancellation" % label
     return report
 
 
@@ -98,7 +146,8 @@ def run_and_compare_full(kind, hp, t, s, tensors, what_dtype, launch=None, decay
                    "What": what_bits(stage.What[i]) if what_dtype == "bf16" else stage.What[i].cpu().numpy()}
             # g is read-only
             assert np.array_equal(stage.g[i].cpu().numpy().view(np.uint32), inp["g"].view(np.uint32)), "g was modified"
-            reports.append(compare(kind, hp, s, inp, ref, got, what_dtype, "%s tensor %d" % (label, i)))
+            reports.append(compare(kind, hp, t, s, inp, ref, got, what_dtype, "%s tensor %d" % (label, i),
+                                   decay_in_prediction))
         return reports
     finally:
         stage.close()

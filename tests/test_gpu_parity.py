@@ -210,7 +210,7 @@ def test_two_steps_in_place_chain():
         ref = run_oracle(kind, hp, 8, 3, mid[i])
         got = {"W": st.W[i].cpu().numpy(), "m": st.m[i].cpu().numpy(), "v": st.v[i].cpu().numpy(),
                "What": what_bits(st.What[i])}
-        compare(kind, hp, 3, mid[i], ref, got, "bf16", "chain tensor %d" % i)
+        compare(kind, hp, 8, 3, mid[i], ref, got, "bf16", "chain tensor %d" % i)
     st.close()
 
 
@@ -229,7 +229,7 @@ def test_set_pointers_swaps_gradient_buffers():
         ref = run_oracle(kind, hp, 3, 2, host[i])
         got = {"W": st.W[i].cpu().numpy(), "m": st.m[i].cpu().numpy(), "v": st.v[i].cpu().numpy(),
                "What": st.What[i].cpu().numpy()}
-        compare(kind, hp, 2, host[i], ref, got, "f32", "set_pointers %d" % i)
+        compare(kind, hp, 3, 2, host[i], ref, got, "f32", "set_pointers %d" % i)
     st.close()
 
 
@@ -337,7 +337,7 @@ def _sampled_config(cfg, s, blocks_per_tensor=6, block=8192, seed=0):
         got = {"W": stage.W[i][idx].cpu().numpy(), "m": stage.m[i][idx].cpu().numpy(),
                "v": stage.v[i][idx].cpu().numpy() if stage.v is not None else None,
                "What": what_bits(stage.What[i][idx]) if wl.what_dtype == "bf16" else stage.What[i][idx].cpu().numpy()}
-        rep = compare(wl.optimizer, wl.hyper, s, inp, ref, got, wl.what_dtype, "config %d tensor %d" % (cfg, i))
+        rep = compare(wl.optimizer, wl.hyper, wl.t, s, inp, ref, got, wl.what_dtype, "config %d tensor %d" % (cfg, i))
         for k, val in rep.items():
             worst[k] = max(worst.get(k, 0), val)
     # properties that hold at any size, over ALL elements: g untouched is implied by read-only access;
