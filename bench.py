@@ -34,7 +34,7 @@ def parse_args():
     ap.add_argument("--config", type=int, default=5, help="workload 1..5 (default: the 0.74B-parameter stage)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-copy-probe", action="store_true")
-    ap.add_argument("--launch", default="", help="comma separated po_launch overrides, e.g. vec=8,unroll=2,chunk_elems=8192")
+    ap.add_argument("--launch", default="", help="comma separated po_launch overrides, e.g. block=64,unroll=1,lds_bytes=16384")
     ap.add_argument("--pipeline-depth", type=int, default=0, help="D of Eq. 4; default: s_max + 1 so that rank 0 gets the config's s")
     return ap.parse_args()
 

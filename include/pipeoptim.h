@@ -82,23 +82,27 @@ typedef struct po_chunk {
 } po_chunk;
 
 /*
- * Launch shape of the fused kernel.  Limits: block in {64,128,256}; vec in {4,8}
- * (fp32 elements per lane per access group; 8 makes the bf16 What store a
- * dwordx4); unroll in {1,2,4} with vec*unroll <= 16; chunk_elems a positive
- * multiple of block*vec*unroll, at most 2^30; max_grid >= 0 (0: one workgroup
- * per chunk; otherwise at most that many workgroups walk the table with a
- * stride); nontemporal in {0,1,2,3}: bit 0 = loads, bit 1 = stores; xcd_remap in {0,1}:
- * 1 hands each of the chip's 8 XCDs (workgroup id mod 8) a contiguous eighth of the chunk table
- * instead of every eighth chunk.
+ * Launch shape of the fused kernel.  The grid has one workgroup per tile of block*4*unroll
+ * elements (each lane moves `unroll` groups of 4 consecutive elements per stream).
+ *   block        64, 128 or 256 threads
+ *   unroll       1, 2 or 4
+ *   cache_policy 0: plain loads and stores; 1: streaming (nt) loads; 2: streaming stores;
+ *                3: both; 4: streaming loads, streaming + write-through (nt sc1) stores
+ *   lds_bytes    0..65536, unused LDS reserved per workgroup to cap how many workgroups a CU
+ *                holds at once (160 KiB of LDS per CU); 0 = no cap
+ *   chunk_elems  granularity of the chunk table: block*4*unroll times a power of two, at most 2^30
+ *   xcd_remap    0 or 1: 1 hands each of the chip's 8 XCDs (workgroup id mod 8) a contiguous
+ *                eighth of the work instead of every eighth tile
+ * The number of chunks times chunk_elems/(block*4*unroll) must stay below 2^31.
  */
 typedef struct po_launch {
     int32_t block;
-    int32_t vec;
     int32_t unroll;
-    int32_t nontemporal;
+    int32_t cache_policy;
+    int32_t lds_bytes;
     int64_t chunk_elems;
-    int32_t max_grid;
     int32_t xcd_remap;
+    int32_t reserved;     /* must be 0 */
 } po_launch;
 
 typedef struct po_plan po_plan;   /* opaque */
@@ -164,8 +168,9 @@ int pipeoptim_coefficients(const po_hyper* hyper, int64_t t, int32_t s, po_coeff
 int pipeoptim_chunk_table_build(int64_t n_tensors, const int64_t* numel, int64_t chunk_elems,
                                 po_chunk* out, int64_t capacity, int64_t* n_chunks);
 
-/* Measurement aid: dst[0..nbytes) = src[0..nbytes) with a plain dwordx4 copy kernel (device pointers,
- * 16-byte aligned, nbytes a multiple of 16).  Gives the box's achievable read+write bandwidth. */
+/* Measurement aid: dst[0..nbytes) = src[0..nbytes) with a plain streaming dwordx4 copy kernel (device
+ * pointers, 16-byte aligned, nbytes a multiple of 16, below 2^41).  Gives the box's achievable
+ * one-read-one-write bandwidth. */
 int pipeoptim_probe_copy(void* dst, const void* src, int64_t nbytes, void* hip_stream);
 
 /* Thread-local description of the last failure on this thread ("" if none). */

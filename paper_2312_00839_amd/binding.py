@@ -41,9 +41,9 @@ class po_chunk(ctypes.Structure):
 
 
 class po_launch(ctypes.Structure):
-    _fields_ = [("block", ctypes.c_int32), ("vec", ctypes.c_int32), ("unroll", ctypes.c_int32),
-                ("nontemporal", ctypes.c_int32), ("chunk_elems", ctypes.c_int64),
-                ("max_grid", ctypes.c_int32), ("xcd_remap", ctypes.c_int32)]
+    _fields_ = [("block", ctypes.c_int32), ("unroll", ctypes.c_int32), ("cache_policy", ctypes.c_int32),
+                ("lds_bytes", ctypes.c_int32), ("chunk_elems", ctypes.c_int64),
+                ("xcd_remap", ctypes.c_int32), ("reserved", ctypes.c_int32)]
 
 
 EXPORTS = (

@@ -37,16 +37,26 @@ constexpr int64_t kMaxChunkElems = int64_t(1) << 30;
 int check_launch(const po_launch& L)
 {
     if (L.block != 64 && L.block != 128 && L.block != 256) return fail(PO_EINVAL, "launch.block must be 64, 128 or 256");
-    if (L.vec != 4 && L.vec != 8) return fail(PO_EINVAL, "launch.vec must be 4 or 8");
     if (L.unroll != 1 && L.unroll != 2 && L.unroll != 4) return fail(PO_EINVAL, "launch.unroll must be 1, 2 or 4");
-    if (L.vec * L.unroll > 16) return fail(PO_EINVAL, "launch.vec * launch.unroll must not exceed 16");
-    if (L.nontemporal < 0 || L.nontemporal > 3) return fail(PO_EINVAL, "launch.nontemporal must be 0..3");
+    if (L.cache_policy < 0 || L.cache_policy > 4) return fail(PO_EINVAL, "launch.cache_policy must be 0..4");
+    if (L.lds_bytes < 0 || L.lds_bytes > 65536) return fail(PO_EINVAL, "launch.lds_bytes must be 0..65536");
     if (L.xcd_remap != 0 && L.xcd_remap != 1) return fail(PO_EINVAL, "launch.xcd_remap must be 0 or 1");
-    if (L.max_grid < 0) return fail(PO_EINVAL, "launch.max_grid must be >= 0");
-    const int64_t tile = (int64_t)L.block * L.vec * L.unroll;
-    if (L.chunk_elems <= 0 || L.chunk_elems > kMaxChunkElems || L.chunk_elems % tile != 0)
-        return fail(PO_EINVAL, "launch.chunk_elems must be a positive multiple of block*vec*unroll (%lld), at most 2^30",
+    if (L.reserved != 0) return fail(PO_EINVAL, "launch.reserved must be 0");
+    const int64_t tile = (int64_t)L.block * 4 * L.unroll;
+    const int64_t ratio = L.chunk_elems > 0 ? L.chunk_elems / tile : 0;
+    if (L.chunk_elems <= 0 || L.chunk_elems > kMaxChunkElems || L.chunk_elems % tile != 0 || (ratio & (ratio - 1)) != 0)
+        return fail(PO_EINVAL, "launch.chunk_elems must be block*4*unroll (%lld) times a power of two, at most 2^30",
                     (long long)tile);
+    return PO_OK;
+}
+
+// one workgroup per tile: the grid must fit HIP's limit
+int check_grid(const po_launch& L, int64_t n_chunks)
+{
+    const int64_t tiles = L.chunk_elems / ((int64_t)L.block * 4 * L.unroll);
+    if (n_chunks > 0 && tiles > (int64_t(0x7FFFFFF8) / n_chunks))
+        return fail(PO_EINVAL, "grid of %lld chunks x %lld tiles exceeds 2^31 workgroups; raise block or unroll",
+                    (long long)n_chunks, (long long)tiles);
     return PO_OK;
 }
 
@@ -141,19 +151,18 @@ void refresh_flags(po_plan* p)
     }
 }
 
-// Default launch shape; chunk size shrinks for small stages so that the grid still fills 256 CUs.
-po_launch default_launch(int64_t n_params, int32_t what_dtype)
+// Default launch shape, as measured on MI355X: single-wave workgroups, one 256-element tile each,
+// streaming loads, streaming write-through stores, at most 10 workgroups resident per CU.
+po_launch default_launch()
 {
     po_launch L{};
-    L.block = 256;
-    L.vec = 4;
-    L.unroll = 4;
-    L.nontemporal = 0;
-    L.max_grid = 0;
+    L.block = 64;
+    L.unroll = 1;
+    L.cache_policy = 4;
+    L.lds_bytes = 16384;
+    L.chunk_elems = 65536;
     L.xcd_remap = 0;
-    (void)what_dtype;
-    const int64_t tile = (int64_t)L.block * L.vec * L.unroll;   // 4096 elements
-    L.chunk_elems = n_params >= (int64_t(1) << 27) ? 4 * tile : tile;
+    L.reserved = 0;
     return L;
 }
 
@@ -260,7 +269,7 @@ int pipeoptim_plan_create(po_plan** out, int64_t n_tensors, const int64_t* numel
         d.numel = numel[i]; d.flags = 0; d.pad = 0;
     }
     refresh_flags(p);
-    p->launch = default_launch(total, what_dtype);
+    p->launch = default_launch();
 
     hipError_t e = hipGetDevice(&p->device);
     if (e != hipSuccess) { delete p; return fail_hip(e, "hipGetDevice"); }
@@ -270,6 +279,7 @@ int pipeoptim_plan_create(po_plan** out, int64_t n_tensors, const int64_t* numel
     }
     int rc = upload_descs(p);
     if (rc == PO_OK) rc = upload_chunks(p);
+    if (rc == PO_OK) rc = check_grid(p->launch, (int64_t)p->chunks.size());
     if (rc != PO_OK) { pipeoptim_plan_destroy(p); return rc; }
     *out = p;
     return PO_OK;
@@ -328,6 +338,10 @@ int pipeoptim_plan_set_launch(po_plan* p, const po_launch* L)
 {
     if (!p || !L) return fail(PO_EINVAL, "plan or launch is NULL");
     int rc = check_launch(*L);
+    if (rc != PO_OK) return rc;
+    int64_t n_new = 0;
+    rc = build_chunks(p->n_tensors, p->numel.data(), L->chunk_elems, nullptr, 0, &n_new);
+    if (rc == PO_OK) rc = check_grid(*L, n_new);
     if (rc != PO_OK) return rc;
     const bool rechunk = L->chunk_elems != p->launch.chunk_elems;
     const po_launch old = p->launch;

@@ -1,9 +1,9 @@
 // Fused optimizer step + weight prediction kernels for gfx950 (MI355X).
 //
 // The path is elementwise and HBM-bound (about 0.4 flop per byte), so there is
-// no MFMA and no LDS here: the whole design is about moving 24-32 bytes per
-// parameter exactly once with full-width, coalesced dwordx4 accesses and enough
-// of them in flight per wave.
+// no MFMA and no LDS traffic here: the whole design is about moving 24-32 bytes
+// per parameter exactly once, as full-width coalesced dwordx4 accesses, in an
+// order the memory system likes.
 //
 //   per element (paper Table 1, Eq. 1, Eq. 5), fp32 arithmetic:
 //     g~ = g + wd_c*W
@@ -13,46 +13,51 @@
 //     W'   = W - lr  *(r + wd_step*W)
 //     What = W - s_lr*(r + wd_pred*W)      (s == 0: What = W)
 //
-// Work decomposition: the host's chunk table lists (tensor, chunk) pairs; a
-// workgroup takes one entry (or strides over the table when the grid is
-// capped), reads the tensor's descriptor through the scalar path and walks the
-// chunk in tiles of block*VEC*UNROLL elements.  In a full tile every lane first
-// issues all of its loads (UNROLL groups x 3-4 streams x VEC/4 dwordx4), then
-// does the arithmetic, then stores.  Only the last chunk of a tensor has a
-// ragged tail, handled by the same lanes with per-group bounds checks and a
-// scalar remainder; a tensor whose base pointers are not 16-byte aligned takes
-// a scalar loop.
+// Work decomposition.  The host's chunk table lists (tensor, chunk) pairs at a
+// coarse granularity (chunk_elems); the grid has one small workgroup per TILE
+// of block*4*UNROLL elements, workgroup -> (chunk, tile in chunk) by shift and
+// mask, and workgroups whose tile starts past the end of the tensor exit at
+// once.  A workgroup reads the chunk entry and the tensor descriptor through
+// the scalar path, builds one buffer resource per stream that covers exactly
+// its tile (so the hardware drops any access outside it), issues all its loads,
+// does the arithmetic and stores.  Measured on MI355X, this streaming pattern
+// runs fastest with single-wave workgroups, one tile each, streaming cache
+// hints on every access (loads nt; stores nt + sc1, which sends them on instead
+// of letting them age in L2) and an occupancy capped to roughly 8-10 waves per
+// CU: a tighter window of addresses in flight per stream keeps more DRAM pages
+// open across the 7-8 concurrent streams.  The cap is applied by giving each
+// workgroup an unused dynamic LDS allocation (lds_bytes).
+//
+// Only the last tile of a tensor can be ragged; it, and any tensor whose base
+// pointers are not 16-byte aligned, takes an element-wise path (dword / short
+// accesses, still coalesced across the wave).
 #include "po_internal.h"
 
 namespace {
 
-typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
-// Tensor pointers come out of a descriptor in memory, so the compiler cannot tell which address
-// space they are in and would emit flat accesses; they are device-global by contract.
-#define PO_GLOBAL __attribute__((address_space(1)))
-typedef PO_GLOBAL float gfloat;
-typedef PO_GLOBAL const float gcfloat;
-typedef PO_GLOBAL void gvoid;
-typedef PO_GLOBAL uint16_t gu16;
+// Cache policy bits of gfx940-family memory instructions as the buffer builtins take them
+// (sc0 = 1 is not used by any shipped policy).
+constexpr int CP_NT = 2, CP_SC1 = 16;
 
-constexpr int NT_LOAD = 1, NT_STORE = 2;
+// launch.cache_policy -> (load bits, store bits)
+template <int POL> struct Policy;
+template <> struct Policy<0> { static constexpr int L = 0,     S = 0; };
+template <> struct Policy<1> { static constexpr int L = CP_NT, S = 0; };
+template <> struct Policy<2> { static constexpr int L = 0,     S = CP_NT; };
+template <> struct Policy<3> { static constexpr int L = CP_NT, S = CP_NT; };
+template <> struct Policy<4> { static constexpr int L = CP_NT, S = CP_NT | CP_SC1; };
 
-template <int NT>
-__device__ __forceinline__ f32x4 load4(gcfloat* p)
+// Raw buffer resource (stride 0) over [p, p + bytes): accesses past `bytes` are dropped by the hardware.
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void* p, uint32_t bytes)
 {
-    if constexpr (NT & NT_LOAD) return __builtin_nontemporal_load((PO_GLOBAL const f32x4*)p);
-    else return *(PO_GLOBAL const f32x4*)p;
+    return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(p), 0, (int)bytes, 0x00020000);
 }
 
-template <int NT, typename V>
-__device__ __forceinline__ void storev(gvoid* p, V x)
-{
-    if constexpr (NT & NT_STORE) __builtin_nontemporal_store(x, (PO_GLOBAL V*)p);
-    else *(PO_GLOBAL V*)p = x;
-}
+__device__ __forceinline__ float as_f(uint32_t x) { return __builtin_bit_cast(float, x); }
+__device__ __forceinline__ uint32_t as_u(float x) { return __builtin_bit_cast(uint32_t, x); }
 
 // fp32 -> bf16, round to nearest even (hardware conversion on gfx950); two values packed low/high.
 __device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi)
@@ -98,179 +103,130 @@ __device__ __forceinline__ void update_element(const po_coeffs& c, float W, floa
     if (c.s_is_zero) W_hat = W;
 }
 
-// VEC consecutive elements held by one lane.
-template <int VEC>
-struct Group {
-    f32x4 W[VEC / 4], g[VEC / 4], m[VEC / 4], v[VEC / 4];
-};
-
-template <int OPT, int VEC, int NT>
-__device__ __forceinline__ void load_group(Group<VEC>& G, gcfloat* W, gcfloat* g, gcfloat* m,
-                                           gcfloat* v, int64_t i)
-{
-#pragma unroll
-    for (int k = 0; k < VEC / 4; ++k) {
-        G.W[k] = load4<NT>(W + i + 4 * k);
-        G.g[k] = load4<NT>(g + i + 4 * k);
-        G.m[k] = load4<NT>(m + i + 4 * k);
-        if constexpr (OPT != PO_SGDM) G.v[k] = load4<NT>(v + i + 4 * k);
-    }
-}
-
-template <int OPT, bool BF16, int VEC, int NT>
-__device__ __forceinline__ void compute_store_group(const po_coeffs& c, Group<VEC>& G, gfloat* W, gfloat* m,
-                                                    gfloat* v, gvoid* What, int64_t i)
-{
-    f32x4 Wn[VEC / 4], Wh[VEC / 4];
-#pragma unroll
-    for (int k = 0; k < VEC / 4; ++k) {
-#pragma unroll
-        for (int e = 0; e < 4; ++e) {
-            float mm = G.m[k][e], vv = (OPT != PO_SGDM) ? G.v[k][e] : 0.f, wn, wh;
-            update_element<OPT>(c, G.W[k][e], G.g[k][e], mm, vv, wn, wh);
-            G.m[k][e] = mm;
-            if constexpr (OPT != PO_SGDM) G.v[k][e] = vv;
-            Wn[k][e] = wn;
-            Wh[k][e] = wh;
-        }
-    }
-#pragma unroll
-    for (int k = 0; k < VEC / 4; ++k) {
-        storev<NT>(W + i + 4 * k, Wn[k]);
-        storev<NT>(m + i + 4 * k, G.m[k]);
-        if constexpr (OPT != PO_SGDM) storev<NT>(v + i + 4 * k, G.v[k]);
-    }
-    if constexpr (BF16) {
-        gu16* out = (gu16*)What + i;
-        if constexpr (VEC == 8) {
-            u32x4 p = {pack_bf16x2(Wh[0][0], Wh[0][1]), pack_bf16x2(Wh[0][2], Wh[0][3]),
-                       pack_bf16x2(Wh[1][0], Wh[1][1]), pack_bf16x2(Wh[1][2], Wh[1][3])};
-            storev<NT>(out, p);
-        } else {
-            u32x2 p = {pack_bf16x2(Wh[0][0], Wh[0][1]), pack_bf16x2(Wh[0][2], Wh[0][3])};
-            storev<NT>(out, p);
-        }
-    } else {
-        gfloat* out = (gfloat*)What + i;
-#pragma unroll
-        for (int k = 0; k < VEC / 4; ++k) storev<NT>(out + 4 * k, Wh[k]);
-    }
-}
-
-template <int OPT, bool BF16>
-__device__ __forceinline__ void scalar_range(const po_coeffs& c, gfloat* W, gcfloat* g, gfloat* m, gfloat* v,
-                                             gvoid* What, int64_t begin, int64_t end, int tid, int nthreads)
-{
-    for (int64_t i = begin + tid; i < end; i += nthreads) {
-        float mm = m[i], vv = (OPT != PO_SGDM) ? v[i] : 0.f, wn, wh;
-        update_element<OPT>(c, W[i], g[i], mm, vv, wn, wh);
-        W[i] = wn;
-        m[i] = mm;
-        if constexpr (OPT != PO_SGDM) v[i] = vv;
-        if constexpr (BF16) ((gu16*)What)[i] = to_bf16(wh);
-        else ((gfloat*)What)[i] = wh;
-    }
-}
-
-template <int OPT, bool BF16, int VEC, int UNROLL, int NT>
+template <int OPT, bool BF16, int UNROLL, int POL>
 __global__ __launch_bounds__(256) void step_predict_kernel(const po_tensor_desc* __restrict__ descs,
                                                            const po_chunk* __restrict__ chunks,
-                                                           uint32_t n_chunks, int64_t chunk_elems,
-                                                           int xcd_remap, po_coeffs c)
+                                                           uint32_t n_slots, uint32_t tiles_log2,
+                                                           int64_t chunk_elems, int xcd_remap, po_coeffs c)
 {
-    const int tid = threadIdx.x;
-    const int nthr = blockDim.x;
-    const int64_t tile = (int64_t)nthr * VEC * UNROLL;
+    constexpr int LP = Policy<POL>::L, SP = Policy<POL>::S;
+    constexpr bool ADAM = OPT != PO_SGDM;
 
-    // With xcd_remap the slot space is 8 equal ranges (one per XCD; workgroup ids go round-robin
-    // over the XCDs), padded to 8*ceil(n/8) slots; padding slots do nothing.
-    const uint32_t per_xcd = (n_chunks + 7u) / 8u;
-    const uint32_t n_slots = xcd_remap ? per_xcd * 8u : n_chunks;
-    for (uint32_t slot = blockIdx.x; slot < n_slots; slot += gridDim.x) {
-        uint32_t ci = slot;
-        if (xcd_remap) {
-            ci = (slot & 7u) * per_xcd + (slot >> 3);
-            if (ci >= n_chunks) continue;
-        }
-        const po_chunk ch = chunks[ci];
-        const po_tensor_desc* d = descs + ch.tensor;
-        const int64_t off = (int64_t)ch.chunk * chunk_elems;
-        const int64_t numel = d->numel;
-        const int64_t len = (numel - off < chunk_elems) ? (numel - off) : chunk_elems;
-        gfloat* W = (gfloat*)d->W + off;
-        gcfloat* g = (gcfloat*)d->g + off;
-        gfloat* m = (gfloat*)d->m + off;
-        gfloat* v = (OPT != PO_SGDM) ? (gfloat*)d->v + off : nullptr;
-        gvoid* What = BF16 ? (gvoid*)((gu16*)d->What + off) : (gvoid*)((gfloat*)d->What + off);
+    // slot = chunk_index * tiles_per_chunk + tile_in_chunk.  With xcd_remap the grid (a multiple of 8)
+    // is cut into 8 equal ranges and workgroup id b (XCDs take workgroups round-robin) works in range b mod 8.
+    uint32_t slot = blockIdx.x;
+    if (xcd_remap) slot = (blockIdx.x & 7u) * (gridDim.x >> 3) + (blockIdx.x >> 3);
+    if (slot >= n_slots) return;
 
-        if (!(d->flags & PO_DESC_VECTOR_OK)) {
-            scalar_range<OPT, BF16>(c, W, g, m, v, What, 0, len, tid, nthr);
-            continue;
-        }
+    const po_chunk ch = chunks[slot >> tiles_log2];
+    const po_tensor_desc* d = descs + ch.tensor;
+    const uint32_t tile = blockDim.x * 4u * UNROLL;
+    const int64_t off = (int64_t)ch.chunk * chunk_elems + (int64_t)(slot & ((1u << tiles_log2) - 1u)) * tile;
+    const int64_t numel = d->numel;
+    if (off >= numel) return;                       // tile past the end of the tensor's last chunk
+    const uint32_t len = (numel - off < (int64_t)tile) ? (uint32_t)(numel - off) : tile;
 
-        int64_t base = 0;
-        for (; base + tile <= len; base += tile) {
-            Group<VEC> G[UNROLL];
+    const __amdgpu_buffer_rsrc_t rW = make_rsrc(d->W + off, len * 4u);
+    const __amdgpu_buffer_rsrc_t rg = make_rsrc(d->g + off, len * 4u);
+    const __amdgpu_buffer_rsrc_t rm = make_rsrc(d->m + off, len * 4u);
+    const __amdgpu_buffer_rsrc_t rv = make_rsrc(ADAM ? d->v + off : d->m + off, len * 4u);
+    const __amdgpu_buffer_rsrc_t rh = BF16 ? make_rsrc(static_cast<uint16_t*>(d->What) + off, len * 2u)
+                                           : make_rsrc(static_cast<float*>(d->What) + off, len * 4u);
+    const uint32_t tid = threadIdx.x;
+
+    if (len == tile && (d->flags & PO_DESC_VECTOR_OK)) {
+        // full tile, aligned: every lane moves UNROLL groups of 4 consecutive elements per stream
+        u32x4 W[UNROLL], g[UNROLL], m[UNROLL], v[UNROLL];
 #pragma unroll
-            for (int u = 0; u < UNROLL; ++u)
-                load_group<OPT, VEC, NT>(G[u], W, g, m, v, base + ((int64_t)u * nthr + tid) * VEC);
-#pragma unroll
-            for (int u = 0; u < UNROLL; ++u)
-                compute_store_group<OPT, BF16, VEC, NT>(c, G[u], W, m, v, What,
-                                                        base + ((int64_t)u * nthr + tid) * VEC);
+        for (int u = 0; u < UNROLL; ++u) {
+            const uint32_t b = (u * blockDim.x + tid) * 16u;
+            W[u] = __builtin_amdgcn_raw_buffer_load_b128(rW, b, 0, LP);
+            g[u] = __builtin_amdgcn_raw_buffer_load_b128(rg, b, 0, LP);
+            m[u] = __builtin_amdgcn_raw_buffer_load_b128(rm, b, 0, LP);
+            if constexpr (ADAM) v[u] = __builtin_amdgcn_raw_buffer_load_b128(rv, b, 0, LP);
         }
-        if (base < len) {
-            // ragged tail of the tensor's last chunk: whole groups while they fit, then single elements
-            const int64_t vec_end = base + ((len - base) / VEC) * VEC;
-            for (int64_t i = base + (int64_t)tid * VEC; i < vec_end; i += (int64_t)nthr * VEC) {
-                Group<VEC> G;
-                load_group<OPT, VEC, NT>(G, W, g, m, v, i);
-                compute_store_group<OPT, BF16, VEC, NT>(c, G, W, m, v, What, i);
+#pragma unroll
+        for (int u = 0; u < UNROLL; ++u) {
+            const uint32_t b = (u * blockDim.x + tid) * 16u;
+            u32x4 Wn, Wh;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                float mm = as_f(m[u][e]), vv = ADAM ? as_f(v[u][e]) : 0.f, wn, wh;
+                update_element<OPT>(c, as_f(W[u][e]), as_f(g[u][e]), mm, vv, wn, wh);
+                m[u][e] = as_u(mm);
+                if constexpr (ADAM) v[u][e] = as_u(vv);
+                Wn[e] = as_u(wn);
+                Wh[e] = as_u(wh);
             }
-            scalar_range<OPT, BF16>(c, W, g, m, v, What, vec_end, len, tid, nthr);
+            __builtin_amdgcn_raw_buffer_store_b128(Wn, rW, b, 0, SP);
+            __builtin_amdgcn_raw_buffer_store_b128(m[u], rm, b, 0, SP);
+            if constexpr (ADAM) __builtin_amdgcn_raw_buffer_store_b128(v[u], rv, b, 0, SP);
+            if constexpr (BF16) {
+                u32x2 p = {pack_bf16x2(as_f(Wh[0]), as_f(Wh[1])), pack_bf16x2(as_f(Wh[2]), as_f(Wh[3]))};
+                __builtin_amdgcn_raw_buffer_store_b64(p, rh, b >> 1, 0, SP);
+            } else {
+                __builtin_amdgcn_raw_buffer_store_b128(Wh, rh, b, 0, SP);
+            }
+        }
+    } else {
+        // ragged last tile of a tensor, or a tensor without 16-byte alignment: one element per lane per step
+        for (uint32_t i = tid; i < len; i += blockDim.x) {
+            const uint32_t b = i * 4u;
+            float W = as_f(__builtin_amdgcn_raw_buffer_load_b32(rW, b, 0, LP));
+            float g = as_f(__builtin_amdgcn_raw_buffer_load_b32(rg, b, 0, LP));
+            float mm = as_f(__builtin_amdgcn_raw_buffer_load_b32(rm, b, 0, LP));
+            float vv = ADAM ? as_f(__builtin_amdgcn_raw_buffer_load_b32(rv, b, 0, LP)) : 0.f;
+            float wn, wh;
+            update_element<OPT>(c, W, g, mm, vv, wn, wh);
+            __builtin_amdgcn_raw_buffer_store_b32(as_u(wn), rW, b, 0, SP);
+            __builtin_amdgcn_raw_buffer_store_b32(as_u(mm), rm, b, 0, SP);
+            if constexpr (ADAM) __builtin_amdgcn_raw_buffer_store_b32(as_u(vv), rv, b, 0, SP);
+            if constexpr (BF16) __builtin_amdgcn_raw_buffer_store_b16(to_bf16(wh), rh, i * 2u, 0, SP);
+            else __builtin_amdgcn_raw_buffer_store_b32(as_u(wh), rh, b, 0, SP);
         }
     }
 }
 
-template <int OPT, bool BF16, int VEC, int UNROLL, int NT>
+template <int OPT, bool BF16, int UNROLL, int POL>
 hipError_t launch_one(const po_launch& L, const po_tensor_desc* descs, const po_chunk* chunks, uint32_t n_chunks,
                       const po_coeffs& c, hipStream_t stream)
 {
-    // one workgroup per slot (xcd_remap pads the slot space to a multiple of 8), capped by max_grid;
-    // any grid size covers every slot exactly once through the kernel's stride loop
-    uint32_t grid = L.xcd_remap ? ((n_chunks + 7u) / 8u) * 8u : n_chunks;
-    if (L.max_grid > 0 && grid > (uint32_t)L.max_grid) {
-        grid = (uint32_t)L.max_grid;
-        if (L.xcd_remap && grid >= 8u) grid &= ~7u;   // keeps a workgroup on one XCD's range
-    }
-    if (grid > (1u << 24)) grid = 1u << 24;           // stay far below the grid-size limits
-    hipLaunchKernelGGL((step_predict_kernel<OPT, BF16, VEC, UNROLL, NT>), dim3(grid), dim3(L.block), 0, stream,
-                       descs, chunks, n_chunks, L.chunk_elems, L.xcd_remap, c);
+    const uint32_t tile = (uint32_t)L.block * 4u * UNROLL;
+    const uint32_t tiles_per_chunk = (uint32_t)(L.chunk_elems / tile);      // a power of two (validated by the host)
+    uint32_t tiles_log2 = 0;
+    while ((1u << tiles_log2) < tiles_per_chunk) ++tiles_log2;
+    const uint64_t n_slots = (uint64_t)n_chunks << tiles_log2;
+    const uint64_t grid = L.xcd_remap ? ((n_slots + 7u) / 8u) * 8u : n_slots;
+    if (grid > 0x7FFFFFFFull) return hipErrorInvalidConfiguration;
+    hipLaunchKernelGGL((step_predict_kernel<OPT, BF16, UNROLL, POL>), dim3((uint32_t)grid), dim3(L.block),
+                       (size_t)L.lds_bytes, stream, descs, chunks, (uint32_t)n_slots, tiles_log2, L.chunk_elems,
+                       L.xcd_remap, c);
     return hipGetLastError();
 }
 
-template <int OPT, bool BF16, int VEC, int UNROLL>
-hipError_t dispatch_nt(const po_launch& L, const po_tensor_desc* d, const po_chunk* ch, uint32_t n,
-                       const po_coeffs& c, hipStream_t s)
+template <int OPT, bool BF16, int UNROLL>
+hipError_t dispatch_policy(const po_launch& L, const po_tensor_desc* d, const po_chunk* ch, uint32_t n,
+                           const po_coeffs& c, hipStream_t s)
 {
-    switch (L.nontemporal) {
-    case 0: return launch_one<OPT, BF16, VEC, UNROLL, 0>(L, d, ch, n, c, s);
-    case 1: return launch_one<OPT, BF16, VEC, UNROLL, 1>(L, d, ch, n, c, s);
-    case 2: return launch_one<OPT, BF16, VEC, UNROLL, 2>(L, d, ch, n, c, s);
-    case 3: return launch_one<OPT, BF16, VEC, UNROLL, 3>(L, d, ch, n, c, s);
+    switch (L.cache_policy) {
+    case 0: return launch_one<OPT, BF16, UNROLL, 0>(L, d, ch, n, c, s);
+    case 1: return launch_one<OPT, BF16, UNROLL, 1>(L, d, ch, n, c, s);
+    case 2: return launch_one<OPT, BF16, UNROLL, 2>(L, d, ch, n, c, s);
+    case 3: return launch_one<OPT, BF16, UNROLL, 3>(L, d, ch, n, c, s);
+    case 4: return launch_one<OPT, BF16, UNROLL, 4>(L, d, ch, n, c, s);
     }
     return hipErrorInvalidValue;
 }
 
 template <int OPT, bool BF16>
-hipError_t dispatch_shape(const po_launch& L, const po_tensor_desc* d, const po_chunk* ch, uint32_t n,
-                          const po_coeffs& c, hipStream_t s)
+hipError_t dispatch_unroll(const po_launch& L, const po_tensor_desc* d, const po_chunk* ch, uint32_t n,
+                           const po_coeffs& c, hipStream_t s)
 {
-    if (L.vec == 4 && L.unroll == 1) return dispatch_nt<OPT, BF16, 4, 1>(L, d, ch, n, c, s);
-    if (L.vec == 4 && L.unroll == 2) return dispatch_nt<OPT, BF16, 4, 2>(L, d, ch, n, c, s);
-    if (L.vec == 4 && L.unroll == 4) return dispatch_nt<OPT, BF16, 4, 4>(L, d, ch, n, c, s);
-    if (L.vec == 8 && L.unroll == 1) return dispatch_nt<OPT, BF16, 8, 1>(L, d, ch, n, c, s);
-    if (L.vec == 8 && L.unroll == 2) return dispatch_nt<OPT, BF16, 8, 2>(L, d, ch, n, c, s);
+    switch (L.unroll) {
+    case 1: return dispatch_policy<OPT, BF16, 1>(L, d, ch, n, c, s);
+    case 2: return dispatch_policy<OPT, BF16, 2>(L, d, ch, n, c, s);
+    case 4: return dispatch_policy<OPT, BF16, 4>(L, d, ch, n, c, s);
+    }
     return hipErrorInvalidValue;
 }
 
@@ -278,28 +234,22 @@ template <int OPT>
 hipError_t dispatch_dtype(int what_dtype, const po_launch& L, const po_tensor_desc* d, const po_chunk* ch,
                           uint32_t n, const po_coeffs& c, hipStream_t s)
 {
-    return what_dtype == PO_WHAT_BF16 ? dispatch_shape<OPT, true>(L, d, ch, n, c, s)
-                                      : dispatch_shape<OPT, false>(L, d, ch, n, c, s);
+    return what_dtype == PO_WHAT_BF16 ? dispatch_unroll<OPT, true>(L, d, ch, n, c, s)
+                                      : dispatch_unroll<OPT, false>(L, d, ch, n, c, s);
 }
 
-// Plain copy: the yardstick for what a read+write stream reaches on this chip.
-__global__ __launch_bounds__(256) void probe_copy_kernel(u32x4* __restrict__ dst, const u32x4* __restrict__ src,
-                                                         int64_t n_vec)
+// Plain copy: the yardstick for what one read stream plus one write stream reach on this chip.
+// One single-wave workgroup per 1 KiB, streaming hints on both sides.
+__global__ __launch_bounds__(64) void probe_copy_kernel(char* __restrict__ dst, const char* __restrict__ src,
+                                                        int64_t nbytes)
 {
-    const int64_t tile = (int64_t)blockDim.x * 4;
-    for (int64_t base = (int64_t)blockIdx.x * tile; base < n_vec; base += (int64_t)gridDim.x * tile) {
-        u32x4 x[4];
-#pragma unroll
-        for (int u = 0; u < 4; ++u) {
-            int64_t i = base + (int64_t)u * blockDim.x + threadIdx.x;
-            if (i < n_vec) x[u] = src[i];
-        }
-#pragma unroll
-        for (int u = 0; u < 4; ++u) {
-            int64_t i = base + (int64_t)u * blockDim.x + threadIdx.x;
-            if (i < n_vec) dst[i] = x[u];
-        }
-    }
+    const int64_t base = (int64_t)blockIdx.x * 1024;
+    const int64_t left = nbytes - base;
+    const uint32_t len = left < 1024 ? (uint32_t)left : 1024u;
+    const __amdgpu_buffer_rsrc_t rs = make_rsrc(src + base, len), rd = make_rsrc(dst + base, len);
+    const uint32_t b = threadIdx.x * 16u;
+    u32x4 x = __builtin_amdgcn_raw_buffer_load_b128(rs, b, 0, CP_NT);
+    __builtin_amdgcn_raw_buffer_store_b128(x, rd, b, 0, CP_NT);
 }
 
 }  // namespace
@@ -319,12 +269,10 @@ hipError_t po_launch_step_predict(int opt, int what_dtype, const po_launch& L, c
 
 hipError_t po_launch_probe_copy(void* dst, const void* src, int64_t nbytes, hipStream_t stream)
 {
-    const int64_t n_vec = nbytes / 16;
-    if (n_vec == 0) return hipSuccess;
-    const int64_t tile = 256 * 4;
-    int64_t grid = (n_vec + tile - 1) / tile;
-    if (grid > (1 << 20)) grid = 1 << 20;
-    hipLaunchKernelGGL(probe_copy_kernel, dim3((uint32_t)grid), dim3(256), 0, stream, static_cast<u32x4*>(dst),
-                       static_cast<const u32x4*>(src), n_vec);
+    if (nbytes <= 0) return hipSuccess;
+    const int64_t grid = (nbytes + 1023) / 1024;
+    if (grid > 0x7FFFFFFFll) return hipErrorInvalidConfiguration;
+    hipLaunchKernelGGL(probe_copy_kernel, dim3((uint32_t)grid), dim3(64), 0, stream, static_cast<char*>(dst),
+                       static_cast<const char*>(src), nbytes);
     return hipGetLastError();
 }

@@ -103,16 +103,16 @@ RAGGED = [1, 2, 3, 5, 7, 8, 9, 4095, 4096, 4097, 0, 12289, 70001, 16384, 65537]
 
 LAUNCHES = [
     None,
-    dict(block=256, vec=4, unroll=4, chunk_elems=4096),
-    dict(block=256, vec=4, unroll=2, chunk_elems=2048, nontemporal=3),
-    dict(block=256, vec=4, unroll=1, chunk_elems=1024 * 7, nontemporal=1),
-    dict(block=256, vec=8, unroll=2, chunk_elems=4096, nontemporal=2),
-    dict(block=256, vec=8, unroll=1, chunk_elems=2048 * 3),
-    dict(block=128, vec=8, unroll=2, chunk_elems=2048, max_grid=16),
-    dict(block=64, vec=4, unroll=4, chunk_elems=1024, max_grid=7),
-    dict(block=256, vec=4, unroll=4, chunk_elems=8192, xcd_remap=1),
-    dict(block=256, vec=8, unroll=2, chunk_elems=4096, xcd_remap=1, max_grid=24),
-    dict(block=256, vec=4, unroll=2, chunk_elems=2048, xcd_remap=1, max_grid=13),
+    dict(block=64, unroll=1, chunk_elems=256, cache_policy=0, lds_bytes=0),
+    dict(block=64, unroll=2, chunk_elems=512 * 8, cache_policy=1, lds_bytes=8192),
+    dict(block=64, unroll=4, chunk_elems=1024 * 64, cache_policy=2),
+    dict(block=128, unroll=1, chunk_elems=512 * 2, cache_policy=3, lds_bytes=65536),
+    dict(block=128, unroll=4, chunk_elems=2048, cache_policy=4, xcd_remap=1),
+    dict(block=256, unroll=1, chunk_elems=1024 * 4, cache_policy=4, lds_bytes=16384),
+    dict(block=256, unroll=2, chunk_elems=2048 * 32, cache_policy=3, xcd_remap=1),
+    dict(block=256, unroll=4, chunk_elems=4096, cache_policy=0, xcd_remap=1, lds_bytes=40960),
+    dict(block=64, unroll=1, chunk_elems=256 * 1024, cache_policy=4, xcd_remap=1),
+    dict(block=64, unroll=2, chunk_elems=512, cache_policy=4, xcd_remap=1, lds_bytes=20480),
 ]
 
 
@@ -258,8 +258,9 @@ def test_error_paths_launch_nothing():
         with pytest.raises(binding.PipeOptimError) as e:
             st.step_predict(make_hyper("sgdm", HP["sgdm"]), bad_t, bad_s)
         assert e.value.status == binding.PO_EINVAL
-    for bad in [dict(block=100), dict(vec=3), dict(unroll=3), dict(vec=8, unroll=4), dict(chunk_elems=1000),
-                dict(chunk_elems=0), dict(nontemporal=4), dict(max_grid=-1), dict(xcd_remap=2)]:
+    for bad in [dict(block=100), dict(block=512), dict(unroll=3), dict(unroll=8), dict(chunk_elems=1000),
+                dict(chunk_elems=0), dict(chunk_elems=256 * 3), dict(chunk_elems=1 << 31), dict(cache_policy=5),
+                dict(cache_policy=-1), dict(lds_bytes=-1), dict(lds_bytes=65537), dict(xcd_remap=2), dict(reserved=1)]:
         with pytest.raises(binding.PipeOptimError) as e:
             st.plan.set_launch(**bad)
         assert e.value.status == binding.PO_EINVAL, bad
