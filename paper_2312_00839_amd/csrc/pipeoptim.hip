@@ -152,14 +152,16 @@ void refresh_flags(po_plan* p)
 }
 
 // Default launch shape, as measured on MI355X: single-wave workgroups, one 256-element tile each,
-// streaming loads, streaming write-through stores, at most 10 workgroups resident per CU.
-po_launch default_launch()
+// streaming loads, streaming write-through stores, and an occupancy cap (unused LDS per workgroup).
+// The best cap grows with the stage: 10 workgroups per CU for stages above ~128M parameters, 11 for
+// mid-sized ones, 16 for small ones whose launch is dominated by ramp-up and ramp-down.
+po_launch default_launch(int64_t n_params)
 {
     po_launch L{};
     L.block = 64;
     L.unroll = 1;
     L.cache_policy = 4;
-    L.lds_bytes = 16384;
+    L.lds_bytes = n_params >= (int64_t(1) << 27) ? 16384 : n_params >= (int64_t(1) << 25) ? 14336 : 10240;
     L.chunk_elems = 65536;
     L.xcd_remap = 0;
     L.reserved = 0;
@@ -269,7 +271,7 @@ int pipeoptim_plan_create(po_plan** out, int64_t n_tensors, const int64_t* numel
         d.numel = numel[i]; d.flags = 0; d.pad = 0;
     }
     refresh_flags(p);
-    p->launch = default_launch();
+    p->launch = default_launch(total);
 
     hipError_t e = hipGetDevice(&p->device);
     if (e != hipSuccess) { delete p; return fail_hip(e, "hipGetDevice"); }

@@ -42,13 +42,15 @@ typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 // (sc0 = 1 is not used by any shipped policy).
 constexpr int CP_NT = 2, CP_SC1 = 16;
 
-// launch.cache_policy -> (load bits, store bits)
+// launch.cache_policy -> bits for: LG loads of g (read once), LS loads of W, m, v (rewritten right after),
+// SS stores of W', m', v', SH stores of What (write-only).  Mixed per-stream settings (plain loads for the
+// rewritten streams, nt-only or sc1-only on one of the store groups) all measured slower than policy 4.
 template <int POL> struct Policy;
-template <> struct Policy<0> { static constexpr int L = 0,     S = 0; };
-template <> struct Policy<1> { static constexpr int L = CP_NT, S = 0; };
-template <> struct Policy<2> { static constexpr int L = 0,     S = CP_NT; };
-template <> struct Policy<3> { static constexpr int L = CP_NT, S = CP_NT; };
-template <> struct Policy<4> { static constexpr int L = CP_NT, S = CP_NT | CP_SC1; };
+template <> struct Policy<0> { static constexpr int LG = 0,     LS = 0,     SS = 0,              SH = 0; };
+template <> struct Policy<1> { static constexpr int LG = CP_NT, LS = CP_NT, SS = 0,              SH = 0; };
+template <> struct Policy<2> { static constexpr int LG = 0,     LS = 0,     SS = CP_NT,          SH = CP_NT; };
+template <> struct Policy<3> { static constexpr int LG = CP_NT, LS = CP_NT, SS = CP_NT,          SH = CP_NT; };
+template <> struct Policy<4> { static constexpr int LG = CP_NT, LS = CP_NT, SS = CP_NT | CP_SC1, SH = CP_NT | CP_SC1; };
 
 // Raw buffer resource (stride 0) over [p, p + bytes): accesses past `bytes` are dropped by the hardware.
 __device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void* p, uint32_t bytes)
@@ -109,7 +111,7 @@ __global__ __launch_bounds__(256) void step_predict_kernel(const po_tensor_desc*
                                                            uint32_t n_slots, uint32_t tiles_log2,
                                                            int64_t chunk_elems, int xcd_remap, po_coeffs c)
 {
-    constexpr int LP = Policy<POL>::L, SP = Policy<POL>::S;
+    constexpr int LG = Policy<POL>::LG, LS = Policy<POL>::LS, SS = Policy<POL>::SS, SH = Policy<POL>::SH;
     constexpr bool ADAM = OPT != PO_SGDM;
 
     // slot = chunk_index * tiles_per_chunk + tile_in_chunk.  With xcd_remap the grid (a multiple of 8)
@@ -140,10 +142,10 @@ __global__ __launch_bounds__(256) void step_predict_kernel(const po_tensor_desc*
 #pragma unroll
         for (int u = 0; u < UNROLL; ++u) {
             const uint32_t b = (u * blockDim.x + tid) * 16u;
-            W[u] = __builtin_amdgcn_raw_buffer_load_b128(rW, b, 0, LP);
-            g[u] = __builtin_amdgcn_raw_buffer_load_b128(rg, b, 0, LP);
-            m[u] = __builtin_amdgcn_raw_buffer_load_b128(rm, b, 0, LP);
-            if constexpr (ADAM) v[u] = __builtin_amdgcn_raw_buffer_load_b128(rv, b, 0, LP);
+            W[u] = __builtin_amdgcn_raw_buffer_load_b128(rW, b, 0, LS);
+            g[u] = __builtin_amdgcn_raw_buffer_load_b128(rg, b, 0, LG);
+            m[u] = __builtin_amdgcn_raw_buffer_load_b128(rm, b, 0, LS);
+            if constexpr (ADAM) v[u] = __builtin_amdgcn_raw_buffer_load_b128(rv, b, 0, LS);
         }
 #pragma unroll
         for (int u = 0; u < UNROLL; ++u) {
@@ -158,31 +160,31 @@ __global__ __launch_bounds__(256) void step_predict_kernel(const po_tensor_desc*
                 Wn[e] = as_u(wn);
                 Wh[e] = as_u(wh);
             }
-            __builtin_amdgcn_raw_buffer_store_b128(Wn, rW, b, 0, SP);
-            __builtin_amdgcn_raw_buffer_store_b128(m[u], rm, b, 0, SP);
-            if constexpr (ADAM) __builtin_amdgcn_raw_buffer_store_b128(v[u], rv, b, 0, SP);
+            __builtin_amdgcn_raw_buffer_store_b128(Wn, rW, b, 0, SS);
+            __builtin_amdgcn_raw_buffer_store_b128(m[u], rm, b, 0, SS);
+            if constexpr (ADAM) __builtin_amdgcn_raw_buffer_store_b128(v[u], rv, b, 0, SS);
             if constexpr (BF16) {
                 u32x2 p = {pack_bf16x2(as_f(Wh[0]), as_f(Wh[1])), pack_bf16x2(as_f(Wh[2]), as_f(Wh[3]))};
-                __builtin_amdgcn_raw_buffer_store_b64(p, rh, b >> 1, 0, SP);
+                __builtin_amdgcn_raw_buffer_store_b64(p, rh, b >> 1, 0, SH);
             } else {
-                __builtin_amdgcn_raw_buffer_store_b128(Wh, rh, b, 0, SP);
+                __builtin_amdgcn_raw_buffer_store_b128(Wh, rh, b, 0, SH);
             }
         }
     } else {
         // ragged last tile of a tensor, or a tensor without 16-byte alignment: one element per lane per step
         for (uint32_t i = tid; i < len; i += blockDim.x) {
             const uint32_t b = i * 4u;
-            float W = as_f(__builtin_amdgcn_raw_buffer_load_b32(rW, b, 0, LP));
-            float g = as_f(__builtin_amdgcn_raw_buffer_load_b32(rg, b, 0, LP));
-            float mm = as_f(__builtin_amdgcn_raw_buffer_load_b32(rm, b, 0, LP));
-            float vv = ADAM ? as_f(__builtin_amdgcn_raw_buffer_load_b32(rv, b, 0, LP)) : 0.f;
+            float W = as_f(__builtin_amdgcn_raw_buffer_load_b32(rW, b, 0, LS));
+            float g = as_f(__builtin_amdgcn_raw_buffer_load_b32(rg, b, 0, LG));
+            float mm = as_f(__builtin_amdgcn_raw_buffer_load_b32(rm, b, 0, LS));
+            float vv = ADAM ? as_f(__builtin_amdgcn_raw_buffer_load_b32(rv, b, 0, LS)) : 0.f;
             float wn, wh;
             update_element<OPT>(c, W, g, mm, vv, wn, wh);
-            __builtin_amdgcn_raw_buffer_store_b32(as_u(wn), rW, b, 0, SP);
-            __builtin_amdgcn_raw_buffer_store_b32(as_u(mm), rm, b, 0, SP);
-            if constexpr (ADAM) __builtin_amdgcn_raw_buffer_store_b32(as_u(vv), rv, b, 0, SP);
-            if constexpr (BF16) __builtin_amdgcn_raw_buffer_store_b16(to_bf16(wh), rh, i * 2u, 0, SP);
-            else __builtin_amdgcn_raw_buffer_store_b32(as_u(wh), rh, b, 0, SP);
+            __builtin_amdgcn_raw_buffer_store_b32(as_u(wn), rW, b, 0, SS);
+            __builtin_amdgcn_raw_buffer_store_b32(as_u(mm), rm, b, 0, SS);
+            if constexpr (ADAM) __builtin_amdgcn_raw_buffer_store_b32(as_u(vv), rv, b, 0, SS);
+            if constexpr (BF16) __builtin_amdgcn_raw_buffer_store_b16(to_bf16(wh), rh, i * 2u, 0, SH);
+            else __builtin_amdgcn_raw_buffer_store_b32(as_u(wh), rh, b, 0, SH);
         }
     }
 }
