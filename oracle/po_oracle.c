@@ -15,6 +15,8 @@
  *   optimizer step   W_{t+1} = W_t - lr * dW_t         -- paper Eq. 1, first line
  *   prediction       What_{t+s} = W_t - lr * s * dW_t  -- paper Eq. 3 / Eq. 5
  *   version difference s = D - rank - 1                -- paper Eq. 4
+ *   prediction from the cached state alone (no new gradient), as Algorithm 1
+ *   sequences it ahead of the forward pass             -- po_oracle_predict
  *
  * Readings of the paper taken here (each is listed in the design document):
  *   - dW_t is built from the *updated* state (m_t, v_t), i.e. from the new
@@ -38,7 +40,10 @@
  * Adam / AdamW, the prediction law against the s = 0, s = 1 and affine-in-s
  * invariants and the constant-direction case of Eq. 2, Table 1 against hand
  * cases and closed forms, Eq. 4 against the indices of the Fig. 2 discussion,
- * the bf16 rounding against an integer formulation and torch's cast.
+ * the bf16 rounding against an integer formulation and torch's cast;
+ * po_oracle_predict against closed forms, hand cases, and its consistency with
+ * the (independently pinned) fused function: predicting s versions ahead from
+ * the state a fused call leaves equals the fused call's own s+1 prediction.
  * Parity unpinned by the paper itself: the choice of prediction base (W_t
  * rather than W_{t+1}) and the AdamW decay reading; both are fixed by the
  * invariants above, not by a printed value.
@@ -156,6 +161,50 @@ int po_oracle_step_predict(int opt, double lr, double beta1, double beta2, doubl
         if (W_out) W_out[i] = (float)Wn;
         if (m_out) m_out[i] = (float)mn;
         if (v_out && opt != PO_ORACLE_SGDM) v_out[i] = (float)vn;
+    }
+    return 0;
+}
+
+/*
+ * Prediction alone, from the cached optimizer state (paper Algorithm 1 computes
+ * dW_t "by a lookup of Table 1" and applies Eq. 5 ahead of the forward pass; the
+ * state was produced by the optimizer step of iteration t).  No gradient is
+ * read and nothing but What is written:
+ *     SGDM : dW = m
+ *     Adam : dW = (m/(1-b1^t)) / (sqrt(v/(1-b2^t)) + eps)      (m, v as stored)
+ *     AdamW: dW = that + wd*W   (r alone if !decay_in_prediction)
+ *     What = W - lr*s*dW  (Eq. 5);  s == 0: What = W
+ * With SGDM and the momentum of the previous step this is also SpecTrain's
+ * predictor What = W_t - lr*s*m_{t-1} (paper Eq. 6, first line).
+ * Host pointers; v may be NULL for SGDM; either output may be NULL.
+ */
+int po_oracle_predict(int opt, double lr, double beta1, double beta2, double eps,
+                      double weight_decay, int decay_in_prediction,
+                      long long t, int s, long long n,
+                      const float* W, const float* m, const float* v,
+                      float* What_f32, uint16_t* What_bf16, int nthreads)
+{
+    if (opt < PO_ORACLE_SGDM || opt > PO_ORACLE_ADAMW) return -1;
+    if (t < 1 || s < 0 || n < 0) return -1;
+    if (n > 0 && (!W || !m)) return -1;
+    if (n > 0 && opt != PO_ORACLE_SGDM && !v) return -1;
+    if (nthreads < 1) nthreads = 1;
+
+    #pragma omp parallel for num_threads(nthreads) schedule(static) if (nthreads > 1)
+    for (long long i = 0; i < n; ++i) {
+        double Wi = (double)W[i], dW;
+        if (opt == PO_ORACLE_SGDM) {
+            dW = (double)m[i];
+        } else {
+            double mhat = (double)m[i] / (1.0 - pow(beta1, (double)t));
+            double vhat = (double)v[i] / (1.0 - pow(beta2, (double)t));
+            dW = mhat / (sqrt(vhat) + eps);
+            if (opt == PO_ORACLE_ADAMW && decay_in_prediction) dW += weight_decay * Wi;
+        }
+        double Wh = (s == 0) ? Wi : Wi - lr * (double)s * dW;
+        float Wh32 = (float)Wh;
+        if (What_f32)  What_f32[i]  = Wh32;
+        if (What_bf16) What_bf16[i] = po_oracle_bf16_from_f32(Wh32);
     }
     return 0;
 }

@@ -42,6 +42,11 @@ def _load():
             ctypes.c_int, ctypes.c_double, ctypes.c_double, ctypes.c_double, ctypes.c_double,
             ctypes.c_double, ctypes.c_int, ctypes.c_longlong, ctypes.c_int, ctypes.c_longlong,
             f32p, f32p, f32p, f32p, f32p, f32p, f32p, f32p, u16p, ctypes.c_int]
+        lib.po_oracle_predict.restype = ctypes.c_int
+        lib.po_oracle_predict.argtypes = [
+            ctypes.c_int, ctypes.c_double, ctypes.c_double, ctypes.c_double, ctypes.c_double,
+            ctypes.c_double, ctypes.c_int, ctypes.c_longlong, ctypes.c_int, ctypes.c_longlong,
+            f32p, f32p, f32p, f32p, u16p, ctypes.c_int]
         lib.po_oracle_bf16_from_f32_array.restype = None
         lib.po_oracle_bf16_from_f32_array.argtypes = [f32p, u16p, ctypes.c_longlong]
         lib.po_oracle_version_difference.restype = ctypes.c_int
@@ -91,6 +96,31 @@ def step_predict(opt, W, g, m, v=None, *, lr, beta1, beta2, eps=0.0, weight_deca
     if rc != 0:
         raise ValueError("oracle: invalid argument (opt=%r t=%r s=%r)" % (opt, t, s))
     return {"W": W_out, "m": m_out, "v": v_out, "What": What, "What_bf16": What16}
+
+
+def predict(opt, W, m, v=None, *, lr, beta1, beta2, eps=0.0, weight_decay=0.0,
+            decay_in_prediction=True, t=1, s=0, nthreads=1):
+    """Prediction from the cached state alone.  Returns ``What`` (fp32) and ``What_bf16`` (uint16 patterns)."""
+    lib = _load()
+    W, pW = _f32(W)
+    m, pm = _f32(m)
+    n = W.size
+    if m.size != n or (v is not None and np.asarray(v).size != n):
+        raise ValueError("oracle: operand sizes differ")
+    if v is not None:
+        v, pv = _f32(v)
+    else:
+        pv = ctypes.POINTER(ctypes.c_float)()
+    What = np.empty(n, np.float32)
+    What16 = np.empty(n, np.uint16)
+    rc = lib.po_oracle_predict(
+        int(opt), float(lr), float(beta1), float(beta2), float(eps), float(weight_decay),
+        int(bool(decay_in_prediction)), int(t), int(s), n, pW, pm, pv,
+        What.ctypes.data_as(ctypes.POINTER(ctypes.c_float)),
+        What16.ctypes.data_as(ctypes.POINTER(ctypes.c_uint16)), int(nthreads))
+    if rc != 0:
+        raise ValueError("oracle: invalid argument (opt=%r t=%r s=%r)" % (opt, t, s))
+    return {"What": What, "What_bf16": What16}
 
 
 def bf16_from_f32(x):

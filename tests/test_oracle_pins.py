@@ -36,7 +36,22 @@ def _read_hand_cases():
     return cases
 
 
-@pytest.mark.parametrize("key,rows", list(_read_hand_cases().items()), ids=lambda k: k[0] if isinstance(k, tuple) else "")
+def _cases(predict):
+    return [(k, r) for k, r in _read_hand_cases().items() if k[0].startswith("predict-") == predict]
+
+
+@pytest.mark.parametrize("key,rows", _cases(True), ids=lambda k: k[0] if isinstance(k, tuple) else "")
+def test_hand_cases_predict_from_cached_state(oracle, key, rows):
+    _, (opt, lr, b1, b2, eps, wd, dip, t, s) = key
+    col = lambda j, src: np.array([float(r[src][j]) for r in rows], dtype=np.float32)
+    v = None if opt == "sgdm" else col(3, 0)
+    r = oracle.predict(OPT[opt], col(0, 0), col(2, 0), v, lr=float(lr), beta1=float(b1), beta2=float(b2),
+                       eps=float(eps), weight_decay=float(wd), decay_in_prediction=bool(int(dip)), t=int(t), s=int(s))
+    np.testing.assert_array_equal(r["What"], col(3, 1))
+    np.testing.assert_array_equal(r["What_bf16"], (col(3, 1).view(np.uint32) >> 16).astype(np.uint16))
+
+
+@pytest.mark.parametrize("key,rows", _cases(False), ids=lambda k: k[0] if isinstance(k, tuple) else "")
 def test_hand_cases_table1_eq1_eq5(oracle, key, rows):
     _, (opt, lr, b1, b2, eps, wd, dip, t, s) = key
     sgdm = opt == "sgdm"
@@ -257,6 +272,88 @@ def test_adamw_readings(oracle):
     assert np.any(adam_l2["m"] != adam["m"])
 
 
+# --------------------------------------------------------------------------- prediction from cached state
+def test_predict_sgdm_is_W_minus_s_lr_m(oracle):
+    # Table 1 (SGDM): dW = m.  With the previous step's momentum this is SpecTrain's predictor (Eq. 6).
+    W, _, m, _ = _rand_state(3000, seed=21, sm=1e-2)
+    for s in (0, 1, 3, 7):
+        r = oracle.predict(0, W, m, lr=0.1, beta1=0.9, beta2=0.0, weight_decay=1e-4, t=5, s=s)
+        want = (W.astype(np.float64) - 0.1 * s * m.astype(np.float64)).astype(np.float32) if s else W
+        np.testing.assert_array_equal(r["What"], want)
+        np.testing.assert_array_equal(r["What_bf16"], oracle.bf16_from_f32(want))
+
+
+def test_predict_adam_bias_corrections_closed_form(oracle):
+    # stored state of a first step from zero: m = (1-b1) g, v = (1-b2) g^2 at t = 1
+    # => mhat = g, vhat = g^2, dW = g/(|g| + eps).  A missing or swapped bias correction breaks this.
+    rng = np.random.default_rng(22)
+    g = (rng.standard_normal(2000) * 1e-3).astype(np.float64)
+    W = (rng.standard_normal(2000) * 0.02).astype(np.float32)
+    b1, b2, eps, lr, s = 0.9, 0.999, 1e-8, 1e-3, 5
+    m = ((1 - b1) * g).astype(np.float32)
+    v = ((1 - b2) * g * g).astype(np.float32)
+    r = oracle.predict(1, W, m, v, lr=lr, beta1=b1, beta2=b2, eps=eps, t=1, s=s)
+    m64, v64 = m.astype(np.float64), v.astype(np.float64)
+    dW = (m64 / (1 - b1)) / (np.sqrt(v64 / (1 - b2)) + eps)
+    want = W.astype(np.float64) - lr * s * dW
+    assert np.all(np.abs(r["What"] - want) <= _ulp32(want))
+    assert np.median(np.abs(dW)) > 0.9                   # and it is about sign(g), as it should be
+    # at huge t the corrections are exactly 1
+    r2 = oracle.predict(1, W, m, v, lr=lr, beta1=b1, beta2=b2, eps=eps, t=10 ** 6, s=s)
+    want2 = W.astype(np.float64) - lr * s * (m64 / (np.sqrt(v64) + eps))
+    assert np.all(np.abs(r2["What"] - want2) <= _ulp32(want2))
+
+
+@pytest.mark.parametrize("kind,hp,t", [c for c in STEP_CASES if c[0] != "adamw"])
+def test_predict_after_fused_step_equals_fused_prediction_one_further(oracle, kind, hp, t):
+    # The state a fused call leaves is (W', m_t, v_t).  Predicting s versions ahead from it gives
+    # W' - s*lr*dW_t = W - (s+1)*lr*dW_t, which is the fused call's own prediction for s+1 (the
+    # post-step-base reading equals the pre-step-base reading one version further).
+    W, g, m, v = _rand_state(4099, seed=31 + t)
+    vv = None if kind == "sgdm" else v
+    for s in (0, 1, 4):
+        fused = oracle.step_predict(OPT[kind], W, g, m, vv, t=t, s=s + 1, **hp)
+        pred = oracle.predict(OPT[kind], fused["W"], fused["m"], fused["v"], t=t, s=s, **hp)
+        a, b = pred["What"].astype(np.float64), fused["What"].astype(np.float64)
+        W64 = W.astype(np.float64)
+        scale = np.abs(W64) + (s + 1) * np.abs(W64 - fused["W"])
+        assert np.all(np.abs(a - b) <= 4 * _ulp32(scale)), s
+    # for AdamW the decay term uses the weights it is applied to, so the two differ by s*lr*wd*(W' - W)
+
+
+def test_predict_s0_affine_and_adamw_readings(oracle):
+    W, _, m, v = _rand_state(2048, seed=23)
+    hp = dict(lr=1e-3, beta1=0.9, beta2=0.999, eps=1e-8)
+    for opt, wd in ((0, 1e-4), (1, 0.0), (2, 0.01)):
+        vv = None if opt == 0 else v
+        what = {s: oracle.predict(opt, W, m, vv, t=9, s=s, weight_decay=wd, **hp)["What"].astype(np.float64)
+                for s in range(6)}
+        np.testing.assert_array_equal(what[0].astype(np.float32).view(np.uint32), W.view(np.uint32))
+        d1 = what[1] - W
+        for s in range(2, 6):
+            assert np.all(np.abs((what[s] - W) - s * d1) <= _ulp32(what[s]) + s * _ulp32(what[1]))
+    adam = oracle.predict(1, W, m, v, t=9, s=3, **hp)["What"]
+    for dip in (True, False):
+        np.testing.assert_array_equal(oracle.predict(2, W, m, v, t=9, s=3, weight_decay=0.0,
+                                                     decay_in_prediction=dip, **hp)["What"], adam)
+    a = oracle.predict(2, W, m, v, t=9, s=3, weight_decay=0.01, decay_in_prediction=False, **hp)["What"]
+    b = oracle.predict(2, W, m, v, t=9, s=3, weight_decay=0.01, decay_in_prediction=True, **hp)["What"]
+    np.testing.assert_array_equal(a, adam)
+    diff = a.astype(np.float64) - b
+    assert np.all(np.abs(diff - 3 * 1e-3 * 0.01 * W.astype(np.float64)) <= _ulp32(a) + _ulp32(b))
+    # Adam's coupled decay lives in m already: it must not appear again in the prediction
+    np.testing.assert_array_equal(oracle.predict(1, W, m, v, t=9, s=3, weight_decay=0.1, **hp)["What"], adam)
+
+
+def test_predict_rejects_bad_arguments(oracle):
+    a = np.ones(4, np.float32)
+    for kw in (dict(t=0, s=1), dict(t=1, s=-1)):
+        with pytest.raises(ValueError):
+            oracle.predict(1, a, a, a, lr=1e-3, beta1=0.9, beta2=0.999, **kw)
+    with pytest.raises(ValueError):
+        oracle.predict(1, a, a, None, lr=1e-3, beta1=0.9, beta2=0.999, t=1, s=1)
+
+
 # --------------------------------------------------------------------------- Eq. 4
 def test_version_difference_eq4_and_fig2_indices(oracle):
     # 4 GPUs: the 5th mini-batch uses What_{2+3}, What_{3+2}, What_{4+1} on GPUs 0, 1, 2; GPU 3 predicts nothing
@@ -311,6 +408,29 @@ def test_brute_force_exact_arithmetic_small_tensors(oracle, kind, hp, t, dip):
                 assert abs(float(r["v"][i]) - vn) <= _ulp32(vn)
             assert abs(float(r["What"][i]) - Wh) <= _ulp32(Wh)
             assert abs(float(r["W"][i]) - Wn) <= 1e-7 * (abs(Wn) + 1e-30)
+
+
+@pytest.mark.parametrize("kind,hp,t", STEP_CASES)
+def test_predict_brute_force_exact_arithmetic(oracle, kind, hp, t):
+    getcontext().prec = 60
+    F = Fraction
+    W, _, m, v = _rand_state(16, seed=41 + t)
+    for s, dip in ((0, True), (1, True), (5, True), (5, False)):
+        r = oracle.predict(OPT[kind], W, m, None if kind == "sgdm" else v, t=t, s=s, decay_in_prediction=dip, **hp)
+        for i in range(16):
+            Wi, mi, vi = F(float(W[i])), F(float(m[i])), F(float(v[i]))
+            if kind == "sgdm":
+                dW = mi
+            else:
+                mhat = mi / (1 - F(hp["beta1"]) ** t)
+                vhat = vi / (1 - F(hp["beta2"]) ** t)
+                root = (Decimal(vhat.numerator) / Decimal(vhat.denominator)).sqrt()
+                dW = mhat / (F(root) + F(hp["eps"]))
+                if kind == "adamw" and dip:
+                    dW += F(hp["weight_decay"]) * Wi
+            want = float(Wi if s == 0 else Wi - F(hp["lr"]) * s * dW)
+            assert abs(float(r["What"][i]) - want) <= _ulp32(want)
+            assert abs(float(r["What"][i]) - want) <= 1e-7 * (abs(want) + 1e-30)
 
 
 # --------------------------------------------------------------------------- bf16 rounding
