@@ -32,6 +32,8 @@ def parse_args():
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--config", type=int, default=5, help="workload 1..5 (default: the 0.74B-parameter stage)")
+    ap.add_argument("--mode", choices=("fused", "predict"), default="fused",
+                    help="fused: optimizer step + prediction (the headline path); predict: prediction alone from cached state")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-copy-probe", action="store_true")
     ap.add_argument("--launch", default="", help="comma separated po_launch overrides, e.g. block=64,unroll=1,lds_bytes=16384")
@@ -39,7 +41,7 @@ def parse_args():
     return ap.parse_args()
 
 
-def cpu_baseline(wl, s):
+def cpu_baseline(wl, s, predict_only=False):
     """The oracle, as it stands, on a bounded sample of the workload (about 10-30 s of CPU work)."""
     import numpy as np
     import oracle
@@ -59,9 +61,14 @@ def cpu_baseline(wl, s):
     arrays = [{k: inp[k][j].numpy() for k in ("W", "g", "m", "v") if inp[k] is not None} for j in range(len(idx))]
     t0 = time.perf_counter()
     for a in arrays:
-        oracle.step_predict(code, a["W"], a["g"], a["m"], a.get("v"), lr=wl.hyper["lr"], beta1=wl.hyper["beta1"],
-                            beta2=wl.hyper["beta2"], eps=wl.hyper["eps"], weight_decay=wl.hyper["weight_decay"],
-                            t=wl.t, s=s, nthreads=threads)
+        if predict_only:
+            oracle.predict(code, a["W"], a["m"], a.get("v"), lr=wl.hyper["lr"], beta1=wl.hyper["beta1"],
+                           beta2=wl.hyper["beta2"], eps=wl.hyper["eps"], weight_decay=wl.hyper["weight_decay"],
+                           t=wl.t, s=s, nthreads=threads)
+        else:
+            oracle.step_predict(code, a["W"], a["g"], a["m"], a.get("v"), lr=wl.hyper["lr"], beta1=wl.hyper["beta1"],
+                                beta2=wl.hyper["beta2"], eps=wl.hyper["eps"], weight_decay=wl.hyper["weight_decay"],
+                                t=wl.t, s=s, nthreads=threads)
     dt = time.perf_counter() - t0
     return {"value": total / dt, "unit": "params/s", "cores": threads, "kind": "oracle",
             "sample": "tensors %d..%d of the stage (%d params), one oracle pass, %.2f s wall" % (idx[0], idx[-1], total, dt)}
@@ -92,17 +99,25 @@ def main():
     rank = D - 1 - s_cfg
     tensors = make_inputs(wl, dev)
     stage = Stage(tensors["W"], tensors["g"], tensors["m"], tensors["v"], wl.what_dtype)
+    predict_only = args.mode == "predict"
     if args.launch:
-        stage.plan.set_launch(**{k: int(v) for k, v in (kv.split("=") for kv in args.launch.split(","))})
-    L = stage.plan.get_launch()
+        kw = {k: int(v) for k, v in (kv.split("=") for kv in args.launch.split(","))}
+        (stage.plan.set_predict_launch if predict_only else stage.plan.set_launch)(**kw)
+    L = stage.plan.get_predict_launch() if predict_only else stage.plan.get_launch()
     hyper = binding.make_hyper(wl.optimizer, wl.hyper["lr"], wl.hyper["beta1"], wl.hyper["beta2"], wl.hyper["eps"],
                                wl.hyper["weight_decay"], True)
     N = stage.n_params
-    bytes_per_launch = wl.bytes_per_param * N
+    bytes_per_param = wl.bytes_per_param
+    if predict_only:       # reads W, m (, v); writes What
+        bytes_per_param = 4 * (2 if wl.optimizer == "sgdm" else 3) + (2 if wl.what_dtype == "bf16" else 4)
+    bytes_per_launch = bytes_per_param * N
 
     def one_step(i):
         s = binding.pipeoptim_version_difference(D, rank)         # Eq. 4
-        stage.step_predict(hyper, wl.t + i, s)                    # coefficients + the fused launch
+        if predict_only:
+            stage.predict(hyper, wl.t, s)                         # coefficients + the prediction launch
+        else:
+            stage.step_predict(hyper, wl.t + i, s)                # coefficients + the fused launch
 
     for i in range(args.warmup):
         one_step(i)
@@ -125,7 +140,8 @@ def main():
     achieved = bytes_per_launch / (avg_ms * 1e-3) / 1e9
 
     out = {
-        "metric": "params/sec, fused optimizer step + weight prediction, 1 GPU",
+        "metric": "params/sec, weight prediction from cached state, 1 GPU" if predict_only
+                  else "params/sec, fused optimizer step + weight prediction, 1 GPU",
         "value": N * K / wall,
         "unit": "params/s",
         "n_gpus": 1, "steps": K, "warmup": args.warmup,
@@ -133,13 +149,14 @@ def main():
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32", "data": "synthetic",
         "config": {"workload": "config %d: %s, %s, t=%d.., s=%d, %s What" % (wl.config, wl.name, wl.optimizer, wl.t, s_cfg, wl.what_dtype),
-                   "n_params": N, "n_tensors": len(wl.shapes), "bytes_per_param": wl.bytes_per_param,
+                   "n_params": N, "n_tensors": len(wl.shapes), "bytes_per_param": bytes_per_param, "mode": args.mode,
                    "launch": {f: getattr(L, f) for f, _ in L._fields_}, "n_chunks": stage.plan.info()["n_chunks"]},
         "kernel_ms": {"avg": avg_ms, "median": med_ms, "min": per_launch_ms[0], "max": per_launch_ms[-1]},
         "achieved_hbm_GBps": achieved,
         "pct_of_hbm_peak": 100.0 * achieved / HBM_PEAK_GBPS,
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
-                     "frac": achieved / HBM_PEAK_GBPS, "traffic": MEASURED_TRAFFIC.get(wl.config)},
+                     "frac": achieved / HBM_PEAK_GBPS,
+                     "traffic": None if predict_only else MEASURED_TRAFFIC.get(wl.config)},
     }
 
     if not args.no_copy_probe:
@@ -165,7 +182,7 @@ def main():
     torch.cuda.empty_cache()
 
     if not args.no_cpu_baseline:
-        out["cpu_baseline"] = cpu_baseline(wl, s_cfg)
+        out["cpu_baseline"] = cpu_baseline(wl, s_cfg, predict_only)
 
     print(json.dumps(out))
 

@@ -154,6 +154,28 @@ int pipeoptim_plan_info(const po_plan* plan, int64_t* n_params, int64_t* n_chunk
 int pipeoptim_step_predict(const po_plan* plan, const po_hyper* hyper, int64_t t, int32_t s,
                            void* hip_stream);
 
+/*
+ * Prediction alone, from the cached optimizer state: how paper Algorithm 1 sequences it (cached
+ * state -> dW_t by Table 1 -> Eq. 5, ahead of the forward pass), for callers whose optimizer step
+ * ran elsewhere or that need What again for another s.  Reads W, m (, v); reads no gradient;
+ * writes only What:
+ *     SGDM : dW = m
+ *     Adam : dW = (m/(1-b1^t)) / (sqrt(v/(1-b2^t)) + eps)        with m, v as stored
+ *     AdamW: dW = that + wd*W   (r alone if !decay_in_prediction)
+ *     What = W - lr*s*dW;  s == 0: What = W
+ * t is the 1-based index of the step that produced the stored m, v.  Called right after
+ * pipeoptim_step_predict(t, .) it predicts from the stepped weights: W' - lr*s*dW_t, which equals the
+ * fused call's own prediction for s+1 (for AdamW up to the decay term being taken at W' instead of W).
+ * With SGDM and the previous step's momentum it is SpecTrain's predictor (paper Eq. 6, first line).
+ * Enqueues exactly one kernel; uses the launch shape set with pipeoptim_plan_set_predict_launch.
+ */
+int pipeoptim_predict(const po_plan* plan, const po_hyper* hyper, int64_t t, int32_t s, void* hip_stream);
+
+/* Launch shape of pipeoptim_predict's kernel (same fields and limits; chunk_elems must equal the
+ * plan's chunk_elems, i.e. the one of pipeoptim_plan_get_launch, or be 0 to mean that). */
+int pipeoptim_plan_get_predict_launch(const po_plan* plan, po_launch* out);
+int pipeoptim_plan_set_predict_launch(po_plan* plan, const po_launch* launch);
+
 /* Paper Eq. 4: s = D - rank - 1 for stage `rank` (0-based) of a depth-D pipeline.  PO_EINVAL unless 0 <= rank < D. */
 int pipeoptim_version_difference(int32_t D, int32_t rank, int32_t* s_out);
 

@@ -49,7 +49,8 @@ class po_launch(ctypes.Structure):
 EXPORTS = (
     "pipeoptim_plan_create", "pipeoptim_plan_destroy", "pipeoptim_plan_set_pointers",
     "pipeoptim_plan_get_launch", "pipeoptim_plan_set_launch", "pipeoptim_plan_info",
-    "pipeoptim_step_predict", "pipeoptim_version_difference", "pipeoptim_coefficients",
+    "pipeoptim_step_predict", "pipeoptim_predict", "pipeoptim_plan_get_predict_launch",
+    "pipeoptim_plan_set_predict_launch", "pipeoptim_version_difference", "pipeoptim_coefficients",
     "pipeoptim_chunk_table_build", "pipeoptim_probe_copy", "pipeoptim_last_error",
 )
 
@@ -73,6 +74,9 @@ def lib():
         L.pipeoptim_plan_set_launch.argtypes = [vp, P(po_launch)]
         L.pipeoptim_plan_info.argtypes = [vp, P(i64), P(i64), P(i64)]
         L.pipeoptim_step_predict.argtypes = [vp, P(po_hyper), i64, i32, vp]
+        L.pipeoptim_predict.argtypes = [vp, P(po_hyper), i64, i32, vp]
+        L.pipeoptim_plan_get_predict_launch.argtypes = [vp, P(po_launch)]
+        L.pipeoptim_plan_set_predict_launch.argtypes = [vp, P(po_launch)]
         L.pipeoptim_version_difference.argtypes = [i32, i32, P(i32)]
         L.pipeoptim_coefficients.argtypes = [P(po_hyper), i64, i32, P(po_coeffs)]
         L.pipeoptim_chunk_table_build.argtypes = [i64, P(i64), i64, P(po_chunk), i64, P(i64)]
@@ -146,6 +150,23 @@ class Plan:
 
     def step_predict(self, hyper: po_hyper, t: int, s: int, stream: int = 0) -> None:
         _check(lib().pipeoptim_step_predict(self._h, ctypes.byref(hyper), int(t), int(s), ctypes.c_void_p(stream)))
+
+    def predict(self, hyper: po_hyper, t: int, s: int, stream: int = 0) -> None:
+        _check(lib().pipeoptim_predict(self._h, ctypes.byref(hyper), int(t), int(s), ctypes.c_void_p(stream)))
+
+    def get_predict_launch(self) -> po_launch:
+        L = po_launch()
+        _check(lib().pipeoptim_plan_get_predict_launch(self._h, ctypes.byref(L)))
+        return L
+
+    def set_predict_launch(self, **kw) -> po_launch:
+        L = self.get_predict_launch()
+        for k, val in kw.items():
+            if not hasattr(L, k):
+                raise TypeError("po_launch has no field %r" % k)
+            setattr(L, k, int(val))
+        _check(lib().pipeoptim_plan_set_predict_launch(self._h, ctypes.byref(L)))
+        return L
 
     def set_pointers(self, which: int, ptrs: Sequence[int]) -> None:
         _check(lib().pipeoptim_plan_set_pointers(self._h, int(which), _ptr_array(ptrs)))

@@ -93,7 +93,8 @@ struct po_plan {
     int32_t what_dtype = PO_WHAT_F32;
     bool has_v = false;
     int device = 0;
-    po_launch launch{};
+    po_launch launch{};           // fused kernel
+    po_launch predict_launch{};   // prediction-only kernel; chunk_elems always equals launch.chunk_elems
     std::vector<int64_t> numel;
     std::vector<po_tensor_desc> descs;    // host mirror
     std::vector<po_chunk> chunks;         // host mirror
@@ -165,6 +166,24 @@ po_launch default_launch(int64_t n_params)
     L.chunk_elems = 65536;
     L.xcd_remap = 0;
     L.reserved = 0;
+    return L;
+}
+
+// The prediction-only kernel is read-dominated (8-12 B read, 2-4 B written per parameter) and likes a
+// looser occupancy cap than the fused kernel (16 workgroups per CU at 0.74B parameters).  Small
+// stages, whose working set largely sits in the memory-side cache, run best with plain accesses and
+// bigger workgroups.
+po_launch default_predict_launch(const po_launch& fused, int64_t n_params)
+{
+    po_launch L = fused;
+    if (n_params >= (int64_t(1) << 25)) {
+        L.lds_bytes = 8192;
+    } else {
+        L.block = 256;
+        L.unroll = 2;
+        L.cache_policy = 0;
+        L.lds_bytes = 0;
+    }
     return L;
 }
 
@@ -272,6 +291,7 @@ int pipeoptim_plan_create(po_plan** out, int64_t n_tensors, const int64_t* numel
     }
     refresh_flags(p);
     p->launch = default_launch(total);
+    p->predict_launch = default_predict_launch(p->launch, total);
 
     hipError_t e = hipGetDevice(&p->device);
     if (e != hipSuccess) { delete p; return fail_hip(e, "hipGetDevice"); }
@@ -346,14 +366,45 @@ int pipeoptim_plan_set_launch(po_plan* p, const po_launch* L)
     if (rc == PO_OK) rc = check_grid(*L, n_new);
     if (rc != PO_OK) return rc;
     const bool rechunk = L->chunk_elems != p->launch.chunk_elems;
+    if (rechunk) {
+        const int64_t ptile = (int64_t)p->predict_launch.block * 4 * p->predict_launch.unroll;
+        const int64_t ratio = L->chunk_elems / ptile;
+        if (L->chunk_elems % ptile != 0 || (ratio & (ratio - 1)) != 0)
+            return fail(PO_EINVAL, "chunk_elems does not fit the prediction kernel's tile (%lld); change that launch first",
+                        (long long)ptile);
+    }
     const po_launch old = p->launch;
     p->launch = *L;
+    p->predict_launch.chunk_elems = L->chunk_elems;
     if (rechunk) {
         hipError_t e = hipDeviceSynchronize();   // a launch may still read the old table
-        if (e != hipSuccess) { p->launch = old; return fail_hip(e, "hipDeviceSynchronize"); }
+        if (e != hipSuccess) { p->launch = old; p->predict_launch.chunk_elems = old.chunk_elems; return fail_hip(e, "hipDeviceSynchronize"); }
         rc = upload_chunks(p);
-        if (rc != PO_OK) { p->launch = old; (void)upload_chunks(p); return rc; }
+        if (rc != PO_OK) { p->launch = old; p->predict_launch.chunk_elems = old.chunk_elems; (void)upload_chunks(p); return rc; }
     }
+    return PO_OK;
+}
+
+int pipeoptim_plan_get_predict_launch(const po_plan* p, po_launch* out)
+{
+    if (!p || !out) return fail(PO_EINVAL, "plan or out is NULL");
+    *out = p->predict_launch;
+    return PO_OK;
+}
+
+int pipeoptim_plan_set_predict_launch(po_plan* p, const po_launch* L_in)
+{
+    if (!p || !L_in) return fail(PO_EINVAL, "plan or launch is NULL");
+    po_launch L = *L_in;
+    if (L.chunk_elems == 0) L.chunk_elems = p->launch.chunk_elems;
+    int rc = check_launch(L);
+    if (rc != PO_OK) return rc;
+    if (L.chunk_elems != p->launch.chunk_elems)
+        return fail(PO_EINVAL, "the prediction kernel shares the plan's chunk table: chunk_elems must be %lld",
+                    (long long)p->launch.chunk_elems);
+    rc = check_grid(L, (int64_t)p->chunks.size());
+    if (rc != PO_OK) return rc;
+    p->predict_launch = L;
     return PO_OK;
 }
 
@@ -377,6 +428,20 @@ int pipeoptim_step_predict(const po_plan* p, const po_hyper* h, int64_t t, int32
     hipError_t e = po_launch_step_predict(h->opt, p->what_dtype, p->launch, p->d_descs, p->d_chunks,
                                           (uint32_t)p->chunks.size(), c, static_cast<hipStream_t>(hip_stream));
     if (e != hipSuccess) return fail_hip(e, "launch of the fused step+predict kernel");
+    return PO_OK;
+}
+
+int pipeoptim_predict(const po_plan* p, const po_hyper* h, int64_t t, int32_t s, void* hip_stream)
+{
+    if (!p) return fail(PO_EINVAL, "plan is NULL");
+    po_coeffs c;
+    int rc = pipeoptim_coefficients(h, t, s, &c);
+    if (rc != PO_OK) return rc;
+    if (h->opt != PO_SGDM && !p->has_v) return fail(PO_EINVAL, "Adam/AdamW needs a plan created with v");
+    if (p->chunks.empty()) return PO_OK;
+    hipError_t e = po_launch_predict(h->opt, p->what_dtype, p->predict_launch, p->d_descs, p->d_chunks,
+                                     (uint32_t)p->chunks.size(), c, static_cast<hipStream_t>(hip_stream));
+    if (e != hipSuccess) return fail_hip(e, "launch of the prediction kernel");
     return PO_OK;
 }
 

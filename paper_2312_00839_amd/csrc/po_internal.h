@@ -29,4 +29,8 @@ hipError_t po_launch_step_predict(int opt, int what_dtype, const po_launch& L,
                                   const po_tensor_desc* d_descs, const po_chunk* d_chunks,
                                   uint32_t n_chunks, const po_coeffs& c, hipStream_t stream);
 
+// Same for the prediction-only kernel (reads W, m, v; writes What).
+hipError_t po_launch_predict(int opt, int what_dtype, const po_launch& L, const po_tensor_desc* d_descs,
+                             const po_chunk* d_chunks, uint32_t n_chunks, const po_coeffs& c, hipStream_t stream);
+
 hipError_t po_launch_probe_copy(void* dst, const void* src, int64_t nbytes, hipStream_t stream);

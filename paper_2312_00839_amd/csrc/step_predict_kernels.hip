@@ -42,6 +42,8 @@ typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 // (sc0 = 1 is not used by any shipped policy).
 constexpr int CP_NT = 2, CP_SC1 = 16;
 
+enum { PO_KERNEL_FUSED = 0, PO_KERNEL_PREDICT = 1 };
+
 // launch.cache_policy -> bits for: LG loads of g (read once), LS loads of W, m, v (rewritten right after),
 // SS stores of W', m', v', SH stores of What (write-only).  Mixed per-stream settings (plain loads for the
 // rewritten streams, nt-only or sc1-only on one of the store groups) all measured slower than policy 4.
@@ -105,6 +107,50 @@ __device__ __forceinline__ void update_element(const po_coeffs& c, float W, floa
     if (c.s_is_zero) W_hat = W;
 }
 
+// Prediction alone from the cached state (no gradient, no state update): dW from the stored m, v.
+template <int OPT>
+__device__ __forceinline__ float predict_element(const po_coeffs& c, float W, float m, float v)
+{
+    float r;
+    if constexpr (OPT == PO_SGDM) {
+        r = m;
+    } else {
+        r = (m * c.inv_bc1) / fmaf(sqrtf(v), c.inv_sqrt_bc2, c.eps);
+        if constexpr (OPT == PO_ADAMW) r = fmaf(c.wd_pred, W, r);
+    }
+    return c.s_is_zero ? W : fmaf(-c.s_lr, r, W);
+}
+
+// Which tile does this workgroup own?  slot = chunk_index * tiles_per_chunk + tile_in_chunk.  With
+// xcd_remap the grid (a multiple of 8) is cut into 8 equal ranges and workgroup id b (XCDs take
+// workgroups round-robin) works in range b mod 8.  Returns false for padding slots and for tiles that
+// start past the end of the tensor's last chunk.
+struct Tile {
+    const po_tensor_desc* d;
+    int64_t off;        // first element of the tile within the tensor
+    uint32_t len;       // elements of the tile that exist (== tile size except at the tensor's end)
+    bool full;          // len == tile size and all base pointers are 16-byte aligned
+};
+
+template <int UNROLL>
+__device__ __forceinline__ bool locate_tile(const po_tensor_desc* __restrict__ descs,
+                                            const po_chunk* __restrict__ chunks, uint32_t n_slots,
+                                            uint32_t tiles_log2, int64_t chunk_elems, int xcd_remap, Tile& t)
+{
+    uint32_t slot = blockIdx.x;
+    if (xcd_remap) slot = (blockIdx.x & 7u) * (gridDim.x >> 3) + (blockIdx.x >> 3);
+    if (slot >= n_slots) return false;
+    const po_chunk ch = chunks[slot >> tiles_log2];
+    t.d = descs + ch.tensor;
+    const uint32_t tile = blockDim.x * 4u * UNROLL;
+    t.off = (int64_t)ch.chunk * chunk_elems + (int64_t)(slot & ((1u << tiles_log2) - 1u)) * tile;
+    const int64_t numel = t.d->numel;
+    if (t.off >= numel) return false;
+    t.len = (numel - t.off < (int64_t)tile) ? (uint32_t)(numel - t.off) : tile;
+    t.full = t.len == tile && (t.d->flags & PO_DESC_VECTOR_OK);
+    return true;
+}
+
 template <int OPT, bool BF16, int UNROLL, int POL>
 __global__ __launch_bounds__(256) void step_predict_kernel(const po_tensor_desc* __restrict__ descs,
                                                            const po_chunk* __restrict__ chunks,
@@ -114,19 +160,11 @@ __global__ __launch_bounds__(256) void step_predict_kernel(const po_tensor_desc*
     constexpr int LG = Policy<POL>::LG, LS = Policy<POL>::LS, SS = Policy<POL>::SS, SH = Policy<POL>::SH;
     constexpr bool ADAM = OPT != PO_SGDM;
 
-    // slot = chunk_index * tiles_per_chunk + tile_in_chunk.  With xcd_remap the grid (a multiple of 8)
-    // is cut into 8 equal ranges and workgroup id b (XCDs take workgroups round-robin) works in range b mod 8.
-    uint32_t slot = blockIdx.x;
-    if (xcd_remap) slot = (blockIdx.x & 7u) * (gridDim.x >> 3) + (blockIdx.x >> 3);
-    if (slot >= n_slots) return;
-
-    const po_chunk ch = chunks[slot >> tiles_log2];
-    const po_tensor_desc* d = descs + ch.tensor;
-    const uint32_t tile = blockDim.x * 4u * UNROLL;
-    const int64_t off = (int64_t)ch.chunk * chunk_elems + (int64_t)(slot & ((1u << tiles_log2) - 1u)) * tile;
-    const int64_t numel = d->numel;
-    if (off >= numel) return;                       // tile past the end of the tensor's last chunk
-    const uint32_t len = (numel - off < (int64_t)tile) ? (uint32_t)(numel - off) : tile;
+    Tile t;
+    if (!locate_tile<UNROLL>(descs, chunks, n_slots, tiles_log2, chunk_elems, xcd_remap, t)) return;
+    const po_tensor_desc* d = t.d;
+    const int64_t off = t.off;
+    const uint32_t len = t.len;
 
     const __amdgpu_buffer_rsrc_t rW = make_rsrc(d->W + off, len * 4u);
     const __amdgpu_buffer_rsrc_t rg = make_rsrc(d->g + off, len * 4u);
@@ -136,7 +174,7 @@ __global__ __launch_bounds__(256) void step_predict_kernel(const po_tensor_desc*
                                            : make_rsrc(static_cast<float*>(d->What) + off, len * 4u);
     const uint32_t tid = threadIdx.x;
 
-    if (len == tile && (d->flags & PO_DESC_VECTOR_OK)) {
+    if (t.full) {
         // full tile, aligned: every lane moves UNROLL groups of 4 consecutive elements per stream
         u32x4 W[UNROLL], g[UNROLL], m[UNROLL], v[UNROLL];
 #pragma unroll
@@ -189,7 +227,66 @@ __global__ __launch_bounds__(256) void step_predict_kernel(const po_tensor_desc*
     }
 }
 
+// What = W - s_lr*dW from the cached m, v: reads W, m (, v) once, writes What.  Same decomposition as above.
 template <int OPT, bool BF16, int UNROLL, int POL>
+__global__ __launch_bounds__(256) void predict_kernel(const po_tensor_desc* __restrict__ descs,
+                                                      const po_chunk* __restrict__ chunks, uint32_t n_slots,
+                                                      uint32_t tiles_log2, int64_t chunk_elems, int xcd_remap,
+                                                      po_coeffs c)
+{
+    constexpr int LD = Policy<POL>::LG, SH = Policy<POL>::SH;      // every input is read once here
+    constexpr bool ADAM = OPT != PO_SGDM;
+
+    Tile t;
+    if (!locate_tile<UNROLL>(descs, chunks, n_slots, tiles_log2, chunk_elems, xcd_remap, t)) return;
+    const po_tensor_desc* d = t.d;
+    const int64_t off = t.off;
+    const uint32_t len = t.len;
+    const __amdgpu_buffer_rsrc_t rW = make_rsrc(d->W + off, len * 4u);
+    const __amdgpu_buffer_rsrc_t rm = make_rsrc(d->m + off, len * 4u);
+    const __amdgpu_buffer_rsrc_t rv = make_rsrc(ADAM ? d->v + off : d->m + off, len * 4u);
+    const __amdgpu_buffer_rsrc_t rh = BF16 ? make_rsrc(static_cast<uint16_t*>(d->What) + off, len * 2u)
+                                           : make_rsrc(static_cast<float*>(d->What) + off, len * 4u);
+    const uint32_t tid = threadIdx.x;
+
+    if (t.full) {
+        u32x4 W[UNROLL], m[UNROLL], v[UNROLL];
+#pragma unroll
+        for (int u = 0; u < UNROLL; ++u) {
+            const uint32_t b = (u * blockDim.x + tid) * 16u;
+            W[u] = __builtin_amdgcn_raw_buffer_load_b128(rW, b, 0, LD);
+            m[u] = __builtin_amdgcn_raw_buffer_load_b128(rm, b, 0, LD);
+            if constexpr (ADAM) v[u] = __builtin_amdgcn_raw_buffer_load_b128(rv, b, 0, LD);
+        }
+#pragma unroll
+        for (int u = 0; u < UNROLL; ++u) {
+            const uint32_t b = (u * blockDim.x + tid) * 16u;
+            float wh[4];
+#pragma unroll
+            for (int e = 0; e < 4; ++e)
+                wh[e] = predict_element<OPT>(c, as_f(W[u][e]), as_f(m[u][e]), ADAM ? as_f(v[u][e]) : 0.f);
+            if constexpr (BF16) {
+                u32x2 p = {pack_bf16x2(wh[0], wh[1]), pack_bf16x2(wh[2], wh[3])};
+                __builtin_amdgcn_raw_buffer_store_b64(p, rh, b >> 1, 0, SH);
+            } else {
+                u32x4 p = {as_u(wh[0]), as_u(wh[1]), as_u(wh[2]), as_u(wh[3])};
+                __builtin_amdgcn_raw_buffer_store_b128(p, rh, b, 0, SH);
+            }
+        }
+    } else {
+        for (uint32_t i = tid; i < len; i += blockDim.x) {
+            const uint32_t b = i * 4u;
+            float W = as_f(__builtin_amdgcn_raw_buffer_load_b32(rW, b, 0, LD));
+            float mm = as_f(__builtin_amdgcn_raw_buffer_load_b32(rm, b, 0, LD));
+            float vv = ADAM ? as_f(__builtin_amdgcn_raw_buffer_load_b32(rv, b, 0, LD)) : 0.f;
+            float wh = predict_element<OPT>(c, W, mm, vv);
+            if constexpr (BF16) __builtin_amdgcn_raw_buffer_store_b16(to_bf16(wh), rh, i * 2u, 0, SH);
+            else __builtin_amdgcn_raw_buffer_store_b32(as_u(wh), rh, b, 0, SH);
+        }
+    }
+}
+
+template <int KIND, int OPT, bool BF16, int UNROLL, int POL>
 hipError_t launch_one(const po_launch& L, const po_tensor_desc* descs, const po_chunk* chunks, uint32_t n_chunks,
                       const po_coeffs& c, hipStream_t stream)
 {
@@ -200,44 +297,45 @@ hipError_t launch_one(const po_launch& L, const po_tensor_desc* descs, const po_
     const uint64_t n_slots = (uint64_t)n_chunks << tiles_log2;
     const uint64_t grid = L.xcd_remap ? ((n_slots + 7u) / 8u) * 8u : n_slots;
     if (grid > 0x7FFFFFFFull) return hipErrorInvalidConfiguration;
-    hipLaunchKernelGGL((step_predict_kernel<OPT, BF16, UNROLL, POL>), dim3((uint32_t)grid), dim3(L.block),
-                       (size_t)L.lds_bytes, stream, descs, chunks, (uint32_t)n_slots, tiles_log2, L.chunk_elems,
-                       L.xcd_remap, c);
+    auto kernel = KIND == PO_KERNEL_PREDICT ? predict_kernel<OPT, BF16, UNROLL, POL>
+                                            : step_predict_kernel<OPT, BF16, UNROLL, POL>;
+    hipLaunchKernelGGL(kernel, dim3((uint32_t)grid), dim3(L.block), (size_t)L.lds_bytes, stream, descs, chunks,
+                       (uint32_t)n_slots, tiles_log2, L.chunk_elems, L.xcd_remap, c);
     return hipGetLastError();
 }
 
-template <int OPT, bool BF16, int UNROLL>
+template <int KIND, int OPT, bool BF16, int UNROLL>
 hipError_t dispatch_policy(const po_launch& L, const po_tensor_desc* d, const po_chunk* ch, uint32_t n,
                            const po_coeffs& c, hipStream_t s)
 {
     switch (L.cache_policy) {
-    case 0: return launch_one<OPT, BF16, UNROLL, 0>(L, d, ch, n, c, s);
-    case 1: return launch_one<OPT, BF16, UNROLL, 1>(L, d, ch, n, c, s);
-    case 2: return launch_one<OPT, BF16, UNROLL, 2>(L, d, ch, n, c, s);
-    case 3: return launch_one<OPT, BF16, UNROLL, 3>(L, d, ch, n, c, s);
-    case 4: return launch_one<OPT, BF16, UNROLL, 4>(L, d, ch, n, c, s);
+    case 0: return launch_one<KIND, OPT, BF16, UNROLL, 0>(L, d, ch, n, c, s);
+    case 1: return launch_one<KIND, OPT, BF16, UNROLL, 1>(L, d, ch, n, c, s);
+    case 2: return launch_one<KIND, OPT, BF16, UNROLL, 2>(L, d, ch, n, c, s);
+    case 3: return launch_one<KIND, OPT, BF16, UNROLL, 3>(L, d, ch, n, c, s);
+    case 4: return launch_one<KIND, OPT, BF16, UNROLL, 4>(L, d, ch, n, c, s);
     }
     return hipErrorInvalidValue;
 }
 
-template <int OPT, bool BF16>
+template <int KIND, int OPT, bool BF16>
 hipError_t dispatch_unroll(const po_launch& L, const po_tensor_desc* d, const po_chunk* ch, uint32_t n,
                            const po_coeffs& c, hipStream_t s)
 {
     switch (L.unroll) {
-    case 1: return dispatch_policy<OPT, BF16, 1>(L, d, ch, n, c, s);
-    case 2: return dispatch_policy<OPT, BF16, 2>(L, d, ch, n, c, s);
-    case 4: return dispatch_policy<OPT, BF16, 4>(L, d, ch, n, c, s);
+    case 1: return dispatch_policy<KIND, OPT, BF16, 1>(L, d, ch, n, c, s);
+    case 2: return dispatch_policy<KIND, OPT, BF16, 2>(L, d, ch, n, c, s);
+    case 4: return dispatch_policy<KIND, OPT, BF16, 4>(L, d, ch, n, c, s);
     }
     return hipErrorInvalidValue;
 }
 
-template <int OPT>
+template <int KIND, int OPT>
 hipError_t dispatch_dtype(int what_dtype, const po_launch& L, const po_tensor_desc* d, const po_chunk* ch,
                           uint32_t n, const po_coeffs& c, hipStream_t s)
 {
-    return what_dtype == PO_WHAT_BF16 ? dispatch_unroll<OPT, true>(L, d, ch, n, c, s)
-                                      : dispatch_unroll<OPT, false>(L, d, ch, n, c, s);
+    return what_dtype == PO_WHAT_BF16 ? dispatch_unroll<KIND, OPT, true>(L, d, ch, n, c, s)
+                                      : dispatch_unroll<KIND, OPT, false>(L, d, ch, n, c, s);
 }
 
 // Plain copy: the yardstick for what one read stream plus one write stream reach on this chip.
@@ -262,9 +360,21 @@ hipError_t po_launch_step_predict(int opt, int what_dtype, const po_launch& L, c
 {
     if (n_chunks == 0) return hipSuccess;
     switch (opt) {
-    case PO_SGDM: return dispatch_dtype<PO_SGDM>(what_dtype, L, d_descs, d_chunks, n_chunks, c, stream);
-    case PO_ADAM: return dispatch_dtype<PO_ADAM>(what_dtype, L, d_descs, d_chunks, n_chunks, c, stream);
-    case PO_ADAMW: return dispatch_dtype<PO_ADAMW>(what_dtype, L, d_descs, d_chunks, n_chunks, c, stream);
+    case PO_SGDM: return dispatch_dtype<PO_KERNEL_FUSED, PO_SGDM>(what_dtype, L, d_descs, d_chunks, n_chunks, c, stream);
+    case PO_ADAM: return dispatch_dtype<PO_KERNEL_FUSED, PO_ADAM>(what_dtype, L, d_descs, d_chunks, n_chunks, c, stream);
+    case PO_ADAMW: return dispatch_dtype<PO_KERNEL_FUSED, PO_ADAMW>(what_dtype, L, d_descs, d_chunks, n_chunks, c, stream);
+    }
+    return hipErrorInvalidValue;
+}
+
+hipError_t po_launch_predict(int opt, int what_dtype, const po_launch& L, const po_tensor_desc* d_descs,
+                             const po_chunk* d_chunks, uint32_t n_chunks, const po_coeffs& c, hipStream_t stream)
+{
+    if (n_chunks == 0) return hipSuccess;
+    switch (opt) {
+    case PO_SGDM: return dispatch_dtype<PO_KERNEL_PREDICT, PO_SGDM>(what_dtype, L, d_descs, d_chunks, n_chunks, c, stream);
+    case PO_ADAM: return dispatch_dtype<PO_KERNEL_PREDICT, PO_ADAM>(what_dtype, L, d_descs, d_chunks, n_chunks, c, stream);
+    case PO_ADAMW: return dispatch_dtype<PO_KERNEL_PREDICT, PO_ADAMW>(what_dtype, L, d_descs, d_chunks, n_chunks, c, stream);
     }
     return hipErrorInvalidValue;
 }

@@ -35,5 +35,8 @@ class Stage:
     def step_predict(self, hyper: binding.po_hyper, t: int, s: int) -> None:
         self.plan.step_predict(hyper, t, s, torch.cuda.current_stream().cuda_stream)
 
+    def predict(self, hyper: binding.po_hyper, t: int, s: int) -> None:
+        self.plan.predict(hyper, t, s, torch.cuda.current_stream().cuda_stream)
+
     def close(self) -> None:
         self.plan.destroy()

@@ -116,6 +116,76 @@ def compare(kind, hp, t, s, inp, ref, got, what_dtype, label="", decay_in_predic
     return report
 
 
+def compare_predict(kind, hp, t, s, inp, ref, got, what_dtype, label="", decay_in_prediction=True):
+    """Prediction-only call: inp has W, m, v; got has What (fp32 array or bf16 bit patterns).
+    scale = |W| + s*lr*dW_abs with dW_abs built from |m| (and wd*|W| for AdamW)."""
+    W = np.abs(inp["W"].astype(np.float64))
+    m = np.abs(inp["m"].astype(np.float64))
+    if kind == "sgdm":
+        d_abs = m
+    else:
+        bc1, bc2 = 1.0 - hp["beta1"] ** t, 1.0 - hp["beta2"] ** t
+        d_abs = m / bc1 / (np.sqrt(inp["v"].astype(np.float64) / bc2) + hp["eps"])
+        if kind == "adamw" and decay_in_prediction:
+            d_abs = d_abs + hp["weight_decay"] * W
+    scale = W + s * hp["lr"] * d_abs
+    tiny = 1e-45
+    ref32 = ref["What"].astype(np.float64)
+    report = {}
+    if what_dtype == "f32":
+        if s == 0:
+            assert np.array_equal(got["What"].view(np.uint32), inp["W"].view(np.uint32)), label + " What(s=0) != W"
+        err = np.abs(got["What"].astype(np.float64) - ref32)
+        report["What"] = float((err / (scale + tiny)).max()) if err.size else 0.0
+        assert (err <= REL_TOL * scale + tiny).all(), "%s predict What: worst ratio %.3e at %d" % (
+            label, report["What"], int(np.argmax(err / (scale + tiny))))
+    else:
+        tol = REL_TOL * scale + tiny
+        lo = bf16_order(oracle.bf16_from_f32((ref32 - tol).astype(np.float32)))
+        hi = bf16_order(oracle.bf16_from_f32((ref32 + tol).astype(np.float32)))
+        code = bf16_order(got["What"])
+        d = np.abs(code - bf16_order(ref["What_bf16"]))
+        report["What_bf16_ulp"] = int(d.max()) if d.size else 0
+        if s == 0:
+            assert report["What_bf16_ulp"] == 0, label + " bf16 What(s=0) is not the rounding of W"
+        outside = (code < np.minimum(lo, hi)) | (code > np.maximum(lo, hi))
+        assert not outside.any(), "%s predict bf16 What: %d codes outside the fp32 band" % (label, int(outside.sum()))
+        wide = d > 1
+        if wide.any():
+            assert (tol[wide] >= 0.25 * np.abs(ref32[wide]) * 2.0 ** -8).all(), label + " bf16 off by >1 ulp away from cancellation"
+    return report
+
+
+def run_oracle_predict(kind, hp, t, s, inp, decay_in_prediction=True, nthreads=8):
+    return oracle.predict(OPT_CODE[kind], inp["W"], inp["m"], inp.get("v"), lr=hp["lr"], beta1=hp["beta1"],
+                          beta2=hp["beta2"], eps=hp["eps"], weight_decay=hp["weight_decay"],
+                          decay_in_prediction=decay_in_prediction, t=t, s=s, nthreads=nthreads)
+
+
+def run_and_compare_predict(kind, hp, t, s, tensors, what_dtype, launch=None, decay_in_prediction=True, label=""):
+    """Prediction-only call on device tensors W, m, v (g is present but must not be read or written)."""
+    keys = [k for k in ("W", "g", "m", "v") if tensors.get(k) is not None]
+    host = [{k: tensors[k][i].cpu().numpy().copy() for k in keys} for i in range(len(tensors["W"]))]
+    stage = Stage(tensors["W"], tensors["g"], tensors["m"], tensors.get("v"), what_dtype)
+    try:
+        if launch:
+            stage.plan.set_launch(**{k: v for k, v in launch.items() if k == "chunk_elems"})
+            stage.plan.set_predict_launch(**launch)
+        stage.predict(make_hyper(kind, hp, decay_in_prediction), t, s)
+        torch.cuda.synchronize()
+        reports = []
+        for i, inp in enumerate(host):
+            for k in keys:      # nothing but What is written
+                assert np.array_equal(getattr(stage, k)[i].cpu().numpy().view(np.uint32), inp[k].view(np.uint32)), k + " was modified"
+            ref = run_oracle_predict(kind, hp, t, s, inp, decay_in_prediction)
+            got = {"What": what_bits(stage.What[i]) if what_dtype == "bf16" else stage.What[i].cpu().numpy()}
+            reports.append(compare_predict(kind, hp, t, s, inp, ref, got, what_dtype, "%s tensor %d" % (label, i),
+                                           decay_in_prediction))
+        return reports
+    finally:
+        stage.close()
+
+
 def run_oracle(kind, hp, t, s, inp, decay_in_prediction=True, nthreads=8):
     return oracle.step_predict(OPT_CODE[kind], inp["W"], inp["g"], inp["m"], inp.get("v"),
                                lr=hp["lr"], beta1=hp["beta1"], beta2=hp["beta2"], eps=hp["eps"],

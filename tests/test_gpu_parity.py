@@ -11,7 +11,8 @@ import torch
 
 pytestmark = pytest.mark.gpu
 
-from parity_util import (compare, make_hyper, run_and_compare_full, run_oracle, what_bits)  # noqa: E402
+from parity_util import (compare, compare_predict, make_hyper, run_and_compare_full, run_and_compare_predict,  # noqa: E402
+                         run_oracle, run_oracle_predict, what_bits)
 
 from paper_2312_00839_amd import binding  # noqa: E402
 from paper_2312_00839_amd.stage import Stage  # noqa: E402
@@ -54,7 +55,7 @@ def _rand_list(sizes, seed, kind, sw=0.02, sg=1e-3, sm=1e-4, sv=1e-3, offset=0):
 
 
 # --------------------------------------------------------------------------- tiny tensors and hand cases
-def _hand_cases():
+def _hand_cases(predict=False):
     cases = {}
     with open(GOLDEN) as f:
         for line in f:
@@ -62,7 +63,8 @@ def _hand_cases():
             if not line or line.startswith("#"):
                 continue
             head, inp, out = [p.split() for p in line.split("|")]
-            cases.setdefault(tuple(head), []).append((inp, out))
+            if head[0].startswith("predict-") == predict:
+                cases.setdefault(tuple(head), []).append((inp, out))
     return list(cases.items())
 
 
@@ -86,6 +88,27 @@ def test_hand_cases_on_gpu(head, rows, what_dtype):
         got = what_bits(stage.What[0]).astype(np.int32)
         want = (expect_What.view(np.uint32) >> 16).astype(np.int32)
         assert np.abs(got - want).max() <= 1
+    stage.close()
+
+
+@pytest.mark.parametrize("head,rows", _hand_cases(True), ids=lambda x: x[0] if isinstance(x, tuple) else "")
+@pytest.mark.parametrize("what_dtype", ["f32", "bf16"])
+def test_predict_hand_cases_on_gpu(head, rows, what_dtype):
+    name, kind, lr, b1, b2, eps, wd, dip, t, s = head
+    _say("hand case %s %s" % (name, what_dtype))
+    hp = dict(lr=float(lr), beta1=float(b1), beta2=float(b2), eps=float(eps), weight_decay=float(wd))
+    col = lambda j, src: torch.tensor([float(r[src][j]) for r in rows], dtype=torch.float32, device=DEV)
+    W, m = col(0, 0), col(2, 0)
+    v = None if kind == "sgdm" else [col(3, 0)]
+    expect = col(3, 1).cpu().numpy()
+    stage = Stage([W], [torch.zeros_like(W)], [m], v, what_dtype)
+    stage.predict(make_hyper(kind, hp, bool(int(dip))), int(t), int(s))
+    torch.cuda.synchronize()
+    if what_dtype == "f32":
+        np.testing.assert_allclose(stage.What[0].cpu().numpy(), expect, rtol=3e-7, atol=1e-7)
+    else:
+        got = what_bits(stage.What[0]).astype(np.int32)
+        assert np.abs(got - (expect.view(np.uint32) >> 16).astype(np.int32)).max() <= 1
     stage.close()
 
 
@@ -231,6 +254,94 @@ def test_set_pointers_swaps_gradient_buffers():
                "What": st.What[i].cpu().numpy()}
         compare(kind, hp, 3, 2, host[i], ref, got, "f32", "set_pointers %d" % i)
     st.close()
+
+
+# --------------------------------------------------------------------------- prediction from the cached state alone
+@pytest.mark.parametrize("kind", ["sgdm", "adam", "adamw"])
+@pytest.mark.parametrize("what_dtype", ["f32", "bf16"])
+def test_predict_tiny_and_ragged(kind, what_dtype):
+    _say("predict tiny+ragged %s %s" % (kind, what_dtype))
+    for s in (0, 1, 6):
+        run_and_compare_predict(kind, HP[kind], 5, s, _rand_list(list(range(0, 17)), 200 + s, kind), what_dtype,
+                                label="predict tiny s=%d" % s)
+    for launch in LAUNCHES:
+        run_and_compare_predict(kind, HP[kind], 100, 3, _rand_list(RAGGED, 8, kind), what_dtype, launch=launch,
+                                label="predict ragged %s" % (launch,))
+    run_and_compare_predict(kind, HP[kind], 9, 2, _rand_list([5, 4096, 9001], 11, kind, offset=1), what_dtype,
+                            label="predict unaligned")
+
+
+def test_predict_adamw_without_decay_and_extremes():
+    _say("predict adamw-A / extremes")
+    run_and_compare_predict("adamw", HP["adamw"], 10, 5, _rand_list([10000, 33], 12, "adamw"), "f32",
+                            decay_in_prediction=False, label="predict adamw-A")
+    for t, s in [(1, 1), (2, 64), (10 ** 6, 1000)]:
+        run_and_compare_predict("adam", HP["adam"], t, s, _rand_list([3001], 15, "adam"), "f32", label="predict t=%d s=%d" % (t, s))
+
+
+@pytest.mark.parametrize("kind", ["sgdm", "adam"])
+def test_predict_after_fused_equals_fused_prediction_one_further(kind):
+    # W' - s*lr*dW_t (prediction from the state the fused call left) == W - (s+1)*lr*dW_t (fused, s+1)
+    _say("predict after fused %s" % kind)
+    hp, t, s = HP[kind], 7, 3
+    a = _rand_list([50000, 77], 31, kind)
+    b = _rand_list([50000, 77], 31, kind)
+    Win = [x.cpu().numpy().astype(np.float64) for x in a["W"]]
+    sa = Stage(a["W"], a["g"], a["m"], a["v"], "f32")
+    sb = Stage(b["W"], b["g"], b["m"], b["v"], "f32")
+    sa.step_predict(make_hyper(kind, hp), t, s + 1)
+    sb.step_predict(make_hyper(kind, hp), t, 0)
+    sb.predict(make_hyper(kind, hp), t, s)
+    torch.cuda.synchronize()
+    for i in range(2):
+        x, y = sa.What[i].cpu().numpy().astype(np.float64), sb.What[i].cpu().numpy().astype(np.float64)
+        scale = np.abs(Win[i]) + (s + 1) * np.abs(Win[i] - sb.W[i].cpu().numpy())
+        assert (np.abs(x - y) <= 2e-6 * scale + 1e-45).all()
+    sa.close()
+    sb.close()
+
+
+def test_predict_config3_full_and_config5_sampled():
+    for cfg, s in ((3, 2), (5, 7)):
+        wl = workload(cfg)
+        _say("predict config %d (%s) s=%d" % (cfg, wl.name, s))
+        tensors = make_inputs(wl, DEV)
+        if cfg == 3:
+            run_and_compare_predict(wl.optimizer, wl.hyper, wl.t, s, tensors, wl.what_dtype, label="predict config 3")
+            continue
+        rng = np.random.default_rng(77)
+        stage = Stage(tensors["W"], tensors["g"], tensors["m"], tensors["v"], wl.what_dtype)
+        stage.predict(make_hyper(wl.optimizer, wl.hyper), wl.t, s)
+        torch.cuda.synchronize()
+        for i, n in enumerate(wl.numels):
+            starts = [0, max(0, n - 8195)] + [int(rng.integers(0, max(1, n - 8192))) for _ in range(6)]
+            idx = torch.cat([torch.arange(a, min(n, a + 8195), device=DEV) for a in starts])
+            inp = {k: tensors[k][i][idx].cpu().numpy() for k in ("W", "m", "v")}     # predict leaves them unchanged
+            ref = run_oracle_predict(wl.optimizer, wl.hyper, wl.t, s, inp)
+            compare_predict(wl.optimizer, wl.hyper, wl.t, s, inp, ref, {"What": what_bits(stage.What[i][idx])},
+                            wl.what_dtype, "predict config 5 tensor %d" % i)
+        stage.close()
+
+
+def test_predict_launch_errors():
+    t = _rand_list([1000], 19, "adam")
+    st = Stage(t["W"], t["g"], t["m"], t["v"], "f32")
+    for bad in [dict(block=100), dict(unroll=3), dict(cache_policy=9), dict(lds_bytes=70000), dict(chunk_elems=4096),
+                dict(reserved=2)]:
+        with pytest.raises(binding.PipeOptimError) as e:
+            st.plan.set_predict_launch(**bad)
+        assert e.value.status == binding.PO_EINVAL, bad
+    st.plan.set_predict_launch(chunk_elems=0, block=128, unroll=2)         # 0 = the plan's chunk size
+    assert st.plan.get_predict_launch().chunk_elems == st.plan.get_launch().chunk_elems
+    with pytest.raises(binding.PipeOptimError):
+        st.plan.set_launch(chunk_elems=256)                                # no longer fits the prediction tile (1024)
+    sg = _rand_list([1000], 19, "sgdm")
+    s2 = Stage(sg["W"], sg["g"], sg["m"], None, "f32")
+    with pytest.raises(binding.PipeOptimError) as e:
+        s2.predict(make_hyper("adam", HP["adam"]), 1, 1)
+    assert e.value.status == binding.PO_EINVAL
+    st.close()
+    s2.close()
 
 
 # --------------------------------------------------------------------------- ABI behaviour on the device
