@@ -34,6 +34,8 @@ def parse_args():
     ap.add_argument("--config", type=int, default=5, help="workload 1..5 (default: the 0.74B-parameter stage)")
     ap.add_argument("--mode", choices=("fused", "predict"), default="fused",
                     help="fused: optimizer step + prediction (the headline path); predict: prediction alone from cached state")
+    ap.add_argument("--grad-dtype", choices=("f32", "bf16"), default="f32",
+                    help="bf16: mixed-precision variant with bf16 gradients (2 bytes fewer read per parameter)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-copy-probe", action="store_true")
     ap.add_argument("--launch", default="", help="comma separated po_launch overrides, e.g. block=64,unroll=1,lds_bytes=16384")
@@ -98,6 +100,8 @@ def main():
     D = args.pipeline_depth or (s_cfg + 1)
     rank = D - 1 - s_cfg
     tensors = make_inputs(wl, dev)
+    if args.grad_dtype == "bf16":
+        tensors["g"] = [x.to(torch.bfloat16) for x in tensors["g"]]
     stage = Stage(tensors["W"], tensors["g"], tensors["m"], tensors["v"], wl.what_dtype)
     predict_only = args.mode == "predict"
     if args.launch:
@@ -107,7 +111,7 @@ def main():
     hyper = binding.make_hyper(wl.optimizer, wl.hyper["lr"], wl.hyper["beta1"], wl.hyper["beta2"], wl.hyper["eps"],
                                wl.hyper["weight_decay"], True)
     N = stage.n_params
-    bytes_per_param = wl.bytes_per_param
+    bytes_per_param = wl.bytes_per_param - (2 if args.grad_dtype == "bf16" else 0)
     if predict_only:       # reads W, m (, v); writes What
         bytes_per_param = 4 * (2 if wl.optimizer == "sgdm" else 3) + (2 if wl.what_dtype == "bf16" else 4)
     bytes_per_launch = bytes_per_param * N
@@ -149,14 +153,14 @@ def main():
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32", "data": "synthetic",
         "config": {"workload": "config %d: %s, %s, t=%d.., s=%d, %s What" % (wl.config, wl.name, wl.optimizer, wl.t, s_cfg, wl.what_dtype),
-                   "n_params": N, "n_tensors": len(wl.shapes), "bytes_per_param": bytes_per_param, "mode": args.mode,
+                   "n_params": N, "n_tensors": len(wl.shapes), "bytes_per_param": bytes_per_param, "mode": args.mode, "grad_dtype": args.grad_dtype,
                    "launch": {f: getattr(L, f) for f, _ in L._fields_}, "n_chunks": stage.plan.info()["n_chunks"]},
         "kernel_ms": {"avg": avg_ms, "median": med_ms, "min": per_launch_ms[0], "max": per_launch_ms[-1]},
         "achieved_hbm_GBps": achieved,
         "pct_of_hbm_peak": 100.0 * achieved / HBM_PEAK_GBPS,
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBPS,
-                     "traffic": None if predict_only else MEASURED_TRAFFIC.get(wl.config)},
+                     "traffic": MEASURED_TRAFFIC.get(wl.config) if (not predict_only and args.grad_dtype == "f32") else None},
     }
 
     if not args.no_copy_probe:

@@ -40,6 +40,7 @@ typedef enum {
 
 typedef enum { PO_SGDM = 0, PO_ADAM = 1, PO_ADAMW = 2 } po_optimizer;   /* rows of paper Table 1 */
 typedef enum { PO_WHAT_F32 = 0, PO_WHAT_BF16 = 1 } po_what_dtype;       /* element type of What */
+typedef enum { PO_GRAD_F32 = 0, PO_GRAD_BF16 = 1 } po_grad_dtype;       /* element type of g */
 
 /*
  * Hyper-parameters, in double; the library derives the fp32 kernel coefficients
@@ -112,7 +113,7 @@ typedef struct po_plan po_plan;   /* opaque */
  * elements at W[i], g[i], m[i], v[i] (device) and a What[i] buffer of numel[i]
  * elements of what_dtype.  numel, W, g, m, v, What are HOST arrays of length
  * n_tensors.  v may be NULL (SGDM-only plan).  numel[i] == 0 and n_tensors == 0
- * are legal.  What[i] must not overlap any other buffer; g is only read;
+ * are legal.  No two buffers of the plan may overlap (checked: PO_EINVAL); g is only read;
  * W, m, v are updated in place.  Buffers aligned to 16 bytes take the vector
  * path; 4-byte (What bf16: 2-byte) alignment is accepted and takes a scalar
  * path for that tensor.  Uploads the tables with a blocking copy (this call
@@ -123,6 +124,17 @@ int pipeoptim_plan_create(po_plan** out, int64_t n_tensors, const int64_t* numel
                           float* const* W, const float* const* g, float* const* m, float* const* v,
                           void* const* What, int32_t what_dtype, void* hip_stream);
 
+/*
+ * As pipeoptim_plan_create, with the element type of the gradients chosen by grad_dtype: mixed-precision
+ * training hands the optimizer bf16 gradients next to fp32 master weights and state.  A bf16 gradient is
+ * widened exactly to fp32 before it enters Table 1's update; everything else is unchanged.  g[i] then
+ * points to numel[i] bf16 values (2-byte aligned; 16-byte aligned for the vector path).
+ */
+int pipeoptim_plan_create_mixed(po_plan** out, int64_t n_tensors, const int64_t* numel,
+                                float* const* W, const void* const* g, int32_t grad_dtype,
+                                float* const* m, float* const* v, void* const* What, int32_t what_dtype,
+                                void* hip_stream);
+
 /* Frees the plan's tables.  Synchronises the device first so no launch still reads them.  NULL is a no-op. */
 int pipeoptim_plan_destroy(po_plan* plan);
 
@@ -130,7 +142,9 @@ int pipeoptim_plan_destroy(po_plan* plan);
  * (host array), e.g. when gradient buffers are re-allocated between steps.  Blocking upload. */
 int pipeoptim_plan_set_pointers(po_plan* plan, int32_t which, void* const* ptrs);
 
-/* Get / set the launch shape (set rebuilds and re-uploads the chunk table if chunk_elems changes; blocking). */
+/* Get / set the launch shape of the fused kernel (set rebuilds and re-uploads the chunk table if chunk_elems
+ * changes; blocking).  The prediction kernel shares the table: if its tile no longer divides the new
+ * chunk_elems by a power of two, its block and unroll are reset to this launch's. */
 int pipeoptim_plan_get_launch(const po_plan* plan, po_launch* out);
 int pipeoptim_plan_set_launch(po_plan* plan, const po_launch* launch);
 

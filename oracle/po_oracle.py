@@ -132,6 +132,11 @@ def bf16_from_f32(x):
     return out
 
 
+def f32_from_bf16(bits):
+    """Widen bf16 bit patterns to fp32 (exact: a bf16 is the upper half of an fp32)."""
+    return (np.asarray(bits, dtype=np.uint16).astype(np.uint32) << 16).view(np.float32)
+
+
 def version_difference(D, rank):
     """Paper Eq. 4."""
     return _load().po_oracle_version_difference(int(D), int(rank))

@@ -14,8 +14,10 @@ LIB_PATH = os.path.join(_HERE, "libpipeoptim.so")
 PO_OK, PO_EINVAL, PO_EALIGN, PO_EHIP, PO_ENOMEM = 0, -1, -2, -3, -4
 PO_SGDM, PO_ADAM, PO_ADAMW = 0, 1, 2
 PO_WHAT_F32, PO_WHAT_BF16 = 0, 1
+PO_GRAD_F32, PO_GRAD_BF16 = 0, 1
 OPTIMIZERS = {"sgdm": PO_SGDM, "adam": PO_ADAM, "adamw": PO_ADAMW}
 WHAT_DTYPES = {"f32": PO_WHAT_F32, "bf16": PO_WHAT_BF16}
+GRAD_DTYPES = {"f32": PO_GRAD_F32, "bf16": PO_GRAD_BF16}
 
 
 class PipeOptimError(RuntimeError):
@@ -47,7 +49,7 @@ class po_launch(ctypes.Structure):
 
 
 EXPORTS = (
-    "pipeoptim_plan_create", "pipeoptim_plan_destroy", "pipeoptim_plan_set_pointers",
+    "pipeoptim_plan_create", "pipeoptim_plan_create_mixed", "pipeoptim_plan_destroy", "pipeoptim_plan_set_pointers",
     "pipeoptim_plan_get_launch", "pipeoptim_plan_set_launch", "pipeoptim_plan_info",
     "pipeoptim_step_predict", "pipeoptim_predict", "pipeoptim_plan_get_predict_launch",
     "pipeoptim_plan_set_predict_launch", "pipeoptim_version_difference", "pipeoptim_coefficients",
@@ -68,6 +70,7 @@ def lib():
         vp, i32, i64 = ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64
         P = ctypes.POINTER
         L.pipeoptim_plan_create.argtypes = [P(vp), i64, P(i64), P(vp), P(vp), P(vp), P(vp), P(vp), i32, vp]
+        L.pipeoptim_plan_create_mixed.argtypes = [P(vp), i64, P(i64), P(vp), P(vp), i32, P(vp), P(vp), P(vp), i32, vp]
         L.pipeoptim_plan_destroy.argtypes = [vp]
         L.pipeoptim_plan_set_pointers.argtypes = [vp, i32, P(vp)]
         L.pipeoptim_plan_get_launch.argtypes = [vp, P(po_launch)]
@@ -136,17 +139,26 @@ class Plan:
     """Owner of a ``po_plan*``.  Pointers are raw device addresses (ints), e.g. ``tensor.data_ptr()``."""
 
     def __init__(self, numel: Sequence[int], W: Sequence[int], g: Sequence[int], m: Sequence[int],
-                 v: Optional[Sequence[int]], What: Sequence[int], what_dtype, stream: int = 0):
+                 v: Optional[Sequence[int]], What: Sequence[int], what_dtype, stream: int = 0, grad_dtype="f32"):
         if isinstance(what_dtype, str):
             what_dtype = WHAT_DTYPES[what_dtype]
+        if isinstance(grad_dtype, str):
+            grad_dtype = GRAD_DTYPES[grad_dtype]
         n = len(numel)
         self._h = ctypes.c_void_p()
         self.n_tensors = n
         self.what_dtype = what_dtype
-        _check(lib().pipeoptim_plan_create(
-            ctypes.byref(self._h), n, (ctypes.c_int64 * max(n, 1))(*numel), _ptr_array(W), _ptr_array(g),
-            _ptr_array(m), _ptr_array(v) if v is not None else None, _ptr_array(What), int(what_dtype),
-            ctypes.c_void_p(stream)))
+        self.grad_dtype = grad_dtype
+        numel_arr = (ctypes.c_int64 * max(n, 1))(*numel)
+        v_arr = _ptr_array(v) if v is not None else None
+        if grad_dtype == PO_GRAD_F32:
+            _check(lib().pipeoptim_plan_create(
+                ctypes.byref(self._h), n, numel_arr, _ptr_array(W), _ptr_array(g), _ptr_array(m), v_arr,
+                _ptr_array(What), int(what_dtype), ctypes.c_void_p(stream)))
+        else:
+            _check(lib().pipeoptim_plan_create_mixed(
+                ctypes.byref(self._h), n, numel_arr, _ptr_array(W), _ptr_array(g), int(grad_dtype), _ptr_array(m),
+                v_arr, _ptr_array(What), int(what_dtype), ctypes.c_void_p(stream)))
 
     def step_predict(self, hyper: po_hyper, t: int, s: int, stream: int = 0) -> None:
         _check(lib().pipeoptim_step_predict(self._h, ctypes.byref(hyper), int(t), int(s), ctypes.c_void_p(stream)))

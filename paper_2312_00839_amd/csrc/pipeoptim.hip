@@ -5,6 +5,7 @@
 // (bias corrections of paper Table 1 in fp64), the version-difference rule of
 // paper Eq. 4, and argument validation.  The kernels live in
 // step_predict_kernels.hip.
+#include <algorithm>
 #include <cmath>
 #include <cstdarg>
 #include <cstdio>
@@ -91,6 +92,7 @@ struct po_plan {
     int64_t n_params = 0;
     int64_t n_unaligned = 0;
     int32_t what_dtype = PO_WHAT_F32;
+    int32_t grad_dtype = PO_GRAD_F32;
     bool has_v = false;
     int device = 0;
     po_launch launch{};           // fused kernel
@@ -104,6 +106,32 @@ struct po_plan {
 };
 
 namespace {
+
+// All buffers of a plan must be pairwise disjoint: W, m, v are rewritten in place while other
+// workgroups still read their own parts, and What is written from values read earlier.
+int check_disjoint(const po_plan* p)
+{
+    struct Range { uintptr_t lo, hi; int64_t tensor; char kind; };
+    std::vector<Range> r;
+    r.reserve((size_t)p->n_tensors * 5);
+    const size_t gsz = p->grad_dtype == PO_GRAD_BF16 ? 2 : 4, hsz = p->what_dtype == PO_WHAT_BF16 ? 2 : 4;
+    for (int64_t i = 0; i < p->n_tensors; ++i) {
+        const po_tensor_desc& d = p->descs[(size_t)i];
+        const size_t n = (size_t)d.numel;
+        if (n == 0) continue;
+        r.push_back({(uintptr_t)d.W, (uintptr_t)d.W + n * 4, i, 'W'});
+        r.push_back({(uintptr_t)d.g, (uintptr_t)d.g + n * gsz, i, 'g'});
+        r.push_back({(uintptr_t)d.m, (uintptr_t)d.m + n * 4, i, 'm'});
+        if (d.v) r.push_back({(uintptr_t)d.v, (uintptr_t)d.v + n * 4, i, 'v'});
+        r.push_back({(uintptr_t)d.What, (uintptr_t)d.What + n * hsz, i, 'h'});
+    }
+    std::sort(r.begin(), r.end(), [](const Range& a, const Range& b) { return a.lo < b.lo; });
+    for (size_t k = 1; k < r.size(); ++k)
+        if (r[k].lo < r[k - 1].hi)
+            return fail(PO_EINVAL, "buffers overlap: %c of tensor %lld and %c of tensor %lld (h = What)", r[k - 1].kind,
+                        (long long)r[k - 1].tensor, r[k].kind, (long long)r[k].tensor);
+    return PO_OK;
+}
 
 int upload_chunks(po_plan* p)
 {
@@ -254,9 +282,9 @@ int pipeoptim_chunk_table_build(int64_t n_tensors, const int64_t* numel, int64_t
     return build_chunks(n_tensors, numel, chunk_elems, out, capacity, n_chunks);
 }
 
-int pipeoptim_plan_create(po_plan** out, int64_t n_tensors, const int64_t* numel, float* const* W,
-                          const float* const* g, float* const* m, float* const* v, void* const* What,
-                          int32_t what_dtype, void* hip_stream)
+int pipeoptim_plan_create_mixed(po_plan** out, int64_t n_tensors, const int64_t* numel, float* const* W,
+                                const void* const* g, int32_t grad_dtype, float* const* m, float* const* v,
+                                void* const* What, int32_t what_dtype, void* hip_stream)
 {
     (void)hip_stream;
     if (!out) return fail(PO_EINVAL, "out is NULL");
@@ -264,15 +292,18 @@ int pipeoptim_plan_create(po_plan** out, int64_t n_tensors, const int64_t* numel
     if (n_tensors < 0) return fail(PO_EINVAL, "n_tensors < 0");
     if (n_tensors > 0 && (!numel || !W || !g || !m || !What)) return fail(PO_EINVAL, "a required pointer array is NULL");
     if (what_dtype != PO_WHAT_F32 && what_dtype != PO_WHAT_BF16) return fail(PO_EINVAL, "unknown what_dtype %d", what_dtype);
+    if (grad_dtype != PO_GRAD_F32 && grad_dtype != PO_GRAD_BF16) return fail(PO_EINVAL, "unknown grad_dtype %d", grad_dtype);
     const uintptr_t what_mask = what_dtype == PO_WHAT_BF16 ? 1u : 3u;
+    const uintptr_t grad_mask = grad_dtype == PO_GRAD_BF16 ? 1u : 3u;
     int64_t total = 0;
     for (int64_t i = 0; i < n_tensors; ++i) {
         if (numel[i] < 0) return fail(PO_EINVAL, "numel[%lld] < 0", (long long)i);
         if (numel[i] == 0) continue;
         if (!W[i] || !g[i] || !m[i] || !What[i] || (v && !v[i]))
             return fail(PO_EINVAL, "tensor %lld has a NULL buffer", (long long)i);
-        if (((uintptr_t)W[i] | (uintptr_t)g[i] | (uintptr_t)m[i] | (v ? (uintptr_t)v[i] : 0)) & 3u)
+        if (((uintptr_t)W[i] | (uintptr_t)m[i] | (v ? (uintptr_t)v[i] : 0)) & 3u)
             return fail(PO_EALIGN, "tensor %lld: fp32 buffer not 4-byte aligned", (long long)i);
+        if ((uintptr_t)g[i] & grad_mask) return fail(PO_EALIGN, "tensor %lld: g not aligned to its element", (long long)i);
         if ((uintptr_t)What[i] & what_mask) return fail(PO_EALIGN, "tensor %lld: What not aligned to its element", (long long)i);
         total += numel[i];
     }
@@ -281,6 +312,7 @@ int pipeoptim_plan_create(po_plan** out, int64_t n_tensors, const int64_t* numel
     p->n_tensors = n_tensors;
     p->n_params = total;
     p->what_dtype = what_dtype;
+    p->grad_dtype = grad_dtype;
     p->has_v = (v != nullptr);
     p->numel.assign(numel, numel + n_tensors);
     p->descs.resize((size_t)n_tensors);
@@ -289,6 +321,8 @@ int pipeoptim_plan_create(po_plan** out, int64_t n_tensors, const int64_t* numel
         d.W = W[i]; d.g = g[i]; d.m = m[i]; d.v = v ? v[i] : nullptr; d.What = What[i];
         d.numel = numel[i]; d.flags = 0; d.pad = 0;
     }
+    int rc = check_disjoint(p);
+    if (rc != PO_OK) { delete p; return rc; }
     refresh_flags(p);
     p->launch = default_launch(total);
     p->predict_launch = default_predict_launch(p->launch, total);
@@ -299,12 +333,20 @@ int pipeoptim_plan_create(po_plan** out, int64_t n_tensors, const int64_t* numel
         e = hipMalloc(reinterpret_cast<void**>(&p->d_descs), (size_t)n_tensors * sizeof(po_tensor_desc));
         if (e != hipSuccess) { delete p; return fail(PO_ENOMEM, "hipMalloc(descriptors): %s", hipGetErrorString(e)); }
     }
-    int rc = upload_descs(p);
+    rc = upload_descs(p);
     if (rc == PO_OK) rc = upload_chunks(p);
     if (rc == PO_OK) rc = check_grid(p->launch, (int64_t)p->chunks.size());
     if (rc != PO_OK) { pipeoptim_plan_destroy(p); return rc; }
     *out = p;
     return PO_OK;
+}
+
+int pipeoptim_plan_create(po_plan** out, int64_t n_tensors, const int64_t* numel, float* const* W,
+                          const float* const* g, float* const* m, float* const* v, void* const* What,
+                          int32_t what_dtype, void* hip_stream)
+{
+    return pipeoptim_plan_create_mixed(out, n_tensors, numel, W, reinterpret_cast<const void* const*>(g), PO_GRAD_F32,
+                                       m, v, What, what_dtype, hip_stream);
 }
 
 int pipeoptim_plan_destroy(po_plan* p)
@@ -327,22 +369,25 @@ int pipeoptim_plan_set_pointers(po_plan* p, int32_t which, void* const* ptrs)
     if (which < 0 || which > 4) return fail(PO_EINVAL, "which must be 0..4");
     if (which == 3 && !p->has_v) return fail(PO_EINVAL, "plan has no v column");
     if (p->n_tensors > 0 && !ptrs) return fail(PO_EINVAL, "ptrs is NULL");
-    const uintptr_t mask = (which == 4 && p->what_dtype == PO_WHAT_BF16) ? 1u : 3u;
+    const uintptr_t mask = ((which == 4 && p->what_dtype == PO_WHAT_BF16) || (which == 1 && p->grad_dtype == PO_GRAD_BF16)) ? 1u : 3u;
     for (int64_t i = 0; i < p->n_tensors; ++i) {
         if (p->numel[(size_t)i] == 0) continue;
         if (!ptrs[i]) return fail(PO_EINVAL, "tensor %lld: NULL pointer", (long long)i);
         if ((uintptr_t)ptrs[i] & mask) return fail(PO_EALIGN, "tensor %lld: pointer not aligned to its element", (long long)i);
     }
+    const std::vector<po_tensor_desc> saved = p->descs;
     for (int64_t i = 0; i < p->n_tensors; ++i) {
         po_tensor_desc& d = p->descs[(size_t)i];
         switch (which) {
         case 0: d.W = static_cast<float*>(ptrs[i]); break;
-        case 1: d.g = static_cast<const float*>(ptrs[i]); break;
+        case 1: d.g = ptrs[i]; break;
         case 2: d.m = static_cast<float*>(ptrs[i]); break;
         case 3: d.v = static_cast<float*>(ptrs[i]); break;
         case 4: d.What = ptrs[i]; break;
         }
     }
+    const int rc_overlap = check_disjoint(p);
+    if (rc_overlap != PO_OK) { p->descs = saved; return rc_overlap; }
     refresh_flags(p);
     hipError_t e = hipDeviceSynchronize();   // a launch may still read the old descriptors
     if (e != hipSuccess) return fail_hip(e, "hipDeviceSynchronize");
@@ -366,21 +411,22 @@ int pipeoptim_plan_set_launch(po_plan* p, const po_launch* L)
     if (rc == PO_OK) rc = check_grid(*L, n_new);
     if (rc != PO_OK) return rc;
     const bool rechunk = L->chunk_elems != p->launch.chunk_elems;
-    if (rechunk) {
-        const int64_t ptile = (int64_t)p->predict_launch.block * 4 * p->predict_launch.unroll;
-        const int64_t ratio = L->chunk_elems / ptile;
-        if (L->chunk_elems % ptile != 0 || (ratio & (ratio - 1)) != 0)
-            return fail(PO_EINVAL, "chunk_elems does not fit the prediction kernel's tile (%lld); change that launch first",
-                        (long long)ptile);
-    }
-    const po_launch old = p->launch;
+    const po_launch old = p->launch, old_predict = p->predict_launch;
     p->launch = *L;
     p->predict_launch.chunk_elems = L->chunk_elems;
+    {   // the two kernels share the chunk table: keep the prediction kernel's tile a power-of-two divisor of it
+        const int64_t ptile = (int64_t)p->predict_launch.block * 4 * p->predict_launch.unroll;
+        const int64_t ratio = L->chunk_elems / ptile;
+        if (L->chunk_elems % ptile != 0 || (ratio & (ratio - 1)) != 0) {
+            p->predict_launch.block = L->block;
+            p->predict_launch.unroll = L->unroll;
+        }
+    }
     if (rechunk) {
         hipError_t e = hipDeviceSynchronize();   // a launch may still read the old table
-        if (e != hipSuccess) { p->launch = old; p->predict_launch.chunk_elems = old.chunk_elems; return fail_hip(e, "hipDeviceSynchronize"); }
+        if (e != hipSuccess) { p->launch = old; p->predict_launch = old_predict; return fail_hip(e, "hipDeviceSynchronize"); }
         rc = upload_chunks(p);
-        if (rc != PO_OK) { p->launch = old; p->predict_launch.chunk_elems = old.chunk_elems; (void)upload_chunks(p); return rc; }
+        if (rc != PO_OK) { p->launch = old; p->predict_launch = old_predict; (void)upload_chunks(p); return rc; }
     }
     return PO_OK;
 }
@@ -425,7 +471,7 @@ int pipeoptim_step_predict(const po_plan* p, const po_hyper* h, int64_t t, int32
     if (rc != PO_OK) return rc;
     if (h->opt != PO_SGDM && !p->has_v) return fail(PO_EINVAL, "Adam/AdamW needs a plan created with v");
     if (p->chunks.empty()) return PO_OK;
-    hipError_t e = po_launch_step_predict(h->opt, p->what_dtype, p->launch, p->d_descs, p->d_chunks,
+    hipError_t e = po_launch_step_predict(h->opt, p->what_dtype, p->grad_dtype, p->launch, p->d_descs, p->d_chunks,
                                           (uint32_t)p->chunks.size(), c, static_cast<hipStream_t>(hip_stream));
     if (e != hipSuccess) return fail_hip(e, "launch of the fused step+predict kernel");
     return PO_OK;

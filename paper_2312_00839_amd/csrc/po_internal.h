@@ -11,7 +11,7 @@
 // 64 bytes so that a workgroup fetches one with a single scalar cache line.
 struct alignas(64) po_tensor_desc {
     float* W;
-    const float* g;
+    const void* g;     // fp32 or bf16, by the plan's grad_dtype
     float* m;
     float* v;          // nullptr in an SGDM-only plan
     void* What;
@@ -25,7 +25,7 @@ enum : uint32_t { PO_DESC_VECTOR_OK = 1u };
 
 // Launches the fused kernel for the given launch shape.  All shape limits were
 // validated by the caller; returns the HIP status of the launch.
-hipError_t po_launch_step_predict(int opt, int what_dtype, const po_launch& L,
+hipError_t po_launch_step_predict(int opt, int what_dtype, int grad_dtype, const po_launch& L,
                                   const po_tensor_desc* d_descs, const po_chunk* d_chunks,
                                   uint32_t n_chunks, const po_coeffs& c, hipStream_t stream);
 

@@ -151,7 +151,12 @@ __device__ __forceinline__ bool locate_tile(const po_tensor_desc* __restrict__ d
     return true;
 }
 
-template <int OPT, bool BF16, int UNROLL, int POL>
+// bf16 -> fp32 is exact: the bf16 pattern is the upper half of the fp32 pattern.
+__device__ __forceinline__ float bf16_lo(uint32_t pair) { return as_f(pair << 16); }
+__device__ __forceinline__ float bf16_hi(uint32_t pair) { return as_f(pair & 0xFFFF0000u); }
+
+// GB16: gradients are bf16 (8 bytes per lane per group instead of 16).
+template <int OPT, bool BF16, bool GB16, int UNROLL, int POL>
 __global__ __launch_bounds__(256) void step_predict_kernel(const po_tensor_desc* __restrict__ descs,
                                                            const po_chunk* __restrict__ chunks,
                                                            uint32_t n_slots, uint32_t tiles_log2,
@@ -167,7 +172,8 @@ __global__ __launch_bounds__(256) void step_predict_kernel(const po_tensor_desc*
     const uint32_t len = t.len;
 
     const __amdgpu_buffer_rsrc_t rW = make_rsrc(d->W + off, len * 4u);
-    const __amdgpu_buffer_rsrc_t rg = make_rsrc(d->g + off, len * 4u);
+    const __amdgpu_buffer_rsrc_t rg = GB16 ? make_rsrc(static_cast<const uint16_t*>(d->g) + off, len * 2u)
+                                           : make_rsrc(static_cast<const float*>(d->g) + off, len * 4u);
     const __amdgpu_buffer_rsrc_t rm = make_rsrc(d->m + off, len * 4u);
     const __amdgpu_buffer_rsrc_t rv = make_rsrc(ADAM ? d->v + off : d->m + off, len * 4u);
     const __amdgpu_buffer_rsrc_t rh = BF16 ? make_rsrc(static_cast<uint16_t*>(d->What) + off, len * 2u)
@@ -181,7 +187,12 @@ __global__ __launch_bounds__(256) void step_predict_kernel(const po_tensor_desc*
         for (int u = 0; u < UNROLL; ++u) {
             const uint32_t b = (u * blockDim.x + tid) * 16u;
             W[u] = __builtin_amdgcn_raw_buffer_load_b128(rW, b, 0, LS);
-            g[u] = __builtin_amdgcn_raw_buffer_load_b128(rg, b, 0, LG);
+            if constexpr (GB16) {
+                const u32x2 p = __builtin_amdgcn_raw_buffer_load_b64(rg, b >> 1, 0, LG);
+                g[u] = u32x4{as_u(bf16_lo(p[0])), as_u(bf16_hi(p[0])), as_u(bf16_lo(p[1])), as_u(bf16_hi(p[1]))};
+            } else {
+                g[u] = __builtin_amdgcn_raw_buffer_load_b128(rg, b, 0, LG);
+            }
             m[u] = __builtin_amdgcn_raw_buffer_load_b128(rm, b, 0, LS);
             if constexpr (ADAM) v[u] = __builtin_amdgcn_raw_buffer_load_b128(rv, b, 0, LS);
         }
@@ -213,7 +224,8 @@ __global__ __launch_bounds__(256) void step_predict_kernel(const po_tensor_desc*
         for (uint32_t i = tid; i < len; i += blockDim.x) {
             const uint32_t b = i * 4u;
             float W = as_f(__builtin_amdgcn_raw_buffer_load_b32(rW, b, 0, LS));
-            float g = as_f(__builtin_amdgcn_raw_buffer_load_b32(rg, b, 0, LG));
+            float g = GB16 ? as_f((uint32_t)__builtin_amdgcn_raw_buffer_load_b16(rg, i * 2u, 0, LG) << 16)
+                           : as_f(__builtin_amdgcn_raw_buffer_load_b32(rg, b, 0, LG));
             float mm = as_f(__builtin_amdgcn_raw_buffer_load_b32(rm, b, 0, LS));
             float vv = ADAM ? as_f(__builtin_amdgcn_raw_buffer_load_b32(rv, b, 0, LS)) : 0.f;
             float wn, wh;
@@ -286,7 +298,7 @@ __global__ __launch_bounds__(256) void predict_kernel(const po_tensor_desc* __re
     }
 }
 
-template <int KIND, int OPT, bool BF16, int UNROLL, int POL>
+template <int KIND, int OPT, bool BF16, bool GB16, int UNROLL, int POL>
 hipError_t launch_one(const po_launch& L, const po_tensor_desc* descs, const po_chunk* chunks, uint32_t n_chunks,
                       const po_coeffs& c, hipStream_t stream)
 {
@@ -298,44 +310,50 @@ hipError_t launch_one(const po_launch& L, const po_tensor_desc* descs, const po_
     const uint64_t grid = L.xcd_remap ? ((n_slots + 7u) / 8u) * 8u : n_slots;
     if (grid > 0x7FFFFFFFull) return hipErrorInvalidConfiguration;
     auto kernel = KIND == PO_KERNEL_PREDICT ? predict_kernel<OPT, BF16, UNROLL, POL>
-                                            : step_predict_kernel<OPT, BF16, UNROLL, POL>;
+                                            : step_predict_kernel<OPT, BF16, GB16, UNROLL, POL>;
     hipLaunchKernelGGL(kernel, dim3((uint32_t)grid), dim3(L.block), (size_t)L.lds_bytes, stream, descs, chunks,
                        (uint32_t)n_slots, tiles_log2, L.chunk_elems, L.xcd_remap, c);
     return hipGetLastError();
 }
 
-template <int KIND, int OPT, bool BF16, int UNROLL>
+template <int KIND, int OPT, bool BF16, bool GB16, int UNROLL>
 hipError_t dispatch_policy(const po_launch& L, const po_tensor_desc* d, const po_chunk* ch, uint32_t n,
                            const po_coeffs& c, hipStream_t s)
 {
     switch (L.cache_policy) {
-    case 0: return launch_one<KIND, OPT, BF16, UNROLL, 0>(L, d, ch, n, c, s);
-    case 1: return launch_one<KIND, OPT, BF16, UNROLL, 1>(L, d, ch, n, c, s);
-    case 2: return launch_one<KIND, OPT, BF16, UNROLL, 2>(L, d, ch, n, c, s);
-    case 3: return launch_one<KIND, OPT, BF16, UNROLL, 3>(L, d, ch, n, c, s);
-    case 4: return launch_one<KIND, OPT, BF16, UNROLL, 4>(L, d, ch, n, c, s);
+    case 0: return launch_one<KIND, OPT, BF16, GB16, UNROLL, 0>(L, d, ch, n, c, s);
+    case 1: return launch_one<KIND, OPT, BF16, GB16, UNROLL, 1>(L, d, ch, n, c, s);
+    case 2: return launch_one<KIND, OPT, BF16, GB16, UNROLL, 2>(L, d, ch, n, c, s);
+    case 3: return launch_one<KIND, OPT, BF16, GB16, UNROLL, 3>(L, d, ch, n, c, s);
+    case 4: return launch_one<KIND, OPT, BF16, GB16, UNROLL, 4>(L, d, ch, n, c, s);
     }
     return hipErrorInvalidValue;
 }
 
-template <int KIND, int OPT, bool BF16>
+template <int KIND, int OPT, bool BF16, bool GB16>
 hipError_t dispatch_unroll(const po_launch& L, const po_tensor_desc* d, const po_chunk* ch, uint32_t n,
                            const po_coeffs& c, hipStream_t s)
 {
     switch (L.unroll) {
-    case 1: return dispatch_policy<KIND, OPT, BF16, 1>(L, d, ch, n, c, s);
-    case 2: return dispatch_policy<KIND, OPT, BF16, 2>(L, d, ch, n, c, s);
-    case 4: return dispatch_policy<KIND, OPT, BF16, 4>(L, d, ch, n, c, s);
+    case 1: return dispatch_policy<KIND, OPT, BF16, GB16, 1>(L, d, ch, n, c, s);
+    case 2: return dispatch_policy<KIND, OPT, BF16, GB16, 2>(L, d, ch, n, c, s);
+    case 4: return dispatch_policy<KIND, OPT, BF16, GB16, 4>(L, d, ch, n, c, s);
     }
     return hipErrorInvalidValue;
 }
 
 template <int KIND, int OPT>
-hipError_t dispatch_dtype(int what_dtype, const po_launch& L, const po_tensor_desc* d, const po_chunk* ch,
-                          uint32_t n, const po_coeffs& c, hipStream_t s)
+hipError_t dispatch_dtype(int what_dtype, int grad_dtype, const po_launch& L, const po_tensor_desc* d,
+                          const po_chunk* ch, uint32_t n, const po_coeffs& c, hipStream_t s)
 {
-    return what_dtype == PO_WHAT_BF16 ? dispatch_unroll<KIND, OPT, true>(L, d, ch, n, c, s)
-                                      : dispatch_unroll<KIND, OPT, false>(L, d, ch, n, c, s);
+    const bool h16 = what_dtype == PO_WHAT_BF16;
+    if constexpr (KIND == PO_KERNEL_FUSED) {
+        if (grad_dtype == PO_GRAD_BF16)
+            return h16 ? dispatch_unroll<KIND, OPT, true, true>(L, d, ch, n, c, s)
+                       : dispatch_unroll<KIND, OPT, false, true>(L, d, ch, n, c, s);
+    }
+    return h16 ? dispatch_unroll<KIND, OPT, true, false>(L, d, ch, n, c, s)
+               : dispatch_unroll<KIND, OPT, false, false>(L, d, ch, n, c, s);
 }
 
 // Plain copy: the yardstick for what one read stream plus one write stream reach on this chip.
@@ -354,15 +372,15 @@ __global__ __launch_bounds__(64) void probe_copy_kernel(char* __restrict__ dst, 
 
 }  // namespace
 
-hipError_t po_launch_step_predict(int opt, int what_dtype, const po_launch& L, const po_tensor_desc* d_descs,
-                                  const po_chunk* d_chunks, uint32_t n_chunks, const po_coeffs& c,
-                                  hipStream_t stream)
+hipError_t po_launch_step_predict(int opt, int what_dtype, int grad_dtype, const po_launch& L,
+                                  const po_tensor_desc* d_descs, const po_chunk* d_chunks, uint32_t n_chunks,
+                                  const po_coeffs& c, hipStream_t stream)
 {
     if (n_chunks == 0) return hipSuccess;
     switch (opt) {
-    case PO_SGDM: return dispatch_dtype<PO_KERNEL_FUSED, PO_SGDM>(what_dtype, L, d_descs, d_chunks, n_chunks, c, stream);
-    case PO_ADAM: return dispatch_dtype<PO_KERNEL_FUSED, PO_ADAM>(what_dtype, L, d_descs, d_chunks, n_chunks, c, stream);
-    case PO_ADAMW: return dispatch_dtype<PO_KERNEL_FUSED, PO_ADAMW>(what_dtype, L, d_descs, d_chunks, n_chunks, c, stream);
+    case PO_SGDM: return dispatch_dtype<PO_KERNEL_FUSED, PO_SGDM>(what_dtype, grad_dtype, L, d_descs, d_chunks, n_chunks, c, stream);
+    case PO_ADAM: return dispatch_dtype<PO_KERNEL_FUSED, PO_ADAM>(what_dtype, grad_dtype, L, d_descs, d_chunks, n_chunks, c, stream);
+    case PO_ADAMW: return dispatch_dtype<PO_KERNEL_FUSED, PO_ADAMW>(what_dtype, grad_dtype, L, d_descs, d_chunks, n_chunks, c, stream);
     }
     return hipErrorInvalidValue;
 }
@@ -372,9 +390,9 @@ hipError_t po_launch_predict(int opt, int what_dtype, const po_launch& L, const 
 {
     if (n_chunks == 0) return hipSuccess;
     switch (opt) {
-    case PO_SGDM: return dispatch_dtype<PO_KERNEL_PREDICT, PO_SGDM>(what_dtype, L, d_descs, d_chunks, n_chunks, c, stream);
-    case PO_ADAM: return dispatch_dtype<PO_KERNEL_PREDICT, PO_ADAM>(what_dtype, L, d_descs, d_chunks, n_chunks, c, stream);
-    case PO_ADAMW: return dispatch_dtype<PO_KERNEL_PREDICT, PO_ADAMW>(what_dtype, L, d_descs, d_chunks, n_chunks, c, stream);
+    case PO_SGDM: return dispatch_dtype<PO_KERNEL_PREDICT, PO_SGDM>(what_dtype, PO_GRAD_F32, L, d_descs, d_chunks, n_chunks, c, stream);
+    case PO_ADAM: return dispatch_dtype<PO_KERNEL_PREDICT, PO_ADAM>(what_dtype, PO_GRAD_F32, L, d_descs, d_chunks, n_chunks, c, stream);
+    case PO_ADAMW: return dispatch_dtype<PO_KERNEL_PREDICT, PO_ADAMW>(what_dtype, PO_GRAD_F32, L, d_descs, d_chunks, n_chunks, c, stream);
     }
     return hipErrorInvalidValue;
 }

@@ -15,10 +15,16 @@ class Stage:
 
     def __init__(self, W: List[torch.Tensor], g: List[torch.Tensor], m: List[torch.Tensor],
                  v: Optional[List[torch.Tensor]], what_dtype: str):
-        for lst in (W, g, m) + ((v,) if v is not None else ()):
+        for lst in (W, m) + ((v,) if v is not None else ()):
             for x in lst:
                 if x.dtype != torch.float32 or not x.is_contiguous() or x.device.type != "cuda":
-                    raise ValueError("stage tensors must be contiguous fp32 tensors on the GPU")
+                    raise ValueError("W, m, v must be contiguous fp32 tensors on the GPU")
+        gdt = {x.dtype for x in g} or {torch.float32}
+        if len(gdt) != 1 or not gdt <= {torch.float32, torch.bfloat16}:
+            raise ValueError("gradients must all be fp32 or all be bf16")
+        if any(not x.is_contiguous() or x.device.type != "cuda" for x in g):
+            raise ValueError("gradients must be contiguous tensors on the GPU")
+        self.grad_dtype = "bf16" if gdt == {torch.bfloat16} else "f32"
         self.W, self.g, self.m, self.v = W, g, m, v
         self.what_dtype = what_dtype
         tdt = torch.bfloat16 if what_dtype == "bf16" else torch.float32
@@ -26,7 +32,8 @@ class Stage:
         self.numel = [x.numel() for x in W]
         ptrs = lambda lst: [x.data_ptr() for x in lst]
         self.plan = binding.Plan(self.numel, ptrs(W), ptrs(g), ptrs(m), ptrs(v) if v is not None else None,
-                                 ptrs(self.What), what_dtype, torch.cuda.current_stream().cuda_stream)
+                                 ptrs(self.What), what_dtype, torch.cuda.current_stream().cuda_stream,
+                                 grad_dtype=self.grad_dtype)
 
     @property
     def n_params(self) -> int:

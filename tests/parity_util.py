@@ -41,6 +41,18 @@ def what_bits(t: torch.Tensor) -> np.ndarray:
     return t.view(torch.int16).cpu().numpy().view(np.uint16)
 
 
+def raw_bits(t: torch.Tensor) -> np.ndarray:
+    """Bit patterns of an fp32 or bf16 device tensor (host)."""
+    return what_bits(t) if t.dtype == torch.bfloat16 else t.cpu().numpy().view(np.uint32).copy()
+
+
+def host_f32(t: torch.Tensor) -> np.ndarray:
+    """Host fp32 copy of a device tensor; a bf16 tensor is widened exactly, by the oracle's own helper."""
+    if t.dtype == torch.bfloat16:
+        return oracle.f32_from_bf16(what_bits(t)).copy()
+    return t.cpu().numpy().copy()
+
+
 def scales(kind, hp, t, s, inp, ref, decay_in_prediction=True):
     """Per-element reference magnitudes (see the module docstring)."""
     W = np.abs(inp["W"].astype(np.float64))
@@ -200,8 +212,9 @@ def make_hyper(kind, hp, decay_in_prediction=True):
 
 def run_and_compare_full(kind, hp, t, s, tensors, what_dtype, launch=None, decay_in_prediction=True, label=""):
     """tensors: dict of lists of device tensors W, g, m, v (v None for sgdm).  Compares every element."""
-    host = [{k: tensors[k][i].cpu().numpy().copy() for k in ("W", "g", "m", "v") if tensors.get(k) is not None}
+    host = [{k: host_f32(tensors[k][i]) for k in ("W", "g", "m", "v") if tensors.get(k) is not None}
             for i in range(len(tensors["W"]))]
+    g_before = [raw_bits(x) for x in tensors["g"]]
     stage = Stage(tensors["W"], tensors["g"], tensors["m"], tensors.get("v"), what_dtype)
     try:
         if launch:
@@ -215,7 +228,7 @@ def run_and_compare_full(kind, hp, t, s, tensors, what_dtype, launch=None, decay
                    "v": stage.v[i].cpu().numpy() if stage.v is not None else None,
                    "What": what_bits(stage.What[i]) if what_dtype == "bf16" else stage.What[i].cpu().numpy()}
             # g is read-only
-            assert np.array_equal(stage.g[i].cpu().numpy().view(np.uint32), inp["g"].view(np.uint32)), "g was modified"
+            assert np.array_equal(raw_bits(stage.g[i]), g_before[i]), "g was modified"
             reports.append(compare(kind, hp, t, s, inp, ref, got, what_dtype, "%s tensor %d" % (label, i),
                                    decay_in_prediction))
         return reports

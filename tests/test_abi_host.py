@@ -162,6 +162,50 @@ def test_plan_create_validation_happens_before_any_device_call():
     assert L.pipeoptim_probe_copy(None, None, 0, None) == binding.PO_OK
 
 
+def test_overlapping_buffers_are_rejected_before_any_device_call():
+    L = binding.lib()
+    h = ctypes.c_void_p()
+    numel = (ctypes.c_int64 * 2)(1024, 256)
+
+    def arr(a, b):
+        return (ctypes.c_void_p * 2)(ctypes.c_void_p(a), ctypes.c_void_p(b))
+
+    base = 1 << 20
+    W, g, m, v, Wh = (arr(base + k * 65536, base + k * 65536 + 8192) for k in range(5))
+
+    def create(W=W, g=g, m=m, v=v, Wh=Wh, what=0):
+        return L.pipeoptim_plan_create(ctypes.byref(h), 2, numel, W, g, m, v, Wh, what, None)
+
+    # What on top of W (the in-place prediction a caller might try), partial overlaps, cross-tensor overlaps
+    assert create(Wh=W) == binding.PO_EINVAL and "overlap" in binding.pipeoptim_last_error()
+    assert create(Wh=arr(base + 4096 - 16, base + 4 * 65536 + 8192)) == binding.PO_EINVAL      # tail of W[0]
+    assert create(m=arr(base + 2 * 65536, base + 8192 + 512)) == binding.PO_EINVAL              # m[1] inside W[1]
+    assert create(g=arr(base + 3 * 65536 + 4092, base + 65536 + 8192)) == binding.PO_EINVAL     # g[0] into v[0]
+    assert create(v=arr(base + 3 * 65536, base + 3 * 65536 + 4092)) == binding.PO_EINVAL       # v[1] starts in the last element of v[0]
+    assert not h.value
+    # adjacent buffers are fine as far as validation goes: it then fails later, at the first device call (no GPU here)
+    # or succeeds (GPU box); either way not with "overlap"
+    rc = create(Wh=arr(base + 4096, base + 4 * 65536 + 8192), what=1)       # bf16 What right behind W[0]
+    assert "overlap" not in binding.pipeoptim_last_error() or rc == 0
+    if rc == 0:
+        L.pipeoptim_plan_destroy(h)
+
+
+def test_mixed_plan_validation():
+    L = binding.lib()
+    h = ctypes.c_void_p()
+    one = (ctypes.c_int64 * 1)(8)
+    p = (ctypes.c_void_p * 1)(ctypes.c_void_p(4096))
+    q = [(ctypes.c_void_p * 1)(ctypes.c_void_p(4096 + 1024 * k)) for k in range(5)]
+    odd = (ctypes.c_void_p * 1)(ctypes.c_void_p(4096 + 1024 + 1))
+    two = (ctypes.c_void_p * 1)(ctypes.c_void_p(4096 + 1024 + 2))
+    assert L.pipeoptim_plan_create_mixed(ctypes.byref(h), 1, one, q[0], q[1], 7, q[2], q[3], q[4], 0, None) == binding.PO_EINVAL
+    assert L.pipeoptim_plan_create_mixed(ctypes.byref(h), 1, one, q[0], odd, 1, q[2], q[3], q[4], 0, None) == binding.PO_EALIGN
+    assert L.pipeoptim_plan_create_mixed(ctypes.byref(h), 1, one, q[0], two, 0, q[2], q[3], q[4], 0, None) == binding.PO_EALIGN
+    assert L.pipeoptim_plan_create_mixed(ctypes.byref(h), 1, one, q[0], None, 1, q[2], q[3], q[4], 0, None) == binding.PO_EINVAL
+    assert not h.value
+
+
 def test_product_path_never_touches_the_oracle():
     """The GPU package must not import, call or link the oracle (and has no CPU fallback)."""
     pkg = os.path.join(ROOT, "paper_2312_00839_amd")

@@ -32,7 +32,7 @@ def _say(msg):
     print("[gpu-parity] " + msg, flush=True)
 
 
-def _rand_list(sizes, seed, kind, sw=0.02, sg=1e-3, sm=1e-4, sv=1e-3, offset=0):
+def _rand_list(sizes, seed, kind, sw=0.02, sg=1e-3, sm=1e-4, sv=1e-3, offset=0, grad_dtype=torch.float32):
     """Device tensors with the given sizes.  offset > 0 makes every tensor a view that starts
     `offset` elements into its allocation (4-byte but not 16-byte aligned for offset 1..3)."""
     gen = torch.Generator(device=DEV)
@@ -47,7 +47,8 @@ def _rand_list(sizes, seed, kind, sw=0.02, sg=1e-3, sm=1e-4, sv=1e-3, offset=0):
     out = {"W": [], "g": [], "m": [], "v": None if kind == "sgdm" else []}
     for n in sizes:
         out["W"].append(draw(n, sw))
-        out["g"].append(draw(n, sg))
+        gfull = draw(n + offset, sg).to(grad_dtype)     # a second offset keeps bf16 views off 16-byte alignment too
+        out["g"].append(gfull[offset:])
         out["m"].append(draw(n, sm))
         if out["v"] is not None:
             out["v"].append(draw(n, sv, True))
@@ -256,6 +257,46 @@ def test_set_pointers_swaps_gradient_buffers():
     st.close()
 
 
+# --------------------------------------------------------------------------- bf16 gradients
+@pytest.mark.parametrize("kind", ["sgdm", "adam", "adamw"])
+@pytest.mark.parametrize("what_dtype", ["f32", "bf16"])
+def test_bf16_gradients(kind, what_dtype):
+    _say("bf16 gradients %s %s" % (kind, what_dtype))
+    bf = torch.bfloat16
+    for s in (0, 2):
+        run_and_compare_full(kind, HP[kind], 5, s, _rand_list(list(range(0, 17)), 300 + s, kind, grad_dtype=bf),
+                             what_dtype, label="bf16-g tiny s=%d" % s)
+    for launch in LAUNCHES[::2]:
+        run_and_compare_full(kind, HP[kind], 100, 3, _rand_list(RAGGED, 9, kind, grad_dtype=bf), what_dtype,
+                             launch=launch, label="bf16-g ragged %s" % (launch,))
+    for offset in (1, 3):
+        run_and_compare_full(kind, HP[kind], 9, 2, _rand_list([5, 4096, 9001], 11, kind, offset=offset, grad_dtype=bf),
+                             what_dtype, label="bf16-g unaligned")
+
+
+def test_bf16_gradients_config3_full():
+    wl = workload(3)
+    _say("bf16 gradients, config 3 shapes, full compare")
+    tensors = make_inputs(wl, DEV)
+    tensors["g"] = [x.to(torch.bfloat16) for x in tensors["g"]]
+    run_and_compare_full(wl.optimizer, wl.hyper, wl.t, 2, tensors, wl.what_dtype, label="bf16-g config 3")
+
+
+def test_overlapping_buffers_rejected_on_device():
+    x = torch.zeros(4096, device=DEV)
+    a = x.data_ptr()
+    with pytest.raises(binding.PipeOptimError) as e:
+        binding.Plan([256], [a], [a + 4096], [a + 8192], None, [a + 512], "f32")       # What inside W
+    assert e.value.status == binding.PO_EINVAL and "overlap" in str(e.value)
+    p = binding.Plan([256], [a], [a + 4096], [a + 8192], None, [a + 12288], "f32")
+    with pytest.raises(binding.PipeOptimError) as e:
+        p.set_pointers(1, [a + 8192 + 1020])                                            # new g into m
+    assert e.value.status == binding.PO_EINVAL
+    p.step_predict(make_hyper("sgdm", HP["sgdm"]), 1, 1)                                # plan still usable
+    torch.cuda.synchronize()
+    p.destroy()
+
+
 # --------------------------------------------------------------------------- prediction from the cached state alone
 @pytest.mark.parametrize("kind", ["sgdm", "adam", "adamw"])
 @pytest.mark.parametrize("what_dtype", ["f32", "bf16"])
@@ -333,8 +374,9 @@ def test_predict_launch_errors():
         assert e.value.status == binding.PO_EINVAL, bad
     st.plan.set_predict_launch(chunk_elems=0, block=128, unroll=2)         # 0 = the plan's chunk size
     assert st.plan.get_predict_launch().chunk_elems == st.plan.get_launch().chunk_elems
-    with pytest.raises(binding.PipeOptimError):
-        st.plan.set_launch(chunk_elems=256)                                # no longer fits the prediction tile (1024)
+    st.plan.set_launch(chunk_elems=256)                                    # no longer fits the prediction tile (1024):
+    pl = st.plan.get_predict_launch()                                      # that kernel falls back to the fused shape
+    assert (pl.block, pl.unroll, pl.chunk_elems) == (64, 1, 256)
     sg = _rand_list([1000], 19, "sgdm")
     s2 = Stage(sg["W"], sg["g"], sg["m"], None, "f32")
     with pytest.raises(binding.PipeOptimError) as e:
