@@ -72,8 +72,22 @@ def cpu_baseline(wl, s, predict_only=False):
                                 beta2=wl.hyper["beta2"], eps=wl.hyper["eps"], weight_decay=wl.hyper["weight_decay"],
                                 t=wl.t, s=s, nthreads=threads)
     dt = time.perf_counter() - t0
+    # the same oracle on one thread, on the first tensor only (a few seconds)
+    a, n1 = arrays[0], arrays[0]["W"].size
+    t1 = time.perf_counter()
+    if predict_only:
+        oracle.predict(code, a["W"], a["m"], a.get("v"), lr=wl.hyper["lr"], beta1=wl.hyper["beta1"],
+                       beta2=wl.hyper["beta2"], eps=wl.hyper["eps"], weight_decay=wl.hyper["weight_decay"],
+                       t=wl.t, s=s, nthreads=1)
+    else:
+        oracle.step_predict(code, a["W"], a["g"], a["m"], a.get("v"), lr=wl.hyper["lr"], beta1=wl.hyper["beta1"],
+                            beta2=wl.hyper["beta2"], eps=wl.hyper["eps"], weight_decay=wl.hyper["weight_decay"],
+                            t=wl.t, s=s, nthreads=1)
+    dt1 = time.perf_counter() - t1
     return {"value": total / dt, "unit": "params/s", "cores": threads, "kind": "oracle",
-            "sample": "tensors %d..%d of the stage (%d params), one oracle pass, %.2f s wall" % (idx[0], idx[-1], total, dt)}
+            "sample": "tensors %d..%d of the stage (%d params), one oracle pass, %.2f s wall" % (idx[0], idx[-1], total, dt),
+            "single_thread_value": n1 / dt1,
+            "single_thread_sample": "tensor %d (%d params), one oracle pass on 1 thread, %.2f s" % (idx[0], n1, dt1)}
 
 
 def main():

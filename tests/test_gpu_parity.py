@@ -528,3 +528,39 @@ def test_config5_s0_prediction_is_rounded_W_everywhere():
     for i in range(len(expect)):
         assert torch.equal(stage.What[i].view(torch.int16), expect[i].view(torch.int16)), i
     stage.close()
+
+
+# --------------------------------------------------------------------------- HIP graph capture
+def test_step_predict_can_be_captured_and_replayed():
+    # the call enqueues exactly one kernel and nothing else (no memset, no allocation, no sync), so a caller
+    # may record it into a graph; every replay must equal an eager call from the same state
+    _say("graph capture")
+    kind, hp, t, s = "adamw", HP["adamw"], 12, 3
+    a = _rand_list([30000, 513], 41, kind)
+    b = _rand_list([30000, 513], 41, kind)
+    sa = Stage(a["W"], a["g"], a["m"], a["v"], "bf16")
+    sb = Stage(b["W"], b["g"], b["m"], b["v"], "bf16")
+    hyper = make_hyper(kind, hp)
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        sa.step_predict(hyper, t, s)                 # warm-up outside the capture (counts as replay 0)
+        torch.cuda.synchronize()
+        with torch.cuda.graph(graph, stream=side):
+            sa.step_predict(hyper, t, s)
+    torch.cuda.current_stream().wait_stream(side)
+    sb.step_predict(hyper, t, s)
+    for replay in range(4):
+        graph.replay()
+        sb.step_predict(hyper, t, s)
+        torch.cuda.synchronize()
+        x = torch.randn(1 << 20, device=DEV).sum().item()      # unrelated eager work between replays
+        assert np.isfinite(x)
+        for i in range(2):
+            for name in ("W", "m", "v", "What"):
+                u, w = getattr(sa, name)[i], getattr(sb, name)[i]
+                assert torch.equal(u.view(torch.int16) if u.dtype == torch.bfloat16 else u,
+                                   w.view(torch.int16) if w.dtype == torch.bfloat16 else w), (replay, i, name)
+    sa.close()
+    sb.close()
