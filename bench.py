@@ -39,6 +39,7 @@ def parse_args():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-copy-probe", action="store_true")
     ap.add_argument("--launch", default="", help="comma separated po_launch overrides, e.g. block=64,unroll=1,lds_bytes=16384")
+    ap.add_argument("--s", type=int, default=-1, help="version difference to run with (default: the config's last s)")
     ap.add_argument("--pipeline-depth", type=int, default=0, help="D of Eq. 4; default: s_max + 1 so that rank 0 gets the config's s")
     return ap.parse_args()
 
@@ -110,7 +111,7 @@ def main():
     torch.cuda.set_device(0)
 
     wl = workload(args.config)
-    s_cfg = wl.s_values[-1]
+    s_cfg = args.s if args.s >= 0 else wl.s_values[-1]
     D = args.pipeline_depth or (s_cfg + 1)
     rank = D - 1 - s_cfg
     tensors = make_inputs(wl, dev)

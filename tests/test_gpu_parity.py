@@ -530,6 +530,36 @@ def test_config5_s0_prediction_is_rounded_W_everywhere():
     stage.close()
 
 
+# --------------------------------------------------------------------------- maximum sizes
+def test_tensor_larger_than_4GiB_sampled():
+    # one tensor of 2^30 + 2^28 + 77 elements: byte offsets pass 2^32, element offsets pass 2^30; sampled
+    # compare around those boundaries, at the head and at the ragged tail
+    n = (1 << 30) + (1 << 28) + 77
+    _say("huge tensor, %d elements (%.1f GiB per fp32 buffer)" % (n, n * 4 / 2 ** 30))
+    kind, hp, t, s = "sgdm", HP["sgdm"], 3, 5
+    gen = torch.Generator(device=DEV)
+    gen.manual_seed(4242)
+    W = torch.randn(n, generator=gen, device=DEV) * 0.05
+    g = torch.randn(n, generator=gen, device=DEV) * 1e-2
+    m = torch.randn(n, generator=gen, device=DEV) * 1e-2
+    marks = [0, (1 << 29) - 300, (1 << 30) - 4000, (1 << 30) + (1 << 27) + 13, n - 9000]
+    idx = torch.cat([torch.arange(a, min(n, a + 9000), device=DEV) for a in marks])
+    inp = {k: x[idx].cpu().numpy() for k, x in (("W", W), ("g", g), ("m", m))}
+    st = Stage([W], [g], [m], None, "f32")
+    assert st.plan.info()["n_params"] == n
+    st.step_predict(make_hyper(kind, hp), t, s)
+    torch.cuda.synchronize()
+    ref = run_oracle(kind, hp, t, s, inp)
+    got = {"W": st.W[0][idx].cpu().numpy(), "m": st.m[0][idx].cpu().numpy(), "v": None,
+           "What": st.What[0][idx].cpu().numpy()}
+    compare(kind, hp, t, s, inp, ref, got, "f32", "huge tensor")
+    # whole-tensor property at this size: the s = 0 prediction is a bit-exact copy of every one of the n weights
+    st.predict(make_hyper(kind, hp), t, 0)
+    torch.cuda.synchronize()
+    assert torch.equal(st.What[0], st.W[0])
+    st.close()
+
+
 # --------------------------------------------------------------------------- HIP graph capture
 def test_step_predict_can_be_captured_and_replayed():
     # the call enqueues exactly one kernel and nothing else (no memset, no allocation, no sync), so a caller
