@@ -103,7 +103,10 @@ def main():
     from paper_2312_00839_amd.stage import Stage
     from paper_2312_00839_amd.workloads import make_inputs, workload
 
-    binding.lib()                                  # fail loudly if the HIP library is missing
+    if not os.path.exists(binding.LIB_PATH):       # load what is built; build only if nothing is
+        from paper_2312_00839_amd import build as hip_build
+        hip_build.build()
+    binding.lib()                                  # fails loudly if the HIP library cannot be loaded
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible", file=sys.stderr)
         sys.exit(1)

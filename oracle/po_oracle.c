@@ -18,7 +18,7 @@
  *   prediction from the cached state alone (no new gradient), as Algorithm 1
  *   sequences it ahead of the forward pass             -- po_oracle_predict
  *
- * Readings of the paper taken here (each is listed in the design document):
+ * Readings of the paper taken here, where it is silent or ambiguous:
  *   - dW_t is built from the *updated* state (m_t, v_t), i.e. from the new
  *     gradient g_t and the cached m_{t-1}, v_{t-1}       (Sec. III-A.3 prose).
  *   - The prediction starts from the same W_t the step starts from, so that
