@@ -10,6 +10,7 @@
 #include <cstdarg>
 #include <cstdio>
 #include <cstring>
+#include <memory>
 #include <new>
 #include <vector>
 
@@ -278,14 +279,16 @@ int pipeoptim_coefficients(const po_hyper* h, int64_t t, int32_t s, po_coeffs* o
 
 int pipeoptim_chunk_table_build(int64_t n_tensors, const int64_t* numel, int64_t chunk_elems, po_chunk* out,
                                 int64_t capacity, int64_t* n_chunks)
-{
+try {
     return build_chunks(n_tensors, numel, chunk_elems, out, capacity, n_chunks);
 }
+catch (const std::bad_alloc&) { return fail(PO_ENOMEM, "pipeoptim_chunk_table_build: out of host memory"); }
+catch (...) { return fail(PO_EINVAL, "pipeoptim_chunk_table_build: unexpected exception"); }
 
 int pipeoptim_plan_create_mixed(po_plan** out, int64_t n_tensors, const int64_t* numel, float* const* W,
                                 const void* const* g, int32_t grad_dtype, float* const* m, float* const* v,
                                 void* const* What, int32_t what_dtype, void* hip_stream)
-{
+try {
     (void)hip_stream;
     if (!out) return fail(PO_EINVAL, "out is NULL");
     *out = nullptr;
@@ -307,7 +310,9 @@ int pipeoptim_plan_create_mixed(po_plan** out, int64_t n_tensors, const int64_t*
         if ((uintptr_t)What[i] & what_mask) return fail(PO_EALIGN, "tensor %lld: What not aligned to its element", (long long)i);
         total += numel[i];
     }
-    po_plan* p = new (std::nothrow) po_plan;
+    // the holder frees the host side if anything below throws or fails before device memory exists
+    std::unique_ptr<po_plan> holder(new (std::nothrow) po_plan);
+    po_plan* p = holder.get();
     if (!p) return fail(PO_ENOMEM, "out of host memory");
     p->n_tensors = n_tensors;
     p->n_params = total;
@@ -322,24 +327,32 @@ int pipeoptim_plan_create_mixed(po_plan** out, int64_t n_tensors, const int64_t*
         d.numel = numel[i]; d.flags = 0; d.pad = 0;
     }
     int rc = check_disjoint(p);
-    if (rc != PO_OK) { delete p; return rc; }
+    if (rc != PO_OK) return rc;
     refresh_flags(p);
     p->launch = default_launch(total);
     p->predict_launch = default_predict_launch(p->launch, total);
 
     hipError_t e = hipGetDevice(&p->device);
-    if (e != hipSuccess) { delete p; return fail_hip(e, "hipGetDevice"); }
+    if (e != hipSuccess) return fail_hip(e, "hipGetDevice");
     if (n_tensors > 0) {
         e = hipMalloc(reinterpret_cast<void**>(&p->d_descs), (size_t)n_tensors * sizeof(po_tensor_desc));
-        if (e != hipSuccess) { delete p; return fail(PO_ENOMEM, "hipMalloc(descriptors): %s", hipGetErrorString(e)); }
+        if (e != hipSuccess) return fail(PO_ENOMEM, "hipMalloc(descriptors): %s", hipGetErrorString(e));
     }
     rc = upload_descs(p);
     if (rc == PO_OK) rc = upload_chunks(p);
     if (rc == PO_OK) rc = check_grid(p->launch, (int64_t)p->chunks.size());
-    if (rc != PO_OK) { pipeoptim_plan_destroy(p); return rc; }
-    *out = p;
+    if (rc != PO_OK) {
+        char keep[sizeof g_err];
+        std::memcpy(keep, g_err, sizeof keep);       // destroy may overwrite the message of the real failure
+        pipeoptim_plan_destroy(holder.release());
+        std::memcpy(g_err, keep, sizeof keep);
+        return rc;
+    }
+    *out = holder.release();
     return PO_OK;
 }
+catch (const std::bad_alloc&) { return fail(PO_ENOMEM, "pipeoptim_plan_create_mixed: out of host memory"); }
+catch (...) { return fail(PO_EINVAL, "pipeoptim_plan_create_mixed: unexpected exception"); }
 
 int pipeoptim_plan_create(po_plan** out, int64_t n_tensors, const int64_t* numel, float* const* W,
                           const float* const* g, float* const* m, float* const* v, void* const* What,
@@ -364,7 +377,7 @@ int pipeoptim_plan_destroy(po_plan* p)
 }
 
 int pipeoptim_plan_set_pointers(po_plan* p, int32_t which, void* const* ptrs)
-{
+try {
     if (!p) return fail(PO_EINVAL, "plan is NULL");
     if (which < 0 || which > 4) return fail(PO_EINVAL, "which must be 0..4");
     if (which == 3 && !p->has_v) return fail(PO_EINVAL, "plan has no v column");
@@ -393,6 +406,8 @@ int pipeoptim_plan_set_pointers(po_plan* p, int32_t which, void* const* ptrs)
     if (e != hipSuccess) return fail_hip(e, "hipDeviceSynchronize");
     return upload_descs(p);
 }
+catch (const std::bad_alloc&) { return fail(PO_ENOMEM, "pipeoptim_plan_set_pointers: out of host memory"); }
+catch (...) { return fail(PO_EINVAL, "pipeoptim_plan_set_pointers: unexpected exception"); }
 
 int pipeoptim_plan_get_launch(const po_plan* p, po_launch* out)
 {
@@ -402,7 +417,7 @@ int pipeoptim_plan_get_launch(const po_plan* p, po_launch* out)
 }
 
 int pipeoptim_plan_set_launch(po_plan* p, const po_launch* L)
-{
+try {
     if (!p || !L) return fail(PO_EINVAL, "plan or launch is NULL");
     int rc = check_launch(*L);
     if (rc != PO_OK) return rc;
@@ -430,6 +445,8 @@ int pipeoptim_plan_set_launch(po_plan* p, const po_launch* L)
     }
     return PO_OK;
 }
+catch (const std::bad_alloc&) { return fail(PO_ENOMEM, "pipeoptim_plan_set_launch: out of host memory"); }
+catch (...) { return fail(PO_EINVAL, "pipeoptim_plan_set_launch: unexpected exception"); }
 
 int pipeoptim_plan_get_predict_launch(const po_plan* p, po_launch* out)
 {
