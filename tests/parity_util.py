@@ -10,7 +10,10 @@ magnitude (the standard running-error bound; about 8 roundings of 2^-24 = 6e-8 f
     g~_abs  = |g| + wd_c*|W|
     m'      : m_abs  = b1*|m| + (1-b1)*g~_abs                  (SGDM: u, 1 - tau)
     v'      : v_abs  = b2*v + (1-b2)*g~_abs^2
-    dW_abs  : SGDM m_abs;  Adam m_abs/(1-b1^t)/(sqrt(v'_ref/(1-b2^t)) + eps);  AdamW that + wd*|W|
+    dW_abs  : SGDM m_abs;  Adam (m_abs + |m'_ref|*(v_abs/v'_ref - 1)/2)/(1-b1^t)/(sqrt(v'_ref/(1-b2^t)) + eps);
+              AdamW that + wd*|W|.  The second term is the denominator's share: an error dv' in v' moves
+              1/(sqrt(v')+eps) by at most dv'/(2 v'), and dv' is proportional to v_abs; it vanishes unless
+              g + wd_c*W cancels (then v_abs > v'), which only Adam with coupled decay can do.
     W'      : |W| + lr*dW_abs
     What    : |W| + s*lr*dW_abs   (AdamW without decay in the prediction: dW_abs without wd*|W|)
 For almost every element scale equals |result| to within a small factor; it differs only
@@ -71,7 +74,10 @@ def scales(kind, hp, t, s, inp, ref, decay_in_prediction=True):
         out["v"] = hp["beta2"] * v + (1.0 - hp["beta2"]) * g_abs * g_abs
         bc1 = 1.0 - hp["beta1"] ** t
         bc2 = 1.0 - hp["beta2"] ** t
-        r_abs = m_abs / bc1 / (np.sqrt(ref["v"].astype(np.float64) / bc2) + hp["eps"])
+        v_ref = ref["v"].astype(np.float64)
+        amp = out["v"] / np.maximum(v_ref, 1e-300)                      # 1 unless g + wd_c*W cancelled
+        m_ref = np.abs(ref["m"].astype(np.float64))
+        r_abs = (m_abs + 0.5 * m_ref * np.maximum(amp - 1.0, 0.0)) / bc1 / (np.sqrt(v_ref / bc2) + hp["eps"])
         d_step = r_abs + (wd * W if kind == "adamw" else 0.0)
         d_pred = d_step if (kind != "adamw" or decay_in_prediction) else r_abs
     out["W"] = W + hp["lr"] * d_step

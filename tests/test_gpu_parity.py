@@ -594,3 +594,37 @@ def test_step_predict_can_be_captured_and_replayed():
                                    w.view(torch.int16) if w.dtype == torch.bfloat16 else w), (replay, i, name)
     sa.close()
     sb.close()
+
+
+# --------------------------------------------------------------------------- seeded random cases
+@pytest.mark.parametrize("case", range(48))
+def test_random_cases(case):
+    """Seeded random hyper-parameters, sizes, dtypes and launch shapes; fused and prediction-only calls."""
+    rng = np.random.default_rng(7000 + case)
+    kind = ("sgdm", "adam", "adamw")[case % 3]
+    what_dtype = ("f32", "bf16")[(case // 3) % 2]
+    grad_dtype = (torch.float32, torch.bfloat16)[(case // 6) % 2]
+    lr = float(10 ** rng.uniform(-5, -0.5))
+    wd = float(rng.choice([0.0, 10 ** rng.uniform(-5, -0.5)]))
+    if kind == "sgdm":
+        hp = dict(lr=lr, beta1=float(rng.uniform(0, 0.99)), beta2=float(rng.choice([0.0, rng.uniform(0, 0.9)])),
+                  eps=0.0, weight_decay=wd)
+    else:
+        hp = dict(lr=lr, beta1=float(rng.uniform(0, 0.99)), beta2=float(rng.uniform(0.5, 0.9999)),
+                  eps=float(10 ** rng.uniform(-10, -3)), weight_decay=wd)
+    t = int(rng.choice([1, 2, 3, 10, 1000, 10 ** 5]))
+    s = int(rng.choice([0, 1, 2, 3, 7, 40]))
+    dip = bool(rng.integers(0, 2))
+    sizes = [int(x) for x in rng.integers(0, 40000, size=int(rng.integers(1, 7)))] + [int(rng.integers(1, 9))]
+    block = int(rng.choice([64, 128, 256]))
+    unroll = int(rng.choice([1, 2, 4]))
+    launch = dict(block=block, unroll=unroll, chunk_elems=block * 4 * unroll * int(2 ** rng.integers(0, 6)),
+                  cache_policy=int(rng.integers(0, 5)), lds_bytes=int(rng.choice([0, 4096, 16384, 40000])),
+                  xcd_remap=int(rng.integers(0, 2)))
+    sig = dict(sw=float(10 ** rng.uniform(-3, 0)), sg=float(10 ** rng.uniform(-6, -1)),
+               sm=float(10 ** rng.uniform(-6, -1)), sv=float(10 ** rng.uniform(-6, -1)))
+    _say("random case %d: %s %s g=%s t=%d s=%d dip=%d sizes=%s launch=%s" % (case, kind, what_dtype, grad_dtype, t, s, dip, sizes, launch))
+    run_and_compare_full(kind, hp, t, s, _rand_list(sizes, 500 + case, kind, grad_dtype=grad_dtype, **sig), what_dtype,
+                         launch=launch, decay_in_prediction=dip, label="random %d" % case)
+    run_and_compare_predict(kind, hp, t, s, _rand_list(sizes, 600 + case, kind, **sig), what_dtype,
+                            launch=launch, decay_in_prediction=dip, label="random predict %d" % case)

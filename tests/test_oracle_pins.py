@@ -528,3 +528,35 @@ def test_operands_are_not_interchangeable(oracle):
     for perm in [(g, W, m, v), (W, m, g, v), (W, g, v, m), (m, g, W, v)]:
         other = oracle.step_predict(2, *perm, t=7, s=5, **hp)
         assert np.any(other["W"] != base["W"])
+
+
+# --------------------------------------------------------------------------- seeded random hyper-parameters
+@pytest.mark.parametrize("case", range(24))
+def test_random_hyperparameters_step_vs_library_and_prediction_law(oracle, case):
+    rng = np.random.default_rng(9000 + case)
+    kind = ("sgdm", "adam", "adamw")[case % 3]
+    lr = float(10 ** rng.uniform(-5, -0.5))
+    wd = float(rng.choice([0.0, 10 ** rng.uniform(-5, -0.5)]))
+    if kind == "sgdm":
+        hp = dict(lr=lr, beta1=float(rng.uniform(0, 0.99)), beta2=float(rng.choice([0.0, rng.uniform(0, 0.9)])),
+                  eps=0.0, weight_decay=wd)
+    else:
+        hp = dict(lr=lr, beta1=float(rng.uniform(0, 0.99)), beta2=float(rng.uniform(0.5, 0.9999)),
+                  eps=float(10 ** rng.uniform(-10, -3)), weight_decay=wd)
+    t = int(rng.choice([1, 2, 3, 10, 1000, 10 ** 5]))
+    s = int(rng.integers(2, 40))
+    W, g, m, v = _rand_state(513, seed=case, sw=float(10 ** rng.uniform(-3, 0)), sg=float(10 ** rng.uniform(-6, -1)),
+                             sm=float(10 ** rng.uniform(-6, -1)), sv=float(10 ** rng.uniform(-6, -1)))
+    vv = None if kind == "sgdm" else v
+    r1 = oracle.step_predict(OPT[kind], W, g, m, vv, t=t, s=1, **hp)
+    Wt, mt, vt = _torch_one_step(kind, W, g, m, v, t, **hp)
+    assert np.all(np.abs(r1["W"].astype(np.float64) - Wt) <= _ulp32(Wt))
+    assert np.all(np.abs(r1["m"].astype(np.float64) - mt) <= _ulp32(mt))
+    if vt is not None:
+        assert np.all(np.abs(r1["v"].astype(np.float64) - vt) <= _ulp32(vt))
+    np.testing.assert_array_equal(r1["What"], r1["W"])                       # s = 1 is the optimizer's own step
+    rs = oracle.step_predict(OPT[kind], W, g, m, vv, t=t, s=s, **hp)
+    W64 = W.astype(np.float64)
+    want = W64 + s * (Wt - W64)                                              # affine in s through (0, W) and (1, W')
+    tol = _ulp32(want) + s * _ulp32(Wt) + s * 1e-15 * np.abs(W64)
+    assert np.all(np.abs(rs["What"].astype(np.float64) - want) <= tol)
