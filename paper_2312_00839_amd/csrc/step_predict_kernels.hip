@@ -121,33 +121,63 @@ __device__ __forceinline__ float predict_element(const po_coeffs& c, float W, fl
     return c.s_is_zero ? W : fmaf(-c.s_lr, r, W);
 }
 
+// Everything a kernel needs besides the tables, as ONE by-value kernel argument of 96 bytes.  Each
+// workgroup lives for one tile only, so the scalar loads in front of its first vector load are a
+// measurable part of its life: the kernel fetches this block with two wide scalar loads at its very top
+// instead of letting the compiler fetch the fields one wait at a time.
+struct alignas(32) KArgs {
+    const po_tensor_desc* descs;
+    const po_chunk* chunks;
+    int64_t chunk_elems;
+    uint32_t n_slots;        // chunks * tiles per chunk
+    uint32_t tiles_log2;     // log2(tiles per chunk)
+    uint32_t xcd_stride;     // 0: slot = workgroup id; else grid/8: slot = (id & 7) * xcd_stride + (id >> 3)
+    uint32_t tile;           // block * 4 * unroll
+    po_coeffs c;             // 52 bytes
+    uint32_t pad;
+};
+static_assert(sizeof(KArgs) == 96, "KArgs is loaded as 64 + 32 bytes");
+
+typedef uint32_t u32x8 __attribute__((ext_vector_type(8)));
+typedef uint32_t u32x16 __attribute__((ext_vector_type(16)));
+#define PO_CONSTANT __attribute__((address_space(4)))
+
+__device__ __forceinline__ KArgs load_kargs()
+{
+    const PO_CONSTANT char* base = (const PO_CONSTANT char*)__builtin_amdgcn_kernarg_segment_ptr();
+    union { struct { u32x16 a; u32x8 b; } raw; KArgs k; } u;
+    u.raw.a = *(const PO_CONSTANT u32x16*)base;
+    u.raw.b = *(const PO_CONSTANT u32x8*)(base + 64);
+    return u.k;
+}
+
 // Which tile does this workgroup own?  slot = chunk_index * tiles_per_chunk + tile_in_chunk.  With
 // xcd_remap the grid (a multiple of 8) is cut into 8 equal ranges and workgroup id b (XCDs take
 // workgroups round-robin) works in range b mod 8.  Returns false for padding slots and for tiles that
-// start past the end of the tensor's last chunk.
+// start past the end of the tensor's last chunk.  The 64-byte descriptor comes in one scalar load.
 struct Tile {
-    const po_tensor_desc* d;
+    po_tensor_desc d;
     int64_t off;        // first element of the tile within the tensor
     uint32_t len;       // elements of the tile that exist (== tile size except at the tensor's end)
     bool full;          // len == tile size and all base pointers are 16-byte aligned
 };
 
-template <int UNROLL>
-__device__ __forceinline__ bool locate_tile(const po_tensor_desc* __restrict__ descs,
-                                            const po_chunk* __restrict__ chunks, uint32_t n_slots,
-                                            uint32_t tiles_log2, int64_t chunk_elems, int xcd_remap, Tile& t)
+__device__ __forceinline__ bool locate_tile(const KArgs& a, Tile& t)
 {
     uint32_t slot = blockIdx.x;
-    if (xcd_remap) slot = (blockIdx.x & 7u) * (gridDim.x >> 3) + (blockIdx.x >> 3);
-    if (slot >= n_slots) return false;
-    const po_chunk ch = chunks[slot >> tiles_log2];
-    t.d = descs + ch.tensor;
-    const uint32_t tile = blockDim.x * 4u * UNROLL;
-    t.off = (int64_t)ch.chunk * chunk_elems + (int64_t)(slot & ((1u << tiles_log2) - 1u)) * tile;
-    const int64_t numel = t.d->numel;
-    if (t.off >= numel) return false;
-    t.len = (numel - t.off < (int64_t)tile) ? (uint32_t)(numel - t.off) : tile;
-    t.full = t.len == tile && (t.d->flags & PO_DESC_VECTOR_OK);
+    if (a.xcd_stride) slot = (blockIdx.x & 7u) * a.xcd_stride + (blockIdx.x >> 3);
+    if (slot >= a.n_slots) return false;
+    // the tables are not written while a kernel runs: read them through the constant address space so that
+    // the (workgroup-uniform) loads go down the scalar path and their results stay in SGPRs
+    const u32x2 entry = *(const PO_CONSTANT u32x2*)(uintptr_t)(a.chunks + (slot >> a.tiles_log2));
+    const po_chunk ch{entry[0], entry[1]};
+    union { u32x16 raw; po_tensor_desc d; } u;
+    u.raw = *(const PO_CONSTANT u32x16*)(uintptr_t)(a.descs + ch.tensor);
+    t.d = u.d;
+    t.off = (int64_t)ch.chunk * a.chunk_elems + (int64_t)(slot & ((1u << a.tiles_log2) - 1u)) * a.tile;
+    if (t.off >= t.d.numel) return false;
+    t.len = (t.d.numel - t.off < (int64_t)a.tile) ? (uint32_t)(t.d.numel - t.off) : a.tile;
+    t.full = t.len == a.tile && (t.d.flags & PO_DESC_VECTOR_OK);
     return true;
 }
 
@@ -157,17 +187,16 @@ __device__ __forceinline__ float bf16_hi(uint32_t pair) { return as_f(pair & 0xF
 
 // GB16: gradients are bf16 (8 bytes per lane per group instead of 16).
 template <int OPT, bool BF16, bool GB16, int UNROLL, int POL>
-__global__ __launch_bounds__(256) void step_predict_kernel(const po_tensor_desc* __restrict__ descs,
-                                                           const po_chunk* __restrict__ chunks,
-                                                           uint32_t n_slots, uint32_t tiles_log2,
-                                                           int64_t chunk_elems, int xcd_remap, po_coeffs c)
+__global__ __launch_bounds__(256) void step_predict_kernel(KArgs)
 {
     constexpr int LG = Policy<POL>::LG, LS = Policy<POL>::LS, SS = Policy<POL>::SS, SH = Policy<POL>::SH;
     constexpr bool ADAM = OPT != PO_SGDM;
 
+    const KArgs a = load_kargs();
+    const po_coeffs& c = a.c;
     Tile t;
-    if (!locate_tile<UNROLL>(descs, chunks, n_slots, tiles_log2, chunk_elems, xcd_remap, t)) return;
-    const po_tensor_desc* d = t.d;
+    if (!locate_tile(a, t)) return;
+    const po_tensor_desc* d = &t.d;
     const int64_t off = t.off;
     const uint32_t len = t.len;
 
@@ -178,14 +207,14 @@ __global__ __launch_bounds__(256) void step_predict_kernel(const po_tensor_desc*
     const __amdgpu_buffer_rsrc_t rv = make_rsrc(ADAM ? d->v + off : d->m + off, len * 4u);
     const __amdgpu_buffer_rsrc_t rh = BF16 ? make_rsrc(static_cast<uint16_t*>(d->What) + off, len * 2u)
                                            : make_rsrc(static_cast<float*>(d->What) + off, len * 4u);
-    const uint32_t tid = threadIdx.x;
+    const uint32_t tid = threadIdx.x, nthr = a.tile / (4u * UNROLL);
 
     if (t.full) {
         // full tile, aligned: every lane moves UNROLL groups of 4 consecutive elements per stream
         u32x4 W[UNROLL], g[UNROLL], m[UNROLL], v[UNROLL];
 #pragma unroll
         for (int u = 0; u < UNROLL; ++u) {
-            const uint32_t b = (u * blockDim.x + tid) * 16u;
+            const uint32_t b = (u * nthr + tid) * 16u;
             W[u] = __builtin_amdgcn_raw_buffer_load_b128(rW, b, 0, LS);
             if constexpr (GB16) {
                 const u32x2 p = __builtin_amdgcn_raw_buffer_load_b64(rg, b >> 1, 0, LG);
@@ -198,7 +227,7 @@ __global__ __launch_bounds__(256) void step_predict_kernel(const po_tensor_desc*
         }
 #pragma unroll
         for (int u = 0; u < UNROLL; ++u) {
-            const uint32_t b = (u * blockDim.x + tid) * 16u;
+            const uint32_t b = (u * nthr + tid) * 16u;
             u32x4 Wn, Wh;
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
@@ -221,7 +250,7 @@ __global__ __launch_bounds__(256) void step_predict_kernel(const po_tensor_desc*
         }
     } else {
         // ragged last tile of a tensor, or a tensor without 16-byte alignment: one element per lane per step
-        for (uint32_t i = tid; i < len; i += blockDim.x) {
+        for (uint32_t i = tid; i < len; i += nthr) {
             const uint32_t b = i * 4u;
             float W = as_f(__builtin_amdgcn_raw_buffer_load_b32(rW, b, 0, LS));
             float g = GB16 ? as_f((uint32_t)__builtin_amdgcn_raw_buffer_load_b16(rg, i * 2u, 0, LG) << 16)
@@ -241,17 +270,16 @@ __global__ __launch_bounds__(256) void step_predict_kernel(const po_tensor_desc*
 
 // What = W - s_lr*dW from the cached m, v: reads W, m (, v) once, writes What.  Same decomposition as above.
 template <int OPT, bool BF16, int UNROLL, int POL>
-__global__ __launch_bounds__(256) void predict_kernel(const po_tensor_desc* __restrict__ descs,
-                                                      const po_chunk* __restrict__ chunks, uint32_t n_slots,
-                                                      uint32_t tiles_log2, int64_t chunk_elems, int xcd_remap,
-                                                      po_coeffs c)
+__global__ __launch_bounds__(256) void predict_kernel(KArgs)
 {
     constexpr int LD = Policy<POL>::LG, SH = Policy<POL>::SH;      // every input is read once here
     constexpr bool ADAM = OPT != PO_SGDM;
 
+    const KArgs a = load_kargs();
+    const po_coeffs& c = a.c;
     Tile t;
-    if (!locate_tile<UNROLL>(descs, chunks, n_slots, tiles_log2, chunk_elems, xcd_remap, t)) return;
-    const po_tensor_desc* d = t.d;
+    if (!locate_tile(a, t)) return;
+    const po_tensor_desc* d = &t.d;
     const int64_t off = t.off;
     const uint32_t len = t.len;
     const __amdgpu_buffer_rsrc_t rW = make_rsrc(d->W + off, len * 4u);
@@ -259,20 +287,20 @@ __global__ __launch_bounds__(256) void predict_kernel(const po_tensor_desc* __re
     const __amdgpu_buffer_rsrc_t rv = make_rsrc(ADAM ? d->v + off : d->m + off, len * 4u);
     const __amdgpu_buffer_rsrc_t rh = BF16 ? make_rsrc(static_cast<uint16_t*>(d->What) + off, len * 2u)
                                            : make_rsrc(static_cast<float*>(d->What) + off, len * 4u);
-    const uint32_t tid = threadIdx.x;
+    const uint32_t tid = threadIdx.x, nthr = a.tile / (4u * UNROLL);
 
     if (t.full) {
         u32x4 W[UNROLL], m[UNROLL], v[UNROLL];
 #pragma unroll
         for (int u = 0; u < UNROLL; ++u) {
-            const uint32_t b = (u * blockDim.x + tid) * 16u;
+            const uint32_t b = (u * nthr + tid) * 16u;
             W[u] = __builtin_amdgcn_raw_buffer_load_b128(rW, b, 0, LD);
             m[u] = __builtin_amdgcn_raw_buffer_load_b128(rm, b, 0, LD);
             if constexpr (ADAM) v[u] = __builtin_amdgcn_raw_buffer_load_b128(rv, b, 0, LD);
         }
 #pragma unroll
         for (int u = 0; u < UNROLL; ++u) {
-            const uint32_t b = (u * blockDim.x + tid) * 16u;
+            const uint32_t b = (u * nthr + tid) * 16u;
             float wh[4];
 #pragma unroll
             for (int e = 0; e < 4; ++e)
@@ -286,7 +314,7 @@ __global__ __launch_bounds__(256) void predict_kernel(const po_tensor_desc* __re
             }
         }
     } else {
-        for (uint32_t i = tid; i < len; i += blockDim.x) {
+        for (uint32_t i = tid; i < len; i += nthr) {
             const uint32_t b = i * 4u;
             float W = as_f(__builtin_amdgcn_raw_buffer_load_b32(rW, b, 0, LD));
             float mm = as_f(__builtin_amdgcn_raw_buffer_load_b32(rm, b, 0, LD));
@@ -309,10 +337,18 @@ hipError_t launch_one(const po_launch& L, const po_tensor_desc* descs, const po_
     const uint64_t n_slots = (uint64_t)n_chunks << tiles_log2;
     const uint64_t grid = L.xcd_remap ? ((n_slots + 7u) / 8u) * 8u : n_slots;
     if (grid > 0x7FFFFFFFull) return hipErrorInvalidConfiguration;
+    KArgs a{};
+    a.descs = descs;
+    a.chunks = chunks;
+    a.chunk_elems = L.chunk_elems;
+    a.n_slots = (uint32_t)n_slots;
+    a.tiles_log2 = tiles_log2;
+    a.xcd_stride = L.xcd_remap ? (uint32_t)(grid >> 3) : 0u;
+    a.tile = tile;
+    a.c = c;
     auto kernel = KIND == PO_KERNEL_PREDICT ? predict_kernel<OPT, BF16, UNROLL, POL>
                                             : step_predict_kernel<OPT, BF16, GB16, UNROLL, POL>;
-    hipLaunchKernelGGL(kernel, dim3((uint32_t)grid), dim3(L.block), (size_t)L.lds_bytes, stream, descs, chunks,
-                       (uint32_t)n_slots, tiles_log2, L.chunk_elems, L.xcd_remap, c);
+    hipLaunchKernelGGL(kernel, dim3((uint32_t)grid), dim3(L.block), (size_t)L.lds_bytes, stream, a);
     return hipGetLastError();
 }
 
