@@ -482,6 +482,7 @@ def _sampled_config(cfg, s, blocks_per_tensor=6, block=8192, seed=0):
         ranges.append(r)
         idx = torch.cat([torch.arange(a, b, device=DEV) for a, b in r])
         saved.append((idx, {k: tensors[k][i][idx].cpu().numpy() for k in ("W", "g", "m", "v") if tensors.get(k) is not None}))
+    W_in = [w.clone() for w in tensors["W"]]
     stage = Stage(tensors["W"], tensors["g"], tensors["m"], tensors.get("v"), wl.what_dtype)
     stage.step_predict(make_hyper(wl.optimizer, wl.hyper), wl.t, s)
     torch.cuda.synchronize()
@@ -494,11 +495,16 @@ def _sampled_config(cfg, s, blocks_per_tensor=6, block=8192, seed=0):
         rep = compare(wl.optimizer, wl.hyper, wl.t, s, inp, ref, got, wl.what_dtype, "config %d tensor %d" % (cfg, i))
         for k, val in rep.items():
             worst[k] = max(worst.get(k, 0), val)
-    # properties that hold at any size, over ALL elements: g untouched is implied by read-only access;
-    # W moved by at most lr*|dW| with |dW| bounded for Adam-family (|r| <= 1/(1-b1) * sqrt(bc2)/bc1 ...): just finiteness
+    # A property that holds at any size, checked over ALL elements on the device: Eq. 1 and Eq. 5 share the
+    # same dW_t, so the three weight-sized results lie on one line: What = W_in + s*(W' - W_in).
     for i in range(len(stage.W)):
-        assert torch.isfinite(stage.W[i]).all() and torch.isfinite(stage.m[i]).all()
-        assert torch.isfinite(stage.What[i].float()).all()
+        Win, Wnew, What = W_in[i], stage.W[i], stage.What[i].float()
+        assert torch.isfinite(Wnew).all() and torch.isfinite(stage.m[i]).all() and torch.isfinite(What).all()
+        line = torch.addcmul(Win, Wnew - Win, torch.tensor(float(s), device=DEV))
+        unit = 2.0 ** -8 if wl.what_dtype == "bf16" else 2.0 ** -22          # one unit of the stored format
+        tol = unit * line.abs() + (s + 1) * 2.0 ** -21 * (Win.abs() + Wnew.abs()) + 1e-30
+        bad = ((What - line).abs() > tol).sum().item()
+        assert bad == 0, "config %d tensor %d: %d elements off the line through W_in and W'" % (cfg, i, bad)
     stage.close()
     _say("config %d s=%d worst: %s" % (cfg, s, worst))
 
