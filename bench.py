@@ -23,7 +23,10 @@ HBM_PEAK_GBPS = 8000.0            # MI355X published HBM3E bandwidth
 
 # HBM traffic per launch measured with rocprofv3 --pmc (FETCH_SIZE, WRITE_SIZE), scaled by the
 # same counters on the plain copy kernel; see the summary under profiles/.  bytes per launch.
-MEASURED_TRAFFIC = {5: 22147919901}      # config 5: 11.813 GB fetched + 10.335 GB written (algorithmic 22.147 GB)
+MEASURED_TRAFFIC = {
+    ("fused", 5): 22148248802,      # 11.813 GB fetched + 10.335 GB written (algorithmic 22.147 GB)
+    ("predict", 5): 10336678221,    #  8.860 GB fetched +  1.476 GB written (algorithmic 10.335 GB)
+}
 
 
 def parse_args():
@@ -178,7 +181,7 @@ def main():
         "pct_of_hbm_peak": 100.0 * achieved / HBM_PEAK_GBPS,
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBPS,
-                     "traffic": MEASURED_TRAFFIC.get(wl.config) if (not predict_only and args.grad_dtype == "f32") else None},
+                     "traffic": MEASURED_TRAFFIC.get((args.mode, wl.config)) if args.grad_dtype == "f32" else None},
     }
 
     if not args.no_copy_probe:
