@@ -1,0 +1,76 @@
+// Host-only exercise of libpipeoptim's entry points that never touch the device, built with
+// AddressSanitizer + UndefinedBehaviorSanitizer on the host side and run by tests/test_host_sanitizers.py.
+// It checks return codes only; the value checks live in the Python tests.
+#include <cstdint>
+#include <cstdio>
+#include <cstdlib>
+#include <cstring>
+#include <vector>
+
+#include "pipeoptim.h"
+
+#define EXPECT(cond) do { if (!(cond)) { std::printf("FAILED line %d: %s (last error: %s)\n", __LINE__, #cond, pipeoptim_last_error()); return 1; } } while (0)
+
+int main()
+{
+    // Eq. 4
+    int32_t s = -1;
+    EXPECT(pipeoptim_version_difference(4, 0, &s) == PO_OK && s == 3);
+    EXPECT(pipeoptim_version_difference(4, 4, &s) == PO_EINVAL);
+    EXPECT(pipeoptim_version_difference(4, 0, nullptr) == PO_EINVAL);
+
+    // coefficients
+    po_hyper h{};
+    h.opt = PO_ADAMW; h.decay_in_prediction = 1; h.lr = 1e-3; h.beta1 = 0.9; h.beta2 = 0.999; h.eps = 1e-8; h.weight_decay = 0.01;
+    po_coeffs c{};
+    EXPECT(pipeoptim_coefficients(&h, 1, 0, &c) == PO_OK && c.s_is_zero == 1);
+    EXPECT(pipeoptim_coefficients(&h, INT64_MAX, INT32_MAX, &c) == PO_OK);
+    EXPECT(pipeoptim_coefficients(&h, 0, 0, &c) == PO_EINVAL);
+    EXPECT(pipeoptim_coefficients(nullptr, 1, 0, &c) == PO_EINVAL);
+    EXPECT(std::strlen(pipeoptim_last_error()) > 0);
+
+    // chunk table: exact-size buffers, count-only calls, a list with huge and empty tensors
+    std::vector<int64_t> numel = {0, 1, 255, 256, 257, 65535, 65536, 65537, 0, 131072000, (int64_t(1) << 32) + 5};
+    for (int64_t chunk : {int64_t(256), int64_t(4096), int64_t(65536), int64_t(1) << 30}) {
+        int64_t n = -1;
+        EXPECT(pipeoptim_chunk_table_build((int64_t)numel.size(), numel.data(), chunk, nullptr, 0, &n) == PO_OK && n > 0);
+        std::vector<po_chunk> table((size_t)n);
+        int64_t n2 = -1;
+        EXPECT(pipeoptim_chunk_table_build((int64_t)numel.size(), numel.data(), chunk, table.data(), n, &n2) == PO_OK && n2 == n);
+        std::vector<int64_t> covered(numel.size(), 0);
+        for (const po_chunk& e : table) {
+            EXPECT(e.tensor < numel.size());
+            EXPECT(covered[e.tensor] == (int64_t)e.chunk * chunk);
+            const int64_t end = (int64_t)(e.chunk + 1) * chunk;
+            covered[e.tensor] = end < numel[e.tensor] ? end : numel[e.tensor];
+        }
+        for (size_t i = 0; i < numel.size(); ++i) EXPECT(covered[i] == numel[i]);
+        if (n > 3) {   // a buffer that is too small is filled up to its capacity and no further
+            std::vector<po_chunk> small(3);
+            EXPECT(pipeoptim_chunk_table_build((int64_t)numel.size(), numel.data(), chunk, small.data(), 3, &n2) == PO_OK && n2 == n);
+        }
+    }
+
+    // plan creation: every validation failure happens before the first device call
+    po_plan* plan = nullptr;
+    int64_t one[1] = {1024};
+    float* W[1] = {reinterpret_cast<float*>(uintptr_t(1) << 20)};
+    float* m[1] = {reinterpret_cast<float*>((uintptr_t(1) << 20) + 65536)};
+    float* v[1] = {reinterpret_cast<float*>((uintptr_t(1) << 20) + 2 * 65536)};
+    const float* g[1] = {reinterpret_cast<const float*>((uintptr_t(1) << 20) + 3 * 65536)};
+    void* Wh[1] = {reinterpret_cast<void*>((uintptr_t(1) << 20) + 4 * 65536)};
+    void* overlapping[1] = {reinterpret_cast<void*>((uintptr_t(1) << 20) + 4092)};
+    void* odd[1] = {reinterpret_cast<void*>((uintptr_t(1) << 20) + 4 * 65536 + 1)};
+    EXPECT(pipeoptim_plan_create(&plan, 1, one, W, g, m, v, overlapping, PO_WHAT_F32, nullptr) == PO_EINVAL && !plan);
+    EXPECT(pipeoptim_plan_create(&plan, 1, one, W, g, m, v, odd, PO_WHAT_BF16, nullptr) == PO_EALIGN && !plan);
+    EXPECT(pipeoptim_plan_create(&plan, 1, one, W, g, m, v, Wh, 9, nullptr) == PO_EINVAL && !plan);
+    EXPECT(pipeoptim_plan_create(nullptr, 1, one, W, g, m, v, Wh, PO_WHAT_F32, nullptr) == PO_EINVAL);
+    EXPECT(pipeoptim_plan_create_mixed(&plan, 1, one, W, reinterpret_cast<const void* const*>(g), 5, m, v, Wh, PO_WHAT_F32, nullptr) == PO_EINVAL);
+    EXPECT(pipeoptim_plan_destroy(nullptr) == PO_OK);
+    EXPECT(pipeoptim_step_predict(nullptr, &h, 1, 1, nullptr) == PO_EINVAL);
+    EXPECT(pipeoptim_predict(nullptr, &h, 1, 1, nullptr) == PO_EINVAL);
+    EXPECT(pipeoptim_probe_copy(nullptr, nullptr, 8, nullptr) == PO_EINVAL);
+
+    std::printf("host checks passed\n");
+    return 0;
+}
