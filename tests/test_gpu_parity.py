@@ -634,3 +634,28 @@ def test_random_cases(case):
                          launch=launch, decay_in_prediction=dip, label="random %d" % case)
     run_and_compare_predict(kind, hp, t, s, _rand_list(sizes, 600 + case, kind, **sig), what_dtype,
                             launch=launch, decay_in_prediction=dip, label="random predict %d" % case)
+
+
+# --------------------------------------------------------------------------- streams and plan lifetime
+def test_two_plans_on_two_streams_and_destroy_while_in_flight():
+    _say("two streams, destroy in flight")
+    kind, hp, t, s = "adam", HP["adam"], 9, 4
+    sets = [_rand_list([300000, 4097], 51 + k, kind) for k in range(2)]
+    hosts = [[{k: ts[k][i].cpu().numpy().copy() for k in ("W", "g", "m", "v")} for i in range(2)] for ts in sets]
+    streams = [torch.cuda.Stream(), torch.cuda.Stream()]
+    stages = []
+    torch.cuda.synchronize()
+    for ts, st in zip(sets, streams):
+        with torch.cuda.stream(st):
+            stage = Stage(ts["W"], ts["g"], ts["m"], ts["v"], "f32")
+            stage.step_predict(make_hyper(kind, hp), t, s)          # enqueued on this side stream
+            stages.append(stage)
+    for stage in stages:
+        stage.close()                                               # destroy waits for the device first
+    torch.cuda.synchronize()
+    for ts, host, stage in zip(sets, hosts, stages):
+        for i in range(2):
+            ref = run_oracle(kind, hp, t, s, host[i])
+            got = {"W": ts["W"][i].cpu().numpy(), "m": ts["m"][i].cpu().numpy(), "v": ts["v"][i].cpu().numpy(),
+                   "What": stage.What[i].cpu().numpy()}
+            compare(kind, hp, t, s, host[i], ref, got, "f32", "two streams tensor %d" % i)
