@@ -52,7 +52,10 @@
 #include <stdint.h>
 #include <string.h>
 
-enum { PO_ORACLE_SGDM = 0, PO_ORACLE_ADAM = 1, PO_ORACLE_ADAMW = 2 };
+/* 0-2: the rows of paper Table 1.  3-5: further optimizers, by the table's own recipe (Sec. III-A.3: dW_t
+ * follows from the update rule of the optimizer in use; Eq. 1 makes it the optimizer's increment over lr). */
+enum { PO_ORACLE_SGDM = 0, PO_ORACLE_ADAM = 1, PO_ORACLE_ADAMW = 2,
+       PO_ORACLE_NESTEROV = 3, PO_ORACLE_RMSPROP = 4, PO_ORACLE_ADAGRAD = 5 };
 
 /* ---- bf16 rounding: nearest representable bf16, ties to the even code ------
  * A bf16 is the upper 16 bits of an fp32.  The two neighbours of x are the
@@ -108,6 +111,24 @@ static void one_element(int opt, double lr, double beta1, double beta2, double e
         *m_new = mt;
         *v_new = v;                               /* SGDM has no second state   */
         dW_step = dW_pred = mt;
+    } else if (opt == PO_ORACLE_NESTEROV) {
+        /* momentum SGD with Nesterov's look-ahead: the buffer takes the gradient, the step takes the
+         * gradient plus u times the updated buffer */
+        double u = beta1;
+        double gt = g + wd * W;
+        double mt = u * m + gt;
+        *m_new = mt;
+        *v_new = v;
+        dW_step = dW_pred = gt + u * mt;
+    } else if (opt == PO_ORACLE_RMSPROP || opt == PO_ORACLE_ADAGRAD) {
+        /* RMSprop: running average of squared gradients with smoothing alpha (= beta2), no momentum,
+         * not centred.  Adagrad: their plain sum.  The step divides the gradient by the root. */
+        double alpha = beta2;
+        double gt = g + wd * W;
+        double vt = (opt == PO_ORACLE_RMSPROP) ? alpha * v + (1.0 - alpha) * gt * gt : v + gt * gt;
+        *m_new = m;
+        *v_new = vt;
+        dW_step = dW_pred = gt / (sqrt(vt) + eps);
     } else {
         double gt = (opt == PO_ORACLE_ADAM) ? g + wd * W : g;
         double mt = beta1 * m + (1.0 - beta1) * gt;            /* Table 1 */
@@ -130,7 +151,8 @@ static void one_element(int opt, double lr, double beta1, double beta2, double e
 }
 
 /*
- * Host pointers, n elements each.  v / v_out may be NULL for SGDM.  Any of the
+ * Host pointers, n elements each.  v / v_out may be NULL for the optimizers without a second-moment
+ * state (SGDM, Nesterov), m / m_out for those without a momentum buffer (RMSprop, Adagrad).  Any of the
  * output pointers may be NULL (that output is skipped).  Outputs may alias the
  * matching inputs (element i is read before element i is written).
  * nthreads > 1 splits the element loop over that many OpenMP threads; it
@@ -143,24 +165,27 @@ int po_oracle_step_predict(int opt, double lr, double beta1, double beta2, doubl
                            float* W_out, float* m_out, float* v_out,
                            float* What_f32, uint16_t* What_bf16, int nthreads)
 {
-    if (opt < PO_ORACLE_SGDM || opt > PO_ORACLE_ADAMW) return -1;
+    if (opt < PO_ORACLE_SGDM || opt > PO_ORACLE_ADAGRAD) return -1;
     if (t < 1 || s < 0 || n < 0) return -1;
-    if (n > 0 && (!W || !g || !m)) return -1;
-    if (n > 0 && opt != PO_ORACLE_SGDM && !v) return -1;
+    const int uses_m = (opt != PO_ORACLE_RMSPROP && opt != PO_ORACLE_ADAGRAD);
+    const int uses_v = (opt != PO_ORACLE_SGDM && opt != PO_ORACLE_NESTEROV);
+    if (n > 0 && (!W || !g)) return -1;
+    if (n > 0 && uses_m && !m) return -1;
+    if (n > 0 && uses_v && !v) return -1;
     if (nthreads < 1) nthreads = 1;
 
     #pragma omp parallel for num_threads(nthreads) schedule(static) if (nthreads > 1)
     for (long long i = 0; i < n; ++i) {
         double Wn, mn, vn, Wh;
         one_element(opt, lr, beta1, beta2, eps, weight_decay, decay_in_prediction, t, s,
-                    (double)W[i], (double)g[i], (double)m[i], v ? (double)v[i] : 0.0,
+                    (double)W[i], (double)g[i], m ? (double)m[i] : 0.0, v ? (double)v[i] : 0.0,
                     &Wn, &mn, &vn, &Wh);
         float Wh32 = (float)Wh;                   /* one rounding, fp64 -> fp32 */
         if (What_f32)  What_f32[i]  = Wh32;
         if (What_bf16) What_bf16[i] = po_oracle_bf16_from_f32(Wh32);
         if (W_out) W_out[i] = (float)Wn;
-        if (m_out) m_out[i] = (float)mn;
-        if (v_out && opt != PO_ORACLE_SGDM) v_out[i] = (float)vn;
+        if (m_out && uses_m) m_out[i] = (float)mn;
+        if (v_out && uses_v) v_out[i] = (float)vn;
     }
     return 0;
 }
@@ -184,7 +209,7 @@ int po_oracle_predict(int opt, double lr, double beta1, double beta2, double eps
                       const float* W, const float* m, const float* v,
                       float* What_f32, uint16_t* What_bf16, int nthreads)
 {
-    if (opt < PO_ORACLE_SGDM || opt > PO_ORACLE_ADAMW) return -1;
+    if (opt < PO_ORACLE_SGDM || opt > PO_ORACLE_ADAMW) return -1;   /* the others need the gradient for dW */
     if (t < 1 || s < 0 || n < 0) return -1;
     if (n > 0 && (!W || !m)) return -1;
     if (n > 0 && opt != PO_ORACLE_SGDM && !v) return -1;

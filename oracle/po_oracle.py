@@ -11,7 +11,7 @@ import subprocess
 
 import numpy as np
 
-SGDM, ADAM, ADAMW = 0, 1, 2
+SGDM, ADAM, ADAMW, NESTEROV, RMSPROP, ADAGRAD = 0, 1, 2, 3, 4, 5
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 SOURCE = os.path.join(_HERE, "po_oracle.c")
@@ -43,7 +43,7 @@ def _f32(a):
 class OracleLib:
     """One loaded build of the oracle."""
 
-    SGDM, ADAM, ADAMW = SGDM, ADAM, ADAMW
+    SGDM, ADAM, ADAMW, NESTEROV, RMSPROP, ADAGRAD = SGDM, ADAM, ADAMW, NESTEROV, RMSPROP, ADAGRAD
 
     def __init__(self, path):
         lib = ctypes.CDLL(path)
@@ -65,17 +65,21 @@ class OracleLib:
                      decay_in_prediction=True, t=1, s=0, nthreads=1):
         """One fused step + prediction on flat fp32 arrays.
 
-        Returns a dict with ``W``, ``m``, ``v`` (None for SGDM), ``What`` (fp32) and
-        ``What_bf16`` (uint16 bit patterns).  For SGDM ``beta1`` is the momentum
-        factor and ``beta2`` the dampening.
+        Returns a dict with ``W``, ``m``, ``v`` (None where the optimizer has no such state),
+        ``What`` (fp32) and ``What_bf16`` (uint16 bit patterns).  SGDM: ``beta1`` is the momentum
+        factor and ``beta2`` the dampening; Nesterov: ``beta1`` is the momentum factor; RMSprop:
+        ``beta2`` is the smoothing constant; Adagrad uses neither.
         """
         W, pW = _f32(W)
         g, pg = _f32(g)
-        m, pm = _f32(m)
         n = W.size
-        if g.size != n or m.size != n or (v is not None and np.asarray(v).size != n):
-            raise ValueError("oracle: operand sizes differ")
         null_f = ctypes.POINTER(ctypes.c_float)()
+        if g.size != n or (m is not None and np.asarray(m).size != n) or (v is not None and np.asarray(v).size != n):
+            raise ValueError("oracle: operand sizes differ")
+        if m is not None:
+            m, pm = _f32(m)
+        else:
+            pm = null_f
         if v is not None:
             v, pv = _f32(v)
             v_out = np.empty(n, np.float32)
@@ -83,14 +87,14 @@ class OracleLib:
         else:
             pv, v_out, pvo = null_f, None, null_f
         W_out = np.empty(n, np.float32)
-        m_out = np.empty(n, np.float32)
+        m_out = np.empty(n, np.float32) if m is not None else None
+        pmo = m_out.ctypes.data_as(ctypes.POINTER(ctypes.c_float)) if m is not None else null_f
         What = np.empty(n, np.float32)
         What16 = np.empty(n, np.uint16)
         rc = self._lib.po_oracle_step_predict(
             int(opt), float(lr), float(beta1), float(beta2), float(eps), float(weight_decay),
             int(bool(decay_in_prediction)), int(t), int(s), n, pW, pg, pm, pv,
-            W_out.ctypes.data_as(ctypes.POINTER(ctypes.c_float)),
-            m_out.ctypes.data_as(ctypes.POINTER(ctypes.c_float)), pvo,
+            W_out.ctypes.data_as(ctypes.POINTER(ctypes.c_float)), pmo, pvo,
             What.ctypes.data_as(ctypes.POINTER(ctypes.c_float)),
             What16.ctypes.data_as(ctypes.POINTER(ctypes.c_uint16)), int(nthreads))
         if rc != 0:

@@ -33,6 +33,14 @@ MUTANTS = [
     ("decoupled decay dropped from the step", "dW_step = r + wd * W;                 /* decoupled decay", "dW_step = r;  /* decoupled decay"),
     ("decay flag inverted", "dW_pred = decay_in_prediction ? dW_step : r;", "dW_pred = decay_in_prediction ? r : dW_step;"),
     ("new state not stored", "*m_new = mt;\n        *v_new = vt;", "*m_new = m;\n        *v_new = vt;"),
+    ("nesterov: buffer with dampening-like factor", "double mt = u * m + gt;\n        *m_new = mt;\n        *v_new = v;\n        dW_step = dW_pred = gt + u * mt;", "double mt = u * m + (1.0 - u) * gt;\n        *m_new = mt;\n        *v_new = v;\n        dW_step = dW_pred = gt + u * mt;"),
+    ("nesterov: no look-ahead (plain momentum)", "dW_step = dW_pred = gt + u * mt;", "dW_step = dW_pred = mt;"),
+    ("nesterov: look-ahead with the stale buffer", "dW_step = dW_pred = gt + u * mt;", "dW_step = dW_pred = gt + u * m;"),
+    ("rmsprop: average without the (1-alpha) weight", "? alpha * v + (1.0 - alpha) * gt * gt : v + gt * gt;", "? alpha * v + gt * gt : v + gt * gt;"),
+    ("adagrad: sum decays", "? alpha * v + (1.0 - alpha) * gt * gt : v + gt * gt;", "? alpha * v + (1.0 - alpha) * gt * gt : alpha * v + gt * gt;"),
+    ("rmsprop/adagrad: epsilon inside the root", "dW_step = dW_pred = gt / (sqrt(vt) + eps);", "dW_step = dW_pred = gt / sqrt(vt + eps);"),
+    ("rmsprop/adagrad: stale second moment", "dW_step = dW_pred = gt / (sqrt(vt) + eps);", "dW_step = dW_pred = gt / (sqrt(v) + eps);"),
+    ("rmsprop/adagrad: raw gradient without decay in the numerator", "dW_step = dW_pred = gt / (sqrt(vt) + eps);", "dW_step = dW_pred = g / (sqrt(vt) + eps);"),
     ("version difference off by one", "return D - rank - 1;", "return D - rank;"),
     ("bf16 ties away from zero", "else                   pick = ((lo_bits >> 16) & 1u) ? hi_bits : lo_bits;", "else                   pick = hi_bits;"),
     ("bf16 truncation", "if (d_lo < d_hi)       pick = lo_bits;", "if (1)       pick = lo_bits;"),
@@ -59,6 +67,7 @@ def _pin_suite(orc):
     pins.test_sgdm_zero_buffer_is_plain_sgd(orc)
     pins.test_adam_first_step_from_zero_state(orc)
     pins.test_adamw_readings(orc)
+    pins.test_new_optimizers_closed_forms(orc)
     pins.test_predict_sgdm_is_W_minus_s_lr_m(orc)
     pins.test_predict_adam_bias_corrections_closed_form(orc)
     pins.test_predict_s0_affine_and_adamw_readings(orc)
@@ -70,7 +79,7 @@ def _pin_suite(orc):
     pins.test_eq2_equals_eq3_when_direction_is_constant_sgd(orc)
     pins.test_eq2_equals_eq3_at_adam_fixed_point(orc)
     for case in pins.STEP_CASES:
-        if case[0] != "adamw":
+        if case[0] in ("sgdm", "adam"):
             pins.test_predict_after_fused_step_equals_fused_prediction_one_further(orc, *case)
 
 

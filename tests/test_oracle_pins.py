@@ -13,7 +13,9 @@ import pytest
 import torch
 
 GOLDEN = os.path.join(os.path.dirname(__file__), "golden", "hand_cases.txt")
-OPT = {"sgdm": 0, "adam": 1, "adamw": 2}
+OPT = {"sgdm": 0, "adam": 1, "adamw": 2, "nesterov": 3, "rmsprop": 4, "adagrad": 5}
+NO_V = ("sgdm", "nesterov")          # optimizers without a second-moment state
+NO_M = ("rmsprop", "adagrad")        # optimizers without a momentum buffer
 
 
 def _ulp32(x):
@@ -54,16 +56,17 @@ def test_hand_cases_predict_from_cached_state(oracle, key, rows):
 @pytest.mark.parametrize("key,rows", _cases(False), ids=lambda k: k[0] if isinstance(k, tuple) else "")
 def test_hand_cases_table1_eq1_eq5(oracle, key, rows):
     _, (opt, lr, b1, b2, eps, wd, dip, t, s) = key
-    sgdm = opt == "sgdm"
     col = lambda j, src: np.array([float(r[src][j]) for r in rows], dtype=np.float32)
-    W, g, m = col(0, 0), col(1, 0), col(2, 0)
-    v = None if sgdm else col(3, 0)
+    W, g = col(0, 0), col(1, 0)
+    m = None if opt in NO_M else col(2, 0)
+    v = None if opt in NO_V else col(3, 0)
     r = oracle.step_predict(OPT[opt], W, g, m, v, lr=float(lr), beta1=float(b1), beta2=float(b2),
                             eps=float(eps), weight_decay=float(wd), decay_in_prediction=bool(int(dip)),
                             t=int(t), s=int(s))
     np.testing.assert_array_equal(r["W"], col(0, 1))
-    np.testing.assert_array_equal(r["m"], col(1, 1))
-    if not sgdm:
+    if opt not in NO_M:
+        np.testing.assert_array_equal(r["m"], col(1, 1))
+    if opt not in NO_V:
         np.testing.assert_array_equal(r["v"], col(2, 1))
     np.testing.assert_array_equal(r["What"], col(3, 1))
     # every hand value is exact in bf16 too
@@ -85,10 +88,20 @@ def _torch_one_step(kind, W, g, m, v, t, **hp):
     """The optimizer's own single step, by torch.optim in fp64, from the given state."""
     p = torch.nn.Parameter(torch.tensor(W, dtype=torch.float64))
     p.grad = torch.tensor(g, dtype=torch.float64)
-    if kind == "sgdm":
-        opt = torch.optim.SGD([p], lr=hp["lr"], momentum=hp["beta1"], dampening=hp["beta2"],
-                              weight_decay=hp["weight_decay"])
+    if kind in ("sgdm", "nesterov"):
+        opt = torch.optim.SGD([p], lr=hp["lr"], momentum=hp["beta1"], dampening=hp["beta2"] if kind == "sgdm" else 0.0,
+                              weight_decay=hp["weight_decay"], nesterov=(kind == "nesterov"))
         opt.state[p]["momentum_buffer"] = torch.tensor(m, dtype=torch.float64)
+    elif kind == "rmsprop":
+        opt = torch.optim.RMSprop([p], lr=hp["lr"], alpha=hp["beta2"], eps=hp["eps"], weight_decay=hp["weight_decay"],
+                                  momentum=0.0, centered=False, foreach=False)
+        opt.state[p]["step"] = torch.tensor(float(t - 1))
+        opt.state[p]["square_avg"] = torch.tensor(v, dtype=torch.float64)
+    elif kind == "adagrad":
+        opt = torch.optim.Adagrad([p], lr=hp["lr"], lr_decay=0.0, eps=hp["eps"], weight_decay=hp["weight_decay"],
+                                  foreach=False)
+        opt.state[p]["step"] = torch.tensor(float(t - 1))
+        opt.state[p]["sum"] = torch.tensor(v, dtype=torch.float64)
     else:
         cls = torch.optim.Adam if kind == "adam" else torch.optim.AdamW
         opt = cls([p], lr=hp["lr"], betas=(hp["beta1"], hp["beta2"]), eps=hp["eps"],
@@ -98,8 +111,12 @@ def _torch_one_step(kind, W, g, m, v, t, **hp):
         opt.state[p]["exp_avg_sq"] = torch.tensor(v, dtype=torch.float64)
     opt.step()
     st = opt.state[p]
-    if kind == "sgdm":
+    if kind in ("sgdm", "nesterov"):
         return p.detach().numpy(), st["momentum_buffer"].numpy(), None
+    if kind == "rmsprop":
+        return p.detach().numpy(), None, st["square_avg"].numpy()
+    if kind == "adagrad":
+        return p.detach().numpy(), None, st["sum"].numpy()
     return p.detach().numpy(), st["exp_avg"].numpy(), st["exp_avg_sq"].numpy()
 
 
@@ -110,18 +127,25 @@ STEP_CASES = [
     ("adam", dict(lr=3e-4, beta1=0.8, beta2=0.99, eps=1e-6, weight_decay=0.1), 3),
     ("adamw", dict(lr=1e-3, beta1=0.9, beta2=0.999, eps=1e-8, weight_decay=0.01), 5000),
     ("adamw", dict(lr=1e-2, beta1=0.5, beta2=0.9, eps=1e-3, weight_decay=0.3), 1),
+    ("nesterov", dict(lr=0.05, beta1=0.9, beta2=0.0, eps=0.0, weight_decay=5e-4), 4),
+    ("nesterov", dict(lr=0.3, beta1=0.5, beta2=0.0, eps=0.0, weight_decay=0.0), 1),
+    ("rmsprop", dict(lr=1e-3, beta1=0.0, beta2=0.99, eps=1e-8, weight_decay=0.0), 7),
+    ("rmsprop", dict(lr=1e-2, beta1=0.0, beta2=0.9, eps=1e-4, weight_decay=0.05), 2),
+    ("adagrad", dict(lr=1e-2, beta1=0.0, beta2=0.0, eps=1e-10, weight_decay=0.0), 9),
+    ("adagrad", dict(lr=0.1, beta1=0.0, beta2=0.0, eps=1e-6, weight_decay=0.01), 1),
 ]
 
 
 @pytest.mark.parametrize("kind,hp,t", STEP_CASES)
 def test_step_equals_library_optimizer(oracle, kind, hp, t):
     W, g, m, v = _rand_state(4099, seed=t + len(kind))
-    r = oracle.step_predict(OPT[kind], W, g, m, None if kind == "sgdm" else v, t=t, s=1, **hp)
+    r = oracle.step_predict(OPT[kind], W, g, None if kind in NO_M else m, None if kind in NO_V else v, t=t, s=1, **hp)
     Wt, mt, vt = _torch_one_step(kind, W, g, m, v, t, **hp)
     # both are fp64 evaluations of the same update in a different operation order:
     # after rounding to fp32 they agree to one unit in the last place
     assert np.all(np.abs(r["W"].astype(np.float64) - Wt) <= _ulp32(Wt))
-    assert np.all(np.abs(r["m"].astype(np.float64) - mt) <= _ulp32(mt))
+    if mt is not None:
+        assert np.all(np.abs(r["m"].astype(np.float64) - mt) <= _ulp32(mt))
     if vt is not None:
         assert np.all(np.abs(r["v"].astype(np.float64) - vt) <= _ulp32(vt))
     # and tightly in relative terms on the bulk (a dropped term would be ~1e-3 off)
@@ -135,6 +159,9 @@ ALL_OPTS = [
     ("sgdm", dict(lr=0.1, beta1=0.9, beta2=0.0, eps=0.0, weight_decay=1e-4), 1),
     ("adam", dict(lr=1e-3, beta1=0.9, beta2=0.999, eps=1e-8, weight_decay=0.0), 100),
     ("adamw", dict(lr=1e-3, beta1=0.9, beta2=0.999, eps=1e-8, weight_decay=0.01), 1000),
+    ("nesterov", dict(lr=0.05, beta1=0.9, beta2=0.0, eps=0.0, weight_decay=5e-4), 3),
+    ("rmsprop", dict(lr=1e-3, beta1=0.0, beta2=0.99, eps=1e-8, weight_decay=1e-4), 5),
+    ("adagrad", dict(lr=1e-2, beta1=0.0, beta2=0.0, eps=1e-10, weight_decay=0.0), 8),
 ]
 
 
@@ -142,20 +169,22 @@ ALL_OPTS = [
 def test_s0_returns_W_unchanged(oracle, kind, hp, t):
     W, g, m, v = _rand_state(1000, seed=1)
     W[:3] = [0.0, -0.0, 1e-38]
-    r = oracle.step_predict(OPT[kind], W, g, m, None if kind == "sgdm" else v, t=t, s=0, **hp)
+    mm, vv = (None if kind in NO_M else m), (None if kind in NO_V else v)
+    r = oracle.step_predict(OPT[kind], W, g, mm, vv, t=t, s=0, **hp)
     np.testing.assert_array_equal(r["What"].view(np.uint32), W.view(np.uint32))
     np.testing.assert_array_equal(r["What_bf16"], oracle.bf16_from_f32(W))
     # the step itself does not depend on s
-    r3 = oracle.step_predict(OPT[kind], W, g, m, None if kind == "sgdm" else v, t=t, s=3, **hp)
-    for k in ("W", "m"):
-        np.testing.assert_array_equal(r[k], r3[k])
+    r3 = oracle.step_predict(OPT[kind], W, g, mm, vv, t=t, s=3, **hp)
+    for k in ("W", "m", "v"):
+        if r[k] is not None:
+            np.testing.assert_array_equal(r[k], r3[k])
 
 
 @pytest.mark.parametrize("kind,hp,t", ALL_OPTS)
 def test_prediction_is_affine_in_s(oracle, kind, hp, t):
     W, g, m, v = _rand_state(2048, seed=2)
-    vv = None if kind == "sgdm" else v
-    what = {s: oracle.step_predict(OPT[kind], W, g, m, vv, t=t, s=s, **hp)["What"].astype(np.float64)
+    mm, vv = (None if kind in NO_M else m), (None if kind in NO_V else v)
+    what = {s: oracle.step_predict(OPT[kind], W, g, mm, vv, t=t, s=s, **hp)["What"].astype(np.float64)
             for s in range(0, 9)}
     W64 = W.astype(np.float64)
     d1 = what[1] - W64
@@ -238,6 +267,40 @@ def test_sgdm_zero_buffer_is_plain_sgd(oracle):
     np.testing.assert_array_equal(r["What"], (W64 - 0.1 * 4 * g64).astype(np.float32))
 
 
+def test_new_optimizers_closed_forms(oracle):
+    W, g, _, _ = _rand_state(999, seed=61)
+    z = np.zeros_like(W)
+    W64, g64 = W.astype(np.float64), g.astype(np.float64)
+    # Nesterov from an empty buffer: m' = g, dW = g + u*g = (1+u) g
+    r = oracle.step_predict(3, W, g, z, lr=0.1, beta1=0.9, beta2=0.0, t=1, s=3)
+    np.testing.assert_array_equal(r["m"], g)
+    assert np.all(np.abs(r["W"] - (W64 - 0.1 * 1.9 * g64)) <= _ulp32(W64 - 0.1 * 1.9 * g64))
+    assert np.all(np.abs(r["What"] - (W64 - 0.3 * 1.9 * g64)) <= _ulp32(W64 - 0.3 * 1.9 * g64))
+    # with u = 0 Nesterov is plain SGD, exactly as SGDM with u = 0 is
+    a = oracle.step_predict(3, W, g, z + 5, lr=0.1, beta1=0.0, beta2=0.0, t=1, s=3)
+    b = oracle.step_predict(0, W, g, z + 5, lr=0.1, beta1=0.0, beta2=0.0, t=1, s=3)
+    np.testing.assert_array_equal(a["W"], b["W"])
+    np.testing.assert_array_equal(a["What"], b["What"])
+    # Adagrad from an empty sum: v' = g^2, dW = g/(|g| + eps) (about sign(g))
+    eps = 1e-10
+    r = oracle.step_predict(5, W, g, None, z, lr=0.01, beta1=0.0, beta2=0.0, eps=eps, t=1, s=4)
+    dW = g64 / (np.abs(g64) + eps)
+    assert np.all(np.abs(r["W"] - (W64 - 0.01 * dW)) <= _ulp32(W64 - 0.01 * dW))
+    assert np.all(np.abs(r["What"] - (W64 - 0.04 * dW)) <= _ulp32(W64 - 0.04 * dW))
+    np.testing.assert_allclose(r["v"], g64 * g64, rtol=1e-7)
+    # RMSprop from an empty average: v' = (1-alpha) g^2, dW = g/(sqrt(1-alpha)|g| + eps)
+    r = oracle.step_predict(4, W, g, None, z, lr=0.01, beta1=0.0, beta2=0.75, eps=eps, t=1, s=4)
+    dW = g64 / (0.5 * np.abs(g64) + eps)
+    assert np.all(np.abs(r["W"] - (W64 - 0.01 * dW)) <= _ulp32(W64 - 0.01 * dW))
+    np.testing.assert_allclose(r["v"], 0.25 * g64 * g64, rtol=1e-7)
+    # RMSprop with alpha = 0 forgets its state: v' = g^2; Adagrad keeps it: v' = v + g^2
+    v0 = (g64 * 3) ** 2
+    r4 = oracle.step_predict(4, W, g, None, v0, lr=0.01, beta1=0.0, beta2=0.0, eps=eps, t=1, s=1)
+    r5 = oracle.step_predict(5, W, g, None, v0, lr=0.01, beta1=0.0, beta2=0.0, eps=eps, t=1, s=1)
+    np.testing.assert_allclose(r4["v"], g64 * g64, rtol=1e-7)
+    np.testing.assert_allclose(r5["v"], v0.astype(np.float32).astype(np.float64) + g64 * g64, rtol=1e-7)
+
+
 def test_direction_uses_updated_state_not_stale(oracle):
     # Sec. III-A.3: dW_t comes from the NEW gradient and the cached state.  With a cached
     # momentum of 5 and a new gradient of 100, What must move by the updated momentum
@@ -304,7 +367,7 @@ def test_predict_adam_bias_corrections_closed_form(oracle):
     assert np.all(np.abs(r2["What"] - want2) <= _ulp32(want2))
 
 
-@pytest.mark.parametrize("kind,hp,t", [c for c in STEP_CASES if c[0] != "adamw"])
+@pytest.mark.parametrize("kind,hp,t", [c for c in STEP_CASES if c[0] in ("sgdm", "adam")])
 def test_predict_after_fused_step_equals_fused_prediction_one_further(oracle, kind, hp, t):
     # The state a fused call leaves is (W', m_t, v_t).  Predicting s versions ahead from it gives
     # W' - s*lr*dW_t = W - (s+1)*lr*dW_t, which is the fused call's own prediction for s+1 (the
@@ -352,6 +415,9 @@ def test_predict_rejects_bad_arguments(oracle):
             oracle.predict(1, a, a, a, lr=1e-3, beta1=0.9, beta2=0.999, **kw)
     with pytest.raises(ValueError):
         oracle.predict(1, a, a, None, lr=1e-3, beta1=0.9, beta2=0.999, t=1, s=1)
+    for opt in (3, 4, 5):          # their direction needs the gradient: no prediction from the state alone
+        with pytest.raises(ValueError):
+            oracle.predict(opt, a, a, a, lr=1e-3, beta1=0.9, beta2=0.999, t=1, s=1)
 
 
 # --------------------------------------------------------------------------- Eq. 4
@@ -375,6 +441,17 @@ def _exact_element(kind, W, g, m, v, lr, b1, b2, eps, wd, dip, t, s):
         mt = b1 * m + (1 - b2) * gt
         vt = v
         d_step = d_pred = mt
+    elif kind == "nesterov":
+        gt = g + wd * W
+        mt = b1 * m + gt
+        vt = v
+        d_step = d_pred = gt + b1 * mt
+    elif kind in ("rmsprop", "adagrad"):
+        gt = g + wd * W
+        mt = m
+        vt = b2 * v + (1 - b2) * gt * gt if kind == "rmsprop" else v + gt * gt
+        root = (Decimal(vt.numerator) / Decimal(vt.denominator)).sqrt()
+        d_step = d_pred = gt / (F(root) + eps)
     else:
         gt = g + wd * W if kind == "adam" else g
         mt = b1 * m + (1 - b1) * gt
@@ -396,21 +473,22 @@ def test_brute_force_exact_arithmetic_small_tensors(oracle, kind, hp, t, dip):
     n = 16
     W, g, m, v = _rand_state(n, seed=11 + t)
     for s in (0, 1, 3, 7):
-        r = oracle.step_predict(OPT[kind], W, g, m, None if kind == "sgdm" else v, t=t, s=s,
+        r = oracle.step_predict(OPT[kind], W, g, None if kind in NO_M else m, None if kind in NO_V else v, t=t, s=s,
                                 decay_in_prediction=dip, **hp)
         for i in range(n):
             Wn, mn, vn, Wh = _exact_element(kind, W[i], g[i], m[i], v[i], hp["lr"], hp["beta1"], hp["beta2"],
                                             hp["eps"], hp["weight_decay"], dip, t, s)
             # the oracle's fp64 chain is ~1e-15 from exact; an fp32 rounding boundary may flip one ulp
             assert abs(float(r["W"][i]) - Wn) <= _ulp32(Wn)
-            assert abs(float(r["m"][i]) - mn) <= _ulp32(mn)
-            if kind != "sgdm":
+            if kind not in NO_M:
+                assert abs(float(r["m"][i]) - mn) <= _ulp32(mn)
+            if kind not in NO_V:
                 assert abs(float(r["v"][i]) - vn) <= _ulp32(vn)
             assert abs(float(r["What"][i]) - Wh) <= _ulp32(Wh)
             assert abs(float(r["W"][i]) - Wn) <= 1e-7 * (abs(Wn) + 1e-30)
 
 
-@pytest.mark.parametrize("kind,hp,t", STEP_CASES)
+@pytest.mark.parametrize("kind,hp,t", [c for c in STEP_CASES if c[0] in ("sgdm", "adam", "adamw")])
 def test_predict_brute_force_exact_arithmetic(oracle, kind, hp, t):
     getcontext().prec = 60
     F = Fraction
@@ -503,7 +581,7 @@ def test_invalid_arguments_rejected(oracle):
     with pytest.raises(ValueError):
         oracle.step_predict(1, a, a, a, None, lr=1e-3, beta1=0.9, beta2=0.999, t=1, s=1)
     with pytest.raises(ValueError):
-        oracle.step_predict(3, a, a, a, a, lr=1e-3, beta1=0.9, beta2=0.999, t=1, s=1)
+        oracle.step_predict(6, a, a, a, a, lr=1e-3, beta1=0.9, beta2=0.999, t=1, s=1)
     e = np.zeros(0, np.float32)
     r = oracle.step_predict(1, e, e, e, e, lr=1e-3, beta1=0.9, beta2=0.999, t=1, s=1)
     assert r["W"].size == 0
