@@ -39,6 +39,8 @@ def parse_args():
                     help="fused: optimizer step + prediction (the headline path); predict: prediction alone from cached state")
     ap.add_argument("--grad-dtype", choices=("f32", "bf16"), default="f32",
                     help="bf16: mixed-precision variant with bf16 gradients (2 bytes fewer read per parameter)")
+    ap.add_argument("--optimizer", default="", choices=("", "sgdm", "adam", "adamw", "nesterov", "rmsprop", "adagrad"),
+                    help="run the config's tensor list under another optimizer (default: the config's own)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-copy-probe", action="store_true")
     ap.add_argument("--launch", default="", help="comma separated po_launch overrides, e.g. block=64,unroll=1,lds_bytes=16384")
@@ -63,8 +65,14 @@ def cpu_baseline(wl, s, predict_only=False):
         total += n
     inp = make_inputs(wl, "cpu", tensors=idx)
     threads = min(16, os.cpu_count() or 1)
-    code = {"sgdm": oracle.SGDM, "adam": oracle.ADAM, "adamw": oracle.ADAMW}[wl.optimizer]
+    code = {"sgdm": oracle.SGDM, "adam": oracle.ADAM, "adamw": oracle.ADAMW, "nesterov": oracle.NESTEROV,
+            "rmsprop": oracle.RMSPROP, "adagrad": oracle.ADAGRAD}[wl.optimizer]
     arrays = [{k: inp[k][j].numpy() for k in ("W", "g", "m", "v") if inp[k] is not None} for j in range(len(idx))]
+    for a in arrays:                                       # state the optimizer in use does not have
+        if wl.optimizer in ("rmsprop", "adagrad"):
+            a.pop("m", None)
+        if wl.optimizer in ("sgdm", "nesterov"):
+            a.pop("v", None)
     t0 = time.perf_counter()
     for a in arrays:
         if predict_only:
@@ -72,7 +80,7 @@ def cpu_baseline(wl, s, predict_only=False):
                            beta2=wl.hyper["beta2"], eps=wl.hyper["eps"], weight_decay=wl.hyper["weight_decay"],
                            t=wl.t, s=s, nthreads=threads)
         else:
-            oracle.step_predict(code, a["W"], a["g"], a["m"], a.get("v"), lr=wl.hyper["lr"], beta1=wl.hyper["beta1"],
+            oracle.step_predict(code, a["W"], a["g"], a.get("m"), a.get("v"), lr=wl.hyper["lr"], beta1=wl.hyper["beta1"],
                                 beta2=wl.hyper["beta2"], eps=wl.hyper["eps"], weight_decay=wl.hyper["weight_decay"],
                                 t=wl.t, s=s, nthreads=threads)
     dt = time.perf_counter() - t0
@@ -84,7 +92,7 @@ def cpu_baseline(wl, s, predict_only=False):
                        beta2=wl.hyper["beta2"], eps=wl.hyper["eps"], weight_decay=wl.hyper["weight_decay"],
                        t=wl.t, s=s, nthreads=1)
     else:
-        oracle.step_predict(code, a["W"], a["g"], a["m"], a.get("v"), lr=wl.hyper["lr"], beta1=wl.hyper["beta1"],
+        oracle.step_predict(code, a["W"], a["g"], a.get("m"), a.get("v"), lr=wl.hyper["lr"], beta1=wl.hyper["beta1"],
                             beta2=wl.hyper["beta2"], eps=wl.hyper["eps"], weight_decay=wl.hyper["weight_decay"],
                             t=wl.t, s=s, nthreads=1)
     dt1 = time.perf_counter() - t1
@@ -121,6 +129,18 @@ def main():
     D = args.pipeline_depth or (s_cfg + 1)
     rank = D - 1 - s_cfg
     tensors = make_inputs(wl, dev)
+    if args.optimizer and args.optimizer != wl.optimizer:
+        if args.mode == "predict" and args.optimizer in ("nesterov", "rmsprop", "adagrad"):
+            print("bench.py: %s has no prediction from the state alone" % args.optimizer, file=sys.stderr)
+            sys.exit(2)
+        import dataclasses
+        wl = dataclasses.replace(wl, optimizer=args.optimizer)
+        if tensors["v"] is None and wl.optimizer not in ("sgdm", "nesterov"):
+            tensors["v"] = [torch.square(x) for x in tensors["m"]]       # the config carries no second moment
+    if wl.optimizer in ("rmsprop", "adagrad"):
+        tensors["m"] = None
+    if wl.optimizer in ("sgdm", "nesterov"):
+        tensors["v"] = None
     if args.grad_dtype == "bf16":
         tensors["g"] = [x.to(torch.bfloat16) for x in tensors["g"]]
     stage = Stage(tensors["W"], tensors["g"], tensors["m"], tensors["v"], wl.what_dtype)
@@ -132,9 +152,11 @@ def main():
     hyper = binding.make_hyper(wl.optimizer, wl.hyper["lr"], wl.hyper["beta1"], wl.hyper["beta2"], wl.hyper["eps"],
                                wl.hyper["weight_decay"], True)
     N = stage.n_params
-    bytes_per_param = wl.bytes_per_param - (2 if args.grad_dtype == "bf16" else 0)
+    n_state = 2 if wl.optimizer in ("adam", "adamw") else 1
+    # reads W, g, state; writes W', state', What
+    bytes_per_param = 4 + (2 if args.grad_dtype == "bf16" else 4) + 4 * n_state + 4 + 4 * n_state + (2 if wl.what_dtype == "bf16" else 4)
     if predict_only:       # reads W, m (, v); writes What
-        bytes_per_param = 4 * (2 if wl.optimizer == "sgdm" else 3) + (2 if wl.what_dtype == "bf16" else 4)
+        bytes_per_param = 4 * (1 + n_state) + (2 if wl.what_dtype == "bf16" else 4)
     bytes_per_launch = bytes_per_param * N
 
     def one_step(i):
@@ -181,7 +203,8 @@ def main():
         "pct_of_hbm_peak": 100.0 * achieved / HBM_PEAK_GBPS,
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBPS,
-                     "traffic": MEASURED_TRAFFIC.get((args.mode, wl.config)) if args.grad_dtype == "f32" else None},
+                     "traffic": MEASURED_TRAFFIC.get((args.mode, wl.config))
+                     if args.grad_dtype == "f32" and not args.optimizer else None},
     }
 
     if not args.no_copy_probe:

@@ -31,14 +31,21 @@ extern "C" {
 typedef enum {
     PO_OK = 0,
     PO_EINVAL = -1,  /* bad argument: NULL where a pointer is required, t < 1, s < 0, negative size,
-                        beta outside [0,1), non-finite hyper-parameter, Adam/AdamW on a plan without v,
+                        beta outside [0,1), non-finite hyper-parameter, an optimizer whose state buffer the plan lacks,
                         launch shape outside the documented limits */
     PO_EALIGN = -2,  /* a tensor base pointer is not aligned to its element size */
     PO_EHIP   = -3,  /* a HIP call failed; the HIP error string is in pipeoptim_last_error() */
     PO_ENOMEM = -4   /* host or device allocation of the plan's tables failed */
 } po_status;
 
-typedef enum { PO_SGDM = 0, PO_ADAM = 1, PO_ADAMW = 2 } po_optimizer;   /* rows of paper Table 1 */
+/* 0-2: the rows of paper Table 1.  3-5: further optimizers by the table's own recipe (paper Sec. III-A.3: dW_t
+ * follows from the update rule of the optimizer in use; by Eq. 1 it is the optimizer's increment over lr). */
+typedef enum {
+    PO_SGDM = 0, PO_ADAM = 1, PO_ADAMW = 2,
+    PO_NESTEROV = 3,   /* momentum SGD with Nesterov look-ahead: state m                 */
+    PO_RMSPROP  = 4,   /* RMSprop, no momentum, not centred: state v                     */
+    PO_ADAGRAD  = 5    /* Adagrad, no learning-rate decay: state v (the running sum)     */
+} po_optimizer;
 typedef enum { PO_WHAT_F32 = 0, PO_WHAT_BF16 = 1 } po_what_dtype;       /* element type of What */
 typedef enum { PO_GRAD_F32 = 0, PO_GRAD_BF16 = 1 } po_grad_dtype;       /* element type of g */
 
@@ -52,11 +59,12 @@ typedef struct po_hyper {
                                      so that Eq. 1 holds and s = 1 predicts the optimizer's own step.
                                      0: the prediction uses Table 1's AdamW row alone (r); the step still decays. */
     double lr;
-    double beta1;                 /* Adam/AdamW beta1;  SGDM: momentum factor u          */
-    double beta2;                 /* Adam/AdamW beta2;  SGDM: dampening tau              */
-    double eps;                   /* Adam/AdamW epsilon (added after the root); SGDM: ignored */
-    double weight_decay;          /* SGDM and Adam: coupled L2, g + wd*W enters the state update.
-                                     AdamW: decoupled, W shrinks by lr*wd*W.              */
+    double beta1;                 /* Adam/AdamW beta1;  SGDM, Nesterov: momentum factor u; RMSprop, Adagrad: ignored */
+    double beta2;                 /* Adam/AdamW beta2;  SGDM: dampening tau;  RMSprop: smoothing constant alpha;
+                                     Nesterov, Adagrad: ignored */
+    double eps;                   /* epsilon, added after the root (Adam, AdamW, RMSprop, Adagrad); else ignored */
+    double weight_decay;          /* AdamW: decoupled, W shrinks by lr*wd*W.  All others: coupled L2,
+                                     g + wd*W enters the state update.                    */
 } po_hyper;
 
 /* fp32 coefficients one launch runs with (what the host derives from po_hyper, t and s). */
@@ -112,7 +120,8 @@ typedef struct po_plan po_plan;   /* opaque */
  * Build a plan for a stage: n_tensors tensors, tensor i having numel[i] fp32
  * elements at W[i], g[i], m[i], v[i] (device) and a What[i] buffer of numel[i]
  * elements of what_dtype.  numel, W, g, m, v, What are HOST arrays of length
- * n_tensors.  v may be NULL (SGDM-only plan).  numel[i] == 0 and n_tensors == 0
+ * n_tensors.  v may be NULL (plan for SGDM / Nesterov only) and m may be NULL (plan for RMSprop /
+ * Adagrad only); a call with an optimizer whose state is missing fails.  numel[i] == 0 and n_tensors == 0
  * are legal.  No two buffers of the plan may overlap (checked: PO_EINVAL); g is only read;
  * W, m, v are updated in place.  Buffers aligned to 16 bytes take the vector
  * path; 4-byte (What bf16: 2-byte) alignment is accepted and takes a scalar
@@ -158,6 +167,10 @@ int pipeoptim_plan_info(const po_plan* plan, int64_t* n_params, int64_t* n_chunk
  *     Adam : g~ = g + wd*W;  m' = b1*m + (1-b1)*g~;  v' = b2*v + (1-b2)*g~^2
  *            dW = (m'/(1-b1^t)) / (sqrt(v'/(1-b2^t)) + eps)
  *     AdamW: as Adam with g~ = g;  dW = r + wd*W  (prediction: r alone if !decay_in_prediction)
+ *   and, beyond Table 1, by the same recipe:
+ *     Nesterov: g~ = g + wd*W;  m' = u*m + g~;  dW = g~ + u*m'
+ *     RMSprop : g~ = g + wd*W;  v' = alpha*v + (1-alpha)*g~^2;  dW = g~ / (sqrt(v') + eps)
+ *     Adagrad : g~ = g + wd*W;  v' = v + g~^2;                  dW = g~ / (sqrt(v') + eps)
  *     W'   = W - lr*dW                      (paper Eq. 1)
  *     What = W - lr*s*dW                    (paper Eq. 5);  s == 0: What = W
  * in fp32 arithmetic.  W, m, v are overwritten with W', m', v'; What receives
@@ -181,6 +194,8 @@ int pipeoptim_step_predict(const po_plan* plan, const po_hyper* hyper, int64_t t
  * pipeoptim_step_predict(t, .) it predicts from the stepped weights: W' - lr*s*dW_t, which equals the
  * fused call's own prediction for s+1 (for AdamW up to the decay term being taken at W' instead of W).
  * With SGDM and the previous step's momentum it is SpecTrain's predictor (paper Eq. 6, first line).
+ * Only the Table 1 optimizers have a direction that follows from the state alone; Nesterov, RMSprop and
+ * Adagrad need the gradient and are rejected here (PO_EINVAL).
  * Enqueues exactly one kernel; uses the launch shape set with pipeoptim_plan_set_predict_launch.
  */
 int pipeoptim_predict(const po_plan* plan, const po_hyper* hyper, int64_t t, int32_t s, void* hip_stream);

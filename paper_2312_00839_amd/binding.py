@@ -12,10 +12,11 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libpipeoptim.so")
 
 PO_OK, PO_EINVAL, PO_EALIGN, PO_EHIP, PO_ENOMEM = 0, -1, -2, -3, -4
-PO_SGDM, PO_ADAM, PO_ADAMW = 0, 1, 2
+PO_SGDM, PO_ADAM, PO_ADAMW, PO_NESTEROV, PO_RMSPROP, PO_ADAGRAD = 0, 1, 2, 3, 4, 5
 PO_WHAT_F32, PO_WHAT_BF16 = 0, 1
 PO_GRAD_F32, PO_GRAD_BF16 = 0, 1
-OPTIMIZERS = {"sgdm": PO_SGDM, "adam": PO_ADAM, "adamw": PO_ADAMW}
+OPTIMIZERS = {"sgdm": PO_SGDM, "adam": PO_ADAM, "adamw": PO_ADAMW, "nesterov": PO_NESTEROV, "rmsprop": PO_RMSPROP,
+              "adagrad": PO_ADAGRAD}
 WHAT_DTYPES = {"f32": PO_WHAT_F32, "bf16": PO_WHAT_BF16}
 GRAD_DTYPES = {"f32": PO_GRAD_F32, "bf16": PO_GRAD_BF16}
 
@@ -138,7 +139,7 @@ def _ptr_array(ptrs: Sequence[int]):
 class Plan:
     """Owner of a ``po_plan*``.  Pointers are raw device addresses (ints), e.g. ``tensor.data_ptr()``."""
 
-    def __init__(self, numel: Sequence[int], W: Sequence[int], g: Sequence[int], m: Sequence[int],
+    def __init__(self, numel: Sequence[int], W: Sequence[int], g: Sequence[int], m: Optional[Sequence[int]],
                  v: Optional[Sequence[int]], What: Sequence[int], what_dtype, stream: int = 0, grad_dtype="f32"):
         if isinstance(what_dtype, str):
             what_dtype = WHAT_DTYPES[what_dtype]
@@ -151,13 +152,14 @@ class Plan:
         self.grad_dtype = grad_dtype
         numel_arr = (ctypes.c_int64 * max(n, 1))(*numel)
         v_arr = _ptr_array(v) if v is not None else None
+        m_arr = _ptr_array(m) if m is not None else None
         if grad_dtype == PO_GRAD_F32:
             _check(lib().pipeoptim_plan_create(
-                ctypes.byref(self._h), n, numel_arr, _ptr_array(W), _ptr_array(g), _ptr_array(m), v_arr,
+                ctypes.byref(self._h), n, numel_arr, _ptr_array(W), _ptr_array(g), m_arr, v_arr,
                 _ptr_array(What), int(what_dtype), ctypes.c_void_p(stream)))
         else:
             _check(lib().pipeoptim_plan_create_mixed(
-                ctypes.byref(self._h), n, numel_arr, _ptr_array(W), _ptr_array(g), int(grad_dtype), _ptr_array(m),
+                ctypes.byref(self._h), n, numel_arr, _ptr_array(W), _ptr_array(g), int(grad_dtype), m_arr,
                 v_arr, _ptr_array(What), int(what_dtype), ctypes.c_void_p(stream)))
 
     def step_predict(self, hyper: po_hyper, t: int, s: int, stream: int = 0) -> None:

@@ -95,6 +95,7 @@ struct po_plan {
     int32_t what_dtype = PO_WHAT_F32;
     int32_t grad_dtype = PO_GRAD_F32;
     bool has_v = false;
+    bool has_m = false;
     int device = 0;
     po_launch launch{};           // fused kernel
     po_launch predict_launch{};   // prediction-only kernel; chunk_elems always equals launch.chunk_elems
@@ -122,7 +123,7 @@ int check_disjoint(const po_plan* p)
         if (n == 0) continue;
         r.push_back({(uintptr_t)d.W, (uintptr_t)d.W + n * 4, i, 'W'});
         r.push_back({(uintptr_t)d.g, (uintptr_t)d.g + n * gsz, i, 'g'});
-        r.push_back({(uintptr_t)d.m, (uintptr_t)d.m + n * 4, i, 'm'});
+        if (d.m) r.push_back({(uintptr_t)d.m, (uintptr_t)d.m + n * 4, i, 'm'});
         if (d.v) r.push_back({(uintptr_t)d.v, (uintptr_t)d.v + n * 4, i, 'v'});
         r.push_back({(uintptr_t)d.What, (uintptr_t)d.What + n * hsz, i, 'h'});
     }
@@ -198,6 +199,16 @@ po_launch default_launch(int64_t n_params)
     return L;
 }
 
+// Does the plan hold the state buffers this optimizer updates?
+int check_state(const po_plan* p, int opt)
+{
+    const bool needs_m = opt != PO_RMSPROP && opt != PO_ADAGRAD;
+    const bool needs_v = opt != PO_SGDM && opt != PO_NESTEROV;
+    if (needs_m && !p->has_m) return fail(PO_EINVAL, "optimizer %d needs a plan created with m", opt);
+    if (needs_v && !p->has_v) return fail(PO_EINVAL, "optimizer %d needs a plan created with v", opt);
+    return PO_OK;
+}
+
 // The prediction-only kernel is read-dominated (8-12 B read, 2-4 B written per parameter) and likes a
 // looser occupancy cap than the fused kernel (16 workgroups per CU at 0.74B parameters).  Small
 // stages, whose working set largely sits in the memory-side cache, run best with plain accesses and
@@ -233,7 +244,7 @@ int pipeoptim_version_difference(int32_t D, int32_t rank, int32_t* s_out)
 int pipeoptim_coefficients(const po_hyper* h, int64_t t, int32_t s, po_coeffs* out)
 {
     if (!h || !out) return fail(PO_EINVAL, "hyper or out is NULL");
-    if (h->opt != PO_SGDM && h->opt != PO_ADAM && h->opt != PO_ADAMW) return fail(PO_EINVAL, "unknown optimizer %d", h->opt);
+    if (h->opt < PO_SGDM || h->opt > PO_ADAGRAD) return fail(PO_EINVAL, "unknown optimizer %d", h->opt);
     if (t < 1) return fail(PO_EINVAL, "t must be >= 1 (got %lld): steps are 1-based", (long long)t);
     if (s < 0) return fail(PO_EINVAL, "s must be >= 0 (got %d)", s);
     if (!finite_d(h->lr) || !finite_d(h->eps) || !finite_d(h->weight_decay) || !finite_d(h->beta1) || !finite_d(h->beta2))
@@ -250,6 +261,22 @@ int pipeoptim_coefficients(const po_hyper* h, int64_t t, int32_t s, po_coeffs* o
         c.inv_bc1 = 1.f;
         c.inv_sqrt_bc2 = 1.f;
         c.eps = 0.f;
+        c.wd_coupled = (float)h->weight_decay;
+    } else if (h->opt == PO_NESTEROV) {
+        if (h->beta1 < 0 || h->beta1 >= 1) return fail(PO_EINVAL, "momentum must be in [0,1)");
+        c.beta1 = (float)h->beta1;
+        c.grad_scale = 1.f;
+        c.inv_bc1 = 1.f;
+        c.inv_sqrt_bc2 = 1.f;
+        c.wd_coupled = (float)h->weight_decay;
+    } else if (h->opt == PO_RMSPROP || h->opt == PO_ADAGRAD) {
+        // one kernel serves both: v' = beta2*v + one_m_beta2*g~^2, Adagrad being the case (1, 1)
+        if (h->opt == PO_RMSPROP && (h->beta2 < 0 || h->beta2 >= 1)) return fail(PO_EINVAL, "alpha must be in [0,1)");
+        c.beta2 = h->opt == PO_RMSPROP ? (float)h->beta2 : 1.f;
+        c.one_m_beta2 = h->opt == PO_RMSPROP ? (float)(1.0 - h->beta2) : 1.f;
+        c.inv_bc1 = 1.f;
+        c.inv_sqrt_bc2 = 1.f;
+        c.eps = (float)h->eps;
         c.wd_coupled = (float)h->weight_decay;
     } else {
         if (h->beta1 < 0 || h->beta1 >= 1 || h->beta2 < 0 || h->beta2 >= 1) return fail(PO_EINVAL, "betas must be in [0,1)");
@@ -293,7 +320,8 @@ try {
     if (!out) return fail(PO_EINVAL, "out is NULL");
     *out = nullptr;
     if (n_tensors < 0) return fail(PO_EINVAL, "n_tensors < 0");
-    if (n_tensors > 0 && (!numel || !W || !g || !m || !What)) return fail(PO_EINVAL, "a required pointer array is NULL");
+    if (n_tensors > 0 && (!numel || !W || !g || !What)) return fail(PO_EINVAL, "a required pointer array is NULL");
+    if (n_tensors > 0 && !m && !v) return fail(PO_EINVAL, "a plan needs at least one of m and v");
     if (what_dtype != PO_WHAT_F32 && what_dtype != PO_WHAT_BF16) return fail(PO_EINVAL, "unknown what_dtype %d", what_dtype);
     if (grad_dtype != PO_GRAD_F32 && grad_dtype != PO_GRAD_BF16) return fail(PO_EINVAL, "unknown grad_dtype %d", grad_dtype);
     const uintptr_t what_mask = what_dtype == PO_WHAT_BF16 ? 1u : 3u;
@@ -302,9 +330,9 @@ try {
     for (int64_t i = 0; i < n_tensors; ++i) {
         if (numel[i] < 0) return fail(PO_EINVAL, "numel[%lld] < 0", (long long)i);
         if (numel[i] == 0) continue;
-        if (!W[i] || !g[i] || !m[i] || !What[i] || (v && !v[i]))
+        if (!W[i] || !g[i] || !What[i] || (m && !m[i]) || (v && !v[i]))
             return fail(PO_EINVAL, "tensor %lld has a NULL buffer", (long long)i);
-        if (((uintptr_t)W[i] | (uintptr_t)m[i] | (v ? (uintptr_t)v[i] : 0)) & 3u)
+        if (((uintptr_t)W[i] | (m ? (uintptr_t)m[i] : 0) | (v ? (uintptr_t)v[i] : 0)) & 3u)
             return fail(PO_EALIGN, "tensor %lld: fp32 buffer not 4-byte aligned", (long long)i);
         if ((uintptr_t)g[i] & grad_mask) return fail(PO_EALIGN, "tensor %lld: g not aligned to its element", (long long)i);
         if ((uintptr_t)What[i] & what_mask) return fail(PO_EALIGN, "tensor %lld: What not aligned to its element", (long long)i);
@@ -319,11 +347,12 @@ try {
     p->what_dtype = what_dtype;
     p->grad_dtype = grad_dtype;
     p->has_v = (v != nullptr);
+    p->has_m = (m != nullptr);
     p->numel.assign(numel, numel + n_tensors);
     p->descs.resize((size_t)n_tensors);
     for (int64_t i = 0; i < n_tensors; ++i) {
         po_tensor_desc& d = p->descs[(size_t)i];
-        d.W = W[i]; d.g = g[i]; d.m = m[i]; d.v = v ? v[i] : nullptr; d.What = What[i];
+        d.W = W[i]; d.g = g[i]; d.m = m ? m[i] : nullptr; d.v = v ? v[i] : nullptr; d.What = What[i];
         d.numel = numel[i]; d.flags = 0; d.pad = 0;
     }
     int rc = check_disjoint(p);
@@ -381,6 +410,7 @@ try {
     if (!p) return fail(PO_EINVAL, "plan is NULL");
     if (which < 0 || which > 4) return fail(PO_EINVAL, "which must be 0..4");
     if (which == 3 && !p->has_v) return fail(PO_EINVAL, "plan has no v column");
+    if (which == 2 && !p->has_m) return fail(PO_EINVAL, "plan has no m column");
     if (p->n_tensors > 0 && !ptrs) return fail(PO_EINVAL, "ptrs is NULL");
     const uintptr_t mask = ((which == 4 && p->what_dtype == PO_WHAT_BF16) || (which == 1 && p->grad_dtype == PO_GRAD_BF16)) ? 1u : 3u;
     for (int64_t i = 0; i < p->n_tensors; ++i) {
@@ -486,7 +516,8 @@ int pipeoptim_step_predict(const po_plan* p, const po_hyper* h, int64_t t, int32
     po_coeffs c;
     int rc = pipeoptim_coefficients(h, t, s, &c);
     if (rc != PO_OK) return rc;
-    if (h->opt != PO_SGDM && !p->has_v) return fail(PO_EINVAL, "Adam/AdamW needs a plan created with v");
+    rc = check_state(p, h->opt);
+    if (rc != PO_OK) return rc;
     if (p->chunks.empty()) return PO_OK;
     hipError_t e = po_launch_step_predict(h->opt, p->what_dtype, p->grad_dtype, p->launch, p->d_descs, p->d_chunks,
                                           (uint32_t)p->chunks.size(), c, static_cast<hipStream_t>(hip_stream));
@@ -500,7 +531,10 @@ int pipeoptim_predict(const po_plan* p, const po_hyper* h, int64_t t, int32_t s,
     po_coeffs c;
     int rc = pipeoptim_coefficients(h, t, s, &c);
     if (rc != PO_OK) return rc;
-    if (h->opt != PO_SGDM && !p->has_v) return fail(PO_EINVAL, "Adam/AdamW needs a plan created with v");
+    if (h->opt > PO_ADAMW)
+        return fail(PO_EINVAL, "optimizer %d: the direction needs the gradient, there is no prediction from the state alone", h->opt);
+    rc = check_state(p, h->opt);
+    if (rc != PO_OK) return rc;
     if (p->chunks.empty()) return PO_OK;
     hipError_t e = po_launch_predict(h->opt, p->what_dtype, p->predict_launch, p->d_descs, p->d_chunks,
                                      (uint32_t)p->chunks.size(), c, static_cast<hipStream_t>(hip_stream));

@@ -12,6 +12,8 @@
 //     r  = (m'*inv_bc1) / (sqrt(v')*inv_sqrt_bc2 + eps)      (SGDM: r = m')
 //     W'   = W - lr  *(r + wd_step*W)
 //     What = W - s_lr*(r + wd_pred*W)      (s == 0: What = W)
+//   and by the same recipe, beyond Table 1: Nesterov (m' = u*m + g~, r = g~ + u*m'), RMSprop and Adagrad
+//   (v' = b2*v + c2*g~*g~ with (b2, c2) = (alpha, 1-alpha) or (1, 1), r = g~ / (sqrt(v') + eps)).
 //
 // Work decomposition.  The host's chunk table lists (tensor, chunk) pairs at a
 // coarse granularity (chunk_elems); the grid has one small workgroup per TILE
@@ -43,6 +45,14 @@ typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 constexpr int CP_NT = 2, CP_SC1 = 16;
 
 enum { PO_KERNEL_FUSED = 0, PO_KERNEL_PREDICT = 1 };
+
+// Kernel-side optimizer families: the three rows of Table 1, Nesterov, and one for RMSprop and Adagrad
+// (which differ only in two coefficients).  Which state streams a family reads and rewrites:
+enum { K_SGDM = PO_SGDM, K_ADAM = PO_ADAM, K_ADAMW = PO_ADAMW, K_NESTEROV = PO_NESTEROV, K_RMS = PO_RMSPROP };
+template <int OPT> struct Streams {
+    static constexpr bool M = OPT != K_RMS;
+    static constexpr bool V = OPT == K_ADAM || OPT == K_ADAMW || OPT == K_RMS;
+};
 
 // launch.cache_policy -> bits for: LG loads of g (read once), LS loads of W, m, v (rewritten right after),
 // SS stores of W', m', v', SH stores of What (write-only).  Mixed per-stream settings (plain loads for the
@@ -84,19 +94,31 @@ __device__ __forceinline__ void update_element(const po_coeffs& c, float W, floa
                                                float& W_new, float& W_hat)
 {
     float r;
-    if constexpr (OPT == PO_SGDM) {
+    if constexpr (OPT == K_SGDM) {
         float gt = fmaf(c.wd_coupled, W, g);
         m = fmaf(c.beta1, m, c.grad_scale * gt);
         r = m;
         W_new = fmaf(-c.lr, r, W);
         W_hat = fmaf(-c.s_lr, r, W);
+    } else if constexpr (OPT == K_NESTEROV) {
+        float gt = fmaf(c.wd_coupled, W, g);
+        m = fmaf(c.beta1, m, gt);
+        r = fmaf(c.beta1, m, gt);
+        W_new = fmaf(-c.lr, r, W);
+        W_hat = fmaf(-c.s_lr, r, W);
+    } else if constexpr (OPT == K_RMS) {
+        float gt = fmaf(c.wd_coupled, W, g);
+        v = fmaf(c.beta2, v, c.one_m_beta2 * (gt * gt));
+        r = gt / (sqrtf(v) + c.eps);
+        W_new = fmaf(-c.lr, r, W);
+        W_hat = fmaf(-c.s_lr, r, W);
     } else {
-        float gt = (OPT == PO_ADAM) ? fmaf(c.wd_coupled, W, g) : g;
+        float gt = (OPT == K_ADAM) ? fmaf(c.wd_coupled, W, g) : g;
         m = fmaf(c.beta1, m, c.grad_scale * gt);
         v = fmaf(c.beta2, v, c.one_m_beta2 * (gt * gt));
         float denom = fmaf(sqrtf(v), c.inv_sqrt_bc2, c.eps);
         r = (m * c.inv_bc1) / denom;
-        if constexpr (OPT == PO_ADAMW) {
+        if constexpr (OPT == K_ADAMW) {
             W_new = fmaf(-c.lr, fmaf(c.wd_step, W, r), W);
             W_hat = fmaf(-c.s_lr, fmaf(c.wd_pred, W, r), W);
         } else {
@@ -190,7 +212,7 @@ template <int OPT, bool BF16, bool GB16, int UNROLL, int POL>
 __global__ __launch_bounds__(256) void step_predict_kernel(KArgs)
 {
     constexpr int LG = Policy<POL>::LG, LS = Policy<POL>::LS, SS = Policy<POL>::SS, SH = Policy<POL>::SH;
-    constexpr bool ADAM = OPT != PO_SGDM;
+    constexpr bool HAS_M = Streams<OPT>::M, HAS_V = Streams<OPT>::V;
 
     const KArgs a = load_kargs();
     const po_coeffs& c = a.c;
@@ -203,8 +225,9 @@ __global__ __launch_bounds__(256) void step_predict_kernel(KArgs)
     const __amdgpu_buffer_rsrc_t rW = make_rsrc(d->W + off, len * 4u);
     const __amdgpu_buffer_rsrc_t rg = GB16 ? make_rsrc(static_cast<const uint16_t*>(d->g) + off, len * 2u)
                                            : make_rsrc(static_cast<const float*>(d->g) + off, len * 4u);
-    const __amdgpu_buffer_rsrc_t rm = make_rsrc(d->m + off, len * 4u);
-    const __amdgpu_buffer_rsrc_t rv = make_rsrc(ADAM ? d->v + off : d->m + off, len * 4u);
+    // a family without a stream never touches its resource (W stands in so that the descriptor is valid)
+    const __amdgpu_buffer_rsrc_t rm = make_rsrc((HAS_M ? d->m : d->W) + off, len * 4u);
+    const __amdgpu_buffer_rsrc_t rv = make_rsrc((HAS_V ? d->v : d->W) + off, len * 4u);
     const __amdgpu_buffer_rsrc_t rh = BF16 ? make_rsrc(static_cast<uint16_t*>(d->What) + off, len * 2u)
                                            : make_rsrc(static_cast<float*>(d->What) + off, len * 4u);
     const uint32_t tid = threadIdx.x, nthr = a.tile / (4u * UNROLL);
@@ -222,8 +245,8 @@ __global__ __launch_bounds__(256) void step_predict_kernel(KArgs)
             } else {
                 g[u] = __builtin_amdgcn_raw_buffer_load_b128(rg, b, 0, LG);
             }
-            m[u] = __builtin_amdgcn_raw_buffer_load_b128(rm, b, 0, LS);
-            if constexpr (ADAM) v[u] = __builtin_amdgcn_raw_buffer_load_b128(rv, b, 0, LS);
+            if constexpr (HAS_M) m[u] = __builtin_amdgcn_raw_buffer_load_b128(rm, b, 0, LS);
+            if constexpr (HAS_V) v[u] = __builtin_amdgcn_raw_buffer_load_b128(rv, b, 0, LS);
         }
 #pragma unroll
         for (int u = 0; u < UNROLL; ++u) {
@@ -231,16 +254,16 @@ __global__ __launch_bounds__(256) void step_predict_kernel(KArgs)
             u32x4 Wn, Wh;
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
-                float mm = as_f(m[u][e]), vv = ADAM ? as_f(v[u][e]) : 0.f, wn, wh;
+                float mm = HAS_M ? as_f(m[u][e]) : 0.f, vv = HAS_V ? as_f(v[u][e]) : 0.f, wn, wh;
                 update_element<OPT>(c, as_f(W[u][e]), as_f(g[u][e]), mm, vv, wn, wh);
-                m[u][e] = as_u(mm);
-                if constexpr (ADAM) v[u][e] = as_u(vv);
+                if constexpr (HAS_M) m[u][e] = as_u(mm);
+                if constexpr (HAS_V) v[u][e] = as_u(vv);
                 Wn[e] = as_u(wn);
                 Wh[e] = as_u(wh);
             }
             __builtin_amdgcn_raw_buffer_store_b128(Wn, rW, b, 0, SS);
-            __builtin_amdgcn_raw_buffer_store_b128(m[u], rm, b, 0, SS);
-            if constexpr (ADAM) __builtin_amdgcn_raw_buffer_store_b128(v[u], rv, b, 0, SS);
+            if constexpr (HAS_M) __builtin_amdgcn_raw_buffer_store_b128(m[u], rm, b, 0, SS);
+            if constexpr (HAS_V) __builtin_amdgcn_raw_buffer_store_b128(v[u], rv, b, 0, SS);
             if constexpr (BF16) {
                 u32x2 p = {pack_bf16x2(as_f(Wh[0]), as_f(Wh[1])), pack_bf16x2(as_f(Wh[2]), as_f(Wh[3]))};
                 __builtin_amdgcn_raw_buffer_store_b64(p, rh, b >> 1, 0, SH);
@@ -255,13 +278,13 @@ __global__ __launch_bounds__(256) void step_predict_kernel(KArgs)
             float W = as_f(__builtin_amdgcn_raw_buffer_load_b32(rW, b, 0, LS));
             float g = GB16 ? as_f((uint32_t)__builtin_amdgcn_raw_buffer_load_b16(rg, i * 2u, 0, LG) << 16)
                            : as_f(__builtin_amdgcn_raw_buffer_load_b32(rg, b, 0, LG));
-            float mm = as_f(__builtin_amdgcn_raw_buffer_load_b32(rm, b, 0, LS));
-            float vv = ADAM ? as_f(__builtin_amdgcn_raw_buffer_load_b32(rv, b, 0, LS)) : 0.f;
+            float mm = HAS_M ? as_f(__builtin_amdgcn_raw_buffer_load_b32(rm, b, 0, LS)) : 0.f;
+            float vv = HAS_V ? as_f(__builtin_amdgcn_raw_buffer_load_b32(rv, b, 0, LS)) : 0.f;
             float wn, wh;
             update_element<OPT>(c, W, g, mm, vv, wn, wh);
             __builtin_amdgcn_raw_buffer_store_b32(as_u(wn), rW, b, 0, SS);
-            __builtin_amdgcn_raw_buffer_store_b32(as_u(mm), rm, b, 0, SS);
-            if constexpr (ADAM) __builtin_amdgcn_raw_buffer_store_b32(as_u(vv), rv, b, 0, SS);
+            if constexpr (HAS_M) __builtin_amdgcn_raw_buffer_store_b32(as_u(mm), rm, b, 0, SS);
+            if constexpr (HAS_V) __builtin_amdgcn_raw_buffer_store_b32(as_u(vv), rv, b, 0, SS);
             if constexpr (BF16) __builtin_amdgcn_raw_buffer_store_b16(to_bf16(wh), rh, i * 2u, 0, SH);
             else __builtin_amdgcn_raw_buffer_store_b32(as_u(wh), rh, b, 0, SH);
         }
@@ -346,9 +369,12 @@ hipError_t launch_one(const po_launch& L, const po_tensor_desc* descs, const po_
     a.xcd_stride = L.xcd_remap ? (uint32_t)(grid >> 3) : 0u;
     a.tile = tile;
     a.c = c;
-    auto kernel = KIND == PO_KERNEL_PREDICT ? predict_kernel<OPT, BF16, UNROLL, POL>
-                                            : step_predict_kernel<OPT, BF16, GB16, UNROLL, POL>;
-    hipLaunchKernelGGL(kernel, dim3((uint32_t)grid), dim3(L.block), (size_t)L.lds_bytes, stream, a);
+    if constexpr (KIND == PO_KERNEL_PREDICT)
+        hipLaunchKernelGGL((predict_kernel<OPT, BF16, UNROLL, POL>), dim3((uint32_t)grid), dim3(L.block),
+                           (size_t)L.lds_bytes, stream, a);
+    else
+        hipLaunchKernelGGL((step_predict_kernel<OPT, BF16, GB16, UNROLL, POL>), dim3((uint32_t)grid), dim3(L.block),
+                           (size_t)L.lds_bytes, stream, a);
     return hipGetLastError();
 }
 
@@ -418,6 +444,9 @@ hipError_t po_launch_step_predict(int opt, int what_dtype, int grad_dtype, const
     case PO_SGDM: return dispatch_dtype<PO_KERNEL_FUSED, PO_SGDM>(what_dtype, grad_dtype, L, d_descs, d_chunks, n_chunks, c, stream);
     case PO_ADAM: return dispatch_dtype<PO_KERNEL_FUSED, PO_ADAM>(what_dtype, grad_dtype, L, d_descs, d_chunks, n_chunks, c, stream);
     case PO_ADAMW: return dispatch_dtype<PO_KERNEL_FUSED, PO_ADAMW>(what_dtype, grad_dtype, L, d_descs, d_chunks, n_chunks, c, stream);
+    case PO_NESTEROV: return dispatch_dtype<PO_KERNEL_FUSED, K_NESTEROV>(what_dtype, grad_dtype, L, d_descs, d_chunks, n_chunks, c, stream);
+    case PO_RMSPROP:
+    case PO_ADAGRAD: return dispatch_dtype<PO_KERNEL_FUSED, K_RMS>(what_dtype, grad_dtype, L, d_descs, d_chunks, n_chunks, c, stream);
     }
     return hipErrorInvalidValue;
 }

@@ -7,15 +7,15 @@ from . import binding
 
 
 class Stage:
-    """Holds flat fp32 W, g, m, v tensors and the What buffers, plus the plan over their addresses.
+    """Holds flat fp32 W, g, m, v tensors (m or v may be None) and the What buffers, plus the plan over their addresses.
 
     All arithmetic happens inside ``pipeoptim_step_predict``; this class only keeps the
     tensors alive, allocates What, and passes pointers and the current stream.
     """
 
-    def __init__(self, W: List[torch.Tensor], g: List[torch.Tensor], m: List[torch.Tensor],
+    def __init__(self, W: List[torch.Tensor], g: List[torch.Tensor], m: Optional[List[torch.Tensor]],
                  v: Optional[List[torch.Tensor]], what_dtype: str):
-        for lst in (W, m) + ((v,) if v is not None else ()):
+        for lst in (W,) + ((m,) if m is not None else ()) + ((v,) if v is not None else ()):
             for x in lst:
                 if x.dtype != torch.float32 or not x.is_contiguous() or x.device.type != "cuda":
                     raise ValueError("W, m, v must be contiguous fp32 tensors on the GPU")
@@ -31,7 +31,8 @@ class Stage:
         self.What = [torch.empty(x.numel(), dtype=tdt, device=x.device) for x in W]
         self.numel = [x.numel() for x in W]
         ptrs = lambda lst: [x.data_ptr() for x in lst]
-        self.plan = binding.Plan(self.numel, ptrs(W), ptrs(g), ptrs(m), ptrs(v) if v is not None else None,
+        self.plan = binding.Plan(self.numel, ptrs(W), ptrs(g), ptrs(m) if m is not None else None,
+                                 ptrs(v) if v is not None else None,
                                  ptrs(self.What), what_dtype, torch.cuda.current_stream().cuda_stream,
                                  grad_dtype=self.grad_dtype)
 

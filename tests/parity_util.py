@@ -16,6 +16,10 @@ magnitude (the standard running-error bound; about 8 roundings of 2^-24 = 6e-8 f
               g + wd_c*W cancels (then v_abs > v'), which only Adam with coupled decay can do.
     W'      : |W| + lr*dW_abs
     What    : |W| + s*lr*dW_abs   (AdamW without decay in the prediction: dW_abs without wd*|W|)
+The optimizers beyond Table 1 follow the same construction:
+    Nesterov: m_abs = u*|m| + g~_abs;  dW_abs = g~_abs + u*m_abs
+    RMSprop : v_abs = alpha*v + (1-alpha)*g~_abs^2;  Adagrad: v_abs = v + g~_abs^2
+              dW_abs = (g~_abs + |g~_ref|*(v_abs/v'_ref - 1)/2) / (sqrt(v'_ref) + eps)
 For almost every element scale equals |result| to within a small factor; it differs only
 where terms cancel.
   bf16 What: at most one bf16 unit in the last place (bit patterns compared in
@@ -30,7 +34,10 @@ from paper_2312_00839_amd import binding
 from paper_2312_00839_amd.stage import Stage
 
 REL_TOL = 1e-6
-OPT_CODE = {"sgdm": oracle.SGDM, "adam": oracle.ADAM, "adamw": oracle.ADAMW}
+OPT_CODE = {"sgdm": oracle.SGDM, "adam": oracle.ADAM, "adamw": oracle.ADAMW, "nesterov": oracle.NESTEROV,
+            "rmsprop": oracle.RMSPROP, "adagrad": oracle.ADAGRAD}
+HAS_M = {"sgdm", "adam", "adamw", "nesterov"}      # optimizers with a momentum buffer
+HAS_V = {"adam", "adamw", "rmsprop", "adagrad"}    # optimizers with a second-moment buffer
 
 
 def bf16_order(bits_u16):
@@ -60,16 +67,26 @@ def scales(kind, hp, t, s, inp, ref, decay_in_prediction=True):
     """Per-element reference magnitudes (see the module docstring)."""
     W = np.abs(inp["W"].astype(np.float64))
     g = np.abs(inp["g"].astype(np.float64))
-    m = np.abs(inp["m"].astype(np.float64))
     wd = hp["weight_decay"]
-    wd_c = wd if kind in ("sgdm", "adam") else 0.0
-    gs = (1.0 - hp["beta2"]) if kind == "sgdm" else (1.0 - hp["beta1"])
+    wd_c = 0.0 if kind == "adamw" else wd
     g_abs = g + wd_c * W
-    m_abs = hp["beta1"] * m + gs * g_abs
-    out = {"m": m_abs}
+    out = {}
     if kind == "sgdm":
-        d_step = d_pred = m_abs
+        out["m"] = hp["beta1"] * np.abs(inp["m"].astype(np.float64)) + (1.0 - hp["beta2"]) * g_abs
+        d_step = d_pred = out["m"]
+    elif kind == "nesterov":
+        out["m"] = hp["beta1"] * np.abs(inp["m"].astype(np.float64)) + g_abs
+        d_step = d_pred = g_abs + hp["beta1"] * out["m"]
+    elif kind in ("rmsprop", "adagrad"):
+        v = inp["v"].astype(np.float64)
+        out["v"] = (hp["beta2"] * v + (1.0 - hp["beta2"]) * g_abs * g_abs) if kind == "rmsprop" else v + g_abs * g_abs
+        v_ref = ref["v"].astype(np.float64)
+        amp = out["v"] / np.maximum(v_ref, 1e-300)                      # 1 unless g + wd*W cancelled
+        g_ref = np.abs(inp["g"].astype(np.float64) + wd_c * inp["W"].astype(np.float64))
+        d_step = d_pred = (g_abs + 0.5 * g_ref * np.maximum(amp - 1.0, 0.0)) / (np.sqrt(v_ref) + hp["eps"])
     else:
+        m_abs = hp["beta1"] * np.abs(inp["m"].astype(np.float64)) + (1.0 - hp["beta1"]) * g_abs
+        out["m"] = m_abs
         v = inp["v"].astype(np.float64)
         out["v"] = hp["beta2"] * v + (1.0 - hp["beta2"]) * g_abs * g_abs
         bc1 = 1.0 - hp["beta1"] ** t
@@ -100,8 +117,9 @@ def compare(kind, hp, t, s, inp, ref, got, what_dtype, label="", decay_in_predic
             label, name, int(bad.sum()), bad.size, report[name], int(np.argmax(ratio)))
 
     check("W", got["W"], ref["W"], sc["W"])
-    check("m", got["m"], ref["m"], sc["m"])
-    if kind != "sgdm":
+    if kind in HAS_M:
+        check("m", got["m"], ref["m"], sc["m"])
+    if kind in HAS_V:
         check("v", got["v"], ref["v"], sc["v"])
     if what_dtype == "f32":
         if s == 0:
@@ -205,7 +223,7 @@ def run_and_compare_predict(kind, hp, t, s, tensors, what_dtype, launch=None, de
 
 
 def run_oracle(kind, hp, t, s, inp, decay_in_prediction=True, nthreads=8):
-    return oracle.step_predict(OPT_CODE[kind], inp["W"], inp["g"], inp["m"], inp.get("v"),
+    return oracle.step_predict(OPT_CODE[kind], inp["W"], inp["g"], inp.get("m"), inp.get("v"),
                                lr=hp["lr"], beta1=hp["beta1"], beta2=hp["beta2"], eps=hp["eps"],
                                weight_decay=hp["weight_decay"], decay_in_prediction=decay_in_prediction,
                                t=t, s=s, nthreads=nthreads)
@@ -217,11 +235,12 @@ def make_hyper(kind, hp, decay_in_prediction=True):
 
 
 def run_and_compare_full(kind, hp, t, s, tensors, what_dtype, launch=None, decay_in_prediction=True, label=""):
-    """tensors: dict of lists of device tensors W, g, m, v (v None for sgdm).  Compares every element."""
+    """tensors: dict of lists of device tensors W, g, m, v (m or v None where the optimizer has no such state).
+    Compares every element."""
     host = [{k: host_f32(tensors[k][i]) for k in ("W", "g", "m", "v") if tensors.get(k) is not None}
             for i in range(len(tensors["W"]))]
     g_before = [raw_bits(x) for x in tensors["g"]]
-    stage = Stage(tensors["W"], tensors["g"], tensors["m"], tensors.get("v"), what_dtype)
+    stage = Stage(tensors["W"], tensors["g"], tensors.get("m"), tensors.get("v"), what_dtype)
     try:
         if launch:
             stage.plan.set_launch(**launch)
@@ -230,7 +249,7 @@ def run_and_compare_full(kind, hp, t, s, tensors, what_dtype, launch=None, decay
         reports = []
         for i, inp in enumerate(host):
             ref = run_oracle(kind, hp, t, s, inp, decay_in_prediction)
-            got = {"W": stage.W[i].cpu().numpy(), "m": stage.m[i].cpu().numpy(),
+            got = {"W": stage.W[i].cpu().numpy(), "m": stage.m[i].cpu().numpy() if stage.m is not None else None,
                    "v": stage.v[i].cpu().numpy() if stage.v is not None else None,
                    "What": what_bits(stage.What[i]) if what_dtype == "bf16" else stage.What[i].cpu().numpy()}
             # g is read-only

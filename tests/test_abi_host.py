@@ -85,6 +85,26 @@ def test_coefficients_sgdm():
     assert c.lr == _f32(0.1) and c.s_lr == _f32(0.3)
 
 
+def test_coefficients_nesterov_rmsprop_adagrad():
+    c = binding.pipeoptim_coefficients(binding.make_hyper("nesterov", 0.1, 0.9, 0.5, 123.0, 1e-4), 4, 3)
+    assert c.beta1 == _f32(0.9) and c.grad_scale == 1 and c.inv_bc1 == 1 and c.inv_sqrt_bc2 == 1 and c.eps == 0
+    assert c.wd_coupled == _f32(1e-4) and c.wd_step == 0 and c.wd_pred == 0
+    assert c.lr == _f32(0.1) and c.s_lr == _f32(0.3) and c.s_is_zero == 0
+    c = binding.pipeoptim_coefficients(binding.make_hyper("rmsprop", 0.01, 0.3, 0.99, 1e-8, 1e-3), 4, 0)
+    assert c.beta2 == _f32(0.99) and c.one_m_beta2 == _f32(1 - 0.99) and c.eps == _f32(1e-8)
+    assert c.inv_bc1 == 1 and c.inv_sqrt_bc2 == 1 and c.wd_coupled == _f32(1e-3) and c.s_is_zero == 1 and c.s_lr == 0
+    # Adagrad is the same kernel with the running sum: v' = 1*v + 1*g~^2; beta1 and beta2 are ignored, even out of range
+    c = binding.pipeoptim_coefficients(binding.make_hyper("adagrad", 0.01, 7.0, -3.0, 1e-10, 0.0), 9, 2)
+    assert c.beta2 == 1 and c.one_m_beta2 == 1 and c.eps == _f32(1e-10) and c.inv_bc1 == 1 and c.inv_sqrt_bc2 == 1
+    assert c.wd_coupled == 0 and c.s_lr == _f32(0.02)
+    for kind, kw in (("nesterov", dict(beta1=1.0)), ("rmsprop", dict(beta2=1.0)), ("rmsprop", dict(eps=-1.0))):
+        base = dict(opt=kind, lr=0.1, beta1=0.9, beta2=0.9, eps=1e-8, weight_decay=0.0)
+        base.update(kw)
+        with pytest.raises(binding.PipeOptimError) as e:
+            binding.pipeoptim_coefficients(binding.make_hyper(**base), 1, 1)
+        assert e.value.status == binding.PO_EINVAL
+
+
 @pytest.mark.parametrize("kw,t,s", [
     (dict(lr=float("nan")), 1, 1), (dict(lr=float("inf")), 1, 1), (dict(beta1=1.0), 1, 1), (dict(beta1=-0.1), 1, 1),
     (dict(beta2=1.0), 1, 1), (dict(eps=-1.0), 1, 1), (dict(weight_decay=float("nan")), 1, 1),

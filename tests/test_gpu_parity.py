@@ -25,7 +25,13 @@ HP = {
     "sgdm": dict(lr=0.1, beta1=0.9, beta2=0.0, eps=0.0, weight_decay=1e-4),
     "adam": dict(lr=1e-3, beta1=0.9, beta2=0.999, eps=1e-8, weight_decay=0.0),
     "adamw": dict(lr=1e-3, beta1=0.9, beta2=0.999, eps=1e-8, weight_decay=0.01),
+    "nesterov": dict(lr=0.1, beta1=0.9, beta2=0.0, eps=0.0, weight_decay=1e-4),
+    "rmsprop": dict(lr=1e-3, beta1=0.0, beta2=0.99, eps=1e-8, weight_decay=1e-4),
+    "adagrad": dict(lr=1e-2, beta1=0.0, beta2=0.0, eps=1e-10, weight_decay=0.0),
 }
+TABLE1 = ["sgdm", "adam", "adamw"]                      # the rows of the paper's Table 1
+BEYOND = ["nesterov", "rmsprop", "adagrad"]             # further optimizers by the same recipe
+NO_M, NO_V = ("rmsprop", "adagrad"), ("sgdm", "nesterov")
 
 
 def _say(msg):
@@ -44,12 +50,13 @@ def _rand_list(sizes, seed, kind, sw=0.02, sg=1e-3, sm=1e-4, sv=1e-3, offset=0, 
             x = x * x
         return x[offset:]
 
-    out = {"W": [], "g": [], "m": [], "v": None if kind == "sgdm" else []}
+    out = {"W": [], "g": [], "m": None if kind in NO_M else [], "v": None if kind in NO_V else []}
     for n in sizes:
         out["W"].append(draw(n, sw))
         gfull = draw(n + offset, sg).to(grad_dtype)     # a second offset keeps bf16 views off 16-byte alignment too
         out["g"].append(gfull[offset:])
-        out["m"].append(draw(n, sm))
+        if out["m"] is not None:
+            out["m"].append(draw(n, sm))
         if out["v"] is not None:
             out["v"].append(draw(n, sv, True))
     return out
@@ -76,13 +83,18 @@ def test_hand_cases_on_gpu(head, rows, what_dtype):
     _say("hand case %s %s" % (name, what_dtype))
     hp = dict(lr=float(lr), beta1=float(b1), beta2=float(b2), eps=float(eps), weight_decay=float(wd))
     col = lambda j, src: torch.tensor([float(r[src][j]) for r in rows], dtype=torch.float32, device=DEV)
-    tensors = {"W": [col(0, 0)], "g": [col(1, 0)], "m": [col(2, 0)], "v": None if kind == "sgdm" else [col(3, 0)]}
+    tensors = {"W": [col(0, 0)], "g": [col(1, 0)], "m": None if kind in NO_M else [col(2, 0)],
+               "v": None if kind in NO_V else [col(3, 0)]}
     expect_W, expect_What = col(0, 1).cpu().numpy(), col(3, 1).cpu().numpy()
     stage = Stage(tensors["W"], tensors["g"], tensors["m"], tensors["v"], what_dtype)
     stage.step_predict(make_hyper(kind, hp, bool(int(dip))), int(t), int(s))
     torch.cuda.synchronize()
     # dyadic values: fp32 arithmetic is exact apart from sqrt/divide, which are within 1 ulp
     np.testing.assert_allclose(stage.W[0].cpu().numpy(), expect_W, rtol=3e-7, atol=0)
+    if stage.m is not None:
+        np.testing.assert_allclose(stage.m[0].cpu().numpy(), col(1, 1).cpu().numpy(), rtol=3e-7, atol=0)
+    if stage.v is not None:
+        np.testing.assert_allclose(stage.v[0].cpu().numpy(), col(2, 1).cpu().numpy(), rtol=3e-7, atol=0)
     if what_dtype == "f32":
         np.testing.assert_allclose(stage.What[0].cpu().numpy(), expect_What, rtol=3e-7, atol=1e-7)
     else:
@@ -113,7 +125,7 @@ def test_predict_hand_cases_on_gpu(head, rows, what_dtype):
     stage.close()
 
 
-@pytest.mark.parametrize("kind", ["sgdm", "adam", "adamw"])
+@pytest.mark.parametrize("kind", TABLE1 + BEYOND)
 @pytest.mark.parametrize("what_dtype", ["f32", "bf16"])
 def test_tiny_tensors_all_lengths_up_to_16(kind, what_dtype):
     _say("tiny %s %s" % (kind, what_dtype))
@@ -255,6 +267,69 @@ def test_set_pointers_swaps_gradient_buffers():
                "What": st.What[i].cpu().numpy()}
         compare(kind, hp, 3, 2, host[i], ref, got, "f32", "set_pointers %d" % i)
     st.close()
+
+
+# --------------------------------------------------------------------------- optimizers beyond Table 1
+@pytest.mark.parametrize("kind", BEYOND)
+@pytest.mark.parametrize("what_dtype", ["f32", "bf16"])
+def test_further_optimizers_ragged_unaligned_bf16_gradients(kind, what_dtype):
+    _say("further optimizer %s %s" % (kind, what_dtype))
+    for launch in LAUNCHES:
+        run_and_compare_full(kind, HP[kind], 100, 3, _rand_list(RAGGED, 7, kind), what_dtype, launch=launch,
+                             label="%s ragged %s" % (kind, launch))
+    for offset in (1, 2, 3):
+        run_and_compare_full(kind, HP[kind], 9, 2, _rand_list([5, 4096, 9001], 11, kind, offset=offset), what_dtype,
+                             label="%s unaligned" % kind)
+    bf = torch.bfloat16
+    for launch in LAUNCHES[::3]:
+        run_and_compare_full(kind, HP[kind], 100, 3, _rand_list(RAGGED, 9, kind, grad_dtype=bf), what_dtype,
+                             launch=launch, label="%s bf16-g ragged %s" % (kind, launch))
+    run_and_compare_full(kind, HP[kind], 9, 0, _rand_list([5, 4096, 9001], 11, kind, offset=1, grad_dtype=bf),
+                         what_dtype, label="%s bf16-g unaligned s=0" % kind)
+
+
+def test_further_optimizers_config_shapes_full():
+    # config 2's ragged ResNet-shaped list under Nesterov, config 3's BERT-shaped list under RMSprop and Adagrad
+    for cfg, kind, s in ((2, "nesterov", 3), (3, "rmsprop", 2), (3, "adagrad", 5)):
+        wl = workload(cfg)
+        _say("%s on config %d shapes, full compare" % (kind, cfg))
+        tensors = make_inputs(wl, DEV)
+        if kind in NO_M:
+            tensors["m"] = None
+        if kind in NO_V:
+            tensors["v"] = None
+        run_and_compare_full(kind, HP[kind], wl.t, s, tensors, wl.what_dtype, label="%s config %d" % (kind, cfg))
+
+
+def test_further_optimizers_state_and_predict_errors():
+    _say("further optimizers: missing state, predict rejected")
+    a = _rand_list([1000], 19, "rmsprop")                  # plan with v only
+    st = Stage(a["W"], a["g"], None, a["v"], "f32")
+    before = a["W"][0].clone()
+    for kind in ("sgdm", "nesterov", "adam", "adamw"):     # all need m
+        with pytest.raises(binding.PipeOptimError) as e:
+            st.step_predict(make_hyper(kind, HP[kind]), 1, 1)
+        assert e.value.status == binding.PO_EINVAL
+    for kind in BEYOND:                                    # their direction needs the gradient
+        with pytest.raises(binding.PipeOptimError) as e:
+            st.predict(make_hyper(kind, HP[kind]), 1, 1)
+        assert e.value.status == binding.PO_EINVAL
+    with pytest.raises(binding.PipeOptimError) as e:
+        st.plan.set_pointers(2, [a["v"][0].data_ptr()])    # no m column to replace
+    assert e.value.status == binding.PO_EINVAL
+    b = _rand_list([1000], 19, "nesterov")                 # plan with m only
+    s2 = Stage(b["W"], b["g"], b["m"], None, "f32")
+    for kind in ("rmsprop", "adagrad"):
+        with pytest.raises(binding.PipeOptimError) as e:
+            s2.step_predict(make_hyper(kind, HP[kind]), 1, 1)
+        assert e.value.status == binding.PO_EINVAL
+    with pytest.raises(binding.PipeOptimError) as e:
+        binding.Plan([8], [a["W"][0].data_ptr()], [a["g"][0].data_ptr()], None, None, [before.data_ptr()], "f32")
+    assert e.value.status == binding.PO_EINVAL             # neither m nor v
+    torch.cuda.synchronize()
+    assert torch.equal(a["W"][0], before)                  # nothing was launched
+    st.close()
+    s2.close()
 
 
 # --------------------------------------------------------------------------- bf16 gradients
@@ -603,16 +678,19 @@ def test_step_predict_can_be_captured_and_replayed():
 
 
 # --------------------------------------------------------------------------- seeded random cases
-@pytest.mark.parametrize("case", range(48))
+@pytest.mark.parametrize("case", range(72))
 def test_random_cases(case):
     """Seeded random hyper-parameters, sizes, dtypes and launch shapes; fused and prediction-only calls."""
     rng = np.random.default_rng(7000 + case)
-    kind = ("sgdm", "adam", "adamw")[case % 3]
+    if case < 48:
+        kind = TABLE1[case % 3]
+    else:
+        kind = BEYOND[case % 3]
     what_dtype = ("f32", "bf16")[(case // 3) % 2]
     grad_dtype = (torch.float32, torch.bfloat16)[(case // 6) % 2]
     lr = float(10 ** rng.uniform(-5, -0.5))
     wd = float(rng.choice([0.0, 10 ** rng.uniform(-5, -0.5)]))
-    if kind == "sgdm":
+    if kind in ("sgdm", "nesterov"):
         hp = dict(lr=lr, beta1=float(rng.uniform(0, 0.99)), beta2=float(rng.choice([0.0, rng.uniform(0, 0.9)])),
                   eps=0.0, weight_decay=wd)
     else:
@@ -632,6 +710,8 @@ def test_random_cases(case):
     _say("random case %d: %s %s g=%s t=%d s=%d dip=%d sizes=%s launch=%s" % (case, kind, what_dtype, grad_dtype, t, s, dip, sizes, launch))
     run_and_compare_full(kind, hp, t, s, _rand_list(sizes, 500 + case, kind, grad_dtype=grad_dtype, **sig), what_dtype,
                          launch=launch, decay_in_prediction=dip, label="random %d" % case)
+    if kind in BEYOND:
+        return                                           # no prediction from the state alone for these
     run_and_compare_predict(kind, hp, t, s, _rand_list(sizes, 600 + case, kind, **sig), what_dtype,
                             launch=launch, decay_in_prediction=dip, label="random predict %d" % case)
 
