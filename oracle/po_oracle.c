@@ -192,7 +192,7 @@ int po_oracle_step_predict(int opt, double lr, double beta1, double beta2, doubl
 
 /*
  * Prediction alone, from the cached optimizer state (paper Algorithm 1 computes
- * dW_t "by a lookup of Table 1" and applies Eq. 5 ahead of the forward pass; the
+ * dW_t from Table 1's row for the optimizer in use and applies Eq. 5 ahead of the forward pass; the
  * state was produced by the optimizer step of iteration t).  No gradient is
  * read and nothing but What is written:
  *     SGDM : dW = m
