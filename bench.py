@@ -188,7 +188,7 @@ def main():
 
     out = {
         "metric": "params/sec, weight prediction from cached state, 1 GPU" if predict_only
-                  else "params/sec, fused optimizer step + weight prediction, 1 GPU",
+                  else "params/sec and achieved HBM GB/s (% of peak), fused Adam step+predict, 1 GPU",
         "value": N * K / wall,
         "unit": "params/s",
         "n_gpus": 1, "steps": K, "warmup": args.warmup,
@@ -197,7 +197,11 @@ def main():
         "dtype": "f32", "data": "synthetic",
         "config": {"workload": "config %d: %s, %s, t=%d.., s=%d, %s What" % (wl.config, wl.name, wl.optimizer, wl.t, s_cfg, wl.what_dtype),
                    "n_params": N, "n_tensors": len(wl.shapes), "bytes_per_param": bytes_per_param, "mode": args.mode, "grad_dtype": args.grad_dtype,
-                   "launch": {f: getattr(L, f) for f, _ in L._fields_}, "n_chunks": stage.plan.info()["n_chunks"]},
+                   "launch": dict({f: getattr(L, f) for f, _ in L._fields_},
+                                  lds_bytes_in_effect=L.lds_bytes if L.lds_bytes >= 0 else binding.pipeoptim_auto_lds_bytes(
+                                      binding.PO_KERNEL_KIND_PREDICT if predict_only else binding.PO_KERNEL_KIND_FUSED,
+                                      wl.optimizer, N)),
+                   "n_chunks": stage.plan.info()["n_chunks"]},
         "kernel_ms": {"avg": avg_ms, "median": med_ms, "min": per_launch_ms[0], "max": per_launch_ms[-1]},
         "achieved_hbm_GBps": achieved,
         "pct_of_hbm_peak": 100.0 * achieved / HBM_PEAK_GBPS,

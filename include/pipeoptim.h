@@ -98,7 +98,10 @@ typedef struct po_chunk {
  *   cache_policy 0: plain loads and stores; 1: streaming (nt) loads; 2: streaming stores;
  *                3: both; 4: streaming loads, streaming + write-through (nt sc1) stores
  *   lds_bytes    0..65536, unused LDS reserved per workgroup to cap how many workgroups a CU
- *                holds at once (160 KiB of LDS per CU); 0 = no cap
+ *                holds at once (160 KiB of LDS per CU); 0 = no cap; PO_LDS_AUTO (-1, the default of
+ *                both kernels on all but small stages) = chosen at each call from the kernel, the
+ *                number of state streams of the optimizer in use and the size of the stage
+ *                (pipeoptim_auto_lds_bytes tells the value)
  *   chunk_elems  granularity of the chunk table: block*4*unroll times a power of two, at most 2^30
  *   xcd_remap    0 or 1: 1 hands each of the chip's 8 XCDs (workgroup id mod 8) a contiguous
  *                eighth of the work instead of every eighth tile
@@ -113,6 +116,9 @@ typedef struct po_launch {
     int32_t xcd_remap;
     int32_t reserved;     /* must be 0 */
 } po_launch;
+
+#define PO_LDS_AUTO (-1)
+enum { PO_KERNEL_KIND_FUSED = 0, PO_KERNEL_KIND_PREDICT = 1 };
 
 typedef struct po_plan po_plan;   /* opaque */
 
@@ -156,6 +162,9 @@ int pipeoptim_plan_set_pointers(po_plan* plan, int32_t which, void* const* ptrs)
  * chunk_elems by a power of two, its block and unroll are reset to this launch's. */
 int pipeoptim_plan_get_launch(const po_plan* plan, po_launch* out);
 int pipeoptim_plan_set_launch(po_plan* plan, const po_launch* launch);
+
+/* Host only: the lds_bytes a call resolves PO_LDS_AUTO to, for kernel (PO_KERNEL_KIND_*), optimizer and stage size. */
+int pipeoptim_auto_lds_bytes(int32_t kernel, int32_t opt, int64_t n_params, int32_t* out);
 
 /* Totals of a plan: parameters, chunk-table entries, tensors on the scalar (unaligned) path. */
 int pipeoptim_plan_info(const po_plan* plan, int64_t* n_params, int64_t* n_chunks, int64_t* n_unaligned);

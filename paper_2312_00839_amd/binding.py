@@ -15,6 +15,8 @@ PO_OK, PO_EINVAL, PO_EALIGN, PO_EHIP, PO_ENOMEM = 0, -1, -2, -3, -4
 PO_SGDM, PO_ADAM, PO_ADAMW, PO_NESTEROV, PO_RMSPROP, PO_ADAGRAD = 0, 1, 2, 3, 4, 5
 PO_WHAT_F32, PO_WHAT_BF16 = 0, 1
 PO_GRAD_F32, PO_GRAD_BF16 = 0, 1
+PO_LDS_AUTO = -1
+PO_KERNEL_KIND_FUSED, PO_KERNEL_KIND_PREDICT = 0, 1
 OPTIMIZERS = {"sgdm": PO_SGDM, "adam": PO_ADAM, "adamw": PO_ADAMW, "nesterov": PO_NESTEROV, "rmsprop": PO_RMSPROP,
               "adagrad": PO_ADAGRAD}
 WHAT_DTYPES = {"f32": PO_WHAT_F32, "bf16": PO_WHAT_BF16}
@@ -54,7 +56,7 @@ EXPORTS = (
     "pipeoptim_plan_get_launch", "pipeoptim_plan_set_launch", "pipeoptim_plan_info",
     "pipeoptim_step_predict", "pipeoptim_predict", "pipeoptim_plan_get_predict_launch",
     "pipeoptim_plan_set_predict_launch", "pipeoptim_version_difference", "pipeoptim_coefficients",
-    "pipeoptim_chunk_table_build", "pipeoptim_probe_copy", "pipeoptim_last_error",
+    "pipeoptim_chunk_table_build", "pipeoptim_probe_copy", "pipeoptim_auto_lds_bytes", "pipeoptim_last_error",
 )
 
 _lib = None
@@ -85,6 +87,7 @@ def lib():
         L.pipeoptim_coefficients.argtypes = [P(po_hyper), i64, i32, P(po_coeffs)]
         L.pipeoptim_chunk_table_build.argtypes = [i64, P(i64), i64, P(po_chunk), i64, P(i64)]
         L.pipeoptim_probe_copy.argtypes = [vp, vp, i64, vp]
+        L.pipeoptim_auto_lds_bytes.argtypes = [i32, i32, i64, P(i32)]
         for name in EXPORTS:
             getattr(L, name).restype = ctypes.c_int
         L.pipeoptim_last_error.restype = ctypes.c_char_p
@@ -119,6 +122,15 @@ def pipeoptim_coefficients(hyper: po_hyper, t: int, s: int) -> po_coeffs:
     c = po_coeffs()
     _check(lib().pipeoptim_coefficients(ctypes.byref(hyper), int(t), int(s), ctypes.byref(c)))
     return c
+
+
+def pipeoptim_auto_lds_bytes(kernel: int, opt, n_params: int) -> int:
+    """The lds_bytes a call resolves PO_LDS_AUTO to."""
+    if isinstance(opt, str):
+        opt = OPTIMIZERS[opt]
+    out = ctypes.c_int32(0)
+    _check(lib().pipeoptim_auto_lds_bytes(int(kernel), int(opt), int(n_params), ctypes.byref(out)))
+    return out.value
 
 
 def pipeoptim_chunk_table_build(numel: Sequence[int], chunk_elems: int):

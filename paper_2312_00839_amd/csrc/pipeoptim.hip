@@ -41,7 +41,7 @@ int check_launch(const po_launch& L)
     if (L.block != 64 && L.block != 128 && L.block != 256) return fail(PO_EINVAL, "launch.block must be 64, 128 or 256");
     if (L.unroll != 1 && L.unroll != 2 && L.unroll != 4) return fail(PO_EINVAL, "launch.unroll must be 1, 2 or 4");
     if (L.cache_policy < 0 || L.cache_policy > 4) return fail(PO_EINVAL, "launch.cache_policy must be 0..4");
-    if (L.lds_bytes < 0 || L.lds_bytes > 65536) return fail(PO_EINVAL, "launch.lds_bytes must be 0..65536");
+    if (L.lds_bytes < PO_LDS_AUTO || L.lds_bytes > 65536) return fail(PO_EINVAL, "launch.lds_bytes must be 0..65536, or -1 (chosen per call)");
     if (L.xcd_remap != 0 && L.xcd_remap != 1) return fail(PO_EINVAL, "launch.xcd_remap must be 0 or 1");
     if (L.reserved != 0) return fail(PO_EINVAL, "launch.reserved must be 0");
     const int64_t tile = (int64_t)L.block * 4 * L.unroll;
@@ -182,17 +182,30 @@ void refresh_flags(po_plan* p)
     }
 }
 
+// Occupancy cap (unused LDS per single-wave workgroup; a CU has 160 KiB) by kernel, number of state streams and
+// stage size, as measured on MI355X.  The streaming pattern runs fastest with roughly 72-75 KB of loads and
+// stores in flight per CU: fewer and the latency is not hidden, more and the DRAM pages of the 4-8 concurrent
+// streams evict each other.  A fused Adam/AdamW tile moves 7.5 KB (10 workgroups per CU), a one-state
+// optimizer's 5.5-6 KB (13), a prediction tile 3.5 KB (20) or 2.5 KB (26).  Smaller stages, whose launch is
+// dominated by ramp-up and ramp-down, like a few more.
+int32_t auto_lds_bytes(int kernel, int opt, int64_t n_params)
+{
+    const bool two_state = opt == PO_ADAM || opt == PO_ADAMW;
+    const bool large = n_params >= (int64_t(1) << 27), mid = n_params >= (int64_t(1) << 25);
+    if (kernel == PO_KERNEL_KIND_PREDICT) return two_state ? 8192 : 6144;
+    if (two_state) return large ? 16384 : mid ? 14336 : 10240;
+    return mid ? 12288 : 10240;
+}
+
 // Default launch shape, as measured on MI355X: single-wave workgroups, one 256-element tile each,
-// streaming loads, streaming write-through stores, and an occupancy cap (unused LDS per workgroup).
-// The best cap grows with the stage: 10 workgroups per CU for stages above ~128M parameters, 11 for
-// mid-sized ones, 16 for small ones whose launch is dominated by ramp-up and ramp-down.
-po_launch default_launch(int64_t n_params)
+// streaming loads, streaming write-through stores, and an occupancy cap chosen per call (see above).
+po_launch default_launch(int64_t)
 {
     po_launch L{};
     L.block = 64;
     L.unroll = 1;
     L.cache_policy = 4;
-    L.lds_bytes = n_params >= (int64_t(1) << 27) ? 16384 : n_params >= (int64_t(1) << 25) ? 14336 : 10240;
+    L.lds_bytes = PO_LDS_AUTO;
     L.chunk_elems = 65536;
     L.xcd_remap = 0;
     L.reserved = 0;
@@ -210,21 +223,26 @@ int check_state(const po_plan* p, int opt)
 }
 
 // The prediction-only kernel is read-dominated (8-12 B read, 2-4 B written per parameter) and likes a
-// looser occupancy cap than the fused kernel (16 workgroups per CU at 0.74B parameters).  Small
-// stages, whose working set largely sits in the memory-side cache, run best with plain accesses and
-// bigger workgroups.
+// looser occupancy cap than the fused kernel.  Small stages, whose working set largely sits in the
+// memory-side cache, run best with plain accesses and bigger workgroups.
 po_launch default_predict_launch(const po_launch& fused, int64_t n_params)
 {
     po_launch L = fused;
-    if (n_params >= (int64_t(1) << 25)) {
-        L.lds_bytes = 8192;
-    } else {
+    if (n_params < (int64_t(1) << 25)) {
         L.block = 256;
         L.unroll = 2;
         L.cache_policy = 0;
         L.lds_bytes = 0;
     }
     return L;
+}
+
+// The launch shape a call runs with: lds_bytes == PO_LDS_AUTO resolved for the optimizer in use.
+po_launch resolve_launch(const po_launch& L, int kernel, int opt, int64_t n_params)
+{
+    po_launch R = L;
+    if (R.lds_bytes == PO_LDS_AUTO) R.lds_bytes = auto_lds_bytes(kernel, opt, n_params);
+    return R;
 }
 
 }  // namespace
@@ -301,6 +319,16 @@ int pipeoptim_coefficients(const po_hyper* h, int64_t t, int32_t s, po_coeffs* o
     c.s_lr = (float)((double)s * h->lr);
     c.s_is_zero = (s == 0);
     *out = c;
+    return PO_OK;
+}
+
+int pipeoptim_auto_lds_bytes(int32_t kernel, int32_t opt, int64_t n_params, int32_t* out)
+{
+    if (!out) return fail(PO_EINVAL, "out is NULL");
+    if (kernel != PO_KERNEL_KIND_FUSED && kernel != PO_KERNEL_KIND_PREDICT) return fail(PO_EINVAL, "kernel must be 0 (fused) or 1 (prediction)");
+    if (opt < PO_SGDM || opt > PO_ADAGRAD) return fail(PO_EINVAL, "unknown optimizer %d", opt);
+    if (n_params < 0) return fail(PO_EINVAL, "n_params < 0");
+    *out = auto_lds_bytes(kernel, opt, n_params);
     return PO_OK;
 }
 
@@ -519,7 +547,8 @@ int pipeoptim_step_predict(const po_plan* p, const po_hyper* h, int64_t t, int32
     rc = check_state(p, h->opt);
     if (rc != PO_OK) return rc;
     if (p->chunks.empty()) return PO_OK;
-    hipError_t e = po_launch_step_predict(h->opt, p->what_dtype, p->grad_dtype, p->launch, p->d_descs, p->d_chunks,
+    const po_launch L = resolve_launch(p->launch, PO_KERNEL_KIND_FUSED, h->opt, p->n_params);
+    hipError_t e = po_launch_step_predict(h->opt, p->what_dtype, p->grad_dtype, L, p->d_descs, p->d_chunks,
                                           (uint32_t)p->chunks.size(), c, static_cast<hipStream_t>(hip_stream));
     if (e != hipSuccess) return fail_hip(e, "launch of the fused step+predict kernel");
     return PO_OK;
@@ -536,7 +565,8 @@ int pipeoptim_predict(const po_plan* p, const po_hyper* h, int64_t t, int32_t s,
     rc = check_state(p, h->opt);
     if (rc != PO_OK) return rc;
     if (p->chunks.empty()) return PO_OK;
-    hipError_t e = po_launch_predict(h->opt, p->what_dtype, p->predict_launch, p->d_descs, p->d_chunks,
+    const po_launch L = resolve_launch(p->predict_launch, PO_KERNEL_KIND_PREDICT, h->opt, p->n_params);
+    hipError_t e = po_launch_predict(h->opt, p->what_dtype, L, p->d_descs, p->d_chunks,
                                      (uint32_t)p->chunks.size(), c, static_cast<hipStream_t>(hip_stream));
     if (e != hipSuccess) return fail_hip(e, "launch of the prediction kernel");
     return PO_OK;

@@ -44,7 +44,7 @@ typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 // (sc0 = 1 is not used by any shipped policy).
 constexpr int CP_NT = 2, CP_SC1 = 16;
 
-enum { PO_KERNEL_FUSED = 0, PO_KERNEL_PREDICT = 1 };
+constexpr int PO_KERNEL_FUSED = PO_KERNEL_KIND_FUSED, PO_KERNEL_PREDICT = PO_KERNEL_KIND_PREDICT;
 
 // Kernel-side optimizer families: the three rows of Table 1, Nesterov, and one for RMSprop and Adagrad
 // (which differ only in two coefficients).  Which state streams a family reads and rewrites:
@@ -360,6 +360,7 @@ hipError_t launch_one(const po_launch& L, const po_tensor_desc* descs, const po_
     const uint64_t n_slots = (uint64_t)n_chunks << tiles_log2;
     const uint64_t grid = L.xcd_remap ? ((n_slots + 7u) / 8u) * 8u : n_slots;
     if (grid > 0x7FFFFFFFull) return hipErrorInvalidConfiguration;
+    if (L.lds_bytes < 0) return hipErrorInvalidValue;      // the host resolves PO_LDS_AUTO before it gets here
     KArgs a{};
     a.descs = descs;
     a.chunks = chunks;

@@ -120,6 +120,24 @@ def test_coefficients_reject_bad_arguments(kw, t, s):
     assert binding.pipeoptim_last_error() != ""
 
 
+def test_auto_lds_bytes():
+    F, Pk = binding.PO_KERNEL_KIND_FUSED, binding.PO_KERNEL_KIND_PREDICT
+    big, mid, small = 738222080, 75577344, 1048576
+    # one-state optimizers move fewer bytes per tile, so more workgroups per CU (less LDS each) than Adam/AdamW
+    for n in (big, mid):
+        two = binding.pipeoptim_auto_lds_bytes(F, "adamw", n)
+        for one in ("sgdm", "nesterov", "rmsprop", "adagrad"):
+            assert 0 < binding.pipeoptim_auto_lds_bytes(F, one, n) < two <= 65536
+        assert binding.pipeoptim_auto_lds_bytes(F, "adam", n) == two
+        assert binding.pipeoptim_auto_lds_bytes(Pk, "sgdm", n) < binding.pipeoptim_auto_lds_bytes(Pk, "adam", n) < two
+    assert binding.pipeoptim_auto_lds_bytes(F, "adamw", big) == 16384
+    assert binding.pipeoptim_auto_lds_bytes(F, "adamw", small) <= binding.pipeoptim_auto_lds_bytes(F, "adamw", mid)
+    for bad in ((2, "adam", 1), (F, 9, 1), (F, "adam", -1)):
+        with pytest.raises(binding.PipeOptimError) as e:
+            binding.pipeoptim_auto_lds_bytes(*bad)
+        assert e.value.status == binding.PO_EINVAL
+
+
 @pytest.mark.parametrize("chunk", [1, 4096, 8192, 65536, 1 << 30])
 def test_chunk_table_covers_every_element_exactly_once(chunk):
     numel = [0, 1, 3, 4095, 4096, 4097, 0, 131072000, 12288, 7]

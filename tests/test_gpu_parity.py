@@ -488,7 +488,7 @@ def test_error_paths_launch_nothing():
         assert e.value.status == binding.PO_EINVAL
     for bad in [dict(block=100), dict(block=512), dict(unroll=3), dict(unroll=8), dict(chunk_elems=1000),
                 dict(chunk_elems=0), dict(chunk_elems=256 * 3), dict(chunk_elems=1 << 31), dict(cache_policy=5),
-                dict(cache_policy=-1), dict(lds_bytes=-1), dict(lds_bytes=65537), dict(xcd_remap=2), dict(reserved=1)]:
+                dict(cache_policy=-1), dict(lds_bytes=-2), dict(lds_bytes=65537), dict(xcd_remap=2), dict(reserved=1)]:
         with pytest.raises(binding.PipeOptimError) as e:
             st.plan.set_launch(**bad)
         assert e.value.status == binding.PO_EINVAL, bad
@@ -506,6 +506,27 @@ def test_error_paths_launch_nothing():
     with pytest.raises(binding.PipeOptimError) as e:
         binding.Plan([8], [ok], [0], [ok], None, [ok], "f32")
     assert e.value.status == binding.PO_EINVAL
+
+
+def test_default_occupancy_cap_is_chosen_per_call():
+    _say("auto lds_bytes")
+    t = _rand_list([70000, 300], 23, "adam")
+    st = Stage(t["W"], t["g"], t["m"], t["v"], "f32")
+    assert st.plan.get_launch().lds_bytes == binding.PO_LDS_AUTO
+    st.plan.set_launch(lds_bytes=4096, chunk_elems=4096)
+    assert st.plan.get_launch().lds_bytes == 4096
+    st.plan.set_launch(lds_bytes=binding.PO_LDS_AUTO)              # back to per-call choice, other fields kept
+    L = st.plan.get_launch()
+    assert (L.lds_bytes, L.chunk_elems) == (binding.PO_LDS_AUTO, 4096)
+    st.close()
+    # the same plan under a two-state and a one-state optimizer (different caps), both against the oracle
+    for kind in ("adam", "rmsprop", "sgdm"):
+        t = _rand_list([70000, 300], 23, "adam")
+        if kind == "rmsprop":
+            t["m"] = None
+        if kind == "sgdm":
+            t["v"] = None
+        run_and_compare_full(kind, HP[kind], 4, 2, t, "bf16", label="auto cap %s" % kind)
 
 
 def test_probe_copy_copies():
