@@ -41,6 +41,9 @@ def parse_args():
                     help="bf16: mixed-precision variant with bf16 gradients (2 bytes fewer read per parameter)")
     ap.add_argument("--optimizer", default="", choices=("", "sgdm", "adam", "adamw", "nesterov", "rmsprop", "adagrad"),
                     help="run the config's tensor list under another optimizer (default: the config's own)")
+    ap.add_argument("--layout", choices=("packed", "skewed"), default="packed",
+                    help="packed: plain allocations, back to back (what an allocator gives by default); skewed: the W, g, "
+                         "m, v buffers of a tensor differ in address bits 12-13")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-copy-probe", action="store_true")
     ap.add_argument("--launch", default="", help="comma separated po_launch overrides, e.g. block=64,unroll=1,lds_bytes=16384")
@@ -128,7 +131,7 @@ def main():
     s_cfg = args.s if args.s >= 0 else wl.s_values[-1]
     D = args.pipeline_depth or (s_cfg + 1)
     rank = D - 1 - s_cfg
-    tensors = make_inputs(wl, dev)
+    tensors = make_inputs(wl, dev, layout=args.layout)
     if args.optimizer and args.optimizer != wl.optimizer:
         if args.mode == "predict" and args.optimizer in ("nesterov", "rmsprop", "adagrad"):
             print("bench.py: %s has no prediction from the state alone" % args.optimizer, file=sys.stderr)
@@ -196,7 +199,7 @@ def main():
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32", "data": "synthetic",
         "config": {"workload": "config %d: %s, %s, t=%d.., s=%d, %s What" % (wl.config, wl.name, wl.optimizer, wl.t, s_cfg, wl.what_dtype),
-                   "n_params": N, "n_tensors": len(wl.shapes), "bytes_per_param": bytes_per_param, "mode": args.mode, "grad_dtype": args.grad_dtype,
+                   "n_params": N, "n_tensors": len(wl.shapes), "bytes_per_param": bytes_per_param, "mode": args.mode, "grad_dtype": args.grad_dtype, "layout": args.layout,
                    "launch": dict({f: getattr(L, f) for f, _ in L._fields_},
                                   lds_bytes_in_effect=L.lds_bytes if L.lds_bytes >= 0 else binding.pipeoptim_auto_lds_bytes(
                                       binding.PO_KERNEL_KIND_PREDICT if predict_only else binding.PO_KERNEL_KIND_FUSED,

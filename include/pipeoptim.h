@@ -185,7 +185,8 @@ int pipeoptim_plan_info(const po_plan* plan, int64_t* n_params, int64_t* n_chunk
  * in fp32 arithmetic.  W, m, v are overwritten with W', m', v'; What receives
  * the prediction (bf16: round-to-nearest-even).  t >= 1 is the 1-based step
  * index of the bias corrections; s >= 0 is the version difference of paper
- * Eq. 4.  Enqueues exactly one kernel on hip_stream and returns.
+ * Eq. 4.  Enqueues exactly one kernel on hip_stream and returns.  hip_stream must belong to the
+ * device that was current when the plan was created, and that device must be current (else PO_EINVAL).
  */
 int pipeoptim_step_predict(const po_plan* plan, const po_hyper* hyper, int64_t t, int32_t s,
                            void* hip_stream);

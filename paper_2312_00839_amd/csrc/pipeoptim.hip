@@ -212,6 +212,17 @@ po_launch default_launch(int64_t)
     return L;
 }
 
+// The plan's tables and the caller's buffers live on the device that was current at plan creation.
+int check_device(const po_plan* p)
+{
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return fail_hip(e, "hipGetDevice");
+    if (dev != p->device)
+        return fail(PO_EINVAL, "plan belongs to device %d but device %d is current", p->device, dev);
+    return PO_OK;
+}
+
 // Does the plan hold the state buffers this optimizer updates?
 int check_state(const po_plan* p, int opt)
 {
@@ -547,6 +558,8 @@ int pipeoptim_step_predict(const po_plan* p, const po_hyper* h, int64_t t, int32
     rc = check_state(p, h->opt);
     if (rc != PO_OK) return rc;
     if (p->chunks.empty()) return PO_OK;
+    rc = check_device(p);
+    if (rc != PO_OK) return rc;
     const po_launch L = resolve_launch(p->launch, PO_KERNEL_KIND_FUSED, h->opt, p->n_params);
     hipError_t e = po_launch_step_predict(h->opt, p->what_dtype, p->grad_dtype, L, p->d_descs, p->d_chunks,
                                           (uint32_t)p->chunks.size(), c, static_cast<hipStream_t>(hip_stream));
@@ -565,6 +578,8 @@ int pipeoptim_predict(const po_plan* p, const po_hyper* h, int64_t t, int32_t s,
     rc = check_state(p, h->opt);
     if (rc != PO_OK) return rc;
     if (p->chunks.empty()) return PO_OK;
+    rc = check_device(p);
+    if (rc != PO_OK) return rc;
     const po_launch L = resolve_launch(p->predict_launch, PO_KERNEL_KIND_PREDICT, h->opt, p->n_params);
     hipError_t e = po_launch_predict(h->opt, p->what_dtype, L, p->d_descs, p->d_chunks,
                                      (uint32_t)p->chunks.size(), c, static_cast<hipStream_t>(hip_stream));
