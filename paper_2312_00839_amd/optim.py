@@ -1,0 +1,125 @@
+"""The weight-handling part of paper Algorithm 1 for the parameters of a ``torch.nn.Module`` pipeline stage.
+
+``StageOptimizer`` binds a stage's parameters to a libpipeoptim plan and exposes what a 1F1B runtime needs
+each iteration (the runtime itself, its schedule and its transfers are not part of this library):
+
+    opt = StageOptimizer(stage_module.parameters(), "adamw", lr=1e-3, weight_decay=0.01, rank=r, depth=D)
+    ...
+    with opt.predicted_weights():        # Algorithm 1: forward pass with What_{t+s}
+        y = stage_module(x)
+    ...                                  # backward pass fills the gradient buffers
+    opt.step()                           # Eq. 1 and, in the same kernel, next iteration's What (Eq. 5)
+
+All arithmetic runs in the library's kernels: this class allocates buffers, points ``param.grad`` at them,
+swaps ``param.data`` between W and What (pointer swaps, no copies: the cache / restore of Algorithm 1 costs
+nothing), and passes pointers.  Parameters must be contiguous fp32 tensors on the GPU.
+"""
+import contextlib
+from typing import Iterable, List, Optional
+
+import torch
+
+from . import binding
+from .stage import Stage, address_slot, alloc_skewed, SKEW_SLOTS
+
+
+class StageOptimizer:
+    def __init__(self, params: Iterable[torch.nn.Parameter], optimizer: str = "adamw", lr: float = 1e-3,
+                 betas=(0.9, 0.999), eps: float = 1e-8, weight_decay: float = 0.0, momentum: float = 0.9,
+                 dampening: float = 0.0, alpha: float = 0.99, rank: int = 0, depth: int = 1,
+                 decay_in_prediction: bool = True):
+        self.params: List[torch.nn.Parameter] = [p for p in params]
+        if not self.params:
+            raise ValueError("no parameters")
+        for p in self.params:
+            if p.dtype != torch.float32 or not p.is_contiguous() or p.device.type != "cuda":
+                raise ValueError("parameters must be contiguous fp32 tensors on the GPU")
+        if optimizer not in binding.OPTIMIZERS:
+            raise ValueError("unknown optimizer %r" % optimizer)
+        self.optimizer = optimizer
+        self.s = binding.pipeoptim_version_difference(depth, rank)            # paper Eq. 4
+        self.rank, self.depth = rank, depth
+        self.t = 0                                                            # steps taken; the next step is t + 1
+        if optimizer == "sgdm":
+            b1, b2 = momentum, dampening
+        elif optimizer == "nesterov":
+            b1, b2 = momentum, 0.0
+        elif optimizer == "rmsprop":
+            b1, b2 = 0.0, alpha
+        elif optimizer == "adagrad":
+            b1, b2 = 0.0, 0.0
+        else:
+            b1, b2 = betas
+        self.hyper = binding.make_hyper(optimizer, lr, b1, b2, eps, weight_decay, decay_in_prediction)
+        binding.pipeoptim_coefficients(self.hyper, 1, self.s)                 # validates the hyper-parameters now
+
+        dev = self.params[0].device
+        self._W = [p.data.view(-1) for p in self.params]
+        has_m = optimizer not in ("rmsprop", "adagrad")
+        has_v = optimizer not in ("sgdm", "nesterov")
+
+        def state_like(slot_offset):
+            # gradient and state buffers: zero-filled, placed in address slots (bits 12-13) next to W's
+            out = []
+            for w in self._W:
+                x = alloc_skewed(w.numel(), torch.float32, dev, (address_slot(w.data_ptr()) + slot_offset) % SKEW_SLOTS)
+                out.append(x.zero_())
+            return out
+
+        self._g = state_like(1)
+        self._m: Optional[List[torch.Tensor]] = state_like(2) if has_m else None
+        self._v: Optional[List[torch.Tensor]] = state_like(3 if has_m else 2) if has_v else None
+        for p, g in zip(self.params, self._g):
+            p.grad = g.view_as(p)                                              # autograd accumulates in place
+        # the prediction is consumed by an fp32 module, so What is fp32 here (the C ABI also offers bf16)
+        self._stage = Stage(self._W, self._g, self._m, self._v, "f32")
+        self._What = self._stage.What
+        self._swapped = False
+
+    # ------------------------------------------------------------------ Algorithm 1
+    def step(self) -> None:
+        """W_{t+1} = W_t - lr*dW_t (Eq. 1) and What = W_t - lr*s*dW_t (Eq. 5), one kernel."""
+        if self._swapped:
+            raise RuntimeError("step() inside predicted_weights(): the parameters currently alias What")
+        for p, g in zip(self.params, self._g):
+            if p.grad is None or p.grad.data_ptr() != g.data_ptr():
+                raise RuntimeError("a parameter's .grad no longer is the buffer this optimizer gave it "
+                                   "(use zero_grad() of this class, or zero_grad(set_to_none=False))")
+        self.t += 1
+        self._stage.step_predict(self.hyper, self.t, self.s)
+
+    def refresh_prediction(self, s: Optional[int] = None) -> None:
+        """What = W - lr*s*dW from the cached state alone (Table 1 optimizers), e.g. for another version difference."""
+        if self.t < 1:
+            raise RuntimeError("no optimizer state yet: call step() first")
+        self._stage.predict(self.hyper, self.t, self.s if s is None else s)
+
+    def zero_grad(self) -> None:
+        for g in self._g:
+            g.zero_()
+
+    @contextlib.contextmanager
+    def predicted_weights(self):
+        """Inside the block the module's parameters ARE the predicted weights (their storage is What); on exit
+        they are W again.  Before the first step(), or on the last stage (s = 0), What is not used and the
+        block runs with W itself, as Algorithm 1's else-branch does."""
+        use = self.s > 0 and self.t > 0
+        if use:
+            for p, h in zip(self.params, self._What):
+                p.data = h.view_as(p)
+            self._swapped = True
+        try:
+            yield
+        finally:
+            if use:
+                for p, w in zip(self.params, self._W):
+                    p.data = w.view_as(p)
+                self._swapped = False
+
+    # ------------------------------------------------------------------ state access
+    def state(self):
+        """The optimizer's buffers (flat views, by parameter order): dict with W, g, m, v, What and the step count."""
+        return {"W": self._W, "g": self._g, "m": self._m, "v": self._v, "What": self._What, "t": self.t, "s": self.s}
+
+    def close(self) -> None:
+        self._stage.close()
