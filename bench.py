@@ -59,7 +59,7 @@ def cpu_baseline(wl, s, predict_only=False):
     from paper_2312_00839_amd.workloads import make_inputs
 
     oracle.build()
-    budget = 112_500_000                       # parameters; ~14 s of single-core oracle time
+    budget = 340_000_000                       # parameters; ~15-20 s of CPU work over all threads
     idx, total = [], 0
     for i, n in enumerate(wl.numels):
         if total + n > budget and idx:
