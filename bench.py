@@ -41,9 +41,10 @@ def parse_args():
                     help="bf16: mixed-precision variant with bf16 gradients (2 bytes fewer read per parameter)")
     ap.add_argument("--optimizer", default="", choices=("", "sgdm", "adam", "adamw", "nesterov", "rmsprop", "adagrad"),
                     help="run the config's tensor list under another optimizer (default: the config's own)")
-    ap.add_argument("--layout", choices=("packed", "skewed"), default="packed",
+    ap.add_argument("--layout", choices=("packed", "skewed", "local"), default="packed",
                     help="packed: plain allocations, back to back (what an allocator gives by default); skewed: the W, g, "
-                         "m, v buffers of a tensor differ in address bits 12-13")
+                         "m, v buffers of a tensor differ in address bits 12-13; local: all streams in the library's "
+                         "near-memory arena, every XCC working on its own die's HBM")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-copy-probe", action="store_true")
     ap.add_argument("--launch", default="", help="comma separated po_launch overrides, e.g. block=64,unroll=1,lds_bytes=16384")
@@ -146,7 +147,8 @@ def main():
         tensors["v"] = None
     if args.grad_dtype == "bf16":
         tensors["g"] = [x.to(torch.bfloat16) for x in tensors["g"]]
-    stage = Stage(tensors["W"], tensors["g"], tensors["m"], tensors["v"], wl.what_dtype)
+    stage = Stage(tensors["W"], tensors["g"], tensors["m"], tensors["v"], wl.what_dtype,
+                  What=tensors.get("What"), arena=tensors.get("arena"))
     predict_only = args.mode == "predict"
     if args.launch:
         kw = {k: int(v) for k, v in (kv.split("=") for kv in args.launch.split(","))}
@@ -201,9 +203,10 @@ def main():
         "config": {"workload": "config %d: %s, %s, t=%d.., s=%d, %s What" % (wl.config, wl.name, wl.optimizer, wl.t, s_cfg, wl.what_dtype),
                    "n_params": N, "n_tensors": len(wl.shapes), "bytes_per_param": bytes_per_param, "mode": args.mode, "grad_dtype": args.grad_dtype, "layout": args.layout,
                    "launch": dict({f: getattr(L, f) for f, _ in L._fields_},
-                                  lds_bytes_in_effect=L.lds_bytes if L.lds_bytes >= 0 else binding.pipeoptim_auto_lds_bytes(
+                                  lds_bytes_in_effect=stage.plan.effective_launch(
                                       binding.PO_KERNEL_KIND_PREDICT if predict_only else binding.PO_KERNEL_KIND_FUSED,
-                                      wl.optimizer, N)),
+                                      wl.optimizer).lds_bytes),
+                   "n_local_params": stage.n_local_params,
                    "n_chunks": stage.plan.info()["n_chunks"]},
         "kernel_ms": {"avg": avg_ms, "median": med_ms, "min": per_launch_ms[0], "max": per_launch_ms[-1]},
         "achieved_hbm_GBps": achieved,
@@ -233,6 +236,8 @@ def main():
         del src, dst
 
     stage.close()
+    if tensors.get("stage_arena") is not None:
+        tensors["stage_arena"].close()
     del stage, tensors
     torch.cuda.empty_cache()
 

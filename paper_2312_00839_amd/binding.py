@@ -57,6 +57,9 @@ EXPORTS = (
     "pipeoptim_step_predict", "pipeoptim_predict", "pipeoptim_plan_get_predict_launch",
     "pipeoptim_plan_set_predict_launch", "pipeoptim_version_difference", "pipeoptim_coefficients",
     "pipeoptim_chunk_table_build", "pipeoptim_probe_copy", "pipeoptim_auto_lds_bytes", "pipeoptim_last_error",
+    "pipeoptim_arena_create", "pipeoptim_arena_alloc", "pipeoptim_arena_set_skew", "pipeoptim_arena_near_half",
+    "pipeoptim_arena_info", "pipeoptim_arena_destroy", "pipeoptim_plan_localize", "pipeoptim_plan_effective_launch",
+    "pipeoptim_local_tile", "pipeoptim_plan_local_params",
 )
 
 _lib = None
@@ -88,6 +91,16 @@ def lib():
         L.pipeoptim_chunk_table_build.argtypes = [i64, P(i64), i64, P(po_chunk), i64, P(i64)]
         L.pipeoptim_probe_copy.argtypes = [vp, vp, i64, vp]
         L.pipeoptim_auto_lds_bytes.argtypes = [i32, i32, i64, P(i32)]
+        L.pipeoptim_arena_create.argtypes = [P(vp), i64]
+        L.pipeoptim_arena_alloc.argtypes = [vp, i64, P(i64), P(vp)]
+        L.pipeoptim_arena_set_skew.argtypes = [vp, i64]
+        L.pipeoptim_arena_near_half.argtypes = [vp, vp, P(i32)]
+        L.pipeoptim_arena_info.argtypes = [vp, P(i64), P(i64), P(i64), P(i32), P(i32)]
+        L.pipeoptim_arena_destroy.argtypes = [vp]
+        L.pipeoptim_plan_localize.argtypes = [vp, vp, P(i64)]
+        L.pipeoptim_plan_local_params.argtypes = [vp, P(i64)]
+        L.pipeoptim_plan_effective_launch.argtypes = [vp, i32, i32, P(po_launch)]
+        L.pipeoptim_local_tile.argtypes = [ctypes.c_uint32, i32, P(ctypes.c_uint32)]
         for name in EXPORTS:
             getattr(L, name).restype = ctypes.c_int
         L.pipeoptim_last_error.restype = ctypes.c_char_p
@@ -142,6 +155,56 @@ def pipeoptim_chunk_table_build(numel: Sequence[int], chunk_elems: int):
     buf = (po_chunk * max(count.value, 1))()
     _check(lib().pipeoptim_chunk_table_build(n, arr, int(chunk_elems), buf, count.value, ctypes.byref(count)))
     return [(buf[i].tensor, buf[i].chunk) for i in range(count.value)]
+
+
+def pipeoptim_local_tile(tile_in_chunk: int, first_block_half: int) -> int:
+    """Host-only: the tile a workgroup at this position of its chunk takes in the near-memory order."""
+    out = ctypes.c_uint32(0)
+    _check(lib().pipeoptim_local_tile(int(tile_in_chunk), int(first_block_half), ctypes.byref(out)))
+    return out.value
+
+
+class Arena:
+    """Owner of a ``po_arena*``: device memory with a known block-to-die layout (MI355X)."""
+
+    def __init__(self, capacity_bytes: int):
+        self._h = ctypes.c_void_p()
+        _check(lib().pipeoptim_arena_create(ctypes.byref(self._h), int(capacity_bytes)))
+
+    def alloc(self, sizes_bytes: Sequence[int]):
+        """Device addresses of len(sizes_bytes) buffers with one layout (the streams of one tensor)."""
+        n = len(sizes_bytes)
+        sizes = (ctypes.c_int64 * max(n, 1))(*[int(b) for b in sizes_bytes])
+        ptrs = (ctypes.c_void_p * max(n, 1))()
+        _check(lib().pipeoptim_arena_alloc(self._h, n, sizes, ptrs))
+        return [int(ptrs[k] or 0) for k in range(n)]
+
+    def set_skew(self, skew_bytes: int) -> None:
+        _check(lib().pipeoptim_arena_set_skew(self._h, int(skew_bytes)))
+
+    def near_half(self, ptr: int) -> int:
+        half = ctypes.c_int32(-2)
+        _check(lib().pipeoptim_arena_near_half(self._h, ctypes.c_void_p(ptr), ctypes.byref(half)))
+        return half.value
+
+    def info(self):
+        a, b, c = ctypes.c_int64(), ctypes.c_int64(), ctypes.c_int64()
+        n, f = ctypes.c_int32(), ctypes.c_int32()
+        _check(lib().pipeoptim_arena_info(self._h, ctypes.byref(a), ctypes.byref(b), ctypes.byref(c), ctypes.byref(n),
+                                          ctypes.byref(f)))
+        return {"backed_bytes": a.value, "used_bytes": b.value, "released_pieces": c.value,
+                "near_cycles": n.value, "far_cycles": f.value}
+
+    def destroy(self) -> None:
+        if self._h:
+            h, self._h = self._h, ctypes.c_void_p()
+            _check(lib().pipeoptim_arena_destroy(h))
+
+    def __del__(self):
+        try:
+            self.destroy()
+        except Exception:
+            pass
 
 
 def _ptr_array(ptrs: Sequence[int]):
@@ -209,6 +272,25 @@ class Plan:
                 raise TypeError("po_launch has no field %r" % k)
             setattr(L, k, int(val))
         _check(lib().pipeoptim_plan_set_launch(self._h, ctypes.byref(L)))
+        return L
+
+    def localize(self, arena: Optional["Arena"]) -> int:
+        """Marks the tensors whose fp32 streams lie in `arena` for the near-memory tile order; returns the
+        number of parameters marked (None clears the marks)."""
+        n = ctypes.c_int64(0)
+        _check(lib().pipeoptim_plan_localize(self._h, arena._h if arena is not None else None, ctypes.byref(n)))
+        return n.value
+
+    def local_params(self) -> int:
+        n = ctypes.c_int64(-1)
+        _check(lib().pipeoptim_plan_local_params(self._h, ctypes.byref(n)))
+        return n.value
+
+    def effective_launch(self, kernel: int, opt) -> po_launch:
+        if isinstance(opt, str):
+            opt = OPTIMIZERS[opt]
+        L = po_launch()
+        _check(lib().pipeoptim_plan_effective_launch(self._h, int(kernel), int(opt), ctypes.byref(L)))
         return L
 
     def info(self):

@@ -17,10 +17,10 @@
 #include "po_internal.h"
 
 namespace {
-
 thread_local char g_err[512] = "";
+}
 
-int fail(int code, const char* fmt, ...)
+int po_fail(int code, const char* fmt, ...)
 {
     va_list ap;
     va_start(ap, fmt);
@@ -29,25 +29,27 @@ int fail(int code, const char* fmt, ...)
     return code;
 }
 
+namespace {
+
 int fail_hip(hipError_t e, const char* what)
 {
-    return fail(PO_EHIP, "%s: %s", what, hipGetErrorString(e));
+    return po_fail(PO_EHIP, "%s: %s", what, hipGetErrorString(e));
 }
 
 constexpr int64_t kMaxChunkElems = int64_t(1) << 30;
 
 int check_launch(const po_launch& L)
 {
-    if (L.block != 64 && L.block != 128 && L.block != 256) return fail(PO_EINVAL, "launch.block must be 64, 128 or 256");
-    if (L.unroll != 1 && L.unroll != 2 && L.unroll != 4) return fail(PO_EINVAL, "launch.unroll must be 1, 2 or 4");
-    if (L.cache_policy < 0 || L.cache_policy > 4) return fail(PO_EINVAL, "launch.cache_policy must be 0..4");
-    if (L.lds_bytes < PO_LDS_AUTO || L.lds_bytes > 65536) return fail(PO_EINVAL, "launch.lds_bytes must be 0..65536, or -1 (chosen per call)");
-    if (L.xcd_remap != 0 && L.xcd_remap != 1) return fail(PO_EINVAL, "launch.xcd_remap must be 0 or 1");
-    if (L.reserved != 0) return fail(PO_EINVAL, "launch.reserved must be 0");
+    if (L.block != 64 && L.block != 128 && L.block != 256) return po_fail(PO_EINVAL, "launch.block must be 64, 128 or 256");
+    if (L.unroll != 1 && L.unroll != 2 && L.unroll != 4) return po_fail(PO_EINVAL, "launch.unroll must be 1, 2 or 4");
+    if (L.cache_policy < 0 || L.cache_policy > 4) return po_fail(PO_EINVAL, "launch.cache_policy must be 0..4");
+    if (L.lds_bytes < PO_LDS_AUTO || L.lds_bytes > 65536) return po_fail(PO_EINVAL, "launch.lds_bytes must be 0..65536, or -1 (chosen per call)");
+    if (L.xcd_remap != 0 && L.xcd_remap != 1) return po_fail(PO_EINVAL, "launch.xcd_remap must be 0 or 1");
+    if (L.reserved != 0) return po_fail(PO_EINVAL, "launch.reserved must be 0");
     const int64_t tile = (int64_t)L.block * 4 * L.unroll;
     const int64_t ratio = L.chunk_elems > 0 ? L.chunk_elems / tile : 0;
     if (L.chunk_elems <= 0 || L.chunk_elems > kMaxChunkElems || L.chunk_elems % tile != 0 || (ratio & (ratio - 1)) != 0)
-        return fail(PO_EINVAL, "launch.chunk_elems must be block*4*unroll (%lld) times a power of two, at most 2^30",
+        return po_fail(PO_EINVAL, "launch.chunk_elems must be block*4*unroll (%lld) times a power of two, at most 2^30",
                     (long long)tile);
     return PO_OK;
 }
@@ -57,7 +59,7 @@ int check_grid(const po_launch& L, int64_t n_chunks)
 {
     const int64_t tiles = L.chunk_elems / ((int64_t)L.block * 4 * L.unroll);
     if (n_chunks > 0 && tiles > (int64_t(0x7FFFFFF8) / n_chunks))
-        return fail(PO_EINVAL, "grid of %lld chunks x %lld tiles exceeds 2^31 workgroups; raise block or unroll",
+        return po_fail(PO_EINVAL, "grid of %lld chunks x %lld tiles exceeds 2^31 workgroups; raise block or unroll",
                     (long long)n_chunks, (long long)tiles);
     return PO_OK;
 }
@@ -65,21 +67,21 @@ int check_grid(const po_launch& L, int64_t n_chunks)
 int build_chunks(int64_t n_tensors, const int64_t* numel, int64_t chunk_elems, po_chunk* out, int64_t capacity,
                  int64_t* n_chunks)
 {
-    if (n_tensors < 0) return fail(PO_EINVAL, "n_tensors < 0");
-    if (n_tensors > 0 && !numel) return fail(PO_EINVAL, "numel is NULL");
-    if (chunk_elems <= 0 || chunk_elems > kMaxChunkElems) return fail(PO_EINVAL, "chunk_elems out of range");
-    if (n_tensors > (int64_t)UINT32_MAX) return fail(PO_EINVAL, "too many tensors");
-    if (capacity < 0 || (capacity > 0 && !out)) return fail(PO_EINVAL, "bad output buffer");
-    if (!n_chunks) return fail(PO_EINVAL, "n_chunks is NULL");
+    if (n_tensors < 0) return po_fail(PO_EINVAL, "n_tensors < 0");
+    if (n_tensors > 0 && !numel) return po_fail(PO_EINVAL, "numel is NULL");
+    if (chunk_elems <= 0 || chunk_elems > kMaxChunkElems) return po_fail(PO_EINVAL, "chunk_elems out of range");
+    if (n_tensors > (int64_t)UINT32_MAX) return po_fail(PO_EINVAL, "too many tensors");
+    if (capacity < 0 || (capacity > 0 && !out)) return po_fail(PO_EINVAL, "bad output buffer");
+    if (!n_chunks) return po_fail(PO_EINVAL, "n_chunks is NULL");
     int64_t total = 0;
     for (int64_t i = 0; i < n_tensors; ++i) {
-        if (numel[i] < 0) return fail(PO_EINVAL, "numel[%lld] < 0", (long long)i);
+        if (numel[i] < 0) return po_fail(PO_EINVAL, "numel[%lld] < 0", (long long)i);
         const int64_t k = (numel[i] + chunk_elems - 1) / chunk_elems;
-        if (k > (int64_t)UINT32_MAX) return fail(PO_EINVAL, "tensor %lld needs too many chunks", (long long)i);
+        if (k > (int64_t)UINT32_MAX) return po_fail(PO_EINVAL, "tensor %lld needs too many chunks", (long long)i);
         for (int64_t j = 0; j < k; ++j, ++total)
             if (total < capacity) out[total] = po_chunk{(uint32_t)i, (uint32_t)j};
     }
-    if (total > (int64_t)UINT32_MAX) return fail(PO_EINVAL, "chunk table too long; raise chunk_elems");
+    if (total > (int64_t)UINT32_MAX) return po_fail(PO_EINVAL, "chunk table too long; raise chunk_elems");
     *n_chunks = total;
     return PO_OK;
 }
@@ -92,6 +94,7 @@ struct po_plan {
     int64_t n_tensors = 0;
     int64_t n_params = 0;
     int64_t n_unaligned = 0;
+    int64_t n_local_params = 0;   // parameters of tensors that run in the near-memory tile order
     int32_t what_dtype = PO_WHAT_F32;
     int32_t grad_dtype = PO_GRAD_F32;
     bool has_v = false;
@@ -130,7 +133,7 @@ int check_disjoint(const po_plan* p)
     std::sort(r.begin(), r.end(), [](const Range& a, const Range& b) { return a.lo < b.lo; });
     for (size_t k = 1; k < r.size(); ++k)
         if (r[k].lo < r[k - 1].hi)
-            return fail(PO_EINVAL, "buffers overlap: %c of tensor %lld and %c of tensor %lld (h = What)", r[k - 1].kind,
+            return po_fail(PO_EINVAL, "buffers overlap: %c of tensor %lld and %c of tensor %lld (h = What)", r[k - 1].kind,
                         (long long)r[k - 1].tensor, r[k].kind, (long long)r[k].tensor);
     return PO_OK;
 }
@@ -152,7 +155,7 @@ int upload_chunks(po_plan* p)
             p->d_chunks_capacity = 0;
         }
         hipError_t e = hipMalloc(reinterpret_cast<void**>(&p->d_chunks), (size_t)n * sizeof(po_chunk));
-        if (e != hipSuccess) return fail(PO_ENOMEM, "hipMalloc(chunk table, %lld entries): %s", (long long)n,
+        if (e != hipSuccess) return po_fail(PO_ENOMEM, "hipMalloc(chunk table, %lld entries): %s", (long long)n,
                                          hipGetErrorString(e));
         p->d_chunks_capacity = n;
     }
@@ -172,9 +175,12 @@ int upload_descs(po_plan* p)
     return PO_OK;
 }
 
+// Recomputes every descriptor's flags from its pointers.  Drops the near-memory marks: they hold for the
+// addresses pipeoptim_plan_localize looked at, not for new ones.
 void refresh_flags(po_plan* p)
 {
     p->n_unaligned = 0;
+    p->n_local_params = 0;
     for (auto& d : p->descs) {
         uintptr_t bits = (uintptr_t)d.W | (uintptr_t)d.g | (uintptr_t)d.m | (uintptr_t)d.v | (uintptr_t)d.What;
         d.flags = (bits & 15u) == 0 ? PO_DESC_VECTOR_OK : 0u;
@@ -188,10 +194,18 @@ void refresh_flags(po_plan* p)
 // streams evict each other.  A fused Adam/AdamW tile moves 7.5 KB (10 workgroups per CU), a one-state
 // optimizer's 5.5-6 KB (13), a prediction tile 3.5 KB (20) or 2.5 KB (26).  Smaller stages, whose launch is
 // dominated by ramp-up and ramp-down, like a few more.
-int32_t auto_lds_bytes(int kernel, int opt, int64_t n_params)
+int32_t auto_lds_bytes(int kernel, int opt, int64_t n_params, bool local = false)
 {
     const bool two_state = opt == PO_ADAM || opt == PO_ADAMW;
     const bool large = n_params >= (int64_t(1) << 27), mid = n_params >= (int64_t(1) << 25);
+    if (local) {
+        // every XCC on its own die's memory: shorter latency, no shared link; the sweeps put the optimum at 10
+        // workgroups per CU for the fused two-state kernel at every size from 64 M parameters up, at 12-13 for the
+        // one-state kernels, and at 16 (20 on mid-sized stages) for the prediction kernel
+        if (kernel == PO_KERNEL_KIND_PREDICT) return two_state ? (large ? 10240 : 8192) : 6144;
+        if (two_state) return mid ? 16384 : 12288;
+        return 12288;
+    }
     if (kernel == PO_KERNEL_KIND_PREDICT) return two_state ? 8192 : 6144;
     if (two_state) return large ? 16384 : mid ? 14336 : 10240;
     return mid ? 12288 : 10240;
@@ -219,7 +233,7 @@ int check_device(const po_plan* p)
     hipError_t e = hipGetDevice(&dev);
     if (e != hipSuccess) return fail_hip(e, "hipGetDevice");
     if (dev != p->device)
-        return fail(PO_EINVAL, "plan belongs to device %d but device %d is current", p->device, dev);
+        return po_fail(PO_EINVAL, "plan belongs to device %d but device %d is current", p->device, dev);
     return PO_OK;
 }
 
@@ -228,8 +242,8 @@ int check_state(const po_plan* p, int opt)
 {
     const bool needs_m = opt != PO_RMSPROP && opt != PO_ADAGRAD;
     const bool needs_v = opt != PO_SGDM && opt != PO_NESTEROV;
-    if (needs_m && !p->has_m) return fail(PO_EINVAL, "optimizer %d needs a plan created with m", opt);
-    if (needs_v && !p->has_v) return fail(PO_EINVAL, "optimizer %d needs a plan created with v", opt);
+    if (needs_m && !p->has_m) return po_fail(PO_EINVAL, "optimizer %d needs a plan created with m", opt);
+    if (needs_v && !p->has_v) return po_fail(PO_EINVAL, "optimizer %d needs a plan created with v", opt);
     return PO_OK;
 }
 
@@ -249,10 +263,11 @@ po_launch default_predict_launch(const po_launch& fused, int64_t n_params)
 }
 
 // The launch shape a call runs with: lds_bytes == PO_LDS_AUTO resolved for the optimizer in use.
-po_launch resolve_launch(const po_launch& L, int kernel, int opt, int64_t n_params)
+po_launch resolve_launch(const po_plan* p, const po_launch& L, int kernel, int opt)
 {
     po_launch R = L;
-    if (R.lds_bytes == PO_LDS_AUTO) R.lds_bytes = auto_lds_bytes(kernel, opt, n_params);
+    const bool local = p->n_local_params * 2 >= p->n_params && p->n_local_params > 0;
+    if (R.lds_bytes == PO_LDS_AUTO) R.lds_bytes = auto_lds_bytes(kernel, opt, p->n_params, local);
     return R;
 }
 
@@ -264,25 +279,25 @@ const char* pipeoptim_last_error(void) { return g_err; }
 
 int pipeoptim_version_difference(int32_t D, int32_t rank, int32_t* s_out)
 {
-    if (!s_out) return fail(PO_EINVAL, "s_out is NULL");
-    if (D < 1 || rank < 0 || rank >= D) return fail(PO_EINVAL, "need 0 <= rank < D (D=%d, rank=%d)", D, rank);
+    if (!s_out) return po_fail(PO_EINVAL, "s_out is NULL");
+    if (D < 1 || rank < 0 || rank >= D) return po_fail(PO_EINVAL, "need 0 <= rank < D (D=%d, rank=%d)", D, rank);
     *s_out = D - rank - 1;   // paper Eq. 4
     return PO_OK;
 }
 
 int pipeoptim_coefficients(const po_hyper* h, int64_t t, int32_t s, po_coeffs* out)
 {
-    if (!h || !out) return fail(PO_EINVAL, "hyper or out is NULL");
-    if (h->opt < PO_SGDM || h->opt > PO_ADAGRAD) return fail(PO_EINVAL, "unknown optimizer %d", h->opt);
-    if (t < 1) return fail(PO_EINVAL, "t must be >= 1 (got %lld): steps are 1-based", (long long)t);
-    if (s < 0) return fail(PO_EINVAL, "s must be >= 0 (got %d)", s);
+    if (!h || !out) return po_fail(PO_EINVAL, "hyper or out is NULL");
+    if (h->opt < PO_SGDM || h->opt > PO_ADAGRAD) return po_fail(PO_EINVAL, "unknown optimizer %d", h->opt);
+    if (t < 1) return po_fail(PO_EINVAL, "t must be >= 1 (got %lld): steps are 1-based", (long long)t);
+    if (s < 0) return po_fail(PO_EINVAL, "s must be >= 0 (got %d)", s);
     if (!finite_d(h->lr) || !finite_d(h->eps) || !finite_d(h->weight_decay) || !finite_d(h->beta1) || !finite_d(h->beta2))
-        return fail(PO_EINVAL, "non-finite hyper-parameter");
-    if (h->eps < 0) return fail(PO_EINVAL, "eps must be >= 0");
+        return po_fail(PO_EINVAL, "non-finite hyper-parameter");
+    if (h->eps < 0) return po_fail(PO_EINVAL, "eps must be >= 0");
     po_coeffs c{};
     if (h->opt == PO_SGDM) {
-        if (h->beta1 < 0 || h->beta1 >= 1) return fail(PO_EINVAL, "momentum must be in [0,1)");
-        if (h->beta2 < 0 || h->beta2 > 1) return fail(PO_EINVAL, "dampening must be in [0,1]");
+        if (h->beta1 < 0 || h->beta1 >= 1) return po_fail(PO_EINVAL, "momentum must be in [0,1)");
+        if (h->beta2 < 0 || h->beta2 > 1) return po_fail(PO_EINVAL, "dampening must be in [0,1]");
         c.beta1 = (float)h->beta1;
         c.grad_scale = (float)(1.0 - h->beta2);
         c.beta2 = 0.f;
@@ -292,7 +307,7 @@ int pipeoptim_coefficients(const po_hyper* h, int64_t t, int32_t s, po_coeffs* o
         c.eps = 0.f;
         c.wd_coupled = (float)h->weight_decay;
     } else if (h->opt == PO_NESTEROV) {
-        if (h->beta1 < 0 || h->beta1 >= 1) return fail(PO_EINVAL, "momentum must be in [0,1)");
+        if (h->beta1 < 0 || h->beta1 >= 1) return po_fail(PO_EINVAL, "momentum must be in [0,1)");
         c.beta1 = (float)h->beta1;
         c.grad_scale = 1.f;
         c.inv_bc1 = 1.f;
@@ -300,7 +315,7 @@ int pipeoptim_coefficients(const po_hyper* h, int64_t t, int32_t s, po_coeffs* o
         c.wd_coupled = (float)h->weight_decay;
     } else if (h->opt == PO_RMSPROP || h->opt == PO_ADAGRAD) {
         // one kernel serves both: v' = beta2*v + one_m_beta2*g~^2, Adagrad being the case (1, 1)
-        if (h->opt == PO_RMSPROP && (h->beta2 < 0 || h->beta2 >= 1)) return fail(PO_EINVAL, "alpha must be in [0,1)");
+        if (h->opt == PO_RMSPROP && (h->beta2 < 0 || h->beta2 >= 1)) return po_fail(PO_EINVAL, "alpha must be in [0,1)");
         c.beta2 = h->opt == PO_RMSPROP ? (float)h->beta2 : 1.f;
         c.one_m_beta2 = h->opt == PO_RMSPROP ? (float)(1.0 - h->beta2) : 1.f;
         c.inv_bc1 = 1.f;
@@ -308,7 +323,7 @@ int pipeoptim_coefficients(const po_hyper* h, int64_t t, int32_t s, po_coeffs* o
         c.eps = (float)h->eps;
         c.wd_coupled = (float)h->weight_decay;
     } else {
-        if (h->beta1 < 0 || h->beta1 >= 1 || h->beta2 < 0 || h->beta2 >= 1) return fail(PO_EINVAL, "betas must be in [0,1)");
+        if (h->beta1 < 0 || h->beta1 >= 1 || h->beta2 < 0 || h->beta2 >= 1) return po_fail(PO_EINVAL, "betas must be in [0,1)");
         // bias corrections of Table 1, in fp64; t >= 1 and beta < 1 keep both strictly positive
         const double bc1 = 1.0 - std::pow(h->beta1, (double)t);
         const double bc2 = 1.0 - std::pow(h->beta2, (double)t);
@@ -335,10 +350,10 @@ int pipeoptim_coefficients(const po_hyper* h, int64_t t, int32_t s, po_coeffs* o
 
 int pipeoptim_auto_lds_bytes(int32_t kernel, int32_t opt, int64_t n_params, int32_t* out)
 {
-    if (!out) return fail(PO_EINVAL, "out is NULL");
-    if (kernel != PO_KERNEL_KIND_FUSED && kernel != PO_KERNEL_KIND_PREDICT) return fail(PO_EINVAL, "kernel must be 0 (fused) or 1 (prediction)");
-    if (opt < PO_SGDM || opt > PO_ADAGRAD) return fail(PO_EINVAL, "unknown optimizer %d", opt);
-    if (n_params < 0) return fail(PO_EINVAL, "n_params < 0");
+    if (!out) return po_fail(PO_EINVAL, "out is NULL");
+    if (kernel != PO_KERNEL_KIND_FUSED && kernel != PO_KERNEL_KIND_PREDICT) return po_fail(PO_EINVAL, "kernel must be 0 (fused) or 1 (prediction)");
+    if (opt < PO_SGDM || opt > PO_ADAGRAD) return po_fail(PO_EINVAL, "unknown optimizer %d", opt);
+    if (n_params < 0) return po_fail(PO_EINVAL, "n_params < 0");
     *out = auto_lds_bytes(kernel, opt, n_params);
     return PO_OK;
 }
@@ -348,39 +363,39 @@ int pipeoptim_chunk_table_build(int64_t n_tensors, const int64_t* numel, int64_t
 try {
     return build_chunks(n_tensors, numel, chunk_elems, out, capacity, n_chunks);
 }
-catch (const std::bad_alloc&) { return fail(PO_ENOMEM, "pipeoptim_chunk_table_build: out of host memory"); }
-catch (...) { return fail(PO_EINVAL, "pipeoptim_chunk_table_build: unexpected exception"); }
+catch (const std::bad_alloc&) { return po_fail(PO_ENOMEM, "pipeoptim_chunk_table_build: out of host memory"); }
+catch (...) { return po_fail(PO_EINVAL, "pipeoptim_chunk_table_build: unexpected exception"); }
 
 int pipeoptim_plan_create_mixed(po_plan** out, int64_t n_tensors, const int64_t* numel, float* const* W,
                                 const void* const* g, int32_t grad_dtype, float* const* m, float* const* v,
                                 void* const* What, int32_t what_dtype, void* hip_stream)
 try {
     (void)hip_stream;
-    if (!out) return fail(PO_EINVAL, "out is NULL");
+    if (!out) return po_fail(PO_EINVAL, "out is NULL");
     *out = nullptr;
-    if (n_tensors < 0) return fail(PO_EINVAL, "n_tensors < 0");
-    if (n_tensors > 0 && (!numel || !W || !g || !What)) return fail(PO_EINVAL, "a required pointer array is NULL");
-    if (n_tensors > 0 && !m && !v) return fail(PO_EINVAL, "a plan needs at least one of m and v");
-    if (what_dtype != PO_WHAT_F32 && what_dtype != PO_WHAT_BF16) return fail(PO_EINVAL, "unknown what_dtype %d", what_dtype);
-    if (grad_dtype != PO_GRAD_F32 && grad_dtype != PO_GRAD_BF16) return fail(PO_EINVAL, "unknown grad_dtype %d", grad_dtype);
+    if (n_tensors < 0) return po_fail(PO_EINVAL, "n_tensors < 0");
+    if (n_tensors > 0 && (!numel || !W || !g || !What)) return po_fail(PO_EINVAL, "a required pointer array is NULL");
+    if (n_tensors > 0 && !m && !v) return po_fail(PO_EINVAL, "a plan needs at least one of m and v");
+    if (what_dtype != PO_WHAT_F32 && what_dtype != PO_WHAT_BF16) return po_fail(PO_EINVAL, "unknown what_dtype %d", what_dtype);
+    if (grad_dtype != PO_GRAD_F32 && grad_dtype != PO_GRAD_BF16) return po_fail(PO_EINVAL, "unknown grad_dtype %d", grad_dtype);
     const uintptr_t what_mask = what_dtype == PO_WHAT_BF16 ? 1u : 3u;
     const uintptr_t grad_mask = grad_dtype == PO_GRAD_BF16 ? 1u : 3u;
     int64_t total = 0;
     for (int64_t i = 0; i < n_tensors; ++i) {
-        if (numel[i] < 0) return fail(PO_EINVAL, "numel[%lld] < 0", (long long)i);
+        if (numel[i] < 0) return po_fail(PO_EINVAL, "numel[%lld] < 0", (long long)i);
         if (numel[i] == 0) continue;
         if (!W[i] || !g[i] || !What[i] || (m && !m[i]) || (v && !v[i]))
-            return fail(PO_EINVAL, "tensor %lld has a NULL buffer", (long long)i);
+            return po_fail(PO_EINVAL, "tensor %lld has a NULL buffer", (long long)i);
         if (((uintptr_t)W[i] | (m ? (uintptr_t)m[i] : 0) | (v ? (uintptr_t)v[i] : 0)) & 3u)
-            return fail(PO_EALIGN, "tensor %lld: fp32 buffer not 4-byte aligned", (long long)i);
-        if ((uintptr_t)g[i] & grad_mask) return fail(PO_EALIGN, "tensor %lld: g not aligned to its element", (long long)i);
-        if ((uintptr_t)What[i] & what_mask) return fail(PO_EALIGN, "tensor %lld: What not aligned to its element", (long long)i);
+            return po_fail(PO_EALIGN, "tensor %lld: fp32 buffer not 4-byte aligned", (long long)i);
+        if ((uintptr_t)g[i] & grad_mask) return po_fail(PO_EALIGN, "tensor %lld: g not aligned to its element", (long long)i);
+        if ((uintptr_t)What[i] & what_mask) return po_fail(PO_EALIGN, "tensor %lld: What not aligned to its element", (long long)i);
         total += numel[i];
     }
     // the holder frees the host side if anything below throws or fails before device memory exists
     std::unique_ptr<po_plan> holder(new (std::nothrow) po_plan);
     po_plan* p = holder.get();
-    if (!p) return fail(PO_ENOMEM, "out of host memory");
+    if (!p) return po_fail(PO_ENOMEM, "out of host memory");
     p->n_tensors = n_tensors;
     p->n_params = total;
     p->what_dtype = what_dtype;
@@ -404,7 +419,7 @@ try {
     if (e != hipSuccess) return fail_hip(e, "hipGetDevice");
     if (n_tensors > 0) {
         e = hipMalloc(reinterpret_cast<void**>(&p->d_descs), (size_t)n_tensors * sizeof(po_tensor_desc));
-        if (e != hipSuccess) return fail(PO_ENOMEM, "hipMalloc(descriptors): %s", hipGetErrorString(e));
+        if (e != hipSuccess) return po_fail(PO_ENOMEM, "hipMalloc(descriptors): %s", hipGetErrorString(e));
     }
     rc = upload_descs(p);
     if (rc == PO_OK) rc = upload_chunks(p);
@@ -419,8 +434,8 @@ try {
     *out = holder.release();
     return PO_OK;
 }
-catch (const std::bad_alloc&) { return fail(PO_ENOMEM, "pipeoptim_plan_create_mixed: out of host memory"); }
-catch (...) { return fail(PO_EINVAL, "pipeoptim_plan_create_mixed: unexpected exception"); }
+catch (const std::bad_alloc&) { return po_fail(PO_ENOMEM, "pipeoptim_plan_create_mixed: out of host memory"); }
+catch (...) { return po_fail(PO_EINVAL, "pipeoptim_plan_create_mixed: unexpected exception"); }
 
 int pipeoptim_plan_create(po_plan** out, int64_t n_tensors, const int64_t* numel, float* const* W,
                           const float* const* g, float* const* m, float* const* v, void* const* What,
@@ -446,16 +461,16 @@ int pipeoptim_plan_destroy(po_plan* p)
 
 int pipeoptim_plan_set_pointers(po_plan* p, int32_t which, void* const* ptrs)
 try {
-    if (!p) return fail(PO_EINVAL, "plan is NULL");
-    if (which < 0 || which > 4) return fail(PO_EINVAL, "which must be 0..4");
-    if (which == 3 && !p->has_v) return fail(PO_EINVAL, "plan has no v column");
-    if (which == 2 && !p->has_m) return fail(PO_EINVAL, "plan has no m column");
-    if (p->n_tensors > 0 && !ptrs) return fail(PO_EINVAL, "ptrs is NULL");
+    if (!p) return po_fail(PO_EINVAL, "plan is NULL");
+    if (which < 0 || which > 4) return po_fail(PO_EINVAL, "which must be 0..4");
+    if (which == 3 && !p->has_v) return po_fail(PO_EINVAL, "plan has no v column");
+    if (which == 2 && !p->has_m) return po_fail(PO_EINVAL, "plan has no m column");
+    if (p->n_tensors > 0 && !ptrs) return po_fail(PO_EINVAL, "ptrs is NULL");
     const uintptr_t mask = ((which == 4 && p->what_dtype == PO_WHAT_BF16) || (which == 1 && p->grad_dtype == PO_GRAD_BF16)) ? 1u : 3u;
     for (int64_t i = 0; i < p->n_tensors; ++i) {
         if (p->numel[(size_t)i] == 0) continue;
-        if (!ptrs[i]) return fail(PO_EINVAL, "tensor %lld: NULL pointer", (long long)i);
-        if ((uintptr_t)ptrs[i] & mask) return fail(PO_EALIGN, "tensor %lld: pointer not aligned to its element", (long long)i);
+        if (!ptrs[i]) return po_fail(PO_EINVAL, "tensor %lld: NULL pointer", (long long)i);
+        if ((uintptr_t)ptrs[i] & mask) return po_fail(PO_EALIGN, "tensor %lld: pointer not aligned to its element", (long long)i);
     }
     const std::vector<po_tensor_desc> saved = p->descs;
     for (int64_t i = 0; i < p->n_tensors; ++i) {
@@ -475,19 +490,19 @@ try {
     if (e != hipSuccess) return fail_hip(e, "hipDeviceSynchronize");
     return upload_descs(p);
 }
-catch (const std::bad_alloc&) { return fail(PO_ENOMEM, "pipeoptim_plan_set_pointers: out of host memory"); }
-catch (...) { return fail(PO_EINVAL, "pipeoptim_plan_set_pointers: unexpected exception"); }
+catch (const std::bad_alloc&) { return po_fail(PO_ENOMEM, "pipeoptim_plan_set_pointers: out of host memory"); }
+catch (...) { return po_fail(PO_EINVAL, "pipeoptim_plan_set_pointers: unexpected exception"); }
 
 int pipeoptim_plan_get_launch(const po_plan* p, po_launch* out)
 {
-    if (!p || !out) return fail(PO_EINVAL, "plan or out is NULL");
+    if (!p || !out) return po_fail(PO_EINVAL, "plan or out is NULL");
     *out = p->launch;
     return PO_OK;
 }
 
 int pipeoptim_plan_set_launch(po_plan* p, const po_launch* L)
 try {
-    if (!p || !L) return fail(PO_EINVAL, "plan or launch is NULL");
+    if (!p || !L) return po_fail(PO_EINVAL, "plan or launch is NULL");
     int rc = check_launch(*L);
     if (rc != PO_OK) return rc;
     int64_t n_new = 0;
@@ -514,25 +529,25 @@ try {
     }
     return PO_OK;
 }
-catch (const std::bad_alloc&) { return fail(PO_ENOMEM, "pipeoptim_plan_set_launch: out of host memory"); }
-catch (...) { return fail(PO_EINVAL, "pipeoptim_plan_set_launch: unexpected exception"); }
+catch (const std::bad_alloc&) { return po_fail(PO_ENOMEM, "pipeoptim_plan_set_launch: out of host memory"); }
+catch (...) { return po_fail(PO_EINVAL, "pipeoptim_plan_set_launch: unexpected exception"); }
 
 int pipeoptim_plan_get_predict_launch(const po_plan* p, po_launch* out)
 {
-    if (!p || !out) return fail(PO_EINVAL, "plan or out is NULL");
+    if (!p || !out) return po_fail(PO_EINVAL, "plan or out is NULL");
     *out = p->predict_launch;
     return PO_OK;
 }
 
 int pipeoptim_plan_set_predict_launch(po_plan* p, const po_launch* L_in)
 {
-    if (!p || !L_in) return fail(PO_EINVAL, "plan or launch is NULL");
+    if (!p || !L_in) return po_fail(PO_EINVAL, "plan or launch is NULL");
     po_launch L = *L_in;
     if (L.chunk_elems == 0) L.chunk_elems = p->launch.chunk_elems;
     int rc = check_launch(L);
     if (rc != PO_OK) return rc;
     if (L.chunk_elems != p->launch.chunk_elems)
-        return fail(PO_EINVAL, "the prediction kernel shares the plan's chunk table: chunk_elems must be %lld",
+        return po_fail(PO_EINVAL, "the prediction kernel shares the plan's chunk table: chunk_elems must be %lld",
                     (long long)p->launch.chunk_elems);
     rc = check_grid(L, (int64_t)p->chunks.size());
     if (rc != PO_OK) return rc;
@@ -540,9 +555,67 @@ int pipeoptim_plan_set_predict_launch(po_plan* p, const po_launch* L_in)
     return PO_OK;
 }
 
+int pipeoptim_plan_localize(po_plan* p, const po_arena* arena, int64_t* n_local_params)
+{
+    if (!p) return po_fail(PO_EINVAL, "plan is NULL");
+    const std::vector<po_tensor_desc> saved = p->descs;
+    int64_t n_local = 0;
+    for (int64_t i = 0; i < p->n_tensors; ++i) {
+        po_tensor_desc& d = p->descs[(size_t)i];
+        d.flags &= ~(PO_DESC_LOCAL | PO_DESC_HALF1);
+        if (!arena || d.numel == 0) continue;
+        // every fp32 stream of the tensor: inside the arena, one class, 16 KiB aligned.  Then the 8 KiB block that
+        // holds elements [2048 j, 2048 j + 2048) of any of them is near to XCC half (j & 1) ^ class.
+        const size_t n = (size_t)d.numel * 4;
+        const void* streams[5] = {d.W, p->grad_dtype == PO_GRAD_F32 ? d.g : nullptr, d.m, d.v,
+                                  p->what_dtype == PO_WHAT_F32 ? d.What : nullptr};
+        int cls = -2;                                   // -2: no stream seen yet; -1: not eligible
+        for (const void* q : streams) {
+            if (!q) continue;
+            const int c = ((uintptr_t)q & 16383u) ? -1 : po_arena_class_of(arena, q, n);
+            cls = (cls == -2 || cls == c) ? c : -1;
+            if (cls == -1) break;
+        }
+        if (cls < 0) continue;
+        d.flags |= PO_DESC_LOCAL | (cls ? PO_DESC_HALF1 : 0u);
+        n_local += d.numel;
+    }
+    hipError_t e = hipDeviceSynchronize();   // a launch may still read the old descriptors
+    if (e != hipSuccess) { p->descs = saved; return fail_hip(e, "hipDeviceSynchronize"); }
+    const int rc = upload_descs(p);
+    if (rc != PO_OK) { p->descs = saved; return rc; }
+    p->n_local_params = n_local;
+    if (n_local_params) *n_local_params = n_local;
+    return PO_OK;
+}
+
+int pipeoptim_plan_local_params(const po_plan* p, int64_t* n_local_params)
+{
+    if (!p || !n_local_params) return po_fail(PO_EINVAL, "plan or n_local_params is NULL");
+    *n_local_params = p->n_local_params;
+    return PO_OK;
+}
+
+int pipeoptim_plan_effective_launch(const po_plan* p, int32_t kernel, int32_t opt, po_launch* out)
+{
+    if (!p || !out) return po_fail(PO_EINVAL, "plan or out is NULL");
+    if (kernel != PO_KERNEL_KIND_FUSED && kernel != PO_KERNEL_KIND_PREDICT) return po_fail(PO_EINVAL, "kernel must be 0 (fused) or 1 (prediction)");
+    if (opt < PO_SGDM || opt > PO_ADAGRAD) return po_fail(PO_EINVAL, "unknown optimizer %d", opt);
+    *out = resolve_launch(p, kernel == PO_KERNEL_KIND_FUSED ? p->launch : p->predict_launch, kernel, opt);
+    return PO_OK;
+}
+
+int pipeoptim_local_tile(uint32_t tile_in_chunk, int32_t first_block_half, uint32_t* out)
+{
+    if (!out) return po_fail(PO_EINVAL, "out is NULL");
+    if (first_block_half != 0 && first_block_half != 1) return po_fail(PO_EINVAL, "first_block_half must be 0 or 1");
+    *out = po_local_tile(tile_in_chunk, (uint32_t)first_block_half);
+    return PO_OK;
+}
+
 int pipeoptim_plan_info(const po_plan* p, int64_t* n_params, int64_t* n_chunks, int64_t* n_unaligned)
 {
-    if (!p) return fail(PO_EINVAL, "plan is NULL");
+    if (!p) return po_fail(PO_EINVAL, "plan is NULL");
     if (n_params) *n_params = p->n_params;
     if (n_chunks) *n_chunks = (int64_t)p->chunks.size();
     if (n_unaligned) *n_unaligned = p->n_unaligned;
@@ -551,7 +624,7 @@ int pipeoptim_plan_info(const po_plan* p, int64_t* n_params, int64_t* n_chunks, 
 
 int pipeoptim_step_predict(const po_plan* p, const po_hyper* h, int64_t t, int32_t s, void* hip_stream)
 {
-    if (!p) return fail(PO_EINVAL, "plan is NULL");
+    if (!p) return po_fail(PO_EINVAL, "plan is NULL");
     po_coeffs c;
     int rc = pipeoptim_coefficients(h, t, s, &c);
     if (rc != PO_OK) return rc;
@@ -560,7 +633,7 @@ int pipeoptim_step_predict(const po_plan* p, const po_hyper* h, int64_t t, int32
     if (p->chunks.empty()) return PO_OK;
     rc = check_device(p);
     if (rc != PO_OK) return rc;
-    const po_launch L = resolve_launch(p->launch, PO_KERNEL_KIND_FUSED, h->opt, p->n_params);
+    const po_launch L = resolve_launch(p, p->launch, PO_KERNEL_KIND_FUSED, h->opt);
     hipError_t e = po_launch_step_predict(h->opt, p->what_dtype, p->grad_dtype, L, p->d_descs, p->d_chunks,
                                           (uint32_t)p->chunks.size(), c, static_cast<hipStream_t>(hip_stream));
     if (e != hipSuccess) return fail_hip(e, "launch of the fused step+predict kernel");
@@ -569,18 +642,18 @@ int pipeoptim_step_predict(const po_plan* p, const po_hyper* h, int64_t t, int32
 
 int pipeoptim_predict(const po_plan* p, const po_hyper* h, int64_t t, int32_t s, void* hip_stream)
 {
-    if (!p) return fail(PO_EINVAL, "plan is NULL");
+    if (!p) return po_fail(PO_EINVAL, "plan is NULL");
     po_coeffs c;
     int rc = pipeoptim_coefficients(h, t, s, &c);
     if (rc != PO_OK) return rc;
     if (h->opt > PO_ADAMW)
-        return fail(PO_EINVAL, "optimizer %d: the direction needs the gradient, there is no prediction from the state alone", h->opt);
+        return po_fail(PO_EINVAL, "optimizer %d: the direction needs the gradient, there is no prediction from the state alone", h->opt);
     rc = check_state(p, h->opt);
     if (rc != PO_OK) return rc;
     if (p->chunks.empty()) return PO_OK;
     rc = check_device(p);
     if (rc != PO_OK) return rc;
-    const po_launch L = resolve_launch(p->predict_launch, PO_KERNEL_KIND_PREDICT, h->opt, p->n_params);
+    const po_launch L = resolve_launch(p, p->predict_launch, PO_KERNEL_KIND_PREDICT, h->opt);
     hipError_t e = po_launch_predict(h->opt, p->what_dtype, L, p->d_descs, p->d_chunks,
                                      (uint32_t)p->chunks.size(), c, static_cast<hipStream_t>(hip_stream));
     if (e != hipSuccess) return fail_hip(e, "launch of the prediction kernel");
@@ -589,10 +662,10 @@ int pipeoptim_predict(const po_plan* p, const po_hyper* h, int64_t t, int32_t s,
 
 int pipeoptim_probe_copy(void* dst, const void* src, int64_t nbytes, void* hip_stream)
 {
-    if (nbytes < 0 || (nbytes & 15)) return fail(PO_EINVAL, "nbytes must be a non-negative multiple of 16");
+    if (nbytes < 0 || (nbytes & 15)) return po_fail(PO_EINVAL, "nbytes must be a non-negative multiple of 16");
     if (nbytes == 0) return PO_OK;
-    if (!dst || !src) return fail(PO_EINVAL, "dst or src is NULL");
-    if (((uintptr_t)dst | (uintptr_t)src) & 15u) return fail(PO_EALIGN, "dst and src must be 16-byte aligned");
+    if (!dst || !src) return po_fail(PO_EINVAL, "dst or src is NULL");
+    if (((uintptr_t)dst | (uintptr_t)src) & 15u) return po_fail(PO_EALIGN, "dst and src must be 16-byte aligned");
     hipError_t e = po_launch_probe_copy(dst, src, nbytes, static_cast<hipStream_t>(hip_stream));
     if (e != hipSuccess) return fail_hip(e, "launch of the copy kernel");
     return PO_OK;

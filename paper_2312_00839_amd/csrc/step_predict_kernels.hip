@@ -156,7 +156,8 @@ struct alignas(32) KArgs {
     uint32_t xcd_stride;     // 0: slot = workgroup id; else grid/8: slot = (id & 7) * xcd_stride + (id >> 3)
     uint32_t tile;           // block * 4 * unroll
     po_coeffs c;             // 52 bytes
-    uint32_t pad;
+    uint32_t local_ok;       // 1: this launch shape supports the near-memory tile order (1 KiB tiles, whole groups
+                             //    of 16 tiles per chunk, slot = workgroup id)
 };
 static_assert(sizeof(KArgs) == 96, "KArgs is loaded as 64 + 32 bytes");
 
@@ -196,7 +197,10 @@ __device__ __forceinline__ bool locate_tile(const KArgs& a, Tile& t)
     union { u32x16 raw; po_tensor_desc d; } u;
     u.raw = *(const PO_CONSTANT u32x16*)(uintptr_t)(a.descs + ch.tensor);
     t.d = u.d;
-    t.off = (int64_t)ch.chunk * a.chunk_elems + (int64_t)(slot & ((1u << a.tiles_log2) - 1u)) * a.tile;
+    uint32_t tile_in_chunk = slot & ((1u << a.tiles_log2) - 1u);
+    // tensors in a near-memory arena: the workgroups on XCCs 0-3 take the tiles whose blocks are near to their die
+    if (a.local_ok && (t.d.flags & PO_DESC_LOCAL)) tile_in_chunk = po_local_tile(tile_in_chunk, (t.d.flags & PO_DESC_HALF1) ? 1u : 0u);
+    t.off = (int64_t)ch.chunk * a.chunk_elems + (int64_t)tile_in_chunk * a.tile;
     if (t.off >= t.d.numel) return false;
     t.len = (t.d.numel - t.off < (int64_t)a.tile) ? (uint32_t)(t.d.numel - t.off) : a.tile;
     t.full = t.len == a.tile && (t.d.flags & PO_DESC_VECTOR_OK);
@@ -370,6 +374,7 @@ hipError_t launch_one(const po_launch& L, const po_tensor_desc* descs, const po_
     a.xcd_stride = L.xcd_remap ? (uint32_t)(grid >> 3) : 0u;
     a.tile = tile;
     a.c = c;
+    a.local_ok = (!L.xcd_remap && tile == PO_LOCAL_TILE_ELEMS && tiles_per_chunk >= PO_LOCAL_GROUP_TILES) ? 1u : 0u;
     if constexpr (KIND == PO_KERNEL_PREDICT)
         hipLaunchKernelGGL((predict_kernel<OPT, BF16, UNROLL, POL>), dim3((uint32_t)grid), dim3(L.block),
                            (size_t)L.lds_bytes, stream, a);

@@ -29,6 +29,76 @@ def alloc_skewed(n: int, dtype: torch.dtype, device, slot: int) -> torch.Tensor:
     return buf[shift // esize: shift // esize + n]
 
 
+class _DeviceSpan:
+    """Describes raw device memory to PyTorch through the array interface it accepts for zero-copy import."""
+
+    def __init__(self, ptr: int, numel: int, typestr: str):
+        self.__cuda_array_interface__ = {"shape": (numel,), "typestr": typestr, "data": (ptr, False), "version": 3,
+                                         "strides": None}
+
+
+def tensor_at(ptr: int, numel: int, dtype: torch.dtype, device, owner) -> torch.Tensor:
+    """A flat tensor over numel elements of device memory at `ptr` that PyTorch did not allocate (no copy).
+    `owner` is whatever keeps that memory alive; the tensor holds a reference to it."""
+    if numel == 0:
+        return torch.empty(0, dtype=dtype, device=device)
+    if dtype == torch.float32:
+        t = torch.as_tensor(_DeviceSpan(ptr, numel, "<f4"), device=device)
+    elif dtype == torch.bfloat16:          # the array interface has no bf16: import the bits, reinterpret
+        t = torch.as_tensor(_DeviceSpan(ptr, numel, "<i2"), device=device).view(torch.bfloat16)
+    else:
+        raise ValueError("tensor_at supports float32 and bfloat16")
+    if t.data_ptr() != ptr:
+        raise RuntimeError("PyTorch copied the arena memory instead of wrapping it")
+    t._pipeoptim_owner = owner
+    return t
+
+
+class StageArena:
+    """All five streams of a stage's tensors (W, g, m, v, What) in one near-memory arena (MI355X).
+
+    The streams of tensor i come from one ``pipeoptim_arena_alloc`` call, so they share one block-to-die layout and a
+    plan over them can be localized (``Plan.localize``).  The tensors are uninitialised views of arena memory;
+    they stay valid until ``close()``.
+    """
+
+    def __init__(self, numels, what_dtype: str, grad_dtype: str = "f32", has_m: bool = True, has_v: bool = True,
+                 device="cuda", skew_bytes: Optional[int] = None):
+        dev = torch.device(device)
+        if dev.index is None:
+            dev = torch.device("cuda", torch.cuda.current_device())
+        wsz = 2 if what_dtype == "bf16" else 4
+        gsz = 2 if grad_dtype == "bf16" else 4
+        per_param = 4 + gsz + (4 if has_m else 0) + (4 if has_v else 0) + wsz
+        # every buffer is 16 KiB aligned and big ones are followed by a gap: leave room for both
+        capacity = sum(n * per_param + 5 * 16384 + 5 * (4 << 20) for n in numels) + (64 << 20)
+        with torch.cuda.device(dev):
+            self.arena = binding.Arena(capacity)
+            if skew_bytes is not None:
+                self.arena.set_skew(skew_bytes)
+            self.W, self.g, self.What = [], [], []
+            self.m = [] if has_m else None
+            self.v = [] if has_v else None
+            gdt = torch.bfloat16 if grad_dtype == "bf16" else torch.float32
+            wdt = torch.bfloat16 if what_dtype == "bf16" else torch.float32
+            for n in numels:
+                sizes = [4 * n, gsz * n] + ([4 * n] if has_m else []) + ([4 * n] if has_v else []) + [wsz * n]
+                ptrs = self.arena.alloc(sizes)
+                k = iter(ptrs)
+                self.W.append(tensor_at(next(k), n, torch.float32, dev, self.arena))
+                self.g.append(tensor_at(next(k), n, gdt, dev, self.arena))
+                if has_m:
+                    self.m.append(tensor_at(next(k), n, torch.float32, dev, self.arena))
+                if has_v:
+                    self.v.append(tensor_at(next(k), n, torch.float32, dev, self.arena))
+                self.What.append(tensor_at(next(k), n, wdt, dev, self.arena))
+        self.what_dtype = what_dtype
+
+    def close(self) -> None:
+        """Frees the arena's memory.  Every tensor it handed out is invalid from here on."""
+        self.arena.destroy()
+
+
 class Stage:
     """Holds flat fp32 W, g, m, v tensors (m or v may be None) and the What buffers, plus the plan over their addresses.
 
@@ -37,7 +107,10 @@ class Stage:
     """
 
     def __init__(self, W: List[torch.Tensor], g: List[torch.Tensor], m: Optional[List[torch.Tensor]],
-                 v: Optional[List[torch.Tensor]], what_dtype: str, skew_what: bool = True):
+                 v: Optional[List[torch.Tensor]], what_dtype: str, skew_what: bool = True,
+                 What: Optional[List[torch.Tensor]] = None, arena: Optional[binding.Arena] = None):
+        """`What`: prediction buffers the caller already holds (else the stage allocates them).  `arena`: the
+        near-memory arena the tensors came from, if any; the plan is then localized over it."""
         for lst in (W,) + ((m,) if m is not None else ()) + ((v,) if v is not None else ()):
             for x in lst:
                 if x.dtype != torch.float32 or not x.is_contiguous() or x.device.type != "cuda":
@@ -51,7 +124,12 @@ class Stage:
         self.W, self.g, self.m, self.v = W, g, m, v
         self.what_dtype = what_dtype
         tdt = torch.bfloat16 if what_dtype == "bf16" else torch.float32
-        if skew_what:
+        if What is not None:
+            if len(What) != len(W) or any(h.dtype != tdt or h.numel() != x.numel() or not h.is_contiguous()
+                                          for h, x in zip(What, W)):
+                raise ValueError("What must match W in length and sizes and have the prediction's dtype")
+            self.What = What
+        elif skew_what:
             # What takes an address slot (bits 12-13) that no other stream of its tensor uses, else the gradient's
             self.What = []
             for i, x in enumerate(W):
@@ -67,6 +145,7 @@ class Stage:
                                  ptrs(v) if v is not None else None,
                                  ptrs(self.What), what_dtype, torch.cuda.current_stream().cuda_stream,
                                  grad_dtype=self.grad_dtype)
+        self.n_local_params = self.plan.localize(arena) if arena is not None else 0
 
     @property
     def n_params(self) -> int:

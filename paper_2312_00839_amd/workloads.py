@@ -182,14 +182,21 @@ def make_inputs(wl: Workload, device, tensors=None, layout="packed"):
     `tensors` optionally restricts the list to a subset of tensor indices (same seeds as in the full list).
     layout "packed": plain allocations, which the allocator places back to back.  "skewed" (GPU only): the
     same values, with the W, g, m, v buffers of a tensor placed so that their addresses differ in bits 12-13
-    (`stage.alloc_skewed`), the placement the memory system of MI355X prefers.
+    (`stage.alloc_skewed`), the placement the memory system of MI355X prefers.  "local" (GPU only): the same
+    values in a near-memory arena (`stage.StageArena`), which also holds the What buffers; the result then has
+    the extra keys "What", "arena" (hand both to `Stage`) and "stage_arena" (close it when done).
     """
     idx = range(len(wl.shapes)) if tensors is None else tensors
     numels = wl.numels
     out = {"W": [], "g": [], "m": [], "v": [] if wl.optimizer != "sgdm" else None, "index": list(idx)}
-    if layout not in ("packed", "skewed"):
-        raise ValueError("layout must be 'packed' or 'skewed'")
-    for i in out["index"]:
+    if layout not in ("packed", "skewed", "local"):
+        raise ValueError("layout must be 'packed', 'skewed' or 'local'")
+    sa = None
+    if layout == "local":
+        from .stage import StageArena
+        sa = StageArena([numels[i] for i in out["index"]], wl.what_dtype, has_v=out["v"] is not None, device=device)
+        out.update(What=sa.What, arena=sa.arena, stage_arena=sa)
+    for pos, i in enumerate(out["index"]):
         for slot, which in enumerate(("W", "g", "m", "v")):
             if out[which] is None:
                 continue
@@ -197,5 +204,7 @@ def make_inputs(wl: Workload, device, tensors=None, layout="packed"):
             if layout == "skewed":
                 from .stage import alloc_skewed
                 dst = alloc_skewed(numels[i], torch.float32, device, slot)
+            elif layout == "local":
+                dst = getattr(sa, which)[pos]
             out[which].append(fill_tensor(wl.config, i, which, numels[i], wl.sigma[which], device, out=dst))
     return out

@@ -192,6 +192,21 @@ def compare_predict(kind, hp, t, s, inp, ref, got, what_dtype, label="", decay_i
     return report
 
 
+def to_arena(tensors, what_dtype, skew_bytes=None):
+    """The same values in a near-memory arena: dict of lists like `tensors`, plus "What", "arena" (hand both to
+    Stage; run_and_compare_* do) and "stage_arena" (close it when done)."""
+    from paper_2312_00839_amd.stage import StageArena
+    gdt = "bf16" if tensors["g"][0].dtype == torch.bfloat16 else "f32"
+    sa = StageArena([x.numel() for x in tensors["W"]], what_dtype, grad_dtype=gdt, has_m=tensors.get("m") is not None,
+                    has_v=tensors.get("v") is not None, device=tensors["W"][0].device, skew_bytes=skew_bytes)
+    out = {"W": sa.W, "g": sa.g, "m": sa.m, "v": sa.v, "What": sa.What, "arena": sa.arena, "stage_arena": sa}
+    for k in ("W", "g", "m", "v"):
+        if tensors.get(k) is not None:
+            for dst, src in zip(out[k], tensors[k]):
+                dst.copy_(src)
+    return out
+
+
 def run_oracle_predict(kind, hp, t, s, inp, decay_in_prediction=True, nthreads=8):
     return oracle.predict(OPT_CODE[kind], inp["W"], inp["m"], inp.get("v"), lr=hp["lr"], beta1=hp["beta1"],
                           beta2=hp["beta2"], eps=hp["eps"], weight_decay=hp["weight_decay"],
@@ -202,7 +217,8 @@ def run_and_compare_predict(kind, hp, t, s, tensors, what_dtype, launch=None, de
     """Prediction-only call on device tensors W, m, v (g is present but must not be read or written)."""
     keys = [k for k in ("W", "g", "m", "v") if tensors.get(k) is not None]
     host = [{k: tensors[k][i].cpu().numpy().copy() for k in keys} for i in range(len(tensors["W"]))]
-    stage = Stage(tensors["W"], tensors["g"], tensors["m"], tensors.get("v"), what_dtype)
+    stage = Stage(tensors["W"], tensors["g"], tensors["m"], tensors.get("v"), what_dtype,
+                  What=tensors.get("What"), arena=tensors.get("arena"))
     try:
         if launch:
             stage.plan.set_launch(**{k: v for k, v in launch.items() if k == "chunk_elems"})
@@ -240,7 +256,8 @@ def run_and_compare_full(kind, hp, t, s, tensors, what_dtype, launch=None, decay
     host = [{k: host_f32(tensors[k][i]) for k in ("W", "g", "m", "v") if tensors.get(k) is not None}
             for i in range(len(tensors["W"]))]
     g_before = [raw_bits(x) for x in tensors["g"]]
-    stage = Stage(tensors["W"], tensors["g"], tensors.get("m"), tensors.get("v"), what_dtype)
+    stage = Stage(tensors["W"], tensors["g"], tensors.get("m"), tensors.get("v"), what_dtype,
+                  What=tensors.get("What"), arena=tensors.get("arena"))
     try:
         if launch:
             stage.plan.set_launch(**launch)

@@ -138,6 +138,50 @@ def test_auto_lds_bytes():
         assert e.value.status == binding.PO_EINVAL
 
 
+def test_near_memory_tile_order_is_a_bijection_and_splits_blocks_by_xcc_half():
+    """Workgroup ids go to XCCs round-robin (id mod 8).  In the near-memory order, within every aligned run of
+    16 positions the eight ids on XCCs 0-3 must take the 8-tile block that is near to their die and the other
+    eight the other block, every tile exactly once."""
+    for half in (0, 1):
+        for base in (0, 16, 240, 65520):
+            tiles = [binding.pipeoptim_local_tile(base + k, half) for k in range(16)]
+            assert sorted(tiles) == list(range(base, base + 16))
+            for k, tile in enumerate(tiles):
+                xcc = k % 8
+                xcc_half = xcc // 4
+                block = (tile - base) // 8               # 8 tiles of 1 KiB = one 8 KiB block per fp32 stream
+                near_half_of_block = block ^ half        # the first block is near to `half`, the second to the other
+                assert near_half_of_block == xcc_half
+            # the four XCCs of a die share a block 1 KiB each per round; the second round takes the other 4 KiB
+            assert {t - base for t in tiles[0:4]} | {t - base for t in tiles[8:12]} == set(range(8 * half, 8 * half + 8))
+    out = ctypes.c_uint32()
+    assert binding.lib().pipeoptim_local_tile(0, 2, ctypes.byref(out)) == binding.PO_EINVAL
+    assert binding.lib().pipeoptim_local_tile(0, 0, None) == binding.PO_EINVAL
+
+
+def test_arena_and_localize_argument_validation():
+    L = binding.lib()
+    h = ctypes.c_void_p()
+    assert L.pipeoptim_arena_create(None, 1 << 20) == binding.PO_EINVAL
+    assert L.pipeoptim_arena_create(ctypes.byref(h), 0) == binding.PO_EINVAL
+    assert L.pipeoptim_arena_create(ctypes.byref(h), -5) == binding.PO_EINVAL
+    assert L.pipeoptim_arena_create(ctypes.byref(h), (1 << 40) + 1) == binding.PO_EINVAL
+    assert not h.value
+    assert L.pipeoptim_arena_destroy(None) == binding.PO_OK
+    one = (ctypes.c_int64 * 1)(64)
+    ptr = (ctypes.c_void_p * 1)()
+    assert L.pipeoptim_arena_alloc(None, 1, one, ptr) == binding.PO_EINVAL
+    assert L.pipeoptim_arena_set_skew(None, 0) == binding.PO_EINVAL
+    half = ctypes.c_int32()
+    assert L.pipeoptim_arena_near_half(None, None, ctypes.byref(half)) == binding.PO_EINVAL
+    assert L.pipeoptim_arena_info(None, None, None, None, None, None) == binding.PO_EINVAL
+    n = ctypes.c_int64()
+    assert L.pipeoptim_plan_localize(None, None, ctypes.byref(n)) == binding.PO_EINVAL
+    assert L.pipeoptim_plan_local_params(None, ctypes.byref(n)) == binding.PO_EINVAL
+    launch = binding.po_launch()
+    assert L.pipeoptim_plan_effective_launch(None, 0, 1, ctypes.byref(launch)) == binding.PO_EINVAL
+
+
 @pytest.mark.parametrize("chunk", [1, 4096, 8192, 65536, 1 << 30])
 def test_chunk_table_covers_every_element_exactly_once(chunk):
     numel = [0, 1, 3, 4095, 4096, 4097, 0, 131072000, 12288, 7]

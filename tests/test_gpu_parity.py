@@ -540,11 +540,13 @@ def test_probe_copy_copies():
 
 
 # --------------------------------------------------------------------------- the five configurations
-def _full_config(cfg, s):
+def _full_config(cfg, s, layout="packed"):
     wl = workload(cfg)
-    _say("config %d (%s) s=%d full compare, N=%d" % (cfg, wl.name, s, wl.n_params))
-    tensors = make_inputs(wl, DEV)
+    _say("config %d (%s) s=%d full compare, N=%d, layout %s" % (cfg, wl.name, s, wl.n_params, layout))
+    tensors = make_inputs(wl, DEV, layout=layout)
     reps = run_and_compare_full(wl.optimizer, wl.hyper, wl.t, s, tensors, wl.what_dtype, label="config %d" % cfg)
+    if layout == "local":
+        tensors["stage_arena"].close()
     worst = {k: max(r[k] for r in reps if k in r) for k in reps[0]}
     _say("config %d s=%d worst error ratios (1.0 = 1e-0 of scale): %s" % (cfg, s, worst))
 
@@ -562,12 +564,12 @@ def test_config3_bert_adam_bf16_full():
     _full_config(3, 2)
 
 
-def _sampled_config(cfg, s, blocks_per_tensor=6, block=8192, seed=0):
+def _sampled_config(cfg, s, blocks_per_tensor=6, block=8192, seed=0, layout="packed"):
     """Full-size run in the default (benchmarked) launch shape; the oracle recomputes sampled
     index ranges of every tensor: its head, its ragged tail and random interior ranges."""
     wl = workload(cfg)
-    _say("config %d (%s) s=%d sampled compare, N=%d" % (cfg, wl.name, s, wl.n_params))
-    tensors = make_inputs(wl, DEV)
+    _say("config %d (%s) s=%d sampled compare, N=%d, layout %s" % (cfg, wl.name, s, wl.n_params, layout))
+    tensors = make_inputs(wl, DEV, layout=layout)
     rng = np.random.default_rng(1234 + cfg * 10 + s + seed)
     ranges, saved = [], []
     for i, n in enumerate(wl.numels):
@@ -579,7 +581,10 @@ def _sampled_config(cfg, s, blocks_per_tensor=6, block=8192, seed=0):
         idx = torch.cat([torch.arange(a, b, device=DEV) for a, b in r])
         saved.append((idx, {k: tensors[k][i][idx].cpu().numpy() for k in ("W", "g", "m", "v") if tensors.get(k) is not None}))
     W_in = [w.clone() for w in tensors["W"]]
-    stage = Stage(tensors["W"], tensors["g"], tensors["m"], tensors.get("v"), wl.what_dtype)
+    stage = Stage(tensors["W"], tensors["g"], tensors["m"], tensors.get("v"), wl.what_dtype,
+                  What=tensors.get("What"), arena=tensors.get("arena"))
+    if layout == "local":
+        assert stage.n_local_params == wl.n_params
     stage.step_predict(make_hyper(wl.optimizer, wl.hyper), wl.t, s)
     torch.cuda.synchronize()
     worst = {}
@@ -602,6 +607,8 @@ def _sampled_config(cfg, s, blocks_per_tensor=6, block=8192, seed=0):
         bad = ((What - line).abs() > tol).sum().item()
         assert bad == 0, "config %d tensor %d: %d elements off the line through W_in and W'" % (cfg, i, bad)
     stage.close()
+    if layout == "local":
+        tensors["stage_arena"].close()
     _say("config %d s=%d worst: %s" % (cfg, s, worst))
 
 
@@ -616,6 +623,19 @@ def test_config4_gpt_adamw_bf16_full():
 
 def test_config5_llama_adamw_bf16_sampled():
     _sampled_config(5, 7, blocks_per_tensor=10)
+
+
+def test_config3_bert_adam_bf16_full_in_near_memory_arena():
+    _full_config(3, 2, layout="local")
+
+
+def test_config2_resnet_sgdm_full_in_near_memory_arena():
+    _full_config(2, 3, layout="local")
+
+
+def test_config5_llama_adamw_bf16_sampled_in_near_memory_arena():
+    # the layout and launch shape bench.py times by default
+    _sampled_config(5, 7, blocks_per_tensor=10, layout="local")
 
 
 def test_config5_s0_prediction_is_rounded_W_everywhere():
