@@ -176,8 +176,12 @@ def fill_tensor(config: int, tensor_index: int, which: str, numel: int, sigma: f
     return x
 
 
-def make_inputs(wl: Workload, device, tensors=None, layout="packed"):
+def make_inputs(wl: Workload, device, tensors=None, layout="packed", optimizer=None):
     """Separately allocated flat tensors for the stage: dict of lists W, g, m, v (v is None for SGDM).
+
+    `optimizer` runs the config's tensor list under another optimizer than its own: the state lists are the ones
+    that optimizer has (m is None for RMSprop and Adagrad, v is None for SGDM and Nesterov), and a second moment
+    the config gives no scale for is the square of a draw with the first moment's scale.
 
     `tensors` optionally restricts the list to a subset of tensor indices (same seeds as in the full list).
     layout "packed": plain allocations, which the allocator places back to back.  "skewed" (GPU only): the
@@ -188,13 +192,19 @@ def make_inputs(wl: Workload, device, tensors=None, layout="packed"):
     """
     idx = range(len(wl.shapes)) if tensors is None else tensors
     numels = wl.numels
-    out = {"W": [], "g": [], "m": [], "v": [] if wl.optimizer != "sgdm" else None, "index": list(idx)}
+    opt = optimizer or wl.optimizer
+    sigma = dict(wl.sigma)
+    if not sigma.get("v"):
+        sigma["v"] = sigma["m"]
+    out = {"W": [], "g": [], "m": [] if opt not in ("rmsprop", "adagrad") else None,
+           "v": [] if opt not in ("sgdm", "nesterov") else None, "index": list(idx)}
     if layout not in ("packed", "skewed", "local"):
         raise ValueError("layout must be 'packed', 'skewed' or 'local'")
     sa = None
     if layout == "local":
         from .stage import StageArena
-        sa = StageArena([numels[i] for i in out["index"]], wl.what_dtype, has_v=out["v"] is not None, device=device)
+        sa = StageArena([numels[i] for i in out["index"]], wl.what_dtype, has_m=out["m"] is not None,
+                        has_v=out["v"] is not None, device=device)
         out.update(What=sa.What, arena=sa.arena, stage_arena=sa)
     for pos, i in enumerate(out["index"]):
         for slot, which in enumerate(("W", "g", "m", "v")):
@@ -206,5 +216,5 @@ def make_inputs(wl: Workload, device, tensors=None, layout="packed"):
                 dst = alloc_skewed(numels[i], torch.float32, device, slot)
             elif layout == "local":
                 dst = getattr(sa, which)[pos]
-            out[which].append(fill_tensor(wl.config, i, which, numels[i], wl.sigma[which], device, out=dst))
+            out[which].append(fill_tensor(wl.config, i, which, numels[i], sigma[which], device, out=dst))
     return out

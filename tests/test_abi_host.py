@@ -152,8 +152,9 @@ def test_near_memory_tile_order_is_a_bijection_and_splits_blocks_by_xcc_half():
                 block = (tile - base) // 8               # 8 tiles of 1 KiB = one 8 KiB block per fp32 stream
                 near_half_of_block = block ^ half        # the first block is near to `half`, the second to the other
                 assert near_half_of_block == xcc_half
-            # the four XCCs of a die share a block 1 KiB each per round; the second round takes the other 4 KiB
+            # the four XCCs of a die share a block; each takes two adjacent tiles (2 KiB), one per round
             assert {t - base for t in tiles[0:4]} | {t - base for t in tiles[8:12]} == set(range(8 * half, 8 * half + 8))
+            assert all(tiles[k + 8] == tiles[k] + 1 and (tiles[k] - base) % 2 == 0 for k in range(8))
     out = ctypes.c_uint32()
     assert binding.lib().pipeoptim_local_tile(0, 2, ctypes.byref(out)) == binding.PO_EINVAL
     assert binding.lib().pipeoptim_local_tile(0, 0, None) == binding.PO_EINVAL
