@@ -213,7 +213,7 @@ def main():
                                   lds_bytes_in_effect=stage.plan.effective_launch(
                                       binding.PO_KERNEL_KIND_PREDICT if predict_only else binding.PO_KERNEL_KIND_FUSED,
                                       wl.optimizer).lds_bytes),
-                   "n_local_params": stage.n_local_params,
+                   "n_local_params": stage.n_local_params, "launch_phase": stage.plan.launch_phase(),
                    "n_chunks": stage.plan.info()["n_chunks"]},
         "kernel_ms": {"avg": avg_ms, "median": med_ms, "min": per_launch_ms[0], "max": per_launch_ms[-1]},
         "achieved_hbm_GBps": achieved,

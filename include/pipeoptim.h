@@ -210,9 +210,17 @@ int pipeoptim_arena_destroy(po_arena* arena);
  * other eight the other block.  Only with 256-element tiles (block 64, unroll 1), chunk_elems >= 4096 and
  * xcd_remap 0; any other launch shape, and every tensor not marked, keeps the plain order.  Results do not depend
  * on the order.  arena == NULL clears all marks; pipeoptim_plan_set_pointers clears them too.  *n_local_params
- * (may be NULL) receives the number of parameters marked.  Blocking.
+ * (may be NULL) receives the number of parameters marked.
+ * On which XCC a launch's round starts depends on the hardware queue behind the stream.  This call finds out for
+ * hip_stream with a tiny kernel; after that every launch of the plan reports where it started (one word written to
+ * pinned host memory) and the next call uses what it finds there, so a plan that moves to another stream runs one
+ * launch with the old value (slower, never wrong) before it follows.  Blocking: waits for the device.
  */
-int pipeoptim_plan_localize(po_plan* plan, const po_arena* arena, int64_t* n_local_params);
+int pipeoptim_plan_localize(po_plan* plan, const po_arena* arena, void* hip_stream, int64_t* n_local_params);
+
+/* The XCC (0-7) on which the last launch of a localized plan that has reported so far started its round, i.e. the
+ * value the next call will hand to its kernel; -1 for a plan that was never localized.  Does not wait for anything. */
+int pipeoptim_plan_launch_phase(const po_plan* plan, int32_t* phase);
 
 /* Parameters of the plan's tensors that are marked for the near-memory tile order right now. */
 int pipeoptim_plan_local_params(const po_plan* plan, int64_t* n_local_params);

@@ -59,7 +59,7 @@ EXPORTS = (
     "pipeoptim_chunk_table_build", "pipeoptim_probe_copy", "pipeoptim_auto_lds_bytes", "pipeoptim_last_error",
     "pipeoptim_arena_create", "pipeoptim_arena_alloc", "pipeoptim_arena_set_skew", "pipeoptim_arena_near_half",
     "pipeoptim_arena_info", "pipeoptim_arena_destroy", "pipeoptim_plan_localize", "pipeoptim_plan_effective_launch",
-    "pipeoptim_local_tile", "pipeoptim_plan_local_params",
+    "pipeoptim_local_tile", "pipeoptim_plan_local_params", "pipeoptim_plan_launch_phase",
 )
 
 _lib = None
@@ -97,8 +97,9 @@ def lib():
         L.pipeoptim_arena_near_half.argtypes = [vp, vp, P(i32)]
         L.pipeoptim_arena_info.argtypes = [vp, P(i64), P(i64), P(i64), P(i32), P(i32)]
         L.pipeoptim_arena_destroy.argtypes = [vp]
-        L.pipeoptim_plan_localize.argtypes = [vp, vp, P(i64)]
+        L.pipeoptim_plan_localize.argtypes = [vp, vp, vp, P(i64)]
         L.pipeoptim_plan_local_params.argtypes = [vp, P(i64)]
+        L.pipeoptim_plan_launch_phase.argtypes = [vp, P(i32)]
         L.pipeoptim_plan_effective_launch.argtypes = [vp, i32, i32, P(po_launch)]
         L.pipeoptim_local_tile.argtypes = [ctypes.c_uint32, i32, P(ctypes.c_uint32)]
         for name in EXPORTS:
@@ -274,12 +275,19 @@ class Plan:
         _check(lib().pipeoptim_plan_set_launch(self._h, ctypes.byref(L)))
         return L
 
-    def localize(self, arena: Optional["Arena"]) -> int:
+    def localize(self, arena: Optional["Arena"], stream: int = 0) -> int:
         """Marks the tensors whose fp32 streams lie in `arena` for the near-memory tile order; returns the
-        number of parameters marked (None clears the marks)."""
+        number of parameters marked (None clears the marks).  `stream`: the stream the plan will run on."""
         n = ctypes.c_int64(0)
-        _check(lib().pipeoptim_plan_localize(self._h, arena._h if arena is not None else None, ctypes.byref(n)))
+        _check(lib().pipeoptim_plan_localize(self._h, arena._h if arena is not None else None,
+                                             ctypes.c_void_p(stream), ctypes.byref(n)))
         return n.value
+
+    def launch_phase(self) -> int:
+        """XCC on which the plan's last reported launch started its round (-1: never localized)."""
+        k = ctypes.c_int32(-2)
+        _check(lib().pipeoptim_plan_launch_phase(self._h, ctypes.byref(k)))
+        return k.value
 
     def local_params(self) -> int:
         n = ctypes.c_int64(-1)

@@ -7,10 +7,12 @@
 // hash works on physical addresses, and half of any stream is far for any XCC.
 //
 // The arena builds virtual ranges in which the hash is known.  It creates physical memory in 2 MiB handles (inside
-// one, every hashed bit above 13 is constant), maps each at a staging address, times a few cold loads from XCC 0
+// one, every hashed bit above 13 is constant), maps each at a staging address, times a few cold loads from one XCC
 // to the two blocks of one 16 KiB group (the near one answers in about 720 cycles, the far one in about 970), and
 // then maps the handle into one of two class ranges: in class c, the 8 KiB block at address A is near to XCC half
-// ((A >> 13) & 1) ^ c (half 0 = XCCs 0-3).  A handle whose two blocks cannot be told apart after three rounds is
+// ((A >> 13) & 1) ^ c.  XCC half 0 is the die of XCCs 0-3, half 1 that of XCCs 4-7, by the id the hardware
+// reports (measured: those are the two sets that see the same blocks as near); which XCC the timing wave runs on
+// depends on the hardware queue, so the wave reads its own id.  A handle whose two blocks cannot be told apart after three rounds is
 // released.  All buffers of one allocation call come from one class, 16 KiB aligned, so the streams of a tensor
 // (W, g, m, v, What) have the same block-to-die layout at every element offset, and the fused kernel's
 // near-memory tile order (po_local_tile) makes all of their fp32 traffic local.
@@ -33,13 +35,6 @@ constexpr int kRounds = 3;                          // timing rounds before a ha
 constexpr int kLinesPerRound = 4;
 constexpr size_t kBigBuffer = size_t(1) << 20;      // buffers from this size on are followed by the skew gap
 
-__device__ __forceinline__ uint32_t xcc_id()
-{
-    uint32_t x;
-    asm volatile("s_getreg_b32 %0, hwreg(HW_REG_XCC_ID)" : "=s"(x));
-    return x & 0xFu;
-}
-
 // One lane of workgroup 0 times cold loads: for region r (2 MiB, all nregions mapped from `base`) and block p
 // (0, 1) of the region's 16 KiB group number 3, lat[r*2 + p] = fastest of kLinesPerRound cache lines, a different
 // set of lines in every round.  Every address lies inside [base, base + nregions * 2 MiB).
@@ -47,7 +42,7 @@ __global__ __launch_bounds__(64) void po_arena_probe_kernel(const char* base, ui
                                                             uint32_t* lat, uint32_t* xcc_out)
 {
     if (blockIdx.x != 0 || threadIdx.x != 0) return;
-    xcc_out[0] = xcc_id();
+    xcc_out[0] = po_xcc_id();
     uint32_t acc = 0;
     for (uint32_t r = 0; r < nregions; ++r) {
         const char* reg = base + (size_t)r * kRegion;
@@ -154,7 +149,8 @@ int grow_once(po_arena* a)
             uint32_t xcc = 0;
             if (e == hipSuccess) e = hipMemcpy(&xcc, a->d_lat + (size_t)kBatch * 2, 4, hipMemcpyDeviceToHost);
             if (e != hipSuccess) { rc = po_fail(PO_EHIP, "arena calibration: %s", hipGetErrorString(e)); break; }
-            if (xcc != 0) { rc = po_fail(PO_EHIP, "arena calibration ran on XCC %u, not on XCC 0: workgroups are not dealt out round-robin here", xcc); break; }
+            if (xcc > 7) { rc = po_fail(PO_EHIP, "arena calibration: the timing wave reports XCC %u of a chip with 8", xcc); break; }
+            const int timing_half = (int)(xcc >> 2);
             bool open = false;
             for (uint32_t i = 0; i < n; ++i) {
                 if (cls[i] >= 0) continue;
@@ -162,7 +158,8 @@ int grow_once(po_arena* a)
                 best1[i] = std::min(best1[i], lat[i * 2 + 1]);
                 const uint32_t lo = std::min(best0[i], best1[i]), hi = std::max(best0[i], best1[i]);
                 if ((hi - lo) * 6u >= lo) {           // at least a sixth apart (measured: about a third)
-                    cls[i] = best0[i] < best1[i] ? 0 : 1;     // block 0 near to XCC 0 -> class 0
+                    // block 0 (address bit 13 = 0) near to the timing wave's half h -> class h, else class 1 - h
+                    cls[i] = best0[i] < best1[i] ? timing_half : 1 - timing_half;
                     a->near_cycles = lo;
                     a->far_cycles = hi;
                 } else {

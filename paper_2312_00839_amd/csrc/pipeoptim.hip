@@ -108,6 +108,10 @@ struct po_plan {
     po_tensor_desc* d_descs = nullptr;
     po_chunk* d_chunks = nullptr;
     int64_t d_chunks_capacity = 0;
+    // Pinned host word (64 bytes allocated) that workgroup 0 of every launch in the near-memory tile order writes
+    // its XCC id to: the XCC on which the stream's hardware queue starts its launches.  The next call passes the
+    // value it finds there to its kernel.  Allocated by pipeoptim_plan_localize, nullptr before.
+    uint32_t* h_phase = nullptr;
 };
 
 namespace {
@@ -455,6 +459,10 @@ int pipeoptim_plan_destroy(po_plan* p)
         if (p->d_descs) (void)hipFree(p->d_descs);
         if (p->d_chunks) (void)hipFree(p->d_chunks);
     }
+    if (p->h_phase) {
+        if (!(p->d_descs || p->d_chunks)) (void)hipDeviceSynchronize();
+        (void)hipHostFree(p->h_phase);
+    }
     delete p;
     return rc;
 }
@@ -555,9 +563,16 @@ int pipeoptim_plan_set_predict_launch(po_plan* p, const po_launch* L_in)
     return PO_OK;
 }
 
-int pipeoptim_plan_localize(po_plan* p, const po_arena* arena, int64_t* n_local_params)
+int pipeoptim_plan_localize(po_plan* p, const po_arena* arena, void* hip_stream, int64_t* n_local_params)
 {
     if (!p) return po_fail(PO_EINVAL, "plan is NULL");
+    int rc_dev = check_device(p);
+    if (rc_dev != PO_OK) return rc_dev;
+    if (arena && !p->h_phase) {
+        hipError_t eh = hipHostMalloc(reinterpret_cast<void**>(&p->h_phase), 64, hipHostMallocDefault);
+        if (eh != hipSuccess) { p->h_phase = nullptr; return po_fail(PO_ENOMEM, "hipHostMalloc(phase word): %s", hipGetErrorString(eh)); }
+        *p->h_phase = 0;
+    }
     const std::vector<po_tensor_desc> saved = p->descs;
     int64_t n_local = 0;
     for (int64_t i = 0; i < p->n_tensors; ++i) {
@@ -580,8 +595,10 @@ int pipeoptim_plan_localize(po_plan* p, const po_arena* arena, int64_t* n_local_
         d.flags |= PO_DESC_LOCAL | (cls ? PO_DESC_HALF1 : 0u);
         n_local += d.numel;
     }
-    hipError_t e = hipDeviceSynchronize();   // a launch may still read the old descriptors
-    if (e != hipSuccess) { p->descs = saved; return fail_hip(e, "hipDeviceSynchronize"); }
+    hipError_t e = hipSuccess;
+    if (arena && n_local > 0) e = po_launch_phase_probe(p->h_phase, static_cast<hipStream_t>(hip_stream));   // where this stream's launches start
+    if (e == hipSuccess) e = hipDeviceSynchronize();   // a launch may still read the old descriptors; the probe has reported
+    if (e != hipSuccess) { p->descs = saved; return fail_hip(e, "phase probe / hipDeviceSynchronize"); }
     const int rc = upload_descs(p);
     if (rc != PO_OK) { p->descs = saved; return rc; }
     p->n_local_params = n_local;
@@ -593,6 +610,13 @@ int pipeoptim_plan_local_params(const po_plan* p, int64_t* n_local_params)
 {
     if (!p || !n_local_params) return po_fail(PO_EINVAL, "plan or n_local_params is NULL");
     *n_local_params = p->n_local_params;
+    return PO_OK;
+}
+
+int pipeoptim_plan_launch_phase(const po_plan* p, int32_t* phase)
+{
+    if (!p || !phase) return po_fail(PO_EINVAL, "plan or phase is NULL");
+    *phase = p->h_phase ? (int32_t)(*static_cast<volatile uint32_t*>(p->h_phase) & 7u) : -1;
     return PO_OK;
 }
 
@@ -634,8 +658,11 @@ int pipeoptim_step_predict(const po_plan* p, const po_hyper* h, int64_t t, int32
     rc = check_device(p);
     if (rc != PO_OK) return rc;
     const po_launch L = resolve_launch(p, p->launch, PO_KERNEL_KIND_FUSED, h->opt);
+    const bool local = p->n_local_params > 0 && p->h_phase;
+    const uint32_t phase = local ? (*static_cast<volatile uint32_t*>(p->h_phase) & 7u) : 0u;
     hipError_t e = po_launch_step_predict(h->opt, p->what_dtype, p->grad_dtype, L, p->d_descs, p->d_chunks,
-                                          (uint32_t)p->chunks.size(), c, static_cast<hipStream_t>(hip_stream));
+                                          (uint32_t)p->chunks.size(), c, static_cast<hipStream_t>(hip_stream), phase,
+                                          local ? p->h_phase : nullptr);
     if (e != hipSuccess) return fail_hip(e, "launch of the fused step+predict kernel");
     return PO_OK;
 }
@@ -654,8 +681,11 @@ int pipeoptim_predict(const po_plan* p, const po_hyper* h, int64_t t, int32_t s,
     rc = check_device(p);
     if (rc != PO_OK) return rc;
     const po_launch L = resolve_launch(p, p->predict_launch, PO_KERNEL_KIND_PREDICT, h->opt);
+    const bool local = p->n_local_params > 0 && p->h_phase;
+    const uint32_t phase = local ? (*static_cast<volatile uint32_t*>(p->h_phase) & 7u) : 0u;
     hipError_t e = po_launch_predict(h->opt, p->what_dtype, L, p->d_descs, p->d_chunks,
-                                     (uint32_t)p->chunks.size(), c, static_cast<hipStream_t>(hip_stream));
+                                     (uint32_t)p->chunks.size(), c, static_cast<hipStream_t>(hip_stream), phase,
+                                     local ? p->h_phase : nullptr);
     if (e != hipSuccess) return fail_hip(e, "launch of the prediction kernel");
     return PO_OK;
 }

@@ -143,7 +143,7 @@ __device__ __forceinline__ float predict_element(const po_coeffs& c, float W, fl
     return c.s_is_zero ? W : fmaf(-c.s_lr, r, W);
 }
 
-// Everything a kernel needs besides the tables, as ONE by-value kernel argument of 96 bytes.  Each
+// Everything a kernel needs besides the tables, as ONE by-value kernel argument of 128 bytes.  Each
 // workgroup lives for one tile only, so the scalar round trips in front of its first vector load are a
 // fixed cost per tile: the kernel fetches this block with two wide scalar loads at its very top instead of
 // letting the compiler fetch the fields one wait at a time (about 1 % on the prediction-only kernel).
@@ -157,9 +157,13 @@ struct alignas(32) KArgs {
     uint32_t tile;           // block * 4 * unroll
     po_coeffs c;             // 52 bytes
     uint32_t local_ok;       // 1: this launch shape supports the near-memory tile order (1 KiB tiles, whole groups
-                             //    of 16 tiles per chunk, slot = workgroup id)
+                             //    of 16 tiles per chunk, no XCD remap)
+    uint32_t* phase_out;     // host-visible word that workgroup 0 writes its XCC id to (or nullptr)
+    uint32_t phase;          // XCC on which this queue's launches start, as last observed: workgroup id b runs
+                             // on XCC (b + phase) mod 8
+    uint32_t pad[5];
 };
-static_assert(sizeof(KArgs) == 96, "KArgs is loaded as 64 + 32 bytes");
+static_assert(sizeof(KArgs) == 128, "KArgs is loaded as 64 + 64 bytes");
 
 typedef uint32_t u32x8 __attribute__((ext_vector_type(8)));
 typedef uint32_t u32x16 __attribute__((ext_vector_type(16)));
@@ -168,9 +172,9 @@ typedef uint32_t u32x16 __attribute__((ext_vector_type(16)));
 __device__ __forceinline__ KArgs load_kargs()
 {
     const PO_CONSTANT char* base = (const PO_CONSTANT char*)__builtin_amdgcn_kernarg_segment_ptr();
-    union { struct { u32x16 a; u32x8 b; } raw; KArgs k; } u;
+    union { struct { u32x16 a; u32x16 b; } raw; KArgs k; } u;
     u.raw.a = *(const PO_CONSTANT u32x16*)base;
-    u.raw.b = *(const PO_CONSTANT u32x8*)(base + 64);
+    u.raw.b = *(const PO_CONSTANT u32x16*)(base + 64);
     return u.k;
 }
 
@@ -189,6 +193,13 @@ __device__ __forceinline__ bool locate_tile(const KArgs& a, Tile& t)
 {
     uint32_t slot = blockIdx.x;
     if (a.xcd_stride) slot = (blockIdx.x & 7u) * a.xcd_stride + (blockIdx.x >> 3);
+    else if (a.local_ok) {
+        // rotate the ids (n_slots is a multiple of 16 here) so that slot p runs on XCC p mod 8 whatever XCC the
+        // queue starts its launches on; the rotation is the same for every workgroup of the launch, so each
+        // slot is still taken exactly once even if `phase` is out of date (then only the locality suffers)
+        slot += a.phase;
+        if (slot >= a.n_slots) slot -= a.n_slots;
+    }
     if (slot >= a.n_slots) return false;
     // the tables are not written while a kernel runs: read them through the constant address space so that
     // the (workgroup-uniform) loads go down the scalar path and their results stay in SGPRs
@@ -207,6 +218,12 @@ __device__ __forceinline__ bool locate_tile(const KArgs& a, Tile& t)
     return true;
 }
 
+// Workgroup 0 tells the host which XCC this queue started the launch on, for the next launch's `phase`.
+__device__ __forceinline__ void report_phase(const KArgs& a)
+{
+    if (a.phase_out && blockIdx.x == 0 && threadIdx.x == 0) *a.phase_out = po_xcc_id();
+}
+
 // bf16 -> fp32 is exact: the bf16 pattern is the upper half of the fp32 pattern.
 __device__ __forceinline__ float bf16_lo(uint32_t pair) { return as_f(pair << 16); }
 __device__ __forceinline__ float bf16_hi(uint32_t pair) { return as_f(pair & 0xFFFF0000u); }
@@ -220,6 +237,7 @@ __global__ __launch_bounds__(256) void step_predict_kernel(KArgs)
 
     const KArgs a = load_kargs();
     const po_coeffs& c = a.c;
+    report_phase(a);
     Tile t;
     if (!locate_tile(a, t)) return;
     const po_tensor_desc* d = &t.d;
@@ -304,6 +322,7 @@ __global__ __launch_bounds__(256) void predict_kernel(KArgs)
 
     const KArgs a = load_kargs();
     const po_coeffs& c = a.c;
+    report_phase(a);
     Tile t;
     if (!locate_tile(a, t)) return;
     const po_tensor_desc* d = &t.d;
@@ -353,9 +372,12 @@ __global__ __launch_bounds__(256) void predict_kernel(KArgs)
     }
 }
 
+// Where a launch starts its round over the XCCs: last observed value, and where workgroup 0 reports the next.
+struct Phase { uint32_t value; uint32_t* report; };
+
 template <int KIND, int OPT, bool BF16, bool GB16, int UNROLL, int POL>
 hipError_t launch_one(const po_launch& L, const po_tensor_desc* descs, const po_chunk* chunks, uint32_t n_chunks,
-                      const po_coeffs& c, hipStream_t stream)
+                      const po_coeffs& c, hipStream_t stream, Phase ph)
 {
     const uint32_t tile = (uint32_t)L.block * 4u * UNROLL;
     const uint32_t tiles_per_chunk = (uint32_t)(L.chunk_elems / tile);      // a power of two (validated by the host)
@@ -375,6 +397,8 @@ hipError_t launch_one(const po_launch& L, const po_tensor_desc* descs, const po_
     a.tile = tile;
     a.c = c;
     a.local_ok = (!L.xcd_remap && tile == PO_LOCAL_TILE_ELEMS && tiles_per_chunk >= PO_LOCAL_GROUP_TILES) ? 1u : 0u;
+    a.phase = a.local_ok ? (ph.value & 7u) : 0u;
+    a.phase_out = a.local_ok ? ph.report : nullptr;
     if constexpr (KIND == PO_KERNEL_PREDICT)
         hipLaunchKernelGGL((predict_kernel<OPT, BF16, UNROLL, POL>), dim3((uint32_t)grid), dim3(L.block),
                            (size_t)L.lds_bytes, stream, a);
@@ -386,42 +410,48 @@ hipError_t launch_one(const po_launch& L, const po_tensor_desc* descs, const po_
 
 template <int KIND, int OPT, bool BF16, bool GB16, int UNROLL>
 hipError_t dispatch_policy(const po_launch& L, const po_tensor_desc* d, const po_chunk* ch, uint32_t n,
-                           const po_coeffs& c, hipStream_t s)
+                           const po_coeffs& c, hipStream_t s, Phase ph)
 {
     switch (L.cache_policy) {
-    case 0: return launch_one<KIND, OPT, BF16, GB16, UNROLL, 0>(L, d, ch, n, c, s);
-    case 1: return launch_one<KIND, OPT, BF16, GB16, UNROLL, 1>(L, d, ch, n, c, s);
-    case 2: return launch_one<KIND, OPT, BF16, GB16, UNROLL, 2>(L, d, ch, n, c, s);
-    case 3: return launch_one<KIND, OPT, BF16, GB16, UNROLL, 3>(L, d, ch, n, c, s);
-    case 4: return launch_one<KIND, OPT, BF16, GB16, UNROLL, 4>(L, d, ch, n, c, s);
+    case 0: return launch_one<KIND, OPT, BF16, GB16, UNROLL, 0>(L, d, ch, n, c, s, ph);
+    case 1: return launch_one<KIND, OPT, BF16, GB16, UNROLL, 1>(L, d, ch, n, c, s, ph);
+    case 2: return launch_one<KIND, OPT, BF16, GB16, UNROLL, 2>(L, d, ch, n, c, s, ph);
+    case 3: return launch_one<KIND, OPT, BF16, GB16, UNROLL, 3>(L, d, ch, n, c, s, ph);
+    case 4: return launch_one<KIND, OPT, BF16, GB16, UNROLL, 4>(L, d, ch, n, c, s, ph);
     }
     return hipErrorInvalidValue;
 }
 
 template <int KIND, int OPT, bool BF16, bool GB16>
 hipError_t dispatch_unroll(const po_launch& L, const po_tensor_desc* d, const po_chunk* ch, uint32_t n,
-                           const po_coeffs& c, hipStream_t s)
+                           const po_coeffs& c, hipStream_t s, Phase ph)
 {
     switch (L.unroll) {
-    case 1: return dispatch_policy<KIND, OPT, BF16, GB16, 1>(L, d, ch, n, c, s);
-    case 2: return dispatch_policy<KIND, OPT, BF16, GB16, 2>(L, d, ch, n, c, s);
-    case 4: return dispatch_policy<KIND, OPT, BF16, GB16, 4>(L, d, ch, n, c, s);
+    case 1: return dispatch_policy<KIND, OPT, BF16, GB16, 1>(L, d, ch, n, c, s, ph);
+    case 2: return dispatch_policy<KIND, OPT, BF16, GB16, 2>(L, d, ch, n, c, s, ph);
+    case 4: return dispatch_policy<KIND, OPT, BF16, GB16, 4>(L, d, ch, n, c, s, ph);
     }
     return hipErrorInvalidValue;
 }
 
 template <int KIND, int OPT>
 hipError_t dispatch_dtype(int what_dtype, int grad_dtype, const po_launch& L, const po_tensor_desc* d,
-                          const po_chunk* ch, uint32_t n, const po_coeffs& c, hipStream_t s)
+                          const po_chunk* ch, uint32_t n, const po_coeffs& c, hipStream_t s, Phase ph)
 {
     const bool h16 = what_dtype == PO_WHAT_BF16;
     if constexpr (KIND == PO_KERNEL_FUSED) {
         if (grad_dtype == PO_GRAD_BF16)
-            return h16 ? dispatch_unroll<KIND, OPT, true, true>(L, d, ch, n, c, s)
-                       : dispatch_unroll<KIND, OPT, false, true>(L, d, ch, n, c, s);
+            return h16 ? dispatch_unroll<KIND, OPT, true, true>(L, d, ch, n, c, s, ph)
+                       : dispatch_unroll<KIND, OPT, false, true>(L, d, ch, n, c, s, ph);
     }
-    return h16 ? dispatch_unroll<KIND, OPT, true, false>(L, d, ch, n, c, s)
-               : dispatch_unroll<KIND, OPT, false, false>(L, d, ch, n, c, s);
+    return h16 ? dispatch_unroll<KIND, OPT, true, false>(L, d, ch, n, c, s, ph)
+               : dispatch_unroll<KIND, OPT, false, false>(L, d, ch, n, c, s, ph);
+}
+
+// One workgroup per XCC; workgroup 0 writes the id of the XCC it runs on.
+__global__ __launch_bounds__(64) void phase_probe_kernel(uint32_t* out)
+{
+    if (blockIdx.x == 0 && threadIdx.x == 0) *out = po_xcc_id();
 }
 
 // Plain copy: the yardstick for what one read stream plus one write stream reach on this chip.
@@ -441,30 +471,37 @@ __global__ __launch_bounds__(64) void probe_copy_kernel(char* __restrict__ dst, 
 
 }  // namespace
 
+hipError_t po_launch_phase_probe(uint32_t* host_visible_word, hipStream_t stream)
+{
+    hipLaunchKernelGGL(phase_probe_kernel, dim3(8), dim3(64), 0, stream, host_visible_word);
+    return hipGetLastError();
+}
+
 hipError_t po_launch_step_predict(int opt, int what_dtype, int grad_dtype, const po_launch& L,
                                   const po_tensor_desc* d_descs, const po_chunk* d_chunks, uint32_t n_chunks,
-                                  const po_coeffs& c, hipStream_t stream)
+                                  const po_coeffs& c, hipStream_t stream, uint32_t phase, uint32_t* phase_report)
 {
     if (n_chunks == 0) return hipSuccess;
     switch (opt) {
-    case PO_SGDM: return dispatch_dtype<PO_KERNEL_FUSED, PO_SGDM>(what_dtype, grad_dtype, L, d_descs, d_chunks, n_chunks, c, stream);
-    case PO_ADAM: return dispatch_dtype<PO_KERNEL_FUSED, PO_ADAM>(what_dtype, grad_dtype, L, d_descs, d_chunks, n_chunks, c, stream);
-    case PO_ADAMW: return dispatch_dtype<PO_KERNEL_FUSED, PO_ADAMW>(what_dtype, grad_dtype, L, d_descs, d_chunks, n_chunks, c, stream);
-    case PO_NESTEROV: return dispatch_dtype<PO_KERNEL_FUSED, K_NESTEROV>(what_dtype, grad_dtype, L, d_descs, d_chunks, n_chunks, c, stream);
+    case PO_SGDM: return dispatch_dtype<PO_KERNEL_FUSED, PO_SGDM>(what_dtype, grad_dtype, L, d_descs, d_chunks, n_chunks, c, stream, Phase{phase, phase_report});
+    case PO_ADAM: return dispatch_dtype<PO_KERNEL_FUSED, PO_ADAM>(what_dtype, grad_dtype, L, d_descs, d_chunks, n_chunks, c, stream, Phase{phase, phase_report});
+    case PO_ADAMW: return dispatch_dtype<PO_KERNEL_FUSED, PO_ADAMW>(what_dtype, grad_dtype, L, d_descs, d_chunks, n_chunks, c, stream, Phase{phase, phase_report});
+    case PO_NESTEROV: return dispatch_dtype<PO_KERNEL_FUSED, K_NESTEROV>(what_dtype, grad_dtype, L, d_descs, d_chunks, n_chunks, c, stream, Phase{phase, phase_report});
     case PO_RMSPROP:
-    case PO_ADAGRAD: return dispatch_dtype<PO_KERNEL_FUSED, K_RMS>(what_dtype, grad_dtype, L, d_descs, d_chunks, n_chunks, c, stream);
+    case PO_ADAGRAD: return dispatch_dtype<PO_KERNEL_FUSED, K_RMS>(what_dtype, grad_dtype, L, d_descs, d_chunks, n_chunks, c, stream, Phase{phase, phase_report});
     }
     return hipErrorInvalidValue;
 }
 
 hipError_t po_launch_predict(int opt, int what_dtype, const po_launch& L, const po_tensor_desc* d_descs,
-                             const po_chunk* d_chunks, uint32_t n_chunks, const po_coeffs& c, hipStream_t stream)
+                             const po_chunk* d_chunks, uint32_t n_chunks, const po_coeffs& c, hipStream_t stream,
+                             uint32_t phase, uint32_t* phase_report)
 {
     if (n_chunks == 0) return hipSuccess;
     switch (opt) {
-    case PO_SGDM: return dispatch_dtype<PO_KERNEL_PREDICT, PO_SGDM>(what_dtype, PO_GRAD_F32, L, d_descs, d_chunks, n_chunks, c, stream);
-    case PO_ADAM: return dispatch_dtype<PO_KERNEL_PREDICT, PO_ADAM>(what_dtype, PO_GRAD_F32, L, d_descs, d_chunks, n_chunks, c, stream);
-    case PO_ADAMW: return dispatch_dtype<PO_KERNEL_PREDICT, PO_ADAMW>(what_dtype, PO_GRAD_F32, L, d_descs, d_chunks, n_chunks, c, stream);
+    case PO_SGDM: return dispatch_dtype<PO_KERNEL_PREDICT, PO_SGDM>(what_dtype, PO_GRAD_F32, L, d_descs, d_chunks, n_chunks, c, stream, Phase{phase, phase_report});
+    case PO_ADAM: return dispatch_dtype<PO_KERNEL_PREDICT, PO_ADAM>(what_dtype, PO_GRAD_F32, L, d_descs, d_chunks, n_chunks, c, stream, Phase{phase, phase_report});
+    case PO_ADAMW: return dispatch_dtype<PO_KERNEL_PREDICT, PO_ADAMW>(what_dtype, PO_GRAD_F32, L, d_descs, d_chunks, n_chunks, c, stream, Phase{phase, phase_report});
     }
     return hipErrorInvalidValue;
 }

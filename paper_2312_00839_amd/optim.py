@@ -13,21 +13,26 @@ each iteration (the runtime itself, its schedule and its transfers are not part 
 All arithmetic runs in the library's kernels: this class allocates buffers, points ``param.grad`` at them,
 swaps ``param.data`` between W and What (pointer swaps, no copies: the cache / restore of Algorithm 1 costs
 nothing), and passes pointers.  Parameters must be contiguous fp32 tensors on the GPU.
+
+With ``arena=True`` (the default) the optimizer owns the stage's memory the way flat-parameter optimizers do:
+the parameters are moved once into the library's near-memory arena, next to their gradient, state and What
+buffers, so that both kernels run with every XCC on its own die's HBM.  ``close()`` moves them back out.
 """
 import contextlib
+import warnings
 from typing import Iterable, List, Optional
 
 import torch
 
 from . import binding
-from .stage import Stage, address_slot, alloc_skewed, SKEW_SLOTS
+from .stage import Stage, StageArena, address_slot, alloc_skewed, SKEW_SLOTS
 
 
 class StageOptimizer:
     def __init__(self, params: Iterable[torch.nn.Parameter], optimizer: str = "adamw", lr: float = 1e-3,
                  betas=(0.9, 0.999), eps: float = 1e-8, weight_decay: float = 0.0, momentum: float = 0.9,
                  dampening: float = 0.0, alpha: float = 0.99, rank: int = 0, depth: int = 1,
-                 decay_in_prediction: bool = True):
+                 decay_in_prediction: bool = True, arena: bool = True):
         self.params: List[torch.nn.Parameter] = [p for p in params]
         if not self.params:
             raise ValueError("no parameters")
@@ -54,9 +59,30 @@ class StageOptimizer:
         binding.pipeoptim_coefficients(self.hyper, 1, self.s)                 # validates the hyper-parameters now
 
         dev = self.params[0].device
-        self._W = [p.data.view(-1) for p in self.params]
         has_m = optimizer not in ("rmsprop", "adagrad")
         has_v = optimizer not in ("sgdm", "nesterov")
+        self._arena: Optional[StageArena] = None
+        if arena:
+            try:
+                self._arena = StageArena([p.numel() for p in self.params], "f32", has_m=has_m, has_v=has_v, device=dev)
+            except binding.PipeOptimError as e:
+                warnings.warn("near-memory arena unavailable (%s): using plain allocations" % e)
+        if self._arena is not None:
+            sa = self._arena
+            for p, w in zip(self.params, sa.W):
+                w.copy_(p.data.view(-1))
+                p.data = w.view_as(p)                                          # the parameter now lives in the arena
+            for lst in (sa.g, sa.m, sa.v):
+                for x in lst or ():
+                    x.zero_()
+            self._W, self._g, self._m, self._v = sa.W, sa.g, sa.m, sa.v
+            for p, g in zip(self.params, self._g):
+                p.grad = g.view_as(p)
+            self._stage = Stage(self._W, self._g, self._m, self._v, "f32", What=sa.What, arena=sa.arena)
+            self._What = self._stage.What
+            self._swapped = False
+            return
+        self._W = [p.data.view(-1) for p in self.params]
 
         def state_like(slot_offset):
             # gradient and state buffers: zero-filled, placed in address slots (bits 12-13) next to W's
@@ -121,5 +147,19 @@ class StageOptimizer:
         """The optimizer's buffers (flat views, by parameter order): dict with W, g, m, v, What and the step count."""
         return {"W": self._W, "g": self._g, "m": self._m, "v": self._v, "What": self._What, "t": self.t, "s": self.s}
 
+    @property
+    def n_local_params(self) -> int:
+        """Parameters whose streams the kernels process in the near-memory tile order."""
+        return self._stage.n_local_params
+
     def close(self) -> None:
+        """Destroys the plan.  With an arena, first gives every parameter an ordinary allocation again (a copy of
+        its current value) and drops the gradient views, since the arena's memory goes away."""
         self._stage.close()
+        if self._arena is not None:
+            for p in self.params:
+                p.data = p.data.clone()
+                p.grad = None
+            torch.cuda.synchronize()
+            self._arena.close()
+            self._arena = None

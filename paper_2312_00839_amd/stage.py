@@ -32,25 +32,26 @@ def alloc_skewed(n: int, dtype: torch.dtype, device, slot: int) -> torch.Tensor:
 class _DeviceSpan:
     """Describes raw device memory to PyTorch through the array interface it accepts for zero-copy import."""
 
-    def __init__(self, ptr: int, numel: int, typestr: str):
+    def __init__(self, ptr: int, numel: int, typestr: str, owner):
+        self.owner = owner      # PyTorch keeps this object for as long as the imported storage lives
         self.__cuda_array_interface__ = {"shape": (numel,), "typestr": typestr, "data": (ptr, False), "version": 3,
                                          "strides": None}
 
 
 def tensor_at(ptr: int, numel: int, dtype: torch.dtype, device, owner) -> torch.Tensor:
     """A flat tensor over numel elements of device memory at `ptr` that PyTorch did not allocate (no copy).
-    `owner` is whatever keeps that memory alive; the tensor holds a reference to it."""
+    `owner` is whatever keeps that memory alive; the tensor's storage holds a reference to it, so the owner is
+    not collected while the tensor or any view of it exists (closing the owner explicitly still invalidates them)."""
     if numel == 0:
         return torch.empty(0, dtype=dtype, device=device)
     if dtype == torch.float32:
-        t = torch.as_tensor(_DeviceSpan(ptr, numel, "<f4"), device=device)
+        t = torch.as_tensor(_DeviceSpan(ptr, numel, "<f4", owner), device=device)
     elif dtype == torch.bfloat16:          # the array interface has no bf16: import the bits, reinterpret
-        t = torch.as_tensor(_DeviceSpan(ptr, numel, "<i2"), device=device).view(torch.bfloat16)
+        t = torch.as_tensor(_DeviceSpan(ptr, numel, "<i2", owner), device=device).view(torch.bfloat16)
     else:
         raise ValueError("tensor_at supports float32 and bfloat16")
     if t.data_ptr() != ptr:
         raise RuntimeError("PyTorch copied the arena memory instead of wrapping it")
-    t._pipeoptim_owner = owner
     return t
 
 
@@ -145,7 +146,8 @@ class Stage:
                                  ptrs(v) if v is not None else None,
                                  ptrs(self.What), what_dtype, torch.cuda.current_stream().cuda_stream,
                                  grad_dtype=self.grad_dtype)
-        self.n_local_params = self.plan.localize(arena) if arena is not None else 0
+        self.n_local_params = (self.plan.localize(arena, torch.cuda.current_stream().cuda_stream)
+                               if arena is not None else 0)
 
     @property
     def n_params(self) -> int:

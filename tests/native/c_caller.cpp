@@ -1,13 +1,16 @@
 // A caller of libpipeoptim that uses nothing but the C ABI and the HIP runtime: no Python, no PyTorch.
 // It builds a small ragged stage in device memory, runs the fused step + prediction (paper Table 1, Eq. 1,
 // Eq. 5) and the prediction-only call on a stream of its own, and checks every element against the CPU
-// oracle (linked as a C library; test infrastructure).  Run by tests/test_gpu_c_caller.py on a GPU machine.
+// oracle (linked as a C library; test infrastructure).  With the argument "arena" the buffers come from the
+// library's near-memory arena instead of hipMalloc and the plan is localized over it.
+// Run by tests/test_gpu_c_caller.py on a GPU machine.
 #include <hip/hip_runtime.h>
 
 #include <cmath>
 #include <cstdint>
 #include <cstdio>
 #include <cstdlib>
+#include <cstring>
 #include <vector>
 
 #include "pipeoptim.h"
@@ -48,8 +51,9 @@ bool bf16_within_band(uint16_t got, float ref, double tol)
 
 }  // namespace
 
-int main()
+int main(int argc, char** argv)
 {
+    const bool use_arena = argc > 1 && std::strcmp(argv[1], "arena") == 0;
     const std::vector<int64_t> numel = {1, 255, 0, 4097, 70001, 12};
     const int n_tensors = (int)numel.size();
     po_hyper h{};
@@ -65,6 +69,8 @@ int main()
     std::vector<const float*> dg(n_tensors, nullptr);
     std::vector<void*> dH(n_tensors, nullptr);
     Rng rng{20231200839ull};
+    po_arena* arena = nullptr;
+    if (use_arena) PO_CHECK(pipeoptim_arena_create(&arena, (int64_t)64 << 20));
     for (int i = 0; i < n_tensors; ++i) {
         const size_t n = (size_t)numel[i];
         hW[i].resize(n); hg[i].resize(n); hm[i].resize(n); hv[i].resize(n);
@@ -74,9 +80,16 @@ int main()
         }
         if (n == 0) continue;
         float* g_dev = nullptr;
-        HIP_OK(hipMalloc((void**)&dW[i], n * 4)); HIP_OK(hipMalloc((void**)&g_dev, n * 4));
-        HIP_OK(hipMalloc((void**)&dm[i], n * 4)); HIP_OK(hipMalloc((void**)&dv[i], n * 4));
-        HIP_OK(hipMalloc(&dH[i], n * 2));
+        if (use_arena) {       // the five streams of a tensor in one call: one block-to-die layout
+            const int64_t bytes[5] = {(int64_t)n * 4, (int64_t)n * 4, (int64_t)n * 4, (int64_t)n * 4, (int64_t)n * 2};
+            void* p[5];
+            PO_CHECK(pipeoptim_arena_alloc(arena, 5, bytes, p));
+            dW[i] = (float*)p[0]; g_dev = (float*)p[1]; dm[i] = (float*)p[2]; dv[i] = (float*)p[3]; dH[i] = p[4];
+        } else {
+            HIP_OK(hipMalloc((void**)&dW[i], n * 4)); HIP_OK(hipMalloc((void**)&g_dev, n * 4));
+            HIP_OK(hipMalloc((void**)&dm[i], n * 4)); HIP_OK(hipMalloc((void**)&dv[i], n * 4));
+            HIP_OK(hipMalloc(&dH[i], n * 2));
+        }
         dg[i] = g_dev;
         HIP_OK(hipMemcpy(dW[i], hW[i].data(), n * 4, hipMemcpyHostToDevice));
         HIP_OK(hipMemcpy(g_dev, hg[i].data(), n * 4, hipMemcpyHostToDevice));
@@ -90,6 +103,12 @@ int main()
     int64_t n_params = 0, n_chunks = 0, n_unaligned = 0;
     PO_CHECK(pipeoptim_plan_info(plan, &n_params, &n_chunks, &n_unaligned));
     std::printf("plan: %lld parameters in %d tensors, %lld chunks\n", (long long)n_params, n_tensors, (long long)n_chunks);
+    if (use_arena) {
+        int64_t n_local = -1;
+        PO_CHECK(pipeoptim_plan_localize(plan, arena, stream, &n_local));
+        std::printf("near-memory tile order for %lld parameters\n", (long long)n_local);
+        if (n_local != n_params) { std::printf("every tensor's streams came from one arena call, all should be marked\n"); return 1; }
+    }
     PO_CHECK(pipeoptim_step_predict(plan, &h, t, s, stream));
     HIP_OK(hipStreamSynchronize(stream));
 
@@ -157,7 +176,8 @@ int main()
     // error paths reachable from C: bad step index, optimizer without its state buffer
     if (pipeoptim_step_predict(plan, &h, 0, s, stream) != PO_EINVAL) { std::printf("t = 0 was accepted\n"); return 1; }
     PO_CHECK(pipeoptim_plan_destroy(plan));
-    for (int i = 0; i < n_tensors; ++i) {
+    if (use_arena) PO_CHECK(pipeoptim_arena_destroy(arena));
+    for (int i = 0; i < n_tensors && !use_arena; ++i) {
         if (!dW[i]) continue;
         HIP_OK(hipFree(dW[i])); HIP_OK(hipFree(const_cast<float*>(dg[i]))); HIP_OK(hipFree(dm[i])); HIP_OK(hipFree(dv[i])); HIP_OK(hipFree(dH[i]));
     }

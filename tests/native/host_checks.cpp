@@ -69,6 +69,37 @@ int main()
     EXPECT(pipeoptim_plan_destroy(nullptr) == PO_OK);
     EXPECT(pipeoptim_step_predict(nullptr, &h, 1, 1, nullptr) == PO_EINVAL);
     EXPECT(pipeoptim_predict(nullptr, &h, 1, 1, nullptr) == PO_EINVAL);
+    // near-memory arena and tile order: argument checks, and the order itself over every aligned run of 16
+    po_arena* arena = nullptr;
+    EXPECT(pipeoptim_arena_create(nullptr, 1 << 20) == PO_EINVAL);
+    EXPECT(pipeoptim_arena_create(&arena, 0) == PO_EINVAL && !arena);
+    EXPECT(pipeoptim_arena_create(&arena, (int64_t(1) << 40) + 1) == PO_EINVAL && !arena);
+    EXPECT(pipeoptim_arena_destroy(nullptr) == PO_OK);
+    void* ptr1[1] = {nullptr};
+    EXPECT(pipeoptim_arena_alloc(nullptr, 1, one, ptr1) == PO_EINVAL);
+    EXPECT(pipeoptim_arena_set_skew(nullptr, 0) == PO_EINVAL);
+    int32_t half = 7;
+    EXPECT(pipeoptim_arena_near_half(nullptr, nullptr, &half) == PO_EINVAL);
+    EXPECT(pipeoptim_arena_info(nullptr, nullptr, nullptr, nullptr, nullptr, nullptr) == PO_EINVAL);
+    int64_t n_local = -1;
+    EXPECT(pipeoptim_plan_localize(nullptr, nullptr, nullptr, &n_local) == PO_EINVAL);
+    EXPECT(pipeoptim_plan_local_params(nullptr, &n_local) == PO_EINVAL);
+    po_launch eff{};
+    EXPECT(pipeoptim_plan_effective_launch(nullptr, PO_KERNEL_KIND_FUSED, PO_ADAM, &eff) == PO_EINVAL);
+    for (int32_t first_half = 0; first_half < 2; ++first_half)
+        for (uint32_t base = 0; base < 4096; base += 16) {
+            uint32_t seen = 0;
+            for (uint32_t k = 0; k < 16; ++k) {
+                uint32_t tile = 0;
+                EXPECT(pipeoptim_local_tile(base + k, first_half, &tile) == PO_OK);
+                EXPECT(tile >= base && tile < base + 16);
+                seen |= 1u << (tile - base);
+            }
+            EXPECT(seen == 0xFFFFu);
+        }
+    uint32_t tile = 0;
+    EXPECT(pipeoptim_local_tile(0, 2, &tile) == PO_EINVAL);
+    EXPECT(pipeoptim_local_tile(0, 0, nullptr) == PO_EINVAL);
     EXPECT(pipeoptim_probe_copy(nullptr, nullptr, 8, nullptr) == PO_EINVAL);
 
     std::printf("host checks passed\n");

@@ -177,8 +177,10 @@ def test_arena_and_localize_argument_validation():
     assert L.pipeoptim_arena_near_half(None, None, ctypes.byref(half)) == binding.PO_EINVAL
     assert L.pipeoptim_arena_info(None, None, None, None, None, None) == binding.PO_EINVAL
     n = ctypes.c_int64()
-    assert L.pipeoptim_plan_localize(None, None, ctypes.byref(n)) == binding.PO_EINVAL
+    assert L.pipeoptim_plan_localize(None, None, None, ctypes.byref(n)) == binding.PO_EINVAL
     assert L.pipeoptim_plan_local_params(None, ctypes.byref(n)) == binding.PO_EINVAL
+    k = ctypes.c_int32()
+    assert L.pipeoptim_plan_launch_phase(None, ctypes.byref(k)) == binding.PO_EINVAL
     launch = binding.po_launch()
     assert L.pipeoptim_plan_effective_launch(None, 0, 1, ctypes.byref(launch)) == binding.PO_EINVAL
 

@@ -29,12 +29,18 @@ CASES = [
 ]
 
 
+@pytest.mark.parametrize("arena", [True, False], ids=["arena", "plain"])
 @pytest.mark.parametrize("kind,kw,hp", CASES, ids=[c[0] for c in CASES])
-def test_training_iterations_match_the_oracle(kind, kw, hp):
-    print("[gpu-stage-optimizer] %s" % kind, flush=True)
+def test_training_iterations_match_the_oracle(kind, kw, hp, arena):
+    print("[gpu-stage-optimizer] %s arena=%s" % (kind, arena), flush=True)
     model = _mlp(3)
-    opt = StageOptimizer(model.parameters(), kind, rank=1, depth=4, **kw)
+    expect_params = [p.detach().clone() for p in model.parameters()]
+    opt = StageOptimizer(model.parameters(), kind, rank=1, depth=4, arena=arena, **kw)
     assert opt.s == 2                                            # Eq. 4: stage 1 of 4
+    n_params = sum(p.numel() for p in model.parameters())
+    assert opt.n_local_params == (n_params if arena else 0)
+    for p, q in zip(model.parameters(), expect_params):          # moving into the arena keeps the values
+        assert torch.equal(p.detach(), q)
     x = torch.randn(64, 37, device=DEV)
     y = torch.randn(64, 11, device=DEV)
     for it in range(3):
