@@ -215,6 +215,8 @@ int pipeoptim_arena_destroy(po_arena* arena);
  * hip_stream with a tiny kernel; after that every launch of the plan reports where it started (one word written to
  * pinned host memory) and the next call uses what it finds there, so a plan that moves to another stream runs one
  * launch with the old value (slower, never wrong) before it follows.  Blocking: waits for the device.
+ * A stage below 2^25 parameters whose prediction launch shape the caller never set gets 256-element tiles for that
+ * kernel too when most of it is marked (its default there is bigger tiles, which the order is not defined for).
  */
 int pipeoptim_plan_localize(po_plan* plan, const po_arena* arena, void* hip_stream, int64_t* n_local_params);
 
