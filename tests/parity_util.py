@@ -115,6 +115,13 @@ def compare(kind, hp, t, s, inp, ref, got, what_dtype, label="", decay_in_predic
         bad = err > REL_TOL * scale + tiny
         assert not bad.any(), "%s %s: %d of %d elements beyond 1e-6*scale; worst ratio %.3e at %d" % (
             label, name, int(bad.sum()), bad.size, report[name], int(np.argmax(ratio)))
+        # The literal reading, error relative to the result itself: it holds for every element whose terms do not
+        # cancel; an element beyond it must be one whose result is less than half the magnitude of its terms.
+        mag = np.abs(reference.astype(np.float64))
+        literal_bad = err > REL_TOL * mag + tiny
+        report[name + "_beyond_1e-6_of_result"] = int(literal_bad.sum())
+        assert (scale[literal_bad] >= 2.0 * mag[literal_bad]).all(), \
+            "%s %s: off by more than 1e-6 of the result where nothing cancels" % (label, name)
 
     check("W", got["W"], ref["W"], sc["W"])
     if kind in HAS_M:
