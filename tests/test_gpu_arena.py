@@ -198,6 +198,49 @@ def test_localized_plan_follows_the_stream_it_runs_on():
         tensors["stage_arena"].close()
 
 
+def test_localized_step_can_be_captured_and_replayed():
+    """A localized call still enqueues exactly one kernel; its only extra effect is one word written to pinned host
+    memory.  The captured launch keeps the phase it was recorded with; every replay must equal, bit for bit, an
+    eager call on a twin stage in plain allocations (the tile order does not change any result)."""
+    _say("graph capture of a localized plan")
+    import numpy as np
+    kind, hp, t, s = "adamw", HP["adamw"], 12, 3
+    sizes = [300000, 4096 * 5 + 3]
+    a = to_arena(_rand_list(sizes, 43, kind), "bf16")
+    b = _rand_list(sizes, 43, kind)
+    sa = Stage(a["W"], a["g"], a["m"], a["v"], "bf16", What=a["What"], arena=a["arena"])
+    sb = Stage(b["W"], b["g"], b["m"], b["v"], "bf16")
+    try:
+        assert sa.n_local_params == sum(sizes)
+        hyper = make_hyper(kind, hp)
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.stream(side):
+            sa.step_predict(hyper, t, s)                 # warm-up outside the capture (counts as replay 0)
+            torch.cuda.synchronize()
+            with torch.cuda.graph(graph, stream=side):
+                sa.step_predict(hyper, t, s)
+        torch.cuda.current_stream().wait_stream(side)
+        sb.step_predict(hyper, t, s)
+        for replay in range(4):
+            graph.replay()
+            sb.step_predict(hyper, t, s)
+            torch.cuda.synchronize()
+            x = torch.randn(1 << 20, device=DEV).sum().item()      # unrelated eager work between replays
+            assert np.isfinite(x)
+            for i in range(2):
+                for name in ("W", "m", "v", "What"):
+                    u, w = getattr(sa, name)[i], getattr(sb, name)[i]
+                    assert torch.equal(u.view(torch.int16) if u.dtype == torch.bfloat16 else u,
+                                       w.view(torch.int16) if w.dtype == torch.bfloat16 else w), (replay, i, name)
+        assert sa.plan.launch_phase() in range(8)
+    finally:
+        sa.close()
+        sb.close()
+        a["stage_arena"].close()
+
+
 def test_occupancy_cap_follows_localization():
     sa = StageArena([1 << 26], "bf16")                     # 64 Mi parameters: a mid-sized stage
     try:
