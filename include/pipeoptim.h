@@ -189,6 +189,9 @@ int pipeoptim_plan_info(const po_plan* plan, int64_t* n_params, int64_t* n_chunk
  *   around ptr, or -1 if ptr is not inside memory the arena handed out.
  * pipeoptim_arena_info: bytes backed by physical memory, bytes handed out (gaps included), pieces given up because
  *   timing could not tell their layout, and the near / far load latency (cycles) of the piece timed last.
+ * pipeoptim_arena_check: times every backed 2 MiB piece again, in place, and counts those whose faster block is not
+ *   the one the arena's layout rule says is near (*n_disagree of the *n_timed pieces that could be told apart): a
+ *   diagnostic of the placement, independent of the sorting pass.  Blocking; about 10 ms per GiB.
  * pipeoptim_arena_destroy: waits for the device, then unmaps and frees everything; destroy plans over the
  *   arena's memory first.  NULL is a no-op.
  * Calls on one arena must not overlap.
@@ -200,6 +203,7 @@ int pipeoptim_arena_set_skew(po_arena* arena, int64_t skew_bytes);
 int pipeoptim_arena_near_half(const po_arena* arena, const void* ptr, int32_t* half);
 int pipeoptim_arena_info(const po_arena* arena, int64_t* backed_bytes, int64_t* used_bytes, int64_t* released_pieces,
                          int32_t* near_cycles, int32_t* far_cycles);
+int pipeoptim_arena_check(po_arena* arena, int64_t* n_timed, int64_t* n_disagree);
 int pipeoptim_arena_destroy(po_arena* arena);
 
 /*

@@ -58,7 +58,7 @@ EXPORTS = (
     "pipeoptim_plan_set_predict_launch", "pipeoptim_version_difference", "pipeoptim_coefficients",
     "pipeoptim_chunk_table_build", "pipeoptim_probe_copy", "pipeoptim_auto_lds_bytes", "pipeoptim_last_error",
     "pipeoptim_arena_create", "pipeoptim_arena_alloc", "pipeoptim_arena_set_skew", "pipeoptim_arena_near_half",
-    "pipeoptim_arena_info", "pipeoptim_arena_destroy", "pipeoptim_plan_localize", "pipeoptim_plan_effective_launch",
+    "pipeoptim_arena_info", "pipeoptim_arena_check", "pipeoptim_arena_destroy", "pipeoptim_plan_localize", "pipeoptim_plan_effective_launch",
     "pipeoptim_local_tile", "pipeoptim_plan_local_params", "pipeoptim_plan_launch_phase",
 )
 
@@ -96,6 +96,7 @@ def lib():
         L.pipeoptim_arena_set_skew.argtypes = [vp, i64]
         L.pipeoptim_arena_near_half.argtypes = [vp, vp, P(i32)]
         L.pipeoptim_arena_info.argtypes = [vp, P(i64), P(i64), P(i64), P(i32), P(i32)]
+        L.pipeoptim_arena_check.argtypes = [vp, P(i64), P(i64)]
         L.pipeoptim_arena_destroy.argtypes = [vp]
         L.pipeoptim_plan_localize.argtypes = [vp, vp, vp, P(i64)]
         L.pipeoptim_plan_local_params.argtypes = [vp, P(i64)]
@@ -195,6 +196,12 @@ class Arena:
                                           ctypes.byref(f)))
         return {"backed_bytes": a.value, "used_bytes": b.value, "released_pieces": c.value,
                 "near_cycles": n.value, "far_cycles": f.value}
+
+    def check(self):
+        """Times every backed piece again: (pieces that could be told apart, pieces that contradict the layout)."""
+        a, b = ctypes.c_int64(), ctypes.c_int64()
+        _check(lib().pipeoptim_arena_check(self._h, ctypes.byref(a), ctypes.byref(b)))
+        return a.value, b.value
 
     def destroy(self) -> None:
         if self._h:

@@ -52,7 +52,7 @@ __global__ __launch_bounds__(64) void po_arena_probe_kernel(const char* base, ui
         for (uint32_t p = 0; p < 2; ++p) {
             uint32_t best = 0xFFFFFFFFu;
             for (uint32_t line = 0; line < (uint32_t)kLinesPerRound; ++line) {
-                const uint32_t l = round * 16u + line * 4u + 1u;                      // < 64 lines per 8 KiB block
+                const uint32_t l = round * 16u + line * 4u + 1u;                      // round <= 3: below the 64 lines of a block
                 const uint32_t* ptr = reinterpret_cast<const uint32_t*>(reg + 3 * kAlign + p * 8192u + l * 128u);
                 const uint64_t t0 = clock64();
                 const uint32_t v = __builtin_nontemporal_load(ptr);
@@ -327,6 +327,44 @@ int pipeoptim_arena_near_half(const po_arena* a, const void* ptr, int32_t* half)
     *half = c < 0 ? -1 : (int32_t)((((uintptr_t)ptr >> 13) & 1u) ^ (uint32_t)c);
     return PO_OK;
 }
+
+int pipeoptim_arena_check(po_arena* a, int64_t* n_timed, int64_t* n_disagree)
+try {
+    if (!a || !n_timed || !n_disagree) return po_fail(PO_EINVAL, "arena, n_timed or n_disagree is NULL");
+    *n_timed = *n_disagree = 0;
+    hipError_t e = hipDeviceSynchronize();          // the timing wants the memory system to itself
+    if (e != hipSuccess) return po_fail(PO_EHIP, "hipDeviceSynchronize: %s", hipGetErrorString(e));
+    std::vector<uint32_t> lat((size_t)kBatch * 2);
+    for (int c = 0; c < 2; ++c) {
+        const size_t regions = a->mapped[c] / kRegion;
+        for (size_t first = 0; first < regions; first += kBatch) {
+            const uint32_t n = (uint32_t)std::min<size_t>(kBatch, regions - first);
+            // cache lines that the sorting pass (rounds 0 .. kRounds-1) never touched, so that they are cold
+            hipLaunchKernelGGL(po_arena_probe_kernel, dim3(8), dim3(64), 0, nullptr,
+                               a->va + (size_t)c * a->capacity + first * kRegion, n, (uint32_t)kRounds, a->d_lat,
+                               a->d_lat + (size_t)kBatch * 2);
+            e = hipGetLastError();
+            if (e == hipSuccess) e = hipDeviceSynchronize();
+            if (e == hipSuccess) e = hipMemcpy(lat.data(), a->d_lat, (size_t)n * 2 * 4, hipMemcpyDeviceToHost);
+            uint32_t xcc = 0;
+            if (e == hipSuccess) e = hipMemcpy(&xcc, a->d_lat + (size_t)kBatch * 2, 4, hipMemcpyDeviceToHost);
+            if (e != hipSuccess) return po_fail(PO_EHIP, "arena check: %s", hipGetErrorString(e));
+            if (xcc > 7) return po_fail(PO_EHIP, "arena check: the timing wave reports XCC %u of a chip with 8", xcc);
+            // in class c the block with address bit 13 = b is near to half b ^ c: the timing half must see block
+            // (half ^ c) as the faster one
+            const uint32_t expect_near = (xcc >> 2) ^ (uint32_t)c;
+            for (uint32_t i = 0; i < n; ++i) {
+                const uint32_t l0 = lat[i * 2], l1 = lat[i * 2 + 1], lo = std::min(l0, l1), hi = std::max(l0, l1);
+                if ((hi - lo) * 6u < lo) continue;           // this time the two blocks cannot be told apart
+                ++*n_timed;
+                if ((l0 < l1 ? 0u : 1u) != expect_near) ++*n_disagree;
+            }
+        }
+    }
+    return PO_OK;
+}
+catch (const std::bad_alloc&) { return po_fail(PO_ENOMEM, "pipeoptim_arena_check: out of host memory"); }
+catch (...) { return po_fail(PO_EINVAL, "pipeoptim_arena_check: unexpected exception"); }
 
 int pipeoptim_arena_info(const po_arena* a, int64_t* backed_bytes, int64_t* used_bytes, int64_t* released_handles,
                          int32_t* near_cycles, int32_t* far_cycles)
