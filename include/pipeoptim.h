@@ -240,6 +240,11 @@ int pipeoptim_plan_effective_launch(const po_plan* plan, int32_t kernel, int32_t
  * (0 or 1).  A bijection on every aligned run of 16 positions. */
 int pipeoptim_local_tile(uint32_t tile_in_chunk, int32_t first_block_half, uint32_t* out);
 
+/* Host only: the rotation in front of it.  *out = the position (chunk * tiles per chunk + tile_in_chunk) that workgroup
+ * id `workgroup` of a launch of n_slots workgroups (a multiple of 8) takes when the queue starts its launches on XCC
+ * `phase` (0-7): position p then runs on XCC p mod 8. */
+int pipeoptim_local_slot(uint32_t workgroup, uint32_t phase, uint32_t n_slots, uint32_t* out);
+
 /*
  * The hot path.  For every element of every tensor of the plan, with dW_t from
  * paper Table 1 (built from the new gradient and the cached state):

@@ -59,7 +59,7 @@ EXPORTS = (
     "pipeoptim_chunk_table_build", "pipeoptim_probe_copy", "pipeoptim_auto_lds_bytes", "pipeoptim_last_error",
     "pipeoptim_arena_create", "pipeoptim_arena_alloc", "pipeoptim_arena_set_skew", "pipeoptim_arena_near_half",
     "pipeoptim_arena_info", "pipeoptim_arena_check", "pipeoptim_arena_destroy", "pipeoptim_plan_localize", "pipeoptim_plan_effective_launch",
-    "pipeoptim_local_tile", "pipeoptim_plan_local_params", "pipeoptim_plan_launch_phase",
+    "pipeoptim_local_tile", "pipeoptim_local_slot", "pipeoptim_plan_local_params", "pipeoptim_plan_launch_phase",
 )
 
 _lib = None
@@ -103,6 +103,7 @@ def lib():
         L.pipeoptim_plan_launch_phase.argtypes = [vp, P(i32)]
         L.pipeoptim_plan_effective_launch.argtypes = [vp, i32, i32, P(po_launch)]
         L.pipeoptim_local_tile.argtypes = [ctypes.c_uint32, i32, P(ctypes.c_uint32)]
+        L.pipeoptim_local_slot.argtypes = [ctypes.c_uint32, ctypes.c_uint32, ctypes.c_uint32, P(ctypes.c_uint32)]
         for name in EXPORTS:
             getattr(L, name).restype = ctypes.c_int
         L.pipeoptim_last_error.restype = ctypes.c_char_p
@@ -163,6 +164,13 @@ def pipeoptim_local_tile(tile_in_chunk: int, first_block_half: int) -> int:
     """Host-only: the tile a workgroup at this position of its chunk takes in the near-memory order."""
     out = ctypes.c_uint32(0)
     _check(lib().pipeoptim_local_tile(int(tile_in_chunk), int(first_block_half), ctypes.byref(out)))
+    return out.value
+
+
+def pipeoptim_local_slot(workgroup: int, phase: int, n_slots: int) -> int:
+    """Host-only: the position workgroup id `workgroup` takes when launches start on XCC `phase`."""
+    out = ctypes.c_uint32(0)
+    _check(lib().pipeoptim_local_slot(int(workgroup), int(phase), int(n_slots), ctypes.byref(out)))
     return out.value
 
 

@@ -647,6 +647,15 @@ int pipeoptim_local_tile(uint32_t tile_in_chunk, int32_t first_block_half, uint3
     return PO_OK;
 }
 
+int pipeoptim_local_slot(uint32_t workgroup, uint32_t phase, uint32_t n_slots, uint32_t* out)
+{
+    if (!out) return po_fail(PO_EINVAL, "out is NULL");
+    if (phase > 7u) return po_fail(PO_EINVAL, "phase must be 0..7");
+    if (n_slots == 0 || (n_slots & 7u) != 0 || workgroup >= n_slots) return po_fail(PO_EINVAL, "n_slots must be a positive multiple of 8 and workgroup below it");
+    *out = po_local_slot(workgroup, phase, n_slots);
+    return PO_OK;
+}
+
 int pipeoptim_plan_info(const po_plan* p, int64_t* n_params, int64_t* n_chunks, int64_t* n_unaligned)
 {
     if (!p) return po_fail(PO_EINVAL, "plan is NULL");

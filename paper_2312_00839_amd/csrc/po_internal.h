@@ -58,6 +58,15 @@ __host__ __device__ inline uint32_t po_local_tile(uint32_t tile_in_chunk, uint32
     const uint32_t block = half ^ (first_block_half & 1u);
     return (tile_in_chunk & ~15u) | (block << 3) | (lane << 1) | round;
 }
+// The slot (position in the launch's round over the XCCs) of workgroup id b when the queue starts its launches on
+// XCC `phase`: workgroup b runs on XCC (b + phase) mod 8, so slot p = b + phase (wrapped around n_slots, a
+// multiple of 8) runs on XCC p mod 8.  A rotation: one-to-one for any phase.
+__host__ __device__ inline uint32_t po_local_slot(uint32_t workgroup, uint32_t phase, uint32_t n_slots)
+{
+    uint32_t slot = workgroup + (phase & 7u);
+    if (slot >= n_slots) slot -= n_slots;
+    return slot;
+}
 constexpr uint32_t PO_LOCAL_TILE_ELEMS = 256;      // the order above is defined for 1 KiB fp32 tiles
 constexpr uint32_t PO_LOCAL_GROUP_TILES = 16;
 

@@ -197,8 +197,7 @@ __device__ __forceinline__ bool locate_tile(const KArgs& a, Tile& t)
         // rotate the ids (n_slots is a multiple of 16 here) so that slot p runs on XCC p mod 8 whatever XCC the
         // queue starts its launches on; the rotation is the same for every workgroup of the launch, so each
         // slot is still taken exactly once even if `phase` is out of date (then only the locality suffers)
-        slot += a.phase;
-        if (slot >= a.n_slots) slot -= a.n_slots;
+        slot = po_local_slot(slot, a.phase, a.n_slots);
     }
     if (slot >= a.n_slots) return false;
     // the tables are not written while a kernel runs: read them through the constant address space so that
