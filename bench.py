@@ -48,6 +48,8 @@ def parse_args():
                          "its own die's HBM; packed: plain PyTorch allocations, back to back; skewed: plain allocations "
                          "whose W, g, m, v buffers differ in address bits 12-13")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-plain-compare", action="store_true",
+                    help="with --layout local: skip the extra, shorter measurement of the same workload in plain allocations")
     ap.add_argument("--no-copy-probe", action="store_true")
     ap.add_argument("--launch", default="", help="comma separated po_launch overrides, e.g. block=64,unroll=1,lds_bytes=16384")
     ap.add_argument("--s", type=int, default=-1, help="version difference to run with (default: the config's last s)")
@@ -247,6 +249,31 @@ def main():
         tensors["stage_arena"].close()
     del stage, tensors
     torch.cuda.empty_cache()
+
+    if layout == "local" and not args.no_plain_compare:
+        # the same workload in plain PyTorch allocations and the plain tile order, for comparison (not `value`)
+        tensors = make_inputs(wl, dev, layout="packed", optimizer=opt)
+        if args.grad_dtype == "bf16":
+            tensors["g"] = [x.to(torch.bfloat16) for x in tensors["g"]]
+        stage = Stage(tensors["W"], tensors["g"], tensors["m"], tensors["v"], wl.what_dtype)
+        if args.launch:
+            (stage.plan.set_predict_launch if predict_only else stage.plan.set_launch)(**kw)
+        for i in range(min(args.warmup, 10)):
+            one_step(i)
+        k2 = max(1, min(K, 50))
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record(stream)
+        for i in range(k2):
+            one_step(i)
+        e1.record(stream)
+        torch.cuda.synchronize()
+        ms2 = e0.elapsed_time(e1) / k2
+        out["plain_allocations"] = {"layout": "packed", "steps": k2, "ms_per_step": ms2,
+                                    "achieved_hbm_GBps": bytes_per_launch / (ms2 * 1e-3) / 1e9,
+                                    "frac": bytes_per_launch / (ms2 * 1e-3) / 1e9 / HBM_PEAK_GBPS}
+        stage.close()
+        del stage, tensors
+        torch.cuda.empty_cache()
 
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(wl, s_cfg, predict_only)
