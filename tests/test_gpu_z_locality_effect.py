@@ -1,4 +1,6 @@
-"""The near-memory tile order must actually pay: on the same buffers, in the same process, a localized plan has to
+"""Timing-based checks of the near-memory layout, collected after the parity tests.
+
+The near-memory tile order must actually pay: on the same buffers, in the same process, a localized plan has to
 beat the plain order.  A mistake that leaves the results right but sends the XCCs to the other die's memory (an
 inverted layout rule, a launch phase that is off) would show up here and nowhere else."""
 import pytest
@@ -50,3 +52,22 @@ def test_localized_plan_is_faster_than_the_plain_order_on_the_same_memory():
     finally:
         stage.close()
         tensors["stage_arena"].close()
+
+
+def test_arena_layout_holds_up_when_timed_again():
+    """The sorting pass decided each piece's layout from one timing; a second, independent timing of every piece
+    in its final place must agree (a systematic mistake, such as the two classes swapped or the layout rule
+    inverted, would contradict it everywhere; single pieces may be mistimed)."""
+    print("[gpu-locality] arena check", flush=True)
+    arena = binding.Arena(2 << 30)
+    try:
+        arena.alloc([600 << 20, 300 << 20])
+        arena.alloc([500 << 20])
+        timed, disagree = arena.check()
+        info = arena.info()
+        print("[gpu-locality] arena check: %d of %d pieces timed, %d disagree; %s" % (timed, info["backed_bytes"] >> 21, disagree, info), flush=True)
+        # one round of four lines decides about 7 pieces in 8; a systematic mistake would contradict nearly all
+        assert timed >= 0.25 * (info["backed_bytes"] >> 21)
+        assert disagree <= 0.25 * timed
+    finally:
+        arena.destroy()
