@@ -95,6 +95,10 @@ class StageArena:
                 self.What.append(tensor_at(next(k), n, wdt, dev, self.arena))
         self.what_dtype = what_dtype
 
+    def stage(self) -> "Stage":
+        """A Stage (plan) over this arena's tensors, localized for the current stream.  Close it before the arena."""
+        return Stage(self.W, self.g, self.m, self.v, self.what_dtype, What=self.What, arena=self.arena)
+
     def close(self) -> None:
         """Frees the arena's memory.  Every tensor it handed out is invalid from here on."""
         self.arena.destroy()
