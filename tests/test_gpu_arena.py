@@ -59,6 +59,13 @@ def test_arena_buffers_are_aligned_disjoint_and_share_one_layout():
         with pytest.raises(binding.PipeOptimError) as e:
             arena.set_skew(1000)
         assert e.value.status == binding.PO_EINVAL
+        # the gap after big buffers is the caller's to choose: none, or another multiple of 16 KiB
+        arena.set_skew(0)
+        q = arena.alloc([2 << 20, 2 << 20, 2 << 20])
+        assert q[1] - q[0] == 2 << 20 and q[2] - q[1] == 2 << 20
+        arena.set_skew(48 << 10)
+        q = arena.alloc([2 << 20, 2 << 20, 100])
+        assert q[1] - q[0] == (2 << 20) + (48 << 10) and q[2] - q[1] == (2 << 20) + (48 << 10)
     finally:
         arena.destroy()
 
