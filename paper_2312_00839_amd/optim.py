@@ -14,9 +14,10 @@ All arithmetic runs in the library's kernels: this class allocates buffers, poin
 swaps ``param.data`` between W and What (pointer swaps, no copies: the cache / restore of Algorithm 1 costs
 nothing), and passes pointers.  Parameters must be contiguous fp32 tensors on the GPU.
 
-With ``arena=True`` (the default) the optimizer owns the stage's memory the way flat-parameter optimizers do:
-the parameters are moved once into the library's near-memory arena, next to their gradient, state and What
-buffers, so that both kernels run with every XCC on its own die's HBM.  ``close()`` moves them back out.
+With ``arena=True`` (the default for stages of 4 Mi parameters and more; smaller ones gain nothing from it) the
+optimizer owns the stage's memory the way flat-parameter optimizers do: the parameters are moved once into the
+library's near-memory arena, next to their gradient, state and What buffers, so that both kernels run with every
+XCC on its own die's HBM.  ``close()`` moves them back out.
 """
 import contextlib
 import warnings
@@ -32,7 +33,7 @@ class StageOptimizer:
     def __init__(self, params: Iterable[torch.nn.Parameter], optimizer: str = "adamw", lr: float = 1e-3,
                  betas=(0.9, 0.999), eps: float = 1e-8, weight_decay: float = 0.0, momentum: float = 0.9,
                  dampening: float = 0.0, alpha: float = 0.99, rank: int = 0, depth: int = 1,
-                 decay_in_prediction: bool = True, arena: bool = True):
+                 decay_in_prediction: bool = True, arena: Optional[bool] = None):
         self.params: List[torch.nn.Parameter] = [p for p in params]
         if not self.params:
             raise ValueError("no parameters")
@@ -62,6 +63,8 @@ class StageOptimizer:
         has_m = optimizer not in ("rmsprop", "adagrad")
         has_v = optimizer not in ("sgdm", "nesterov")
         self._arena: Optional[StageArena] = None
+        if arena is None:
+            arena = sum(p.numel() for p in self.params) >= (1 << 22)
         if arena:
             try:
                 self._arena = StageArena([p.numel() for p in self.params], "f32", has_m=has_m, has_v=has_v, device=dev)
