@@ -110,10 +110,13 @@ class StageOptimizer:
         """W_{t+1} = W_t - lr*dW_t (Eq. 1) and What = W_t - lr*s*dW_t (Eq. 5), one kernel."""
         if self._swapped:
             raise RuntimeError("step() inside predicted_weights(): the parameters currently alias What")
-        for p, g in zip(self.params, self._g):
+        for p, g, w in zip(self.params, self._g, self._W):
             if p.grad is None or p.grad.data_ptr() != g.data_ptr():
                 raise RuntimeError("a parameter's .grad no longer is the buffer this optimizer gave it "
                                    "(use zero_grad() of this class, or zero_grad(set_to_none=False))")
+            if p.data_ptr() != w.data_ptr():
+                raise RuntimeError("a parameter's storage was replaced after this optimizer was created "
+                                   "(e.g. by module.to() or by assigning .data): create the optimizer afterwards")
         self.t += 1
         self._stage.step_predict(self.hyper, self.t, self.s)
 

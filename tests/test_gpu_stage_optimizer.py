@@ -111,6 +111,12 @@ def test_last_stage_and_misuse():
         p.grad = None
     with pytest.raises(RuntimeError):
         opt3.step()                                                     # gradient buffers were detached
+    opt4 = StageOptimizer(_mlp(9).parameters(), "adam", rank=0, depth=2)
+    for p in opt4.params:
+        p.data = p.data.clone()
+    with pytest.raises(RuntimeError):
+        opt4.step()                                                     # the parameters moved to other storage
+    opt4.close()
     with pytest.raises(ValueError):
         StageOptimizer([torch.nn.Parameter(torch.zeros(4))], "adam")     # not on the GPU
     with pytest.raises(Exception):
