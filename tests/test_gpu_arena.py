@@ -18,7 +18,7 @@ from paper_2312_00839_amd import binding  # noqa: E402
 from paper_2312_00839_amd.stage import Stage, StageArena, tensor_at  # noqa: E402
 
 # spans several chunks (65,536 elements), several 16-tile groups, ragged tails, tensors below one group
-SIZES = [1, 255, 256, 4095, 4096, 4097, 65536, 70001, 3 * 65536 + 5, 1 << 20, 1234567]
+SIZES = [1, 0, 255, 256, 4095, 4096, 4097, 65536, 70001, 3 * 65536 + 5, 1 << 20, 1234567]
 
 
 def test_arena_buffers_are_aligned_disjoint_and_share_one_layout():
