@@ -132,6 +132,47 @@ def test_prediction_alone_on_a_localized_stage(kind):
         tensors["stage_arena"].close()
 
 
+@pytest.mark.parametrize("case", range(24))
+def test_random_cases_in_the_arena(case):
+    """Seeded random hyper-parameters, sizes and dtypes on localized stages, in launch shapes that keep the near-memory
+    order switched on (256-element tiles, whole groups of 16 per chunk); fused and prediction-only calls."""
+    rng = np.random.default_rng(9000 + case)
+    kind = (TABLE1 + BEYOND)[case % 6]
+    what_dtype = ("f32", "bf16")[(case // 6) % 2]
+    grad_dtype = (torch.float32, torch.bfloat16)[(case // 12) % 2]
+    lr = float(10 ** rng.uniform(-5, -0.5))
+    wd = float(rng.choice([0.0, 10 ** rng.uniform(-5, -0.5)]))
+    if kind in ("sgdm", "nesterov"):
+        hp = dict(lr=lr, beta1=float(rng.uniform(0, 0.99)), beta2=float(rng.choice([0.0, rng.uniform(0, 0.9)])),
+                  eps=0.0, weight_decay=wd)
+    else:
+        hp = dict(lr=lr, beta1=float(rng.uniform(0, 0.99)), beta2=float(rng.uniform(0.5, 0.9999)),
+                  eps=float(10 ** rng.uniform(-10, -3)), weight_decay=wd)
+    t = int(rng.choice([1, 2, 10, 1000, 10 ** 5]))
+    s = int(rng.choice([0, 1, 2, 3, 7, 40]))
+    dip = bool(rng.integers(0, 2))
+    sizes = [int(x) for x in rng.integers(0, 300000, size=int(rng.integers(1, 6)))] + [int(rng.integers(1, 5000))]
+    launch = dict(block=64, unroll=1, chunk_elems=256 * int(2 ** rng.integers(4, 9)), cache_policy=int(rng.integers(0, 5)),
+                  lds_bytes=int(rng.choice([0, 8192, 16384])), xcd_remap=0)
+    sig = dict(sw=float(10 ** rng.uniform(-3, 0)), sg=float(10 ** rng.uniform(-6, -1)),
+               sm=float(10 ** rng.uniform(-6, -1)), sv=float(10 ** rng.uniform(-6, -1)))
+    _say("arena random case %d: %s %s g=%s t=%d s=%d dip=%d sizes=%s launch=%s" % (case, kind, what_dtype, grad_dtype, t, s, dip, sizes, launch))
+    tensors = to_arena(_rand_list(sizes, 800 + case, kind, grad_dtype=grad_dtype, **sig), what_dtype)
+    try:
+        run_and_compare_full(kind, hp, t, s, tensors, what_dtype, launch=launch, decay_in_prediction=dip,
+                             label="arena random %d" % case)
+    finally:
+        tensors["stage_arena"].close()
+    if kind in BEYOND:
+        return
+    tensors = to_arena(_rand_list(sizes, 900 + case, kind, **sig), what_dtype)
+    try:
+        run_and_compare_predict(kind, hp, t, s, tensors, what_dtype, launch=launch, decay_in_prediction=dip,
+                                label="arena random predict %d" % case)
+    finally:
+        tensors["stage_arena"].close()
+
+
 def test_localize_marks_exactly_the_tensors_whose_streams_share_an_arena_layout():
     _say("localize: mixed stage")
     sizes = [70001, 4096, 300000, 8192]
