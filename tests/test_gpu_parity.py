@@ -633,6 +633,11 @@ def test_config2_resnet_sgdm_full_in_near_memory_arena():
     _full_config(2, 3, layout="local")
 
 
+@pytest.mark.parametrize("s", [0, 7])
+def test_config4_gpt_adamw_bf16_sampled_in_near_memory_arena(s):
+    _sampled_config(4, s, layout="local")
+
+
 def test_config5_llama_adamw_bf16_sampled_in_near_memory_arena():
     # the layout and launch shape bench.py times by default
     _sampled_config(5, 7, blocks_per_tensor=10, layout="local")
