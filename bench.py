@@ -243,6 +243,24 @@ def main():
         out["copy_kernel_GBps"] = copy_gbps
         out["frac_of_copy_kernel"] = achieved / copy_gbps
         del src, dst
+        if layout == "local":
+            # the same yardstick with both buffers in an arena and the near-memory tile order (best of three caps)
+            half = 2 << 30
+            ca = binding.Arena(5 << 30)
+            d2, s2 = ca.alloc([half, half])
+            best = 0.0
+            for lds in (4096, 8192, 12288):
+                for _ in range(3):
+                    ca.probe_copy(d2, s2, half, lds, stream.cuda_stream)
+                e0.record(stream)
+                for _ in range(reps):
+                    ca.probe_copy(d2, s2, half, lds, stream.cuda_stream)
+                e1.record(stream)
+                torch.cuda.synchronize()
+                best = max(best, 2.0 * half * reps / (e0.elapsed_time(e1) * 1e-3) / 1e9)
+            ca.destroy()
+            out["copy_kernel_near_GBps"] = best
+            out["frac_of_copy_kernel_near"] = achieved / best
 
     stage.close()
     if tensors.get("stage_arena") is not None:

@@ -317,6 +317,13 @@ int pipeoptim_chunk_table_build(int64_t n_tensors, const int64_t* numel, int64_t
  * one-read-one-write bandwidth. */
 int pipeoptim_probe_copy(void* dst, const void* src, int64_t nbytes, void* hip_stream);
 
+/* Measurement aid: the same copy in the near-memory tile order, the yardstick for one read plus one write stream
+ * with every XCC on its own die's memory.  dst and src: 16 KiB aligned, from ONE pipeoptim_arena_alloc call of
+ * `arena`; nbytes a multiple of 16 KiB; lds_bytes (0..65536) caps the occupancy as in po_launch.  Like a localized
+ * plan, it learns the XCC on which the stream's launches start from its own previous launch (run it twice). */
+int pipeoptim_probe_copy_near(const po_arena* arena, void* dst, const void* src, int64_t nbytes, int32_t lds_bytes,
+                              void* hip_stream);
+
 /* Thread-local description of the last failure on this thread ("" if none). */
 const char* pipeoptim_last_error(void);
 

@@ -56,7 +56,8 @@ EXPORTS = (
     "pipeoptim_plan_get_launch", "pipeoptim_plan_set_launch", "pipeoptim_plan_info",
     "pipeoptim_step_predict", "pipeoptim_predict", "pipeoptim_plan_get_predict_launch",
     "pipeoptim_plan_set_predict_launch", "pipeoptim_version_difference", "pipeoptim_coefficients",
-    "pipeoptim_chunk_table_build", "pipeoptim_probe_copy", "pipeoptim_auto_lds_bytes", "pipeoptim_last_error",
+    "pipeoptim_chunk_table_build", "pipeoptim_probe_copy", "pipeoptim_probe_copy_near", "pipeoptim_auto_lds_bytes",
+    "pipeoptim_last_error",
     "pipeoptim_arena_create", "pipeoptim_arena_alloc", "pipeoptim_arena_set_skew", "pipeoptim_arena_near_half",
     "pipeoptim_arena_info", "pipeoptim_arena_check", "pipeoptim_arena_destroy", "pipeoptim_plan_localize", "pipeoptim_plan_effective_launch",
     "pipeoptim_local_tile", "pipeoptim_local_slot", "pipeoptim_plan_local_params", "pipeoptim_plan_launch_phase",
@@ -90,6 +91,7 @@ def lib():
         L.pipeoptim_coefficients.argtypes = [P(po_hyper), i64, i32, P(po_coeffs)]
         L.pipeoptim_chunk_table_build.argtypes = [i64, P(i64), i64, P(po_chunk), i64, P(i64)]
         L.pipeoptim_probe_copy.argtypes = [vp, vp, i64, vp]
+        L.pipeoptim_probe_copy_near.argtypes = [vp, vp, vp, i64, i32, vp]
         L.pipeoptim_auto_lds_bytes.argtypes = [i32, i32, i64, P(i32)]
         L.pipeoptim_arena_create.argtypes = [P(vp), i64]
         L.pipeoptim_arena_alloc.argtypes = [vp, i64, P(i64), P(vp)]
@@ -204,6 +206,11 @@ class Arena:
                                           ctypes.byref(f)))
         return {"backed_bytes": a.value, "used_bytes": b.value, "released_pieces": c.value,
                 "near_cycles": n.value, "far_cycles": f.value}
+
+    def probe_copy(self, dst: int, src: int, nbytes: int, lds_bytes: int = 0, stream: int = 0) -> None:
+        """dst[0..nbytes) = src[0..nbytes) in the near-memory tile order (both from one alloc call of this arena)."""
+        _check(lib().pipeoptim_probe_copy_near(self._h, ctypes.c_void_p(dst), ctypes.c_void_p(src), int(nbytes),
+                                               int(lds_bytes), ctypes.c_void_p(stream)))
 
     def check(self):
         """Times every backed piece again: (pieces that could be told apart, pieces that contradict the layout)."""

@@ -84,6 +84,7 @@ struct po_arena {
     int64_t n_released = 0;         // handles whose blocks could not be told apart
     int64_t n_allocs = 0;
     uint32_t near_cycles = 0, far_cycles = 0;   // last calibrated handle, for pipeoptim_arena_info
+    uint32_t* h_phase = nullptr;    // pinned host word: the XCC on which pipeoptim_probe_copy_near's last launch started
 };
 
 namespace {
@@ -235,7 +236,10 @@ try {
     if (e != hipSuccess) return po_fail(PO_ENOMEM, "hipMemAddressReserve(%zu bytes): %s", 2 * a->capacity, hipGetErrorString(e));
     e = hipMemAddressReserve(reinterpret_cast<void**>(&a->staging), kBatch * kRegion, kRegion, nullptr, 0);
     if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void**>(&a->d_lat), ((size_t)kBatch * 2 + 2) * 4);
+    if (e == hipSuccess) e = hipHostMalloc(reinterpret_cast<void**>(&a->h_phase), 64, hipHostMallocDefault);
+    if (e == hipSuccess) *a->h_phase = 0;
     if (e != hipSuccess || ((uintptr_t)a->va % kRegion) != 0 || ((uintptr_t)a->staging % kRegion) != 0) {
+        if (a->h_phase) (void)hipHostFree(a->h_phase);
         if (a->d_lat) (void)hipFree(a->d_lat);
         if (a->staging) (void)hipMemAddressFree(a->staging, kBatch * kRegion);
         (void)hipMemAddressFree(a->va, 2 * a->capacity);
@@ -260,6 +264,7 @@ int pipeoptim_arena_destroy(po_arena* a)
             (void)hipMemRelease(a->handles[c][i]);
         }
     }
+    if (a->h_phase) (void)hipHostFree(a->h_phase);
     if (a->d_lat) (void)hipFree(a->d_lat);
     if (a->staging) (void)hipMemAddressFree(a->staging, kBatch * kRegion);
     if (a->va) (void)hipMemAddressFree(a->va, 2 * a->capacity);
@@ -365,6 +370,27 @@ try {
 }
 catch (const std::bad_alloc&) { return po_fail(PO_ENOMEM, "pipeoptim_arena_check: out of host memory"); }
 catch (...) { return po_fail(PO_EINVAL, "pipeoptim_arena_check: unexpected exception"); }
+
+int pipeoptim_probe_copy_near(const po_arena* a, void* dst, const void* src, int64_t nbytes, int32_t lds_bytes, void* hip_stream)
+{
+    if (!a) return po_fail(PO_EINVAL, "arena is NULL");
+    if (nbytes < 0 || nbytes % (int64_t)kAlign != 0 || nbytes / 1024 > 0x7FFFFFF0ll)
+        return po_fail(PO_EINVAL, "nbytes must be a non-negative multiple of 16 KiB below 2^41");
+    if (lds_bytes < 0 || lds_bytes > 65536) return po_fail(PO_EINVAL, "lds_bytes must be 0..65536");
+    if (nbytes == 0) return PO_OK;
+    if (!dst || !src) return po_fail(PO_EINVAL, "dst or src is NULL");
+    if ((((uintptr_t)dst | (uintptr_t)src) & (kAlign - 1)) != 0) return po_fail(PO_EALIGN, "dst and src must be 16 KiB aligned");
+    const int cd = po_arena_class_of(a, dst, (size_t)nbytes), cs = po_arena_class_of(a, src, (size_t)nbytes);
+    if (cd < 0 || cd != cs) return po_fail(PO_EINVAL, "dst and src must lie in memory that one pipeoptim_arena_alloc call of this arena handed out");
+    const char* d = static_cast<const char*>(dst);
+    const char* s = static_cast<const char*>(src);
+    if (d < s + nbytes && s < d + nbytes) return po_fail(PO_EINVAL, "dst and src overlap");
+    const uint32_t phase = *static_cast<volatile uint32_t*>(a->h_phase) & 7u;
+    hipError_t e = po_launch_probe_copy_near(dst, src, nbytes, (uint32_t)cd, phase, a->h_phase, lds_bytes,
+                                             static_cast<hipStream_t>(hip_stream));
+    if (e != hipSuccess) return po_fail(PO_EHIP, "launch of the near-memory copy kernel: %s", hipGetErrorString(e));
+    return PO_OK;
+}
 
 int pipeoptim_arena_info(const po_arena* a, int64_t* backed_bytes, int64_t* used_bytes, int64_t* released_handles,
                          int32_t* near_cycles, int32_t* far_cycles)

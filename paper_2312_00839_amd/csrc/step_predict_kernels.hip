@@ -468,7 +468,34 @@ __global__ __launch_bounds__(64) void probe_copy_kernel(char* __restrict__ dst, 
     __builtin_amdgcn_raw_buffer_store_b128(x, rd, b, 0, CP_NT | CP_SC1);
 }
 
+// The same copy in the near-memory tile order, for buffers from one class range of an arena: the yardstick for
+// what one read stream plus one write stream reach when every XCC stays on its own die's memory.
+__global__ __launch_bounds__(64) void probe_copy_near_kernel(char* __restrict__ dst, const char* __restrict__ src,
+                                                             uint32_t n_tiles, uint32_t first_block_half, uint32_t phase,
+                                                             uint32_t* phase_out)
+{
+    if (phase_out && blockIdx.x == 0 && threadIdx.x == 0) *phase_out = po_xcc_id();
+    const uint32_t tile = po_local_tile(po_local_slot(blockIdx.x, phase, n_tiles), first_block_half);
+    const int64_t base = (int64_t)tile * 1024;
+    const __amdgpu_buffer_rsrc_t rs = make_rsrc(src + base, 1024u), rd = make_rsrc(dst + base, 1024u);
+    const uint32_t b = threadIdx.x * 16u;
+    u32x4 x = __builtin_amdgcn_raw_buffer_load_b128(rs, b, 0, CP_NT);
+    __builtin_amdgcn_raw_buffer_store_b128(x, rd, b, 0, CP_NT | CP_SC1);
+}
+
 }  // namespace
+
+hipError_t po_launch_probe_copy_near(void* dst, const void* src, int64_t nbytes, uint32_t first_block_half, uint32_t phase,
+                                     uint32_t* phase_report, int32_t lds_bytes, hipStream_t stream)
+{
+    if (nbytes <= 0) return hipSuccess;
+    const int64_t n_tiles = nbytes / 1024;                 // the caller checked: a multiple of 16 tiles, below 2^31
+    if (nbytes % 16384 != 0 || n_tiles > 0x7FFFFFF0ll) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(probe_copy_near_kernel, dim3((uint32_t)n_tiles), dim3(64), (size_t)lds_bytes, stream,
+                       static_cast<char*>(dst), static_cast<const char*>(src), (uint32_t)n_tiles, first_block_half & 1u,
+                       phase & 7u, phase_report);
+    return hipGetLastError();
+}
 
 hipError_t po_launch_phase_probe(uint32_t* host_visible_word, hipStream_t stream)
 {

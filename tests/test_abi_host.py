@@ -202,6 +202,7 @@ def test_arena_and_localize_argument_validation():
     half = ctypes.c_int32()
     assert L.pipeoptim_arena_near_half(None, None, ctypes.byref(half)) == binding.PO_EINVAL
     assert L.pipeoptim_arena_info(None, None, None, None, None, None) == binding.PO_EINVAL
+    assert L.pipeoptim_probe_copy_near(None, None, None, 16384, 0, None) == binding.PO_EINVAL
     assert L.pipeoptim_arena_check(None, ctypes.byref(ctypes.c_int64()), ctypes.byref(ctypes.c_int64())) == binding.PO_EINVAL
     n = ctypes.c_int64()
     assert L.pipeoptim_plan_localize(None, None, None, ctypes.byref(n)) == binding.PO_EINVAL

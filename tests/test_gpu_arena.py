@@ -70,6 +70,38 @@ def test_arena_buffers_are_aligned_disjoint_and_share_one_layout():
         arena.destroy()
 
 
+def test_near_memory_copy_copies_and_validates():
+    _say("near-memory copy")
+    arena = binding.Arena(256 << 20)
+    other = binding.Arena(64 << 20)
+    try:
+        n = (8 << 20) + 16384 * 3                     # 16 KiB multiple, not a power of two
+        dst, src = arena.alloc([n, n])
+        a = tensor_at(src, n // 4, torch.float32, DEV, arena)
+        b = tensor_at(dst, n // 4, torch.float32, DEV, arena)
+        a.copy_(torch.arange(n // 4, device=DEV, dtype=torch.float32))
+        for lds in (0, 12288):
+            b.zero_()
+            arena.probe_copy(dst, src, n, lds)
+            torch.cuda.synchronize()
+            assert torch.equal(a, b)
+        arena.probe_copy(dst, src, 0)
+        stray = arena.alloc([n])[0]                   # another call: may sit in the other class
+        foreign = other.alloc([n])[0]
+        for args, status in (((dst, src, n - 4096), binding.PO_EINVAL), ((dst + 4096, src, 16384), binding.PO_EALIGN),
+                             ((dst, foreign, n), binding.PO_EINVAL), ((dst, dst + 16384, 32768), binding.PO_EINVAL),
+                             ((dst, src, n, 70000), binding.PO_EINVAL)):
+            with pytest.raises(binding.PipeOptimError) as e:
+                arena.probe_copy(*args)
+            assert e.value.status == status, args
+        if arena.near_half(stray) != arena.near_half(dst):
+            with pytest.raises(binding.PipeOptimError):
+                arena.probe_copy(stray, src, n)
+    finally:
+        arena.destroy()
+        other.destroy()
+
+
 def test_arena_capacity_is_enforced():
     arena = binding.Arena(4 << 20)
     try:
