@@ -81,6 +81,15 @@ int main()
     int32_t half = 7;
     EXPECT(pipeoptim_arena_near_half(nullptr, nullptr, &half) == PO_EINVAL);
     EXPECT(pipeoptim_arena_info(nullptr, nullptr, nullptr, nullptr, nullptr, nullptr) == PO_EINVAL);
+    int64_t n_timed = 0, n_disagree = 0;
+    EXPECT(pipeoptim_arena_check(nullptr, &n_timed, &n_disagree) == PO_EINVAL);
+    EXPECT(pipeoptim_probe_copy_near(nullptr, nullptr, nullptr, 16384, 0, nullptr) == PO_EINVAL);
+    uint32_t slot = 0;
+    EXPECT(pipeoptim_local_slot(3, 7, 16, &slot) == PO_OK && slot == 10);
+    EXPECT(pipeoptim_local_slot(12, 7, 16, &slot) == PO_OK && slot == 3);
+    EXPECT(pipeoptim_local_slot(0, 8, 16, &slot) == PO_EINVAL);
+    int32_t phase = 0;
+    EXPECT(pipeoptim_plan_launch_phase(nullptr, &phase) == PO_EINVAL);
     int64_t n_local = -1;
     EXPECT(pipeoptim_plan_localize(nullptr, nullptr, nullptr, &n_local) == PO_EINVAL);
     EXPECT(pipeoptim_plan_local_params(nullptr, &n_local) == PO_EINVAL);
