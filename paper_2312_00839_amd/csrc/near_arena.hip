@@ -98,19 +98,16 @@ hipMemAllocationProp device_prop(int device)
     return prop;
 }
 
-int map_rw(po_arena* a, char* at, hipMemGenericAllocationHandle_t h)
+// Read-write access for the arena's device to [at, at + bytes), a range that is mapped already.
+int set_access(po_arena* a, char* at, size_t bytes)
 {
-    hipError_t e = hipMemMap(at, kRegion, 0, h, 0);
-    if (e != hipSuccess) return po_fail(PO_EHIP, "hipMemMap: %s", hipGetErrorString(e));
+    if (bytes == 0) return PO_OK;
     hipMemAccessDesc acc{};
     acc.location.type = hipMemLocationTypeDevice;
     acc.location.id = a->device;
     acc.flags = hipMemAccessFlagsProtReadWrite;
-    e = hipMemSetAccess(at, kRegion, &acc, 1);
-    if (e != hipSuccess) {
-        (void)hipMemUnmap(at, kRegion);
-        return po_fail(PO_EHIP, "hipMemSetAccess: %s", hipGetErrorString(e));
-    }
+    hipError_t e = hipMemSetAccess(at, bytes, &acc, 1);
+    if (e != hipSuccess) return po_fail(PO_EHIP, "hipMemSetAccess: %s", hipGetErrorString(e));
     return PO_OK;
 }
 
@@ -137,10 +134,11 @@ int grow_once(po_arena* a)
     }
     const uint32_t n = (uint32_t)h.size();
     uint32_t n_staged = 0;
-    for (; n_staged < n && rc == PO_OK; ++n_staged) {
-        rc = map_rw(a, a->staging + (size_t)n_staged * kRegion, h[n_staged]);
-        if (rc != PO_OK) break;
+    for (; n_staged < n; ++n_staged) {
+        hipError_t e = hipMemMap(a->staging + (size_t)n_staged * kRegion, kRegion, 0, h[n_staged], 0);
+        if (e != hipSuccess) { rc = po_fail(PO_EHIP, "hipMemMap(staging): %s", hipGetErrorString(e)); break; }
     }
+    if (rc == PO_OK) rc = set_access(a, a->staging, (size_t)n_staged * kRegion);
     std::vector<int> cls(n, -1);                      // -1: not decided yet
     std::vector<uint32_t> best0(n, 0xFFFFFFFFu), best1(n, 0xFFFFFFFFu), lat((size_t)n * 2);
     if (rc == PO_OK) {
@@ -178,18 +176,36 @@ int grow_once(po_arena* a)
         hipError_t e = hipMemUnmap(a->staging + (size_t)i * kRegion, kRegion);
         if (e != hipSuccess && rc == PO_OK) rc = po_fail(PO_EHIP, "hipMemUnmap(staging): %s", hipGetErrorString(e));
     }
+    // map each decided handle at the end of its class range; access is granted per class for the whole new span,
+    // and a->mapped only moves once that has succeeded (a span that is mapped but not accessible is taken back)
+    size_t added[2] = {0, 0};
     for (uint32_t i = 0; i < n; ++i) {
         const int c = cls[i];
-        if (rc == PO_OK && c >= 0 && a->mapped[c] + kRegion <= a->capacity) {
-            rc = map_rw(a, a->va + (size_t)c * a->capacity + a->mapped[c], h[i]);
-            if (rc == PO_OK) {
-                a->mapped[c] += kRegion;
+        if (rc == PO_OK && c >= 0 && a->mapped[c] + added[c] + kRegion <= a->capacity) {
+            hipError_t e = hipMemMap(a->va + (size_t)c * a->capacity + a->mapped[c] + added[c], kRegion, 0, h[i], 0);
+            if (e == hipSuccess) {
+                added[c] += kRegion;
                 a->handles[c].push_back(h[i]);
                 continue;
             }
+            rc = po_fail(PO_EHIP, "hipMemMap: %s", hipGetErrorString(e));
         }
         if (rc == PO_OK && c < 0) ++a->n_released;
         (void)hipMemRelease(h[i]);
+    }
+    for (int c = 0; c < 2; ++c) {
+        char* span = a->va + (size_t)c * a->capacity + a->mapped[c];
+        const int rc_c = set_access(a, span, added[c]);
+        if (rc_c == PO_OK) {
+            a->mapped[c] += added[c];
+            continue;
+        }
+        if (rc == PO_OK) rc = rc_c;
+        for (size_t off = 0; off < added[c]; off += kRegion) {
+            (void)hipMemUnmap(span + off, kRegion);
+            (void)hipMemRelease(a->handles[c].back());
+            a->handles[c].pop_back();
+        }
     }
     return rc;
 }
