@@ -207,7 +207,7 @@ int32_t auto_lds_bytes(int kernel, int opt, int64_t n_params, bool local = false
         // every XCC on its own die's memory: shorter latency, no shared link; the sweeps put the optimum at 10
         // workgroups per CU for the fused two-state kernel at every size from 64 M parameters up, at 12-13 for the
         // one-state kernels, and at 16 (20 on mid-sized stages) for the prediction kernel
-        if (kernel == PO_KERNEL_KIND_PREDICT) return two_state ? (large ? 10240 : 8192) : 6144;
+        if (kernel == PO_KERNEL_KIND_PREDICT) return two_state ? (large ? 10240 : 8192) : (large ? 7168 : 6144);
         if (two_state) return mid ? 16384 : 12288;
         return 12288;
     }
