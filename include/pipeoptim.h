@@ -17,12 +17,17 @@
  *
  * Conventions for every function
  *   - extern "C"; returns PO_OK (0) or a negative po_status; never throws.
- *   - Tensor pointers are DEVICE pointers owned by the caller.  The library
- *     never allocates, frees or keeps tensor memory; a plan owns only its own
- *     small device tables (tensor descriptors + chunk table).
+ *   - Tensor pointers are DEVICE pointers.  Who owns the memory behind them:
+ *       * Buffers the caller allocated (e.g. through PyTorch) stay the caller's: the plan_* and step/predict
+ *         calls never allocate, free, move or keep tensor memory; a plan owns only its own small tables
+ *         (tensor descriptors + chunk table on the device, their pinned staging copies on the host).
+ *       * Buffers handed out by pipeoptim_arena_alloc are device memory that the LIBRARY allocates (HIP virtual
+ *         memory management) and owns: they live until pipeoptim_arena_destroy, the caller only uses them.
+ *         A caller opts into that by creating an arena; nothing else in the library allocates tensor memory.
  *   - `hip_stream` is a hipStream_t passed as void* (NULL = the null stream).
  *     Work is enqueued and not waited for, except where a function says it
- *     synchronises.
+ *     waits.  No call that a training loop makes per step (pipeoptim_step_predict, pipeoptim_predict,
+ *     pipeoptim_plan_set_pointers) waits for the device or for a stream; the set-up calls that do say so.
  *   - On failure nothing is launched and pipeoptim_last_error() describes it.
  */
 #ifndef PIPEOPTIM_H
@@ -97,30 +102,21 @@ typedef struct po_chunk {
 } po_chunk;
 
 /*
- * Launch shape of the fused kernel.  The grid has one workgroup per tile of block*4*unroll
- * elements (each lane moves `unroll` groups of 4 consecutive elements per stream).
- *   block        64, 128 or 256 threads
- *   unroll       1, 2 or 4
- *   cache_policy 0: plain loads and stores; 1: streaming (nt) loads; 2: streaming stores;
- *                3: both; 4: streaming loads, streaming + write-through (nt sc1) stores
+ * Launch shape of a kernel.  The grid has one workgroup per tile of block*4 elements (each lane moves 4
+ * consecutive elements per stream, one dwordx4 access).
+ *   block        64, 128 or 256 threads (64, the default, measured fastest at every stage size; the near-memory
+ *                tile order is defined for it alone)
  *   lds_bytes    0..65536, unused LDS reserved per workgroup to cap how many workgroups a CU
- *                holds at once (160 KiB of LDS per CU); 0 = no cap; PO_LDS_AUTO (-1, the default of
- *                both kernels on all but small stages) = chosen at each call from the kernel, the
- *                number of state streams of the optimizer in use and the size of the stage
- *                (pipeoptim_auto_lds_bytes tells the value)
- *   chunk_elems  granularity of the chunk table: block*4*unroll times a power of two, at most 2^30
- *   xcd_remap    0 or 1: 1 hands each of the chip's 8 XCDs (workgroup id mod 8) a contiguous
- *                eighth of the work instead of every eighth tile
- * The number of chunks times chunk_elems/(block*4*unroll) must stay below 2^31.
+ *                holds at once (160 KiB of LDS per CU); 0 = no cap; PO_LDS_AUTO (-1, the default) = chosen at
+ *                each call from the kernel, the number of state streams of the optimizer in use and the size
+ *                of the stage (pipeoptim_auto_lds_bytes tells the value)
+ *   chunk_elems  granularity of the chunk table: block*4 times a power of two, at most 2^30
+ * The number of chunks times chunk_elems/(block*4) must stay below 2^31.
  */
 typedef struct po_launch {
     int32_t block;
-    int32_t unroll;
-    int32_t cache_policy;
     int32_t lds_bytes;
     int64_t chunk_elems;
-    int32_t xcd_remap;
-    int32_t reserved;     /* must be 0 */
 } po_launch;
 
 #define PO_LDS_AUTO (-1)
@@ -137,8 +133,10 @@ typedef struct po_plan po_plan;   /* opaque */
  * are legal.  No two buffers of the plan may overlap (checked: PO_EINVAL); g is only read;
  * W, m, v are updated in place.  Buffers aligned to 16 bytes take the vector
  * path; 4-byte (What bf16: 2-byte) alignment is accepted and takes a scalar
- * path for that tensor.  Uploads the tables with a blocking copy (this call
- * synchronises with its own copy, not with `hip_stream`'s other work).
+ * path for that tensor.  The tables are uploaded with one asynchronous copy each, enqueued on `hip_stream`
+ * from pinned staging memory that the plan owns: the call does not wait for the device or for the stream.
+ * A later launch of the plan on another stream is made to wait for the upload by the library (an event), so
+ * the plan can be used on any stream of the device right away.
  * The caller keeps all buffers alive and at the same addresses while the plan lives.
  */
 int pipeoptim_plan_create(po_plan** out, int64_t n_tensors, const int64_t* numel,
@@ -156,16 +154,24 @@ int pipeoptim_plan_create_mixed(po_plan** out, int64_t n_tensors, const int64_t*
                                 float* const* m, float* const* v, void* const* What, int32_t what_dtype,
                                 void* hip_stream);
 
-/* Frees the plan's tables.  Synchronises the device first so no launch still reads them.  NULL is a no-op. */
+/* Frees the plan's tables.  Waits first for the two streams the plan used last (that of its latest launch and
+ * that of its latest table upload), not for the device: launches of the plan that are still pending on any
+ * other stream are the caller's to wait for.  NULL is a no-op. */
 int pipeoptim_plan_destroy(po_plan* plan);
 
 /* Replace one pointer column (which: 0 W, 1 g, 2 m, 3 v, 4 What) with n_tensors new device pointers
- * (host array), e.g. when gradient buffers are re-allocated between steps.  Blocking upload. */
-int pipeoptim_plan_set_pointers(po_plan* plan, int32_t which, void* const* ptrs);
+ * (host array), e.g. when gradient buffers are re-allocated between steps.  May be called every step: the new
+ * descriptors go to the device with one asynchronous copy enqueued on `hip_stream`, ordered like any other work
+ * there (after the launches already enqueued on it, before the later ones); nothing is waited for.  Launches of
+ * the plan enqueued afterwards on another stream wait for the copy (an event); launches enqueued BEFORE the call
+ * on another stream and still running are the caller's to order, as for any write to memory a kernel reads.
+ * On failure the plan is left exactly as it was.  Clears the near-memory marks (pipeoptim_plan_localize). */
+int pipeoptim_plan_set_pointers(po_plan* plan, int32_t which, void* const* ptrs, void* hip_stream);
 
-/* Get / set the launch shape of the fused kernel (set rebuilds and re-uploads the chunk table if chunk_elems
- * changes; blocking).  The prediction kernel shares the table: if its tile no longer divides the new
- * chunk_elems by a power of two, its block and unroll are reset to this launch's. */
+/* Get / set the launch shape of the fused kernel.  A set-up call: if chunk_elems changes, set rebuilds the
+ * chunk table, waits for the plan's latest launch and upload streams (a running launch may still read the old
+ * table), and uploads the new one on the stream of the latest upload.  The prediction kernel shares the table:
+ * if its tile no longer divides the new chunk_elems by a power of two, its block is reset to this launch's. */
 int pipeoptim_plan_get_launch(const po_plan* plan, po_launch* out);
 int pipeoptim_plan_set_launch(po_plan* plan, const po_launch* launch);
 
@@ -225,7 +231,9 @@ int pipeoptim_arena_destroy(po_arena* arena);
  * On which XCC a launch's round starts depends on the hardware queue behind the stream.  This call finds out for
  * hip_stream with a tiny kernel; after that every launch of the plan reports where it started (one word written to
  * pinned host memory) and the next call uses what it finds there, so a plan that moves to another stream runs one
- * launch with the old value (slower, never wrong) before it follows.  Blocking: waits for the device.
+ * launch with the old value (slower, never wrong) before it follows.  A set-up call: waits for hip_stream (the
+ * tiny kernel's answer), not for the device; the descriptors are then uploaded on hip_stream like in
+ * pipeoptim_plan_set_pointers.
  * A stage below 2^25 parameters whose prediction launch shape the caller never set gets 256-element tiles for that
  * kernel too when most of it is marked (its default there is bigger tiles, which the order is not defined for).
  */
@@ -326,6 +334,11 @@ int pipeoptim_probe_copy_near(const po_arena* arena, void* dst, const void* src,
 
 /* Thread-local description of the last failure on this thread ("" if none). */
 const char* pipeoptim_last_error(void);
+
+/* Diagnostic: how many times this process's library has waited for the WHOLE device (hipDeviceSynchronize) so
+ * far.  Only the arena calls and the fallbacks of pipeoptim_plan_destroy / pipeoptim_plan_set_launch (a stream
+ * of the plan no longer exists) ever do; tests use the counter to show that the per-step calls do not. */
+int pipeoptim_device_sync_count(int64_t* count);
 
 #ifdef __cplusplus
 }

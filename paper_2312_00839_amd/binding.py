@@ -46,9 +46,7 @@ class po_chunk(ctypes.Structure):
 
 
 class po_launch(ctypes.Structure):
-    _fields_ = [("block", ctypes.c_int32), ("unroll", ctypes.c_int32), ("cache_policy", ctypes.c_int32),
-                ("lds_bytes", ctypes.c_int32), ("chunk_elems", ctypes.c_int64),
-                ("xcd_remap", ctypes.c_int32), ("reserved", ctypes.c_int32)]
+    _fields_ = [("block", ctypes.c_int32), ("lds_bytes", ctypes.c_int32), ("chunk_elems", ctypes.c_int64)]
 
 
 EXPORTS = (
@@ -61,6 +59,7 @@ EXPORTS = (
     "pipeoptim_arena_create", "pipeoptim_arena_alloc", "pipeoptim_arena_set_skew", "pipeoptim_arena_near_half",
     "pipeoptim_arena_info", "pipeoptim_arena_check", "pipeoptim_arena_destroy", "pipeoptim_plan_localize", "pipeoptim_plan_effective_launch",
     "pipeoptim_local_tile", "pipeoptim_local_slot", "pipeoptim_plan_local_params", "pipeoptim_plan_launch_phase",
+    "pipeoptim_device_sync_count",
 )
 
 _lib = None
@@ -79,7 +78,8 @@ def lib():
         L.pipeoptim_plan_create.argtypes = [P(vp), i64, P(i64), P(vp), P(vp), P(vp), P(vp), P(vp), i32, vp]
         L.pipeoptim_plan_create_mixed.argtypes = [P(vp), i64, P(i64), P(vp), P(vp), i32, P(vp), P(vp), P(vp), i32, vp]
         L.pipeoptim_plan_destroy.argtypes = [vp]
-        L.pipeoptim_plan_set_pointers.argtypes = [vp, i32, P(vp)]
+        L.pipeoptim_plan_set_pointers.argtypes = [vp, i32, P(vp), vp]
+        L.pipeoptim_device_sync_count.argtypes = [P(i64)]
         L.pipeoptim_plan_get_launch.argtypes = [vp, P(po_launch)]
         L.pipeoptim_plan_set_launch.argtypes = [vp, P(po_launch)]
         L.pipeoptim_plan_info.argtypes = [vp, P(i64), P(i64), P(i64)]
@@ -280,8 +280,8 @@ class Plan:
         _check(lib().pipeoptim_plan_set_predict_launch(self._h, ctypes.byref(L)))
         return L
 
-    def set_pointers(self, which: int, ptrs: Sequence[int]) -> None:
-        _check(lib().pipeoptim_plan_set_pointers(self._h, int(which), _ptr_array(ptrs)))
+    def set_pointers(self, which: int, ptrs: Sequence[int], stream: int = 0) -> None:
+        _check(lib().pipeoptim_plan_set_pointers(self._h, int(which), _ptr_array(ptrs), ctypes.c_void_p(stream)))
 
     def get_launch(self) -> po_launch:
         L = po_launch()
@@ -338,6 +338,13 @@ class Plan:
             self.destroy()
         except Exception:
             pass
+
+
+def pipeoptim_device_sync_count() -> int:
+    """How often the library has waited for the whole device so far (diagnostic)."""
+    n = ctypes.c_int64(-1)
+    _check(lib().pipeoptim_device_sync_count(ctypes.byref(n)))
+    return n.value
 
 
 def pipeoptim_probe_copy(dst: int, src: int, nbytes: int, stream: int = 0) -> None:

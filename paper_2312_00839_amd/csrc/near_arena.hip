@@ -121,7 +121,7 @@ int grow_once(po_arena* a)
     h.reserve(kBatch);
     int rc = PO_OK;
     // the timing below wants the memory system to itself: wait for whatever the caller still has in flight
-    hipError_t e0 = hipDeviceSynchronize();
+    hipError_t e0 = po_device_sync();
     if (e0 != hipSuccess) return po_fail(PO_EHIP, "hipDeviceSynchronize: %s", hipGetErrorString(e0));
     for (int i = 0; i < kBatch; ++i) {
         hipMemGenericAllocationHandle_t x;
@@ -146,7 +146,7 @@ int grow_once(po_arena* a)
             hipLaunchKernelGGL(po_arena_probe_kernel, dim3(8), dim3(64), 0, nullptr, a->staging, n, (uint32_t)round,
                                a->d_lat, a->d_lat + (size_t)kBatch * 2);
             hipError_t e = hipGetLastError();
-            if (e == hipSuccess) e = hipDeviceSynchronize();
+            if (e == hipSuccess) e = po_device_sync();
             if (e == hipSuccess) e = hipMemcpy(lat.data(), a->d_lat, (size_t)n * 2 * 4, hipMemcpyDeviceToHost);
             uint32_t xcc = 0;
             if (e == hipSuccess) e = hipMemcpy(&xcc, a->d_lat + (size_t)kBatch * 2, 4, hipMemcpyDeviceToHost);
@@ -271,7 +271,7 @@ int pipeoptim_arena_destroy(po_arena* a)
 {
     if (!a) return PO_OK;
     int rc = PO_OK;
-    hipError_t e = hipDeviceSynchronize();          // no kernel may still touch the arena's memory
+    hipError_t e = po_device_sync();          // no kernel may still touch the arena's memory
     if (e != hipSuccess) rc = po_fail(PO_EHIP, "hipDeviceSynchronize: %s", hipGetErrorString(e));
     for (int c = 0; c < 2; ++c) {
         char* lo = a->va + (size_t)c * a->capacity;
@@ -353,7 +353,7 @@ int pipeoptim_arena_check(po_arena* a, int64_t* n_timed, int64_t* n_disagree)
 try {
     if (!a || !n_timed || !n_disagree) return po_fail(PO_EINVAL, "arena, n_timed or n_disagree is NULL");
     *n_timed = *n_disagree = 0;
-    hipError_t e = hipDeviceSynchronize();          // the timing wants the memory system to itself
+    hipError_t e = po_device_sync();          // the timing wants the memory system to itself
     if (e != hipSuccess) return po_fail(PO_EHIP, "hipDeviceSynchronize: %s", hipGetErrorString(e));
     std::vector<uint32_t> lat((size_t)kBatch * 2);
     for (int c = 0; c < 2; ++c) {
@@ -365,7 +365,7 @@ try {
                                a->va + (size_t)c * a->capacity + first * kRegion, n, (uint32_t)kRounds, a->d_lat,
                                a->d_lat + (size_t)kBatch * 2);
             e = hipGetLastError();
-            if (e == hipSuccess) e = hipDeviceSynchronize();
+            if (e == hipSuccess) e = po_device_sync();
             if (e == hipSuccess) e = hipMemcpy(lat.data(), a->d_lat, (size_t)n * 2 * 4, hipMemcpyDeviceToHost);
             uint32_t xcc = 0;
             if (e == hipSuccess) e = hipMemcpy(&xcc, a->d_lat + (size_t)kBatch * 2, 4, hipMemcpyDeviceToHost);

@@ -6,6 +6,7 @@
 // paper Eq. 4, and argument validation.  The kernels live in
 // step_predict_kernels.hip.
 #include <algorithm>
+#include <atomic>
 #include <cmath>
 #include <cstdarg>
 #include <cstdio>
@@ -41,15 +42,11 @@ constexpr int64_t kMaxChunkElems = int64_t(1) << 30;
 int check_launch(const po_launch& L)
 {
     if (L.block != 64 && L.block != 128 && L.block != 256) return po_fail(PO_EINVAL, "launch.block must be 64, 128 or 256");
-    if (L.unroll != 1 && L.unroll != 2 && L.unroll != 4) return po_fail(PO_EINVAL, "launch.unroll must be 1, 2 or 4");
-    if (L.cache_policy < 0 || L.cache_policy > 4) return po_fail(PO_EINVAL, "launch.cache_policy must be 0..4");
     if (L.lds_bytes < PO_LDS_AUTO || L.lds_bytes > 65536) return po_fail(PO_EINVAL, "launch.lds_bytes must be 0..65536, or -1 (chosen per call)");
-    if (L.xcd_remap != 0 && L.xcd_remap != 1) return po_fail(PO_EINVAL, "launch.xcd_remap must be 0 or 1");
-    if (L.reserved != 0) return po_fail(PO_EINVAL, "launch.reserved must be 0");
-    const int64_t tile = (int64_t)L.block * 4 * L.unroll;
+    const int64_t tile = (int64_t)L.block * 4;
     const int64_t ratio = L.chunk_elems > 0 ? L.chunk_elems / tile : 0;
     if (L.chunk_elems <= 0 || L.chunk_elems > kMaxChunkElems || L.chunk_elems % tile != 0 || (ratio & (ratio - 1)) != 0)
-        return po_fail(PO_EINVAL, "launch.chunk_elems must be block*4*unroll (%lld) times a power of two, at most 2^30",
+        return po_fail(PO_EINVAL, "launch.chunk_elems must be block*4 (%lld) times a power of two, at most 2^30",
                     (long long)tile);
     return PO_OK;
 }
@@ -57,9 +54,9 @@ int check_launch(const po_launch& L)
 // one workgroup per tile: the grid must fit HIP's limit
 int check_grid(const po_launch& L, int64_t n_chunks)
 {
-    const int64_t tiles = L.chunk_elems / ((int64_t)L.block * 4 * L.unroll);
+    const int64_t tiles = L.chunk_elems / ((int64_t)L.block * 4);
     if (n_chunks > 0 && tiles > (int64_t(0x7FFFFFF8) / n_chunks))
-        return po_fail(PO_EINVAL, "grid of %lld chunks x %lld tiles exceeds 2^31 workgroups; raise block or unroll",
+        return po_fail(PO_EINVAL, "grid of %lld chunks x %lld tiles exceeds 2^31 workgroups; raise block or lower chunk_elems",
                     (long long)n_chunks, (long long)tiles);
     return PO_OK;
 }
@@ -90,6 +87,16 @@ bool finite_d(double x) { return std::isfinite(x); }
 
 }  // namespace
 
+// The library waits for the whole device in very few places (arena set-up, and as a fallback when a stream a
+// plan remembers no longer exists); every such wait goes through here so that it can be counted.
+static std::atomic<int64_t> g_device_syncs{0};
+
+hipError_t po_device_sync()
+{
+    g_device_syncs.fetch_add(1, std::memory_order_relaxed);
+    return hipDeviceSynchronize();
+}
+
 struct po_plan {
     int64_t n_tensors = 0;
     int64_t n_params = 0;
@@ -102,13 +109,30 @@ struct po_plan {
     int device = 0;
     po_launch launch{};           // fused kernel
     po_launch predict_launch{};   // prediction-only kernel; chunk_elems always equals launch.chunk_elems
-    bool predict_launch_set = false;   // the caller chose it (pipeoptim_plan_set_predict_launch): never replaced
     std::vector<int64_t> numel;
     std::vector<po_tensor_desc> descs;    // host mirror
     std::vector<po_chunk> chunks;         // host mirror
     po_tensor_desc* d_descs = nullptr;
     po_chunk* d_chunks = nullptr;
     int64_t d_chunks_capacity = 0;
+    // Pinned staging memory for the asynchronous table uploads.  Descriptors: two buffers used in turn, each
+    // guarded by the event recorded behind its last copy, so that pipeoptim_plan_set_pointers may be called again
+    // while the previous upload is still queued.  Chunk table: one buffer (it is rewritten only by
+    // pipeoptim_plan_set_launch, which waits for the plan's streams first).
+    po_tensor_desc* h_descs[2] = {nullptr, nullptr};
+    hipEvent_t ev_descs[2] = {nullptr, nullptr};
+    bool ev_recorded[2] = {false, false};
+    int next_staging = 0;
+    po_chunk* h_chunks = nullptr;
+    int64_t h_chunks_capacity = 0;
+    // The latest upload: its stream, and the event behind it.  A launch on any other stream first makes that
+    // stream wait for the event; `ordered_stream` is the stream known to be ordered behind the upload already.
+    hipEvent_t ev_upload = nullptr;            // one of ev_descs, or ev_chunks
+    hipEvent_t ev_chunks = nullptr;
+    hipStream_t upload_stream = nullptr;
+    mutable hipStream_t ordered_stream = nullptr;
+    mutable hipStream_t last_launch_stream = nullptr;
+    mutable bool launched = false;
     // Pinned host word (64 bytes allocated) that workgroup 0 of every launch in the near-memory tile order writes
     // its XCC id to: the XCC on which the stream's hardware queue starts its launches.  The next call passes the
     // value it finds there to its kernel.  Allocated by pipeoptim_plan_localize, nullptr before.
@@ -117,23 +141,23 @@ struct po_plan {
 
 namespace {
 
-// All buffers of a plan must be pairwise disjoint: W, m, v are rewritten in place while other
+// All buffers of a stage must be pairwise disjoint: W, m, v are rewritten in place while other
 // workgroups still read their own parts, and What is written from values read earlier.
-int check_disjoint(const po_plan* p)
+int check_disjoint(const std::vector<po_tensor_desc>& descs, int grad_dtype, int what_dtype)
 {
     struct Range { uintptr_t lo, hi; int64_t tensor; char kind; };
     std::vector<Range> r;
-    r.reserve((size_t)p->n_tensors * 5);
-    const size_t gsz = p->grad_dtype == PO_GRAD_BF16 ? 2 : 4, hsz = p->what_dtype == PO_WHAT_BF16 ? 2 : 4;
-    for (int64_t i = 0; i < p->n_tensors; ++i) {
-        const po_tensor_desc& d = p->descs[(size_t)i];
+    r.reserve(descs.size() * 5);
+    const size_t gsz = grad_dtype == PO_GRAD_BF16 ? 2 : 4, hsz = what_dtype == PO_WHAT_BF16 ? 2 : 4;
+    for (size_t i = 0; i < descs.size(); ++i) {
+        const po_tensor_desc& d = descs[i];
         const size_t n = (size_t)d.numel;
         if (n == 0) continue;
-        r.push_back({(uintptr_t)d.W, (uintptr_t)d.W + n * 4, i, 'W'});
-        r.push_back({(uintptr_t)d.g, (uintptr_t)d.g + n * gsz, i, 'g'});
-        if (d.m) r.push_back({(uintptr_t)d.m, (uintptr_t)d.m + n * 4, i, 'm'});
-        if (d.v) r.push_back({(uintptr_t)d.v, (uintptr_t)d.v + n * 4, i, 'v'});
-        r.push_back({(uintptr_t)d.What, (uintptr_t)d.What + n * hsz, i, 'h'});
+        r.push_back({(uintptr_t)d.W, (uintptr_t)d.W + n * 4, (int64_t)i, 'W'});
+        r.push_back({(uintptr_t)d.g, (uintptr_t)d.g + n * gsz, (int64_t)i, 'g'});
+        if (d.m) r.push_back({(uintptr_t)d.m, (uintptr_t)d.m + n * 4, (int64_t)i, 'm'});
+        if (d.v) r.push_back({(uintptr_t)d.v, (uintptr_t)d.v + n * 4, (int64_t)i, 'v'});
+        r.push_back({(uintptr_t)d.What, (uintptr_t)d.What + n * hsz, (int64_t)i, 'h'});
     }
     std::sort(r.begin(), r.end(), [](const Range& a, const Range& b) { return a.lo < b.lo; });
     for (size_t k = 1; k < r.size(); ++k)
@@ -143,54 +167,59 @@ int check_disjoint(const po_plan* p)
     return PO_OK;
 }
 
-int upload_chunks(po_plan* p)
+// Recomputes every descriptor's flags from its pointers (this drops near-memory marks: they hold for the
+// addresses pipeoptim_plan_localize looked at, not for new ones).  Returns the tensors on the scalar path.
+int64_t refresh_flags(std::vector<po_tensor_desc>& descs)
 {
-    int64_t n = 0;
-    int rc = build_chunks(p->n_tensors, p->numel.data(), p->launch.chunk_elems, nullptr, 0, &n);
-    if (rc != PO_OK) return rc;
-    p->chunks.resize((size_t)n);
-    rc = build_chunks(p->n_tensors, p->numel.data(), p->launch.chunk_elems, p->chunks.data(), n, &n);
-    if (rc != PO_OK) return rc;
-    if (n > p->d_chunks_capacity) {
-        if (p->d_chunks) {
-            hipError_t e = hipDeviceSynchronize();   // a launch may still read the old table
-            if (e != hipSuccess) return fail_hip(e, "hipDeviceSynchronize");
-            (void)hipFree(p->d_chunks);
-            p->d_chunks = nullptr;
-            p->d_chunks_capacity = 0;
-        }
-        hipError_t e = hipMalloc(reinterpret_cast<void**>(&p->d_chunks), (size_t)n * sizeof(po_chunk));
-        if (e != hipSuccess) return po_fail(PO_ENOMEM, "hipMalloc(chunk table, %lld entries): %s", (long long)n,
-                                         hipGetErrorString(e));
-        p->d_chunks_capacity = n;
-    }
-    if (n > 0) {
-        hipError_t e = hipMemcpy(p->d_chunks, p->chunks.data(), (size_t)n * sizeof(po_chunk), hipMemcpyHostToDevice);
-        if (e != hipSuccess) return fail_hip(e, "hipMemcpy(chunk table)");
-    }
-    return PO_OK;
-}
-
-int upload_descs(po_plan* p)
-{
-    if (p->n_tensors == 0) return PO_OK;
-    hipError_t e = hipMemcpy(p->d_descs, p->descs.data(), (size_t)p->n_tensors * sizeof(po_tensor_desc),
-                             hipMemcpyHostToDevice);
-    if (e != hipSuccess) return fail_hip(e, "hipMemcpy(tensor descriptors)");
-    return PO_OK;
-}
-
-// Recomputes every descriptor's flags from its pointers.  Drops the near-memory marks: they hold for the
-// addresses pipeoptim_plan_localize looked at, not for new ones.
-void refresh_flags(po_plan* p)
-{
-    p->n_unaligned = 0;
-    p->n_local_params = 0;
-    for (auto& d : p->descs) {
+    int64_t n_unaligned = 0;
+    for (auto& d : descs) {
         uintptr_t bits = (uintptr_t)d.W | (uintptr_t)d.g | (uintptr_t)d.m | (uintptr_t)d.v | (uintptr_t)d.What;
         d.flags = (bits & 15u) == 0 ? PO_DESC_VECTOR_OK : 0u;
-        if (!d.flags && d.numel > 0) ++p->n_unaligned;
+        if (!d.flags && d.numel > 0) ++n_unaligned;
     }
+    return n_unaligned;
+}
+
+}  // namespace
+
+// Validates a ragged list as the plan and the allocation-free entry point take it, and turns it into
+// descriptors (flags set).  Nothing here touches the device.
+int po_describe_list(int64_t n_tensors, const int64_t* numel, float* const* W, const void* const* g, int32_t grad_dtype,
+                     float* const* m, float* const* v, void* const* What, int32_t what_dtype,
+                     std::vector<po_tensor_desc>& descs, int64_t* n_params, int64_t* n_unaligned)
+{
+    if (n_tensors < 0) return po_fail(PO_EINVAL, "n_tensors < 0");
+    if (n_tensors > (int64_t)UINT32_MAX) return po_fail(PO_EINVAL, "too many tensors");
+    if (n_tensors > 0 && (!numel || !W || !g || !What)) return po_fail(PO_EINVAL, "a required pointer array is NULL");
+    if (n_tensors > 0 && !m && !v) return po_fail(PO_EINVAL, "a stage needs at least one of m and v");
+    if (what_dtype != PO_WHAT_F32 && what_dtype != PO_WHAT_BF16) return po_fail(PO_EINVAL, "unknown what_dtype %d", what_dtype);
+    if (grad_dtype != PO_GRAD_F32 && grad_dtype != PO_GRAD_BF16) return po_fail(PO_EINVAL, "unknown grad_dtype %d", grad_dtype);
+    const uintptr_t what_mask = what_dtype == PO_WHAT_BF16 ? 1u : 3u;
+    const uintptr_t grad_mask = grad_dtype == PO_GRAD_BF16 ? 1u : 3u;
+    int64_t total = 0;
+    for (int64_t i = 0; i < n_tensors; ++i) {
+        if (numel[i] < 0) return po_fail(PO_EINVAL, "numel[%lld] < 0", (long long)i);
+        if (numel[i] == 0) continue;
+        if (!W[i] || !g[i] || !What[i] || (m && !m[i]) || (v && !v[i]))
+            return po_fail(PO_EINVAL, "tensor %lld has a NULL buffer", (long long)i);
+        if (((uintptr_t)W[i] | (m ? (uintptr_t)m[i] : 0) | (v ? (uintptr_t)v[i] : 0)) & 3u)
+            return po_fail(PO_EALIGN, "tensor %lld: fp32 buffer not 4-byte aligned", (long long)i);
+        if ((uintptr_t)g[i] & grad_mask) return po_fail(PO_EALIGN, "tensor %lld: g not aligned to its element", (long long)i);
+        if ((uintptr_t)What[i] & what_mask) return po_fail(PO_EALIGN, "tensor %lld: What not aligned to its element", (long long)i);
+        total += numel[i];
+    }
+    descs.resize((size_t)n_tensors);
+    for (int64_t i = 0; i < n_tensors; ++i) {
+        po_tensor_desc& d = descs[(size_t)i];
+        d.W = W[i]; d.g = g[i]; d.m = m ? m[i] : nullptr; d.v = v ? v[i] : nullptr; d.What = What[i];
+        d.numel = numel[i]; d.flags = 0; d.pad = 0;
+    }
+    const int rc = check_disjoint(descs, grad_dtype, what_dtype);
+    if (rc != PO_OK) return rc;
+    const int64_t un = refresh_flags(descs);
+    if (n_params) *n_params = total;
+    if (n_unaligned) *n_unaligned = un;
+    return PO_OK;
 }
 
 // Occupancy cap (unused LDS per single-wave workgroup; a CU has 160 KiB) by kernel, number of state streams and
@@ -199,7 +228,7 @@ void refresh_flags(po_plan* p)
 // streams evict each other.  A fused Adam/AdamW tile moves 7.5 KB (10 workgroups per CU), a one-state
 // optimizer's 5.5-6 KB (13), a prediction tile 3.5 KB (20) or 2.5 KB (26).  Smaller stages, whose launch is
 // dominated by ramp-up and ramp-down, like a few more.
-int32_t auto_lds_bytes(int kernel, int opt, int64_t n_params, bool local = false)
+int32_t po_auto_lds_bytes(int kernel, int opt, int64_t n_params, bool local)
 {
     const bool two_state = opt == PO_ADAM || opt == PO_ADAMW;
     const bool large = n_params >= (int64_t(1) << 27), mid = n_params >= (int64_t(1) << 25);
@@ -216,20 +245,18 @@ int32_t auto_lds_bytes(int kernel, int opt, int64_t n_params, bool local = false
     return mid ? 12288 : 10240;
 }
 
-// Default launch shape, as measured on MI355X: single-wave workgroups, one 256-element tile each,
-// streaming loads, streaming write-through stores, and an occupancy cap chosen per call (see above).
-po_launch default_launch(int64_t)
+// Default launch shape, as measured on MI355X: single-wave workgroups, one 256-element tile each, and an
+// occupancy cap chosen per call (see above).  Bigger workgroups measured slower at every stage size.
+po_launch po_default_launch()
 {
     po_launch L{};
     L.block = 64;
-    L.unroll = 1;
-    L.cache_policy = 4;
     L.lds_bytes = PO_LDS_AUTO;
     L.chunk_elems = 65536;
-    L.xcd_remap = 0;
-    L.reserved = 0;
     return L;
 }
+
+namespace {
 
 // The plan's tables and the caller's buffers live on the device that was current at plan creation.
 int check_device(const po_plan* p)
@@ -252,30 +279,103 @@ int check_state(const po_plan* p, int opt)
     return PO_OK;
 }
 
-// The prediction-only kernel is read-dominated (8-12 B read, 2-4 B written per parameter) and likes a
-// looser occupancy cap than the fused kernel.  Small stages, whose working set largely sits in the
-// memory-side cache, run best with plain accesses and bigger workgroups.
-// A small stage that is localized keeps the plain accesses but takes 1 KiB tiles, the only tile size the
-// near-memory order is defined for (config 2's shapes: 47.7 -> 39.0 us).
-po_launch default_predict_launch(const po_launch& fused, int64_t n_params, bool local = false)
-{
-    po_launch L = fused;
-    if (n_params < (int64_t(1) << 25)) {
-        L.block = local ? 64 : 256;
-        L.unroll = local ? 1 : 2;
-        L.cache_policy = 0;
-        L.lds_bytes = local ? 6144 : 0;
-    }
-    return L;
-}
-
 // The launch shape a call runs with: lds_bytes == PO_LDS_AUTO resolved for the optimizer in use.
 po_launch resolve_launch(const po_plan* p, const po_launch& L, int kernel, int opt)
 {
     po_launch R = L;
     const bool local = p->n_local_params * 2 >= p->n_params && p->n_local_params > 0;
-    if (R.lds_bytes == PO_LDS_AUTO) R.lds_bytes = auto_lds_bytes(kernel, opt, p->n_params, local);
+    if (R.lds_bytes == PO_LDS_AUTO) R.lds_bytes = po_auto_lds_bytes(kernel, opt, p->n_params, local);
     return R;
+}
+
+// Waits for the two streams the plan used last: a launch there may still read the tables.  If one of them no
+// longer exists (the caller destroyed it), waits for the device instead.
+int wait_for_plan_streams(const po_plan* p)
+{
+    hipError_t e = hipSuccess;
+    if (p->launched) e = hipStreamSynchronize(p->last_launch_stream);
+    if (e == hipSuccess && p->ev_upload && p->upload_stream != p->last_launch_stream) e = hipStreamSynchronize(p->upload_stream);
+    if (e != hipSuccess) {
+        (void)hipGetLastError();
+        e = po_device_sync();
+    }
+    if (e != hipSuccess) return fail_hip(e, "waiting for the plan's streams");
+    return PO_OK;
+}
+
+// Copies the host descriptors into the staging buffer whose turn it is and enqueues its upload on `stream`.
+int upload_descs(po_plan* p, hipStream_t stream)
+{
+    if (p->n_tensors == 0) return PO_OK;
+    const int k = p->next_staging;
+    hipError_t e = hipSuccess;
+    if (p->ev_recorded[k]) e = hipEventSynchronize(p->ev_descs[k]);      // the copy out of this buffer two uploads ago
+    if (e != hipSuccess) return fail_hip(e, "hipEventSynchronize(staging buffer)");
+    const size_t bytes = (size_t)p->n_tensors * sizeof(po_tensor_desc);
+    std::memcpy(p->h_descs[k], p->descs.data(), bytes);
+    e = hipMemcpyAsync(p->d_descs, p->h_descs[k], bytes, hipMemcpyHostToDevice, stream);
+    if (e != hipSuccess) return fail_hip(e, "hipMemcpyAsync(tensor descriptors)");
+    e = hipEventRecord(p->ev_descs[k], stream);
+    if (e != hipSuccess) return fail_hip(e, "hipEventRecord(tensor descriptors)");
+    p->ev_recorded[k] = true;
+    p->next_staging = k ^ 1;
+    p->ev_upload = p->ev_descs[k];
+    p->upload_stream = stream;
+    p->ordered_stream = stream;
+    return PO_OK;
+}
+
+// Rebuilds the chunk table for the plan's chunk_elems and enqueues its upload on `stream`.  The caller has made
+// sure that no launch still reads the old table and that the previous upload out of h_chunks is done.
+int upload_chunks(po_plan* p, hipStream_t stream)
+{
+    int64_t n = 0;
+    int rc = build_chunks(p->n_tensors, p->numel.data(), p->launch.chunk_elems, nullptr, 0, &n);
+    if (rc != PO_OK) return rc;
+    p->chunks.resize((size_t)n);
+    rc = build_chunks(p->n_tensors, p->numel.data(), p->launch.chunk_elems, p->chunks.data(), n, &n);
+    if (rc != PO_OK) return rc;
+    if (n > p->d_chunks_capacity) {
+        if (p->d_chunks) (void)hipFree(p->d_chunks);
+        p->d_chunks = nullptr;
+        p->d_chunks_capacity = 0;
+        hipError_t e = hipMalloc(reinterpret_cast<void**>(&p->d_chunks), (size_t)n * sizeof(po_chunk));
+        if (e != hipSuccess) return po_fail(PO_ENOMEM, "hipMalloc(chunk table, %lld entries): %s", (long long)n,
+                                         hipGetErrorString(e));
+        p->d_chunks_capacity = n;
+    }
+    if (n > p->h_chunks_capacity) {
+        if (p->h_chunks) (void)hipHostFree(p->h_chunks);
+        p->h_chunks = nullptr;
+        p->h_chunks_capacity = 0;
+        hipError_t e = hipHostMalloc(reinterpret_cast<void**>(&p->h_chunks), (size_t)n * sizeof(po_chunk), hipHostMallocDefault);
+        if (e != hipSuccess) return po_fail(PO_ENOMEM, "hipHostMalloc(chunk table staging): %s", hipGetErrorString(e));
+        p->h_chunks_capacity = n;
+    }
+    if (n > 0) {
+        std::memcpy(p->h_chunks, p->chunks.data(), (size_t)n * sizeof(po_chunk));
+        hipError_t e = hipMemcpyAsync(p->d_chunks, p->h_chunks, (size_t)n * sizeof(po_chunk), hipMemcpyHostToDevice, stream);
+        if (e != hipSuccess) return fail_hip(e, "hipMemcpyAsync(chunk table)");
+        e = hipEventRecord(p->ev_chunks, stream);
+        if (e != hipSuccess) return fail_hip(e, "hipEventRecord(chunk table)");
+        p->ev_upload = p->ev_chunks;
+        p->upload_stream = stream;
+        p->ordered_stream = stream;
+    }
+    return PO_OK;
+}
+
+// Before a launch on `stream`: if the latest table upload went to another stream, make `stream` wait for it.
+hipError_t order_behind_upload(const po_plan* p, hipStream_t stream)
+{
+    if (p->ev_upload && stream != p->ordered_stream) {
+        hipError_t e = hipStreamWaitEvent(stream, p->ev_upload, 0);
+        if (e != hipSuccess) return e;
+        p->ordered_stream = stream;
+    }
+    p->last_launch_stream = stream;
+    p->launched = true;
+    return hipSuccess;
 }
 
 }  // namespace
@@ -283,6 +383,13 @@ po_launch resolve_launch(const po_plan* p, const po_launch& L, int kernel, int o
 extern "C" {
 
 const char* pipeoptim_last_error(void) { return g_err; }
+
+int pipeoptim_device_sync_count(int64_t* count)
+{
+    if (!count) return po_fail(PO_EINVAL, "count is NULL");
+    *count = g_device_syncs.load(std::memory_order_relaxed);
+    return PO_OK;
+}
 
 int pipeoptim_version_difference(int32_t D, int32_t rank, int32_t* s_out)
 {
@@ -361,7 +468,7 @@ int pipeoptim_auto_lds_bytes(int32_t kernel, int32_t opt, int64_t n_params, int3
     if (kernel != PO_KERNEL_KIND_FUSED && kernel != PO_KERNEL_KIND_PREDICT) return po_fail(PO_EINVAL, "kernel must be 0 (fused) or 1 (prediction)");
     if (opt < PO_SGDM || opt > PO_ADAGRAD) return po_fail(PO_EINVAL, "unknown optimizer %d", opt);
     if (n_params < 0) return po_fail(PO_EINVAL, "n_params < 0");
-    *out = auto_lds_bytes(kernel, opt, n_params);
+    *out = po_auto_lds_bytes(kernel, opt, n_params, false);
     return PO_OK;
 }
 
@@ -377,59 +484,45 @@ int pipeoptim_plan_create_mixed(po_plan** out, int64_t n_tensors, const int64_t*
                                 const void* const* g, int32_t grad_dtype, float* const* m, float* const* v,
                                 void* const* What, int32_t what_dtype, void* hip_stream)
 try {
-    (void)hip_stream;
     if (!out) return po_fail(PO_EINVAL, "out is NULL");
     *out = nullptr;
-    if (n_tensors < 0) return po_fail(PO_EINVAL, "n_tensors < 0");
-    if (n_tensors > 0 && (!numel || !W || !g || !What)) return po_fail(PO_EINVAL, "a required pointer array is NULL");
-    if (n_tensors > 0 && !m && !v) return po_fail(PO_EINVAL, "a plan needs at least one of m and v");
-    if (what_dtype != PO_WHAT_F32 && what_dtype != PO_WHAT_BF16) return po_fail(PO_EINVAL, "unknown what_dtype %d", what_dtype);
-    if (grad_dtype != PO_GRAD_F32 && grad_dtype != PO_GRAD_BF16) return po_fail(PO_EINVAL, "unknown grad_dtype %d", grad_dtype);
-    const uintptr_t what_mask = what_dtype == PO_WHAT_BF16 ? 1u : 3u;
-    const uintptr_t grad_mask = grad_dtype == PO_GRAD_BF16 ? 1u : 3u;
-    int64_t total = 0;
-    for (int64_t i = 0; i < n_tensors; ++i) {
-        if (numel[i] < 0) return po_fail(PO_EINVAL, "numel[%lld] < 0", (long long)i);
-        if (numel[i] == 0) continue;
-        if (!W[i] || !g[i] || !What[i] || (m && !m[i]) || (v && !v[i]))
-            return po_fail(PO_EINVAL, "tensor %lld has a NULL buffer", (long long)i);
-        if (((uintptr_t)W[i] | (m ? (uintptr_t)m[i] : 0) | (v ? (uintptr_t)v[i] : 0)) & 3u)
-            return po_fail(PO_EALIGN, "tensor %lld: fp32 buffer not 4-byte aligned", (long long)i);
-        if ((uintptr_t)g[i] & grad_mask) return po_fail(PO_EALIGN, "tensor %lld: g not aligned to its element", (long long)i);
-        if ((uintptr_t)What[i] & what_mask) return po_fail(PO_EALIGN, "tensor %lld: What not aligned to its element", (long long)i);
-        total += numel[i];
-    }
     // the holder frees the host side if anything below throws or fails before device memory exists
     std::unique_ptr<po_plan> holder(new (std::nothrow) po_plan);
     po_plan* p = holder.get();
     if (!p) return po_fail(PO_ENOMEM, "out of host memory");
+    int rc = po_describe_list(n_tensors, numel, W, g, grad_dtype, m, v, What, what_dtype, p->descs, &p->n_params,
+                              &p->n_unaligned);
+    if (rc != PO_OK) return rc;
     p->n_tensors = n_tensors;
-    p->n_params = total;
     p->what_dtype = what_dtype;
     p->grad_dtype = grad_dtype;
     p->has_v = (v != nullptr);
     p->has_m = (m != nullptr);
     p->numel.assign(numel, numel + n_tensors);
-    p->descs.resize((size_t)n_tensors);
-    for (int64_t i = 0; i < n_tensors; ++i) {
-        po_tensor_desc& d = p->descs[(size_t)i];
-        d.W = W[i]; d.g = g[i]; d.m = m ? m[i] : nullptr; d.v = v ? v[i] : nullptr; d.What = What[i];
-        d.numel = numel[i]; d.flags = 0; d.pad = 0;
-    }
-    int rc = check_disjoint(p);
-    if (rc != PO_OK) return rc;
-    refresh_flags(p);
-    p->launch = default_launch(total);
-    p->predict_launch = default_predict_launch(p->launch, total);
+    p->launch = po_default_launch();
+    p->predict_launch = p->launch;
 
+    const hipStream_t stream = static_cast<hipStream_t>(hip_stream);
     hipError_t e = hipGetDevice(&p->device);
     if (e != hipSuccess) return fail_hip(e, "hipGetDevice");
+    rc = PO_OK;
     if (n_tensors > 0) {
-        e = hipMalloc(reinterpret_cast<void**>(&p->d_descs), (size_t)n_tensors * sizeof(po_tensor_desc));
-        if (e != hipSuccess) return po_fail(PO_ENOMEM, "hipMalloc(descriptors): %s", hipGetErrorString(e));
+        const size_t bytes = (size_t)n_tensors * sizeof(po_tensor_desc);
+        e = hipMalloc(reinterpret_cast<void**>(&p->d_descs), bytes);
+        if (e != hipSuccess) rc = po_fail(PO_ENOMEM, "hipMalloc(descriptors): %s", hipGetErrorString(e));
+        for (int k = 0; k < 2 && rc == PO_OK; ++k) {
+            e = hipHostMalloc(reinterpret_cast<void**>(&p->h_descs[k]), bytes, hipHostMallocDefault);
+            if (e != hipSuccess) { p->h_descs[k] = nullptr; rc = po_fail(PO_ENOMEM, "hipHostMalloc(descriptor staging): %s", hipGetErrorString(e)); break; }
+            e = hipEventCreateWithFlags(&p->ev_descs[k], hipEventDisableTiming);
+            if (e != hipSuccess) { p->ev_descs[k] = nullptr; rc = fail_hip(e, "hipEventCreateWithFlags"); }
+        }
+        if (rc == PO_OK) {
+            e = hipEventCreateWithFlags(&p->ev_chunks, hipEventDisableTiming);
+            if (e != hipSuccess) { p->ev_chunks = nullptr; rc = fail_hip(e, "hipEventCreateWithFlags"); }
+        }
     }
-    rc = upload_descs(p);
-    if (rc == PO_OK) rc = upload_chunks(p);
+    if (rc == PO_OK) rc = upload_descs(p, stream);
+    if (rc == PO_OK) rc = upload_chunks(p, stream);
     if (rc == PO_OK) rc = check_grid(p->launch, (int64_t)p->chunks.size());
     if (rc != PO_OK) {
         char keep[sizeof g_err];
@@ -456,21 +549,21 @@ int pipeoptim_plan_destroy(po_plan* p)
 {
     if (!p) return PO_OK;
     int rc = PO_OK;
-    if (p->d_descs || p->d_chunks) {
-        hipError_t e = hipDeviceSynchronize();
-        if (e != hipSuccess) rc = fail_hip(e, "hipDeviceSynchronize");
-        if (p->d_descs) (void)hipFree(p->d_descs);
-        if (p->d_chunks) (void)hipFree(p->d_chunks);
+    if (p->d_descs || p->d_chunks || p->h_phase) rc = wait_for_plan_streams(p);
+    if (p->d_descs) (void)hipFree(p->d_descs);
+    if (p->d_chunks) (void)hipFree(p->d_chunks);
+    for (int k = 0; k < 2; ++k) {
+        if (p->h_descs[k]) (void)hipHostFree(p->h_descs[k]);
+        if (p->ev_descs[k]) (void)hipEventDestroy(p->ev_descs[k]);
     }
-    if (p->h_phase) {
-        if (!(p->d_descs || p->d_chunks)) (void)hipDeviceSynchronize();
-        (void)hipHostFree(p->h_phase);
-    }
+    if (p->h_chunks) (void)hipHostFree(p->h_chunks);
+    if (p->ev_chunks) (void)hipEventDestroy(p->ev_chunks);
+    if (p->h_phase) (void)hipHostFree(p->h_phase);
     delete p;
     return rc;
 }
 
-int pipeoptim_plan_set_pointers(po_plan* p, int32_t which, void* const* ptrs)
+int pipeoptim_plan_set_pointers(po_plan* p, int32_t which, void* const* ptrs, void* hip_stream)
 try {
     if (!p) return po_fail(PO_EINVAL, "plan is NULL");
     if (which < 0 || which > 4) return po_fail(PO_EINVAL, "which must be 0..4");
@@ -483,7 +576,11 @@ try {
         if (!ptrs[i]) return po_fail(PO_EINVAL, "tensor %lld: NULL pointer", (long long)i);
         if ((uintptr_t)ptrs[i] & mask) return po_fail(PO_EALIGN, "tensor %lld: pointer not aligned to its element", (long long)i);
     }
+    int rc = check_device(p);
+    if (rc != PO_OK) return rc;
+    // everything the call changes, so that any failure below leaves the plan exactly as it was
     const std::vector<po_tensor_desc> saved = p->descs;
+    const int64_t saved_unaligned = p->n_unaligned, saved_local = p->n_local_params;
     for (int64_t i = 0; i < p->n_tensors; ++i) {
         po_tensor_desc& d = p->descs[(size_t)i];
         switch (which) {
@@ -494,12 +591,18 @@ try {
         case 4: d.What = ptrs[i]; break;
         }
     }
-    const int rc_overlap = check_disjoint(p);
-    if (rc_overlap != PO_OK) { p->descs = saved; return rc_overlap; }
-    refresh_flags(p);
-    hipError_t e = hipDeviceSynchronize();   // a launch may still read the old descriptors
-    if (e != hipSuccess) return fail_hip(e, "hipDeviceSynchronize");
-    return upload_descs(p);
+    rc = check_disjoint(p->descs, p->grad_dtype, p->what_dtype);
+    if (rc == PO_OK) {
+        p->n_unaligned = refresh_flags(p->descs);
+        p->n_local_params = 0;
+        rc = upload_descs(p, static_cast<hipStream_t>(hip_stream));
+    }
+    if (rc != PO_OK) {      // the device table was not touched: upload_descs fails before or at the enqueue of its copy
+        p->descs = saved;
+        p->n_unaligned = saved_unaligned;
+        p->n_local_params = saved_local;
+    }
+    return rc;
 }
 catch (const std::bad_alloc&) { return po_fail(PO_ENOMEM, "pipeoptim_plan_set_pointers: out of host memory"); }
 catch (...) { return po_fail(PO_EINVAL, "pipeoptim_plan_set_pointers: unexpected exception"); }
@@ -525,18 +628,16 @@ try {
     p->launch = *L;
     p->predict_launch.chunk_elems = L->chunk_elems;
     {   // the two kernels share the chunk table: keep the prediction kernel's tile a power-of-two divisor of it
-        const int64_t ptile = (int64_t)p->predict_launch.block * 4 * p->predict_launch.unroll;
+        const int64_t ptile = (int64_t)p->predict_launch.block * 4;
         const int64_t ratio = L->chunk_elems / ptile;
-        if (L->chunk_elems % ptile != 0 || (ratio & (ratio - 1)) != 0) {
-            p->predict_launch.block = L->block;
-            p->predict_launch.unroll = L->unroll;
-        }
+        if (L->chunk_elems % ptile != 0 || (ratio & (ratio - 1)) != 0) p->predict_launch.block = L->block;
     }
-    if (rechunk) {
-        hipError_t e = hipDeviceSynchronize();   // a launch may still read the old table
-        if (e != hipSuccess) { p->launch = old; p->predict_launch = old_predict; return fail_hip(e, "hipDeviceSynchronize"); }
-        rc = upload_chunks(p);
-        if (rc != PO_OK) { p->launch = old; p->predict_launch = old_predict; (void)upload_chunks(p); return rc; }
+    if (rechunk && p->n_tensors > 0) {
+        rc = check_device(p);
+        if (rc == PO_OK) rc = wait_for_plan_streams(p);   // a launch may still read the old table; the old upload is done
+        if (rc != PO_OK) { p->launch = old; p->predict_launch = old_predict; return rc; }
+        rc = upload_chunks(p, p->upload_stream);
+        if (rc != PO_OK) { p->launch = old; p->predict_launch = old_predict; (void)upload_chunks(p, p->upload_stream); return rc; }
     }
     return PO_OK;
 }
@@ -563,15 +664,15 @@ int pipeoptim_plan_set_predict_launch(po_plan* p, const po_launch* L_in)
     rc = check_grid(L, (int64_t)p->chunks.size());
     if (rc != PO_OK) return rc;
     p->predict_launch = L;
-    p->predict_launch_set = true;
     return PO_OK;
 }
 
 int pipeoptim_plan_localize(po_plan* p, const po_arena* arena, void* hip_stream, int64_t* n_local_params)
-{
+try {
     if (!p) return po_fail(PO_EINVAL, "plan is NULL");
     int rc_dev = check_device(p);
     if (rc_dev != PO_OK) return rc_dev;
+    const hipStream_t stream = static_cast<hipStream_t>(hip_stream);
     if (arena && !p->h_phase) {
         hipError_t eh = hipHostMalloc(reinterpret_cast<void**>(&p->h_phase), 64, hipHostMallocDefault);
         if (eh != hipSuccess) { p->h_phase = nullptr; return po_fail(PO_ENOMEM, "hipHostMalloc(phase word): %s", hipGetErrorString(eh)); }
@@ -600,21 +701,20 @@ int pipeoptim_plan_localize(po_plan* p, const po_arena* arena, void* hip_stream,
         n_local += d.numel;
     }
     hipError_t e = hipSuccess;
-    if (arena && n_local > 0) e = po_launch_phase_probe(p->h_phase, static_cast<hipStream_t>(hip_stream));   // where this stream's launches start
-    if (e == hipSuccess) e = hipDeviceSynchronize();   // a launch may still read the old descriptors; the probe has reported
-    if (e != hipSuccess) { p->descs = saved; return fail_hip(e, "phase probe / hipDeviceSynchronize"); }
-    const int rc = upload_descs(p);
+    if (arena && n_local > 0) {
+        // where this stream's launches start: a tiny kernel reports it, and the answer is needed before the next launch
+        e = po_launch_phase_probe(p->h_phase, stream);
+        if (e == hipSuccess) e = hipStreamSynchronize(stream);
+    }
+    if (e != hipSuccess) { p->descs = saved; return fail_hip(e, "phase probe"); }
+    const int rc = upload_descs(p, stream);
     if (rc != PO_OK) { p->descs = saved; return rc; }
     p->n_local_params = n_local;
     if (n_local_params) *n_local_params = n_local;
-    if (!p->predict_launch_set) {
-        const po_launch d = default_predict_launch(p->launch, p->n_params, n_local * 2 >= p->n_params && n_local > 0);
-        const int64_t tile = (int64_t)d.block * 4 * d.unroll, ratio = p->launch.chunk_elems / tile;
-        if (p->launch.chunk_elems % tile == 0 && (ratio & (ratio - 1)) == 0 && check_grid(d, (int64_t)p->chunks.size()) == PO_OK)
-            p->predict_launch = d;
-    }
     return PO_OK;
 }
+catch (const std::bad_alloc&) { return po_fail(PO_ENOMEM, "pipeoptim_plan_localize: out of host memory"); }
+catch (...) { return po_fail(PO_EINVAL, "pipeoptim_plan_localize: unexpected exception"); }
 
 int pipeoptim_plan_local_params(const po_plan* p, int64_t* n_local_params)
 {
@@ -676,12 +776,14 @@ int pipeoptim_step_predict(const po_plan* p, const po_hyper* h, int64_t t, int32
     if (p->chunks.empty()) return PO_OK;
     rc = check_device(p);
     if (rc != PO_OK) return rc;
+    const hipStream_t stream = static_cast<hipStream_t>(hip_stream);
     const po_launch L = resolve_launch(p, p->launch, PO_KERNEL_KIND_FUSED, h->opt);
     const bool local = p->n_local_params > 0 && p->h_phase;
     const uint32_t phase = local ? (*static_cast<volatile uint32_t*>(p->h_phase) & 7u) : 0u;
-    hipError_t e = po_launch_step_predict(h->opt, p->what_dtype, p->grad_dtype, L, p->d_descs, p->d_chunks,
-                                          (uint32_t)p->chunks.size(), c, static_cast<hipStream_t>(hip_stream), phase,
-                                          local ? p->h_phase : nullptr);
+    hipError_t e = order_behind_upload(p, stream);
+    if (e == hipSuccess)
+        e = po_launch_step_predict(h->opt, p->what_dtype, p->grad_dtype, L, p->d_descs, p->d_chunks,
+                                   (uint32_t)p->chunks.size(), c, stream, phase, local ? p->h_phase : nullptr);
     if (e != hipSuccess) return fail_hip(e, "launch of the fused step+predict kernel");
     return PO_OK;
 }
@@ -699,12 +801,14 @@ int pipeoptim_predict(const po_plan* p, const po_hyper* h, int64_t t, int32_t s,
     if (p->chunks.empty()) return PO_OK;
     rc = check_device(p);
     if (rc != PO_OK) return rc;
+    const hipStream_t stream = static_cast<hipStream_t>(hip_stream);
     const po_launch L = resolve_launch(p, p->predict_launch, PO_KERNEL_KIND_PREDICT, h->opt);
     const bool local = p->n_local_params > 0 && p->h_phase;
     const uint32_t phase = local ? (*static_cast<volatile uint32_t*>(p->h_phase) & 7u) : 0u;
-    hipError_t e = po_launch_predict(h->opt, p->what_dtype, L, p->d_descs, p->d_chunks,
-                                     (uint32_t)p->chunks.size(), c, static_cast<hipStream_t>(hip_stream), phase,
-                                     local ? p->h_phase : nullptr);
+    hipError_t e = order_behind_upload(p, stream);
+    if (e == hipSuccess)
+        e = po_launch_predict(h->opt, p->what_dtype, L, p->d_descs, p->d_chunks, (uint32_t)p->chunks.size(), c,
+                              stream, phase, local ? p->h_phase : nullptr);
     if (e != hipSuccess) return fail_hip(e, "launch of the prediction kernel");
     return PO_OK;
 }

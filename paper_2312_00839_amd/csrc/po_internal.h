@@ -5,6 +5,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <vector>
+
 #include "pipeoptim.h"
 
 // Per-tensor descriptor, resident in device memory for the life of a plan.
@@ -72,6 +74,20 @@ constexpr uint32_t PO_LOCAL_GROUP_TILES = 16;
 
 // Stores a printf-style description of a failure in the calling thread's error string and returns `code`.
 int po_fail(int code, const char* fmt, ...) __attribute__((format(printf, 2, 3)));
+
+// hipDeviceSynchronize, counted (pipeoptim_device_sync_count): the library waits for the whole device only in
+// arena set-up calls and as a fallback when a stream that a plan remembers no longer exists.
+hipError_t po_device_sync();
+
+// Validates a ragged tensor list (NULL and alignment checks, pairwise disjoint buffers) and fills `descs` with
+// one descriptor per tensor, flags set.  Host only.  *n_params / *n_unaligned (may be NULL) receive the totals.
+int po_describe_list(int64_t n_tensors, const int64_t* numel, float* const* W, const void* const* g, int32_t grad_dtype,
+                     float* const* m, float* const* v, void* const* What, int32_t what_dtype,
+                     std::vector<po_tensor_desc>& descs, int64_t* n_params, int64_t* n_unaligned);
+
+// The occupancy cap PO_LDS_AUTO stands for, and the default launch shape of both kernels.
+int32_t po_auto_lds_bytes(int kernel, int opt, int64_t n_params, bool local);
+po_launch po_default_launch();
 
 // Near-memory arena internals the plan needs (near_arena.hip).
 struct po_arena;

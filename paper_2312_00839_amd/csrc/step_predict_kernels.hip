@@ -17,7 +17,7 @@
 //
 // Work decomposition.  The host's chunk table lists (tensor, chunk) pairs at a
 // coarse granularity (chunk_elems); the grid has one small workgroup per TILE
-// of block*4*UNROLL elements, workgroup -> (chunk, tile in chunk) by shift and
+// of block*4 elements, workgroup -> (chunk, tile in chunk) by shift and
 // mask, and workgroups whose tile starts past the end of the tensor exit at
 // once.  A workgroup reads the chunk entry and the tensor descriptor through
 // the scalar path, builds one buffer resource per stream that covers exactly
@@ -40,8 +40,7 @@ namespace {
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
-// Cache policy bits of gfx940-family memory instructions as the buffer builtins take them
-// (sc0 = 1 is not used by any shipped policy).
+// Cache policy bits of gfx940-family memory instructions as the buffer builtins take them.
 constexpr int CP_NT = 2, CP_SC1 = 16;
 
 constexpr int PO_KERNEL_FUSED = PO_KERNEL_KIND_FUSED, PO_KERNEL_PREDICT = PO_KERNEL_KIND_PREDICT;
@@ -54,15 +53,10 @@ template <int OPT> struct Streams {
     static constexpr bool V = OPT == K_ADAM || OPT == K_ADAMW || OPT == K_RMS;
 };
 
-// launch.cache_policy -> bits for: LG loads of g (read once), LS loads of W, m, v (rewritten right after),
-// SS stores of W', m', v', SH stores of What (write-only).  Mixed per-stream settings (plain loads for the
-// rewritten streams, nt-only or sc1-only on one of the store groups) all measured slower than policy 4.
-template <int POL> struct Policy;
-template <> struct Policy<0> { static constexpr int LG = 0,     LS = 0,     SS = 0,              SH = 0; };
-template <> struct Policy<1> { static constexpr int LG = CP_NT, LS = CP_NT, SS = 0,              SH = 0; };
-template <> struct Policy<2> { static constexpr int LG = 0,     LS = 0,     SS = CP_NT,          SH = CP_NT; };
-template <> struct Policy<3> { static constexpr int LG = CP_NT, LS = CP_NT, SS = CP_NT,          SH = CP_NT; };
-template <> struct Policy<4> { static constexpr int LG = CP_NT, LS = CP_NT, SS = CP_NT | CP_SC1, SH = CP_NT | CP_SC1; };
+// Cache policy of every access (measured on MI355X against plain accesses and every mix of the two, per stream
+// group): loads streaming (nt), whether the line is read once (g) or rewritten right after (W, m, v); stores
+// streaming and written through (nt + sc1), i.e. sent on instead of left to age in L2.
+constexpr int LD_POLICY = CP_NT, ST_POLICY = CP_NT | CP_SC1;
 
 // Raw buffer resource (stride 0) over [p, p + bytes): accesses past `bytes` are dropped by the hardware.
 __device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void* p, uint32_t bytes)
@@ -153,11 +147,11 @@ struct alignas(32) KArgs {
     int64_t chunk_elems;
     uint32_t n_slots;        // chunks * tiles per chunk
     uint32_t tiles_log2;     // log2(tiles per chunk)
-    uint32_t xcd_stride;     // 0: slot = workgroup id; else grid/8: slot = (id & 7) * xcd_stride + (id >> 3)
-    uint32_t tile;           // block * 4 * unroll
+    uint32_t reserved;
+    uint32_t tile;           // block * 4
     po_coeffs c;             // 52 bytes
     uint32_t local_ok;       // 1: this launch shape supports the near-memory tile order (1 KiB tiles, whole groups
-                             //    of 16 tiles per chunk, no XCD remap)
+                             //    of 16 tiles per chunk)
     uint32_t* phase_out;     // host-visible word that workgroup 0 writes its XCC id to (or nullptr)
     uint32_t phase;          // XCC on which this queue's launches start, as last observed: workgroup id b runs
                              // on XCC (b + phase) mod 8
@@ -178,10 +172,8 @@ __device__ __forceinline__ KArgs load_kargs()
     return u.k;
 }
 
-// Which tile does this workgroup own?  slot = chunk_index * tiles_per_chunk + tile_in_chunk.  With
-// xcd_remap the grid (a multiple of 8) is cut into 8 equal ranges and workgroup id b (XCDs take
-// workgroups round-robin) works in range b mod 8.  Returns false for padding slots and for tiles that
-// start past the end of the tensor's last chunk.  The 64-byte descriptor comes in one scalar load.
+// Which tile does this workgroup own?  slot = chunk_index * tiles_per_chunk + tile_in_chunk.  Returns false
+// for tiles that start past the end of the tensor's last chunk.  The 64-byte descriptor comes in one scalar load.
 struct Tile {
     po_tensor_desc d;
     int64_t off;        // first element of the tile within the tensor
@@ -192,8 +184,7 @@ struct Tile {
 __device__ __forceinline__ bool locate_tile(const KArgs& a, Tile& t)
 {
     uint32_t slot = blockIdx.x;
-    if (a.xcd_stride) slot = (blockIdx.x & 7u) * a.xcd_stride + (blockIdx.x >> 3);
-    else if (a.local_ok) {
+    if (a.local_ok) {
         // rotate the ids (n_slots is a multiple of 16 here) so that slot p runs on XCC p mod 8 whatever XCC the
         // queue starts its launches on; the rotation is the same for every workgroup of the launch, so each
         // slot is still taken exactly once even if `phase` is out of date (then only the locality suffers)
@@ -227,11 +218,10 @@ __device__ __forceinline__ void report_phase(const KArgs& a)
 __device__ __forceinline__ float bf16_lo(uint32_t pair) { return as_f(pair << 16); }
 __device__ __forceinline__ float bf16_hi(uint32_t pair) { return as_f(pair & 0xFFFF0000u); }
 
-// GB16: gradients are bf16 (8 bytes per lane per group instead of 16).
-template <int OPT, bool BF16, bool GB16, int UNROLL, int POL>
+// GB16: gradients are bf16 (8 bytes per lane instead of 16).
+template <int OPT, bool BF16, bool GB16>
 __global__ __launch_bounds__(256) void step_predict_kernel(KArgs)
 {
-    constexpr int LG = Policy<POL>::LG, LS = Policy<POL>::LS, SS = Policy<POL>::SS, SH = Policy<POL>::SH;
     constexpr bool HAS_M = Streams<OPT>::M, HAS_V = Streams<OPT>::V;
 
     const KArgs a = load_kargs();
@@ -251,72 +241,64 @@ __global__ __launch_bounds__(256) void step_predict_kernel(KArgs)
     const __amdgpu_buffer_rsrc_t rv = make_rsrc((HAS_V ? d->v : d->W) + off, len * 4u);
     const __amdgpu_buffer_rsrc_t rh = BF16 ? make_rsrc(static_cast<uint16_t*>(d->What) + off, len * 2u)
                                            : make_rsrc(static_cast<float*>(d->What) + off, len * 4u);
-    const uint32_t tid = threadIdx.x, nthr = a.tile / (4u * UNROLL);
+    const uint32_t tid = threadIdx.x, nthr = a.tile / 4u;
 
     if (t.full) {
-        // full tile, aligned: every lane moves UNROLL groups of 4 consecutive elements per stream
-        u32x4 W[UNROLL], g[UNROLL], m[UNROLL], v[UNROLL];
-#pragma unroll
-        for (int u = 0; u < UNROLL; ++u) {
-            const uint32_t b = (u * nthr + tid) * 16u;
-            W[u] = __builtin_amdgcn_raw_buffer_load_b128(rW, b, 0, LS);
-            if constexpr (GB16) {
-                const u32x2 p = __builtin_amdgcn_raw_buffer_load_b64(rg, b >> 1, 0, LG);
-                g[u] = u32x4{as_u(bf16_lo(p[0])), as_u(bf16_hi(p[0])), as_u(bf16_lo(p[1])), as_u(bf16_hi(p[1]))};
-            } else {
-                g[u] = __builtin_amdgcn_raw_buffer_load_b128(rg, b, 0, LG);
-            }
-            if constexpr (HAS_M) m[u] = __builtin_amdgcn_raw_buffer_load_b128(rm, b, 0, LS);
-            if constexpr (HAS_V) v[u] = __builtin_amdgcn_raw_buffer_load_b128(rv, b, 0, LS);
+        // full tile, aligned: every lane moves 4 consecutive elements per stream; all loads go out before any use
+        const uint32_t b = tid * 16u;
+        u32x4 W, g, m, v;
+        W = __builtin_amdgcn_raw_buffer_load_b128(rW, b, 0, LD_POLICY);
+        if constexpr (GB16) {
+            const u32x2 p = __builtin_amdgcn_raw_buffer_load_b64(rg, b >> 1, 0, LD_POLICY);
+            g = u32x4{as_u(bf16_lo(p[0])), as_u(bf16_hi(p[0])), as_u(bf16_lo(p[1])), as_u(bf16_hi(p[1]))};
+        } else {
+            g = __builtin_amdgcn_raw_buffer_load_b128(rg, b, 0, LD_POLICY);
         }
+        if constexpr (HAS_M) m = __builtin_amdgcn_raw_buffer_load_b128(rm, b, 0, LD_POLICY);
+        if constexpr (HAS_V) v = __builtin_amdgcn_raw_buffer_load_b128(rv, b, 0, LD_POLICY);
+        u32x4 Wn, Wh;
 #pragma unroll
-        for (int u = 0; u < UNROLL; ++u) {
-            const uint32_t b = (u * nthr + tid) * 16u;
-            u32x4 Wn, Wh;
-#pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                float mm = HAS_M ? as_f(m[u][e]) : 0.f, vv = HAS_V ? as_f(v[u][e]) : 0.f, wn, wh;
-                update_element<OPT>(c, as_f(W[u][e]), as_f(g[u][e]), mm, vv, wn, wh);
-                if constexpr (HAS_M) m[u][e] = as_u(mm);
-                if constexpr (HAS_V) v[u][e] = as_u(vv);
-                Wn[e] = as_u(wn);
-                Wh[e] = as_u(wh);
-            }
-            __builtin_amdgcn_raw_buffer_store_b128(Wn, rW, b, 0, SS);
-            if constexpr (HAS_M) __builtin_amdgcn_raw_buffer_store_b128(m[u], rm, b, 0, SS);
-            if constexpr (HAS_V) __builtin_amdgcn_raw_buffer_store_b128(v[u], rv, b, 0, SS);
-            if constexpr (BF16) {
-                u32x2 p = {pack_bf16x2(as_f(Wh[0]), as_f(Wh[1])), pack_bf16x2(as_f(Wh[2]), as_f(Wh[3]))};
-                __builtin_amdgcn_raw_buffer_store_b64(p, rh, b >> 1, 0, SH);
-            } else {
-                __builtin_amdgcn_raw_buffer_store_b128(Wh, rh, b, 0, SH);
-            }
+        for (int e = 0; e < 4; ++e) {
+            float mm = HAS_M ? as_f(m[e]) : 0.f, vv = HAS_V ? as_f(v[e]) : 0.f, wn, wh;
+            update_element<OPT>(c, as_f(W[e]), as_f(g[e]), mm, vv, wn, wh);
+            if constexpr (HAS_M) m[e] = as_u(mm);
+            if constexpr (HAS_V) v[e] = as_u(vv);
+            Wn[e] = as_u(wn);
+            Wh[e] = as_u(wh);
+        }
+        __builtin_amdgcn_raw_buffer_store_b128(Wn, rW, b, 0, ST_POLICY);
+        if constexpr (HAS_M) __builtin_amdgcn_raw_buffer_store_b128(m, rm, b, 0, ST_POLICY);
+        if constexpr (HAS_V) __builtin_amdgcn_raw_buffer_store_b128(v, rv, b, 0, ST_POLICY);
+        if constexpr (BF16) {
+            u32x2 p = {pack_bf16x2(as_f(Wh[0]), as_f(Wh[1])), pack_bf16x2(as_f(Wh[2]), as_f(Wh[3]))};
+            __builtin_amdgcn_raw_buffer_store_b64(p, rh, b >> 1, 0, ST_POLICY);
+        } else {
+            __builtin_amdgcn_raw_buffer_store_b128(Wh, rh, b, 0, ST_POLICY);
         }
     } else {
         // ragged last tile of a tensor, or a tensor without 16-byte alignment: one element per lane per step
         for (uint32_t i = tid; i < len; i += nthr) {
             const uint32_t b = i * 4u;
-            float W = as_f(__builtin_amdgcn_raw_buffer_load_b32(rW, b, 0, LS));
-            float g = GB16 ? as_f((uint32_t)__builtin_amdgcn_raw_buffer_load_b16(rg, i * 2u, 0, LG) << 16)
-                           : as_f(__builtin_amdgcn_raw_buffer_load_b32(rg, b, 0, LG));
-            float mm = HAS_M ? as_f(__builtin_amdgcn_raw_buffer_load_b32(rm, b, 0, LS)) : 0.f;
-            float vv = HAS_V ? as_f(__builtin_amdgcn_raw_buffer_load_b32(rv, b, 0, LS)) : 0.f;
+            float W = as_f(__builtin_amdgcn_raw_buffer_load_b32(rW, b, 0, LD_POLICY));
+            float g = GB16 ? as_f((uint32_t)__builtin_amdgcn_raw_buffer_load_b16(rg, i * 2u, 0, LD_POLICY) << 16)
+                           : as_f(__builtin_amdgcn_raw_buffer_load_b32(rg, b, 0, LD_POLICY));
+            float mm = HAS_M ? as_f(__builtin_amdgcn_raw_buffer_load_b32(rm, b, 0, LD_POLICY)) : 0.f;
+            float vv = HAS_V ? as_f(__builtin_amdgcn_raw_buffer_load_b32(rv, b, 0, LD_POLICY)) : 0.f;
             float wn, wh;
             update_element<OPT>(c, W, g, mm, vv, wn, wh);
-            __builtin_amdgcn_raw_buffer_store_b32(as_u(wn), rW, b, 0, SS);
-            if constexpr (HAS_M) __builtin_amdgcn_raw_buffer_store_b32(as_u(mm), rm, b, 0, SS);
-            if constexpr (HAS_V) __builtin_amdgcn_raw_buffer_store_b32(as_u(vv), rv, b, 0, SS);
-            if constexpr (BF16) __builtin_amdgcn_raw_buffer_store_b16(to_bf16(wh), rh, i * 2u, 0, SH);
-            else __builtin_amdgcn_raw_buffer_store_b32(as_u(wh), rh, b, 0, SH);
+            __builtin_amdgcn_raw_buffer_store_b32(as_u(wn), rW, b, 0, ST_POLICY);
+            if constexpr (HAS_M) __builtin_amdgcn_raw_buffer_store_b32(as_u(mm), rm, b, 0, ST_POLICY);
+            if constexpr (HAS_V) __builtin_amdgcn_raw_buffer_store_b32(as_u(vv), rv, b, 0, ST_POLICY);
+            if constexpr (BF16) __builtin_amdgcn_raw_buffer_store_b16(to_bf16(wh), rh, i * 2u, 0, ST_POLICY);
+            else __builtin_amdgcn_raw_buffer_store_b32(as_u(wh), rh, b, 0, ST_POLICY);
         }
     }
 }
 
 // What = W - s_lr*dW from the cached m, v: reads W, m (, v) once, writes What.  Same decomposition as above.
-template <int OPT, bool BF16, int UNROLL, int POL>
+template <int OPT, bool BF16>
 __global__ __launch_bounds__(256) void predict_kernel(KArgs)
 {
-    constexpr int LD = Policy<POL>::LG, SH = Policy<POL>::SH;      // every input is read once here
     constexpr bool ADAM = OPT != PO_SGDM;
 
     const KArgs a = load_kargs();
@@ -332,41 +314,34 @@ __global__ __launch_bounds__(256) void predict_kernel(KArgs)
     const __amdgpu_buffer_rsrc_t rv = make_rsrc(ADAM ? d->v + off : d->m + off, len * 4u);
     const __amdgpu_buffer_rsrc_t rh = BF16 ? make_rsrc(static_cast<uint16_t*>(d->What) + off, len * 2u)
                                            : make_rsrc(static_cast<float*>(d->What) + off, len * 4u);
-    const uint32_t tid = threadIdx.x, nthr = a.tile / (4u * UNROLL);
+    const uint32_t tid = threadIdx.x, nthr = a.tile / 4u;
 
     if (t.full) {
-        u32x4 W[UNROLL], m[UNROLL], v[UNROLL];
+        const uint32_t b = tid * 16u;
+        u32x4 W, m, v;
+        W = __builtin_amdgcn_raw_buffer_load_b128(rW, b, 0, LD_POLICY);
+        m = __builtin_amdgcn_raw_buffer_load_b128(rm, b, 0, LD_POLICY);
+        if constexpr (ADAM) v = __builtin_amdgcn_raw_buffer_load_b128(rv, b, 0, LD_POLICY);
+        float wh[4];
 #pragma unroll
-        for (int u = 0; u < UNROLL; ++u) {
-            const uint32_t b = (u * nthr + tid) * 16u;
-            W[u] = __builtin_amdgcn_raw_buffer_load_b128(rW, b, 0, LD);
-            m[u] = __builtin_amdgcn_raw_buffer_load_b128(rm, b, 0, LD);
-            if constexpr (ADAM) v[u] = __builtin_amdgcn_raw_buffer_load_b128(rv, b, 0, LD);
-        }
-#pragma unroll
-        for (int u = 0; u < UNROLL; ++u) {
-            const uint32_t b = (u * nthr + tid) * 16u;
-            float wh[4];
-#pragma unroll
-            for (int e = 0; e < 4; ++e)
-                wh[e] = predict_element<OPT>(c, as_f(W[u][e]), as_f(m[u][e]), ADAM ? as_f(v[u][e]) : 0.f);
-            if constexpr (BF16) {
-                u32x2 p = {pack_bf16x2(wh[0], wh[1]), pack_bf16x2(wh[2], wh[3])};
-                __builtin_amdgcn_raw_buffer_store_b64(p, rh, b >> 1, 0, SH);
-            } else {
-                u32x4 p = {as_u(wh[0]), as_u(wh[1]), as_u(wh[2]), as_u(wh[3])};
-                __builtin_amdgcn_raw_buffer_store_b128(p, rh, b, 0, SH);
-            }
+        for (int e = 0; e < 4; ++e)
+            wh[e] = predict_element<OPT>(c, as_f(W[e]), as_f(m[e]), ADAM ? as_f(v[e]) : 0.f);
+        if constexpr (BF16) {
+            u32x2 p = {pack_bf16x2(wh[0], wh[1]), pack_bf16x2(wh[2], wh[3])};
+            __builtin_amdgcn_raw_buffer_store_b64(p, rh, b >> 1, 0, ST_POLICY);
+        } else {
+            u32x4 p = {as_u(wh[0]), as_u(wh[1]), as_u(wh[2]), as_u(wh[3])};
+            __builtin_amdgcn_raw_buffer_store_b128(p, rh, b, 0, ST_POLICY);
         }
     } else {
         for (uint32_t i = tid; i < len; i += nthr) {
             const uint32_t b = i * 4u;
-            float W = as_f(__builtin_amdgcn_raw_buffer_load_b32(rW, b, 0, LD));
-            float mm = as_f(__builtin_amdgcn_raw_buffer_load_b32(rm, b, 0, LD));
-            float vv = ADAM ? as_f(__builtin_amdgcn_raw_buffer_load_b32(rv, b, 0, LD)) : 0.f;
+            float W = as_f(__builtin_amdgcn_raw_buffer_load_b32(rW, b, 0, LD_POLICY));
+            float mm = as_f(__builtin_amdgcn_raw_buffer_load_b32(rm, b, 0, LD_POLICY));
+            float vv = ADAM ? as_f(__builtin_amdgcn_raw_buffer_load_b32(rv, b, 0, LD_POLICY)) : 0.f;
             float wh = predict_element<OPT>(c, W, mm, vv);
-            if constexpr (BF16) __builtin_amdgcn_raw_buffer_store_b16(to_bf16(wh), rh, i * 2u, 0, SH);
-            else __builtin_amdgcn_raw_buffer_store_b32(as_u(wh), rh, b, 0, SH);
+            if constexpr (BF16) __builtin_amdgcn_raw_buffer_store_b16(to_bf16(wh), rh, i * 2u, 0, ST_POLICY);
+            else __builtin_amdgcn_raw_buffer_store_b32(as_u(wh), rh, b, 0, ST_POLICY);
         }
     }
 }
@@ -374,63 +349,34 @@ __global__ __launch_bounds__(256) void predict_kernel(KArgs)
 // Where a launch starts its round over the XCCs: last observed value, and where workgroup 0 reports the next.
 struct Phase { uint32_t value; uint32_t* report; };
 
-template <int KIND, int OPT, bool BF16, bool GB16, int UNROLL, int POL>
+template <int KIND, int OPT, bool BF16, bool GB16>
 hipError_t launch_one(const po_launch& L, const po_tensor_desc* descs, const po_chunk* chunks, uint32_t n_chunks,
                       const po_coeffs& c, hipStream_t stream, Phase ph)
 {
-    const uint32_t tile = (uint32_t)L.block * 4u * UNROLL;
+    const uint32_t tile = (uint32_t)L.block * 4u;
     const uint32_t tiles_per_chunk = (uint32_t)(L.chunk_elems / tile);      // a power of two (validated by the host)
     uint32_t tiles_log2 = 0;
     while ((1u << tiles_log2) < tiles_per_chunk) ++tiles_log2;
-    const uint64_t n_slots = (uint64_t)n_chunks << tiles_log2;
-    const uint64_t grid = L.xcd_remap ? ((n_slots + 7u) / 8u) * 8u : n_slots;
+    const uint64_t grid = (uint64_t)n_chunks << tiles_log2;
     if (grid > 0x7FFFFFFFull) return hipErrorInvalidConfiguration;
     if (L.lds_bytes < 0) return hipErrorInvalidValue;      // the host resolves PO_LDS_AUTO before it gets here
     KArgs a{};
     a.descs = descs;
     a.chunks = chunks;
     a.chunk_elems = L.chunk_elems;
-    a.n_slots = (uint32_t)n_slots;
+    a.n_slots = (uint32_t)grid;
     a.tiles_log2 = tiles_log2;
-    a.xcd_stride = L.xcd_remap ? (uint32_t)(grid >> 3) : 0u;
     a.tile = tile;
     a.c = c;
-    a.local_ok = (!L.xcd_remap && tile == PO_LOCAL_TILE_ELEMS && tiles_per_chunk >= PO_LOCAL_GROUP_TILES) ? 1u : 0u;
+    a.local_ok = (tile == PO_LOCAL_TILE_ELEMS && tiles_per_chunk >= PO_LOCAL_GROUP_TILES) ? 1u : 0u;
     a.phase = a.local_ok ? (ph.value & 7u) : 0u;
     a.phase_out = a.local_ok ? ph.report : nullptr;
     if constexpr (KIND == PO_KERNEL_PREDICT)
-        hipLaunchKernelGGL((predict_kernel<OPT, BF16, UNROLL, POL>), dim3((uint32_t)grid), dim3(L.block),
-                           (size_t)L.lds_bytes, stream, a);
+        hipLaunchKernelGGL((predict_kernel<OPT, BF16>), dim3((uint32_t)grid), dim3(L.block), (size_t)L.lds_bytes, stream, a);
     else
-        hipLaunchKernelGGL((step_predict_kernel<OPT, BF16, GB16, UNROLL, POL>), dim3((uint32_t)grid), dim3(L.block),
+        hipLaunchKernelGGL((step_predict_kernel<OPT, BF16, GB16>), dim3((uint32_t)grid), dim3(L.block),
                            (size_t)L.lds_bytes, stream, a);
     return hipGetLastError();
-}
-
-template <int KIND, int OPT, bool BF16, bool GB16, int UNROLL>
-hipError_t dispatch_policy(const po_launch& L, const po_tensor_desc* d, const po_chunk* ch, uint32_t n,
-                           const po_coeffs& c, hipStream_t s, Phase ph)
-{
-    switch (L.cache_policy) {
-    case 0: return launch_one<KIND, OPT, BF16, GB16, UNROLL, 0>(L, d, ch, n, c, s, ph);
-    case 1: return launch_one<KIND, OPT, BF16, GB16, UNROLL, 1>(L, d, ch, n, c, s, ph);
-    case 2: return launch_one<KIND, OPT, BF16, GB16, UNROLL, 2>(L, d, ch, n, c, s, ph);
-    case 3: return launch_one<KIND, OPT, BF16, GB16, UNROLL, 3>(L, d, ch, n, c, s, ph);
-    case 4: return launch_one<KIND, OPT, BF16, GB16, UNROLL, 4>(L, d, ch, n, c, s, ph);
-    }
-    return hipErrorInvalidValue;
-}
-
-template <int KIND, int OPT, bool BF16, bool GB16>
-hipError_t dispatch_unroll(const po_launch& L, const po_tensor_desc* d, const po_chunk* ch, uint32_t n,
-                           const po_coeffs& c, hipStream_t s, Phase ph)
-{
-    switch (L.unroll) {
-    case 1: return dispatch_policy<KIND, OPT, BF16, GB16, 1>(L, d, ch, n, c, s, ph);
-    case 2: return dispatch_policy<KIND, OPT, BF16, GB16, 2>(L, d, ch, n, c, s, ph);
-    case 4: return dispatch_policy<KIND, OPT, BF16, GB16, 4>(L, d, ch, n, c, s, ph);
-    }
-    return hipErrorInvalidValue;
 }
 
 template <int KIND, int OPT>
@@ -440,11 +386,11 @@ hipError_t dispatch_dtype(int what_dtype, int grad_dtype, const po_launch& L, co
     const bool h16 = what_dtype == PO_WHAT_BF16;
     if constexpr (KIND == PO_KERNEL_FUSED) {
         if (grad_dtype == PO_GRAD_BF16)
-            return h16 ? dispatch_unroll<KIND, OPT, true, true>(L, d, ch, n, c, s, ph)
-                       : dispatch_unroll<KIND, OPT, false, true>(L, d, ch, n, c, s, ph);
+            return h16 ? launch_one<KIND, OPT, true, true>(L, d, ch, n, c, s, ph)
+                       : launch_one<KIND, OPT, false, true>(L, d, ch, n, c, s, ph);
     }
-    return h16 ? dispatch_unroll<KIND, OPT, true, false>(L, d, ch, n, c, s, ph)
-               : dispatch_unroll<KIND, OPT, false, false>(L, d, ch, n, c, s, ph);
+    return h16 ? launch_one<KIND, OPT, true, false>(L, d, ch, n, c, s, ph)
+               : launch_one<KIND, OPT, false, false>(L, d, ch, n, c, s, ph);
 }
 
 // One workgroup per XCC; workgroup 0 writes the id of the XCC it runs on.

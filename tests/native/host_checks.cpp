@@ -110,6 +110,10 @@ int main()
     EXPECT(pipeoptim_local_tile(0, 2, &tile) == PO_EINVAL);
     EXPECT(pipeoptim_local_tile(0, 0, nullptr) == PO_EINVAL);
     EXPECT(pipeoptim_probe_copy(nullptr, nullptr, 8, nullptr) == PO_EINVAL);
+    EXPECT(pipeoptim_plan_set_pointers(nullptr, 1, Wh, nullptr) == PO_EINVAL);
+    int64_t syncs = -1;
+    EXPECT(pipeoptim_device_sync_count(&syncs) == PO_OK && syncs == 0);
+    EXPECT(pipeoptim_device_sync_count(nullptr) == PO_EINVAL);
 
     std::printf("host checks passed\n");
     return 0;

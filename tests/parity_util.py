@@ -26,6 +26,9 @@ where terms cancel.
     sign-magnitude order); s = 0 must be exact (What is a copy of W).
   fp32 What at s = 0: bit-exact copy of W.
 """
+import os
+from concurrent.futures import ThreadPoolExecutor
+
 import numpy as np
 import torch
 
@@ -189,6 +192,7 @@ def compare_predict(kind, hp, t, s, inp, ref, got, what_dtype, label="", decay_i
         code = bf16_order(got["What"])
         d = np.abs(code - bf16_order(ref["What_bf16"]))
         report["What_bf16_ulp"] = int(d.max()) if d.size else 0
+        report["What_bf16_over_1ulp"] = int((d > 1).sum())
         if s == 0:
             assert report["What_bf16_ulp"] == 0, label + " bf16 What(s=0) is not the rounding of W"
         outside = (code < np.minimum(lo, hi)) | (code > np.maximum(lo, hi))
@@ -197,6 +201,63 @@ def compare_predict(kind, hp, t, s, inp, ref, got, what_dtype, label="", decay_i
         if wide.any():
             assert (tol[wide] >= 0.25 * np.abs(ref32[wide]) * 2.0 ** -8).all(), label + " bf16 off by >1 ulp away from cancellation"
     return report
+
+
+def merge_reports(reports):
+    """One report for many: counts (integer entries) add up, worst ratios and ulp distances take the maximum."""
+    out = {}
+    for r in reports:
+        for k, val in r.items():
+            if k.endswith("_over_1ulp") or k.endswith("_of_result"):
+                out[k] = out.get(k, 0) + val
+            else:
+                out[k] = max(out.get(k, 0), val)
+    return out
+
+
+def compare_stage_streamed(kind, hp, t, s, before, stage, what_dtype, predict=False, decay_in_prediction=True,
+                           label="", slice_elems=1 << 22, workers=None):
+    """Every element of every output of a stage-sized call against the oracle, tensor by tensor.
+
+    before: dict of lists of DEVICE tensors holding W, g, m, v as they were when the call started (m or v None
+    where the optimizer has no such state; g may be missing for the prediction-only call); stage: the Stage after
+    the call (synchronised).  One tensor at a time is copied to the host, cut into slices, and each slice goes
+    through the oracle (one thread per slice) and through `compare` / `compare_predict` on a pool of threads
+    (numpy and the oracle's C code both release the interpreter lock), so host memory stays at one tensor's
+    inputs and outputs plus the slices in flight.  Returns the merged report; asserts like `compare`."""
+    workers = workers or min(16, os.cpu_count() or 1)
+    keys = [k for k in (("W", "m", "v") if predict else ("W", "g", "m", "v")) if before.get(k) is not None]
+    reports = []
+    n_elems = 0
+    with ThreadPoolExecutor(max_workers=workers) as pool:
+        for i in range(len(stage.W)):
+            n = stage.W[i].numel()
+            if n == 0:
+                continue
+            inp = {k: host_f32(before[k][i]) for k in keys}
+            What = what_bits(stage.What[i]) if what_dtype == "bf16" else stage.What[i].cpu().numpy()
+            if predict:
+                got = {"What": What}
+            else:
+                got = {"W": stage.W[i].cpu().numpy(), "m": stage.m[i].cpu().numpy() if stage.m is not None else None,
+                       "v": stage.v[i].cpu().numpy() if stage.v is not None else None, "What": What}
+
+            def one(lo, i=i, inp=inp, got=got, n=n):
+                hi = min(n, lo + slice_elems)
+                sl_in = {k: a[lo:hi] for k, a in inp.items()}
+                sl_got = {k: (a[lo:hi] if a is not None else None) for k, a in got.items()}
+                tag = "%s tensor %d [%d:%d)" % (label, i, lo, hi)
+                if predict:
+                    ref = run_oracle_predict(kind, hp, t, s, sl_in, decay_in_prediction, nthreads=1)
+                    return compare_predict(kind, hp, t, s, sl_in, ref, sl_got, what_dtype, tag, decay_in_prediction)
+                ref = run_oracle(kind, hp, t, s, sl_in, decay_in_prediction, nthreads=1)
+                return compare(kind, hp, t, s, sl_in, ref, sl_got, what_dtype, tag, decay_in_prediction)
+
+            reports.extend(pool.map(one, range(0, n, slice_elems)))      # re-raises a slice's assertion here
+            n_elems += n
+    rep = merge_reports(reports)
+    rep["elements_compared"] = n_elems
+    return rep
 
 
 def to_arena(tensors, what_dtype, skew_bytes=None):

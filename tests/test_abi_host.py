@@ -34,7 +34,7 @@ def test_struct_layouts_match_header():
     assert ctypes.sizeof(binding.po_hyper) == 48
     assert ctypes.sizeof(binding.po_coeffs) == 52
     assert ctypes.sizeof(binding.po_chunk) == 8
-    assert ctypes.sizeof(binding.po_launch) == 32
+    assert ctypes.sizeof(binding.po_launch) == 16
 
 
 def test_version_difference_eq4():
@@ -302,6 +302,14 @@ def test_overlapping_buffers_are_rejected_before_any_device_call():
     assert "overlap" not in binding.pipeoptim_last_error() or rc == 0
     if rc == 0:
         L.pipeoptim_plan_destroy(h)
+
+
+def test_device_sync_counter_and_set_pointers_argument_checks():
+    L = binding.lib()
+    assert L.pipeoptim_device_sync_count(None) == binding.PO_EINVAL
+    assert binding.pipeoptim_device_sync_count() >= 0
+    p = (ctypes.c_void_p * 1)(ctypes.c_void_p(4096))
+    assert L.pipeoptim_plan_set_pointers(None, 1, p, None) == binding.PO_EINVAL
 
 
 def test_mixed_plan_validation():

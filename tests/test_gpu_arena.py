@@ -139,9 +139,9 @@ def test_localized_stage_with_bf16_gradients(kind):
 @pytest.mark.parametrize("launch", [
     dict(chunk_elems=4096),                                # one 16-tile group per chunk: still localized
     dict(chunk_elems=1024),                                # 4 tiles per chunk: no whole group, plain order
-    dict(block=128, unroll=1, chunk_elems=65536),          # 512-element tiles: plain order
-    dict(block=64, unroll=1, chunk_elems=65536, xcd_remap=1),
-    dict(block=64, unroll=4, chunk_elems=1 << 20, lds_bytes=0),
+    dict(block=128, chunk_elems=65536),                    # 512-element tiles: plain order
+    dict(block=256, chunk_elems=1 << 20, lds_bytes=0),     # 1024-element tiles: plain order
+    dict(block=64, chunk_elems=1 << 20, lds_bytes=0),
 ], ids=lambda L: "-".join("%s%d" % (k[0], v) for k, v in L.items()))
 def test_localized_stage_under_other_launch_shapes(launch):
     _say("arena stage, launch %s" % launch)
@@ -159,7 +159,7 @@ def test_prediction_alone_on_a_localized_stage(kind):
     try:
         run_and_compare_predict(kind, HP[kind], 50, 4, tensors, "bf16", label="arena predict")
         run_and_compare_predict(kind, HP[kind], 50, 4, tensors, "bf16", label="arena predict 1 KiB tiles",
-                                launch=dict(block=64, unroll=1, cache_policy=4, lds_bytes=8192))
+                                launch=dict(block=64, lds_bytes=8192))
     finally:
         tensors["stage_arena"].close()
 
@@ -184,8 +184,7 @@ def test_random_cases_in_the_arena(case):
     s = int(rng.choice([0, 1, 2, 3, 7, 40]))
     dip = bool(rng.integers(0, 2))
     sizes = [int(x) for x in rng.integers(0, 300000, size=int(rng.integers(1, 6)))] + [int(rng.integers(1, 5000))]
-    launch = dict(block=64, unroll=1, chunk_elems=256 * int(2 ** rng.integers(4, 9)), cache_policy=int(rng.integers(0, 5)),
-                  lds_bytes=int(rng.choice([0, 8192, 16384])), xcd_remap=0)
+    launch = dict(block=64, chunk_elems=256 * int(2 ** rng.integers(4, 9)), lds_bytes=int(rng.choice([0, 8192, 16384])))
     sig = dict(sw=float(10 ** rng.uniform(-3, 0)), sg=float(10 ** rng.uniform(-6, -1)),
                sm=float(10 ** rng.uniform(-6, -1)), sv=float(10 ** rng.uniform(-6, -1)))
     _say("arena random case %d: %s %s g=%s t=%d s=%d dip=%d sizes=%s launch=%s" % (case, kind, what_dtype, grad_dtype, t, s, dip, sizes, launch))

@@ -11,8 +11,8 @@ import torch
 
 pytestmark = pytest.mark.gpu
 
-from parity_util import (compare, compare_predict, make_hyper, run_and_compare_full, run_and_compare_predict,  # noqa: E402
-                         run_oracle, run_oracle_predict, what_bits)
+from parity_util import (compare, make_hyper, run_and_compare_full, run_and_compare_predict,  # noqa: E402
+                         run_oracle, what_bits)
 
 from paper_2312_00839_amd import binding  # noqa: E402
 from paper_2312_00839_amd.stage import Stage  # noqa: E402
@@ -98,9 +98,9 @@ def test_hand_cases_on_gpu(head, rows, what_dtype):
     if what_dtype == "f32":
         np.testing.assert_allclose(stage.What[0].cpu().numpy(), expect_What, rtol=3e-7, atol=1e-7)
     else:
-        got = what_bits(stage.What[0]).astype(np.int32)
-        want = (expect_What.view(np.uint32) >> 16).astype(np.int32)
-        assert np.abs(got - want).max() <= 1
+        # every expected value is a short dyadic number, exact in bf16 and far from a rounding boundary: the 1-ulp
+        # slack of the fp32 root and divide cannot move the code
+        assert np.array_equal(what_bits(stage.What[0]), (expect_What.view(np.uint32) >> 16).astype(np.uint16))
     stage.close()
 
 
@@ -120,8 +120,7 @@ def test_predict_hand_cases_on_gpu(head, rows, what_dtype):
     if what_dtype == "f32":
         np.testing.assert_allclose(stage.What[0].cpu().numpy(), expect, rtol=3e-7, atol=1e-7)
     else:
-        got = what_bits(stage.What[0]).astype(np.int32)
-        assert np.abs(got - (expect.view(np.uint32) >> 16).astype(np.int32)).max() <= 1
+        assert np.array_equal(what_bits(stage.What[0]), (expect.view(np.uint32) >> 16).astype(np.uint16))
     stage.close()
 
 
@@ -139,16 +138,14 @@ RAGGED = [1, 2, 3, 5, 7, 8, 9, 4095, 4096, 4097, 0, 12289, 70001, 16384, 65537]
 
 LAUNCHES = [
     None,
-    dict(block=64, unroll=1, chunk_elems=256, cache_policy=0, lds_bytes=0),
-    dict(block=64, unroll=2, chunk_elems=512 * 8, cache_policy=1, lds_bytes=8192),
-    dict(block=64, unroll=4, chunk_elems=1024 * 64, cache_policy=2),
-    dict(block=128, unroll=1, chunk_elems=512 * 2, cache_policy=3, lds_bytes=65536),
-    dict(block=128, unroll=4, chunk_elems=2048, cache_policy=4, xcd_remap=1),
-    dict(block=256, unroll=1, chunk_elems=1024 * 4, cache_policy=4, lds_bytes=16384),
-    dict(block=256, unroll=2, chunk_elems=2048 * 32, cache_policy=3, xcd_remap=1),
-    dict(block=256, unroll=4, chunk_elems=4096, cache_policy=0, xcd_remap=1, lds_bytes=40960),
-    dict(block=64, unroll=1, chunk_elems=256 * 1024, cache_policy=4, xcd_remap=1),
-    dict(block=64, unroll=2, chunk_elems=512, cache_policy=4, xcd_remap=1, lds_bytes=20480),
+    dict(block=64, chunk_elems=256, lds_bytes=0),
+    dict(block=64, chunk_elems=256 * 16, lds_bytes=8192),
+    dict(block=64, chunk_elems=256 * 1024),
+    dict(block=128, chunk_elems=512 * 2, lds_bytes=65536),
+    dict(block=128, chunk_elems=512 * 128, lds_bytes=0),
+    dict(block=256, chunk_elems=1024 * 4, lds_bytes=16384),
+    dict(block=256, chunk_elems=1024, lds_bytes=40960),
+    dict(block=256, chunk_elems=1024 * 64),
 ]
 
 
@@ -227,6 +224,50 @@ def test_nonfinite_values_propagate():
     st.close()
 
 
+def test_nonfinite_values_in_the_bf16_prediction():
+    # NaN, +-Inf and overflow on the way to bf16, against the oracle's rounding routine: s = 0 makes What the bf16
+    # rounding of W itself, so W carries the special values straight into the conversion
+    _say("nan/inf/overflow into bf16")
+    import oracle
+    special = np.array([np.inf, -np.inf, 3.4e38, -3.4e38, 3.3895314e38, 3.3961775e38, 3.38953139e38 * (1 + 2 ** -9),
+                        1e-40, -1e-40, 0.0, -0.0, 1.0], dtype=np.float32)
+    nan_bits = np.array([0x7FC00000, 0xFFC00000, 0x7F800001, 0xFF800001, 0x7FFFFFFF, 0x7FC12345], dtype=np.uint32)
+    Wh = np.concatenate([special, nan_bits.view(np.float32)])
+    n = Wh.size
+    t = _rand_list([n], 20, "adam")
+    t["W"][0].copy_(torch.from_numpy(Wh).to(DEV))
+    st = Stage(t["W"], t["g"], t["m"], t["v"], "bf16")
+    for predict in (False, True):
+        t["W"][0].copy_(torch.from_numpy(Wh).to(DEV))
+        (st.predict if predict else st.step_predict)(make_hyper("adam", HP["adam"]), 4, 0)
+        torch.cuda.synchronize()
+        got = what_bits(st.What[0])
+        want = oracle.bf16_from_f32(Wh)
+        finite = ~np.isnan(Wh)
+        assert np.array_equal(got[finite], want[finite]), (predict, got[finite], want[finite])   # Inf, overflow to Inf, denormals, zeros
+        # NaN stays NaN, sign kept, quiet (the payload below the quiet bit is the converter's own business)
+        g_nan, w_nan = got[~finite], want[~finite]
+        assert ((g_nan & 0x7F80) == 0x7F80).all() and ((g_nan & 0x007F) != 0).all()
+        assert np.array_equal(g_nan & 0x8000, w_nan & 0x8000) and ((g_nan & 0x0040) != 0).all()
+    st.close()
+    # s > 0 with an overflowing and a non-finite update: the same classes as the oracle, element by element
+    t = _rand_list([64], 21, "adam")
+    t["W"][0][1] = 3.4e38
+    t["g"][0][2] = float("nan")
+    t["g"][0][3] = float("inf")
+    t["W"][0][4] = float("-inf")
+    host = {k: t[k][0].cpu().numpy().copy() for k in ("W", "g", "m", "v")}
+    st = Stage(t["W"], t["g"], t["m"], t["v"], "bf16")
+    st.step_predict(make_hyper("adam", HP["adam"]), 4, 3)
+    torch.cuda.synchronize()
+    ref = run_oracle("adam", HP["adam"], 4, 3, host)
+    got = oracle.f32_from_bf16(what_bits(st.What[0]))
+    want = oracle.f32_from_bf16(ref["What_bf16"])
+    assert np.array_equal(np.isnan(got), np.isnan(want)) and np.array_equal(np.isinf(got), np.isinf(want))
+    assert np.array_equal(np.signbit(got[np.isinf(got)]), np.signbit(want[np.isinf(want)]))
+    st.close()
+
+
 def test_two_steps_in_place_chain():
     # the state a call leaves in place is the next call's input: check the second of two chained calls
     # against the oracle started from the state the first call left on the device
@@ -267,6 +308,66 @@ def test_set_pointers_swaps_gradient_buffers():
                "What": st.What[i].cpu().numpy()}
         compare(kind, hp, 3, 2, host[i], ref, got, "f32", "set_pointers %d" % i)
     st.close()
+
+
+def test_set_pointers_between_steps_is_stream_ordered_and_waits_for_nothing():
+    # a training loop whose gradient buffers move every step: step, new pointers, step, on a side stream, while
+    # another stream is kept busy with unrelated work.  Neither plan creation, set_pointers, the steps nor the
+    # destruction may wait for the device; every step is checked against the oracle from the state before it.
+    _say("set_pointers per step on a side stream")
+    kind, hp = "adamw", HP["adamw"]
+    sizes = [300000, 4097, 70001]
+    t = _rand_list(sizes, 61, kind)
+    grads = [[torch.randn_like(x) * 1e-3 for x in t["g"]] for _ in range(3)]
+    side, busy = torch.cuda.Stream(), torch.cuda.Stream()
+    torch.cuda.synchronize()
+    syncs_before = binding.pipeoptim_device_sync_count()
+    a = torch.randn(4096, 4096, device=DEV)
+    done = torch.cuda.Event()
+    with torch.cuda.stream(busy):
+        for _ in range(300):                       # several hundred milliseconds of unrelated work
+            a = (a @ a).mul_(1e-3)
+        done.record(busy)
+    states, still_busy = [], []
+    with torch.cuda.stream(side):
+        st = Stage(t["W"], t["g"], t["m"], t["v"], "bf16")
+        for k in range(3):
+            st.plan.set_pointers(1, [x.data_ptr() for x in grads[k]], side.cuda_stream)
+            still_busy.append(not done.query())
+            side.synchronize()                     # (the test's own wait, to read the state the step starts from)
+            states.append([{"W": st.W[i].cpu().numpy().copy(), "g": grads[k][i].cpu().numpy().copy(),
+                            "m": st.m[i].cpu().numpy().copy(), "v": st.v[i].cpu().numpy().copy()} for i in range(len(sizes))])
+            st.step_predict(make_hyper(kind, hp), 5 + k, 3)
+            side.synchronize()
+            for i in range(len(sizes)):
+                ref = run_oracle(kind, hp, 5 + k, 3, states[k][i])
+                got = {"W": st.W[i].cpu().numpy(), "m": st.m[i].cpu().numpy(), "v": st.v[i].cpu().numpy(),
+                       "What": what_bits(st.What[i])}
+                compare(kind, hp, 5 + k, 3, states[k][i], ref, got, "bf16", "moving gradients step %d tensor %d" % (k, i))
+        # two replacements in a row without anything in between: the second must not overwrite staging memory the
+        # first upload still reads (the last one wins)
+        st.plan.set_pointers(1, [x.data_ptr() for x in grads[0]], side.cuda_stream)
+        st.plan.set_pointers(1, [x.data_ptr() for x in grads[1]], side.cuda_stream)
+        st.plan.set_pointers(1, [x.data_ptr() for x in grads[2]], side.cuda_stream)
+        side.synchronize()
+        last = [{"W": st.W[i].cpu().numpy().copy(), "g": grads[2][i].cpu().numpy().copy(),
+                 "m": st.m[i].cpu().numpy().copy(), "v": st.v[i].cpu().numpy().copy()} for i in range(len(sizes))]
+        st.step_predict(make_hyper(kind, hp), 9, 1)
+        side.synchronize()
+        for i in range(len(sizes)):
+            ref = run_oracle(kind, hp, 9, 1, last[i])
+            got = {"W": st.W[i].cpu().numpy(), "m": st.m[i].cpu().numpy(), "v": st.v[i].cpu().numpy(), "What": what_bits(st.What[i])}
+            compare(kind, hp, 9, 1, last[i], ref, got, "bf16", "three replacements tensor %d" % i)
+        # a failing replacement leaves the plan as it was
+        with pytest.raises(binding.PipeOptimError):
+            st.plan.set_pointers(1, [st.m[i].data_ptr() for i in range(len(sizes))], side.cuda_stream)    # g onto m: overlap
+        st.step_predict(make_hyper(kind, hp), 10, 1)
+        st.close()
+    busy_at_end = not done.query()
+    assert binding.pipeoptim_device_sync_count() == syncs_before, "a per-step call waited for the whole device"
+    _say("unrelated stream still busy after set_pointers %s, at the end: %s" % (still_busy, busy_at_end))
+    assert still_busy[0], "plan creation or set_pointers waited for the other stream's work"
+    torch.cuda.synchronize()
 
 
 # --------------------------------------------------------------------------- optimizers beyond Table 1
@@ -417,41 +518,24 @@ def test_predict_after_fused_equals_fused_prediction_one_further(kind):
     sb.close()
 
 
-def test_predict_config3_full_and_config5_sampled():
-    for cfg, s in ((3, 2), (5, 7)):
-        wl = workload(cfg)
-        _say("predict config %d (%s) s=%d" % (cfg, wl.name, s))
-        tensors = make_inputs(wl, DEV)
-        if cfg == 3:
-            run_and_compare_predict(wl.optimizer, wl.hyper, wl.t, s, tensors, wl.what_dtype, label="predict config 3")
-            continue
-        rng = np.random.default_rng(77)
-        stage = Stage(tensors["W"], tensors["g"], tensors["m"], tensors["v"], wl.what_dtype)
-        stage.predict(make_hyper(wl.optimizer, wl.hyper), wl.t, s)
-        torch.cuda.synchronize()
-        for i, n in enumerate(wl.numels):
-            starts = [0, max(0, n - 8195)] + [int(rng.integers(0, max(1, n - 8192))) for _ in range(6)]
-            idx = torch.cat([torch.arange(a, min(n, a + 8195), device=DEV) for a in starts])
-            inp = {k: tensors[k][i][idx].cpu().numpy() for k in ("W", "m", "v")}     # predict leaves them unchanged
-            ref = run_oracle_predict(wl.optimizer, wl.hyper, wl.t, s, inp)
-            compare_predict(wl.optimizer, wl.hyper, wl.t, s, inp, ref, {"What": what_bits(stage.What[i][idx])},
-                            wl.what_dtype, "predict config 5 tensor %d" % i)
-        stage.close()
+def test_predict_config3_full():
+    wl = workload(3)
+    _say("predict config 3 (%s) s=2" % wl.name)
+    run_and_compare_predict(wl.optimizer, wl.hyper, wl.t, 2, make_inputs(wl, DEV), wl.what_dtype, label="predict config 3")
 
 
 def test_predict_launch_errors():
     t = _rand_list([1000], 19, "adam")
     st = Stage(t["W"], t["g"], t["m"], t["v"], "f32")
-    for bad in [dict(block=100), dict(unroll=3), dict(cache_policy=9), dict(lds_bytes=70000), dict(chunk_elems=4096),
-                dict(reserved=2)]:
+    for bad in [dict(block=100), dict(block=32), dict(lds_bytes=70000), dict(lds_bytes=-2), dict(chunk_elems=4096)]:
         with pytest.raises(binding.PipeOptimError) as e:
             st.plan.set_predict_launch(**bad)
         assert e.value.status == binding.PO_EINVAL, bad
-    st.plan.set_predict_launch(chunk_elems=0, block=128, unroll=2)         # 0 = the plan's chunk size
+    st.plan.set_predict_launch(chunk_elems=0, block=256)                   # 0 = the plan's chunk size
     assert st.plan.get_predict_launch().chunk_elems == st.plan.get_launch().chunk_elems
     st.plan.set_launch(chunk_elems=256)                                    # no longer fits the prediction tile (1024):
     pl = st.plan.get_predict_launch()                                      # that kernel falls back to the fused shape
-    assert (pl.block, pl.unroll, pl.chunk_elems) == (64, 1, 256)
+    assert (pl.block, pl.chunk_elems) == (64, 256)
     sg = _rand_list([1000], 19, "sgdm")
     s2 = Stage(sg["W"], sg["g"], sg["m"], None, "f32")
     with pytest.raises(binding.PipeOptimError) as e:
@@ -486,9 +570,9 @@ def test_error_paths_launch_nothing():
         with pytest.raises(binding.PipeOptimError) as e:
             st.step_predict(make_hyper("sgdm", HP["sgdm"]), bad_t, bad_s)
         assert e.value.status == binding.PO_EINVAL
-    for bad in [dict(block=100), dict(block=512), dict(unroll=3), dict(unroll=8), dict(chunk_elems=1000),
-                dict(chunk_elems=0), dict(chunk_elems=256 * 3), dict(chunk_elems=1 << 31), dict(cache_policy=5),
-                dict(cache_policy=-1), dict(lds_bytes=-2), dict(lds_bytes=65537), dict(xcd_remap=2), dict(reserved=1)]:
+    for bad in [dict(block=100), dict(block=512), dict(block=0), dict(chunk_elems=1000),
+                dict(chunk_elems=0), dict(chunk_elems=256 * 3), dict(chunk_elems=1 << 31), dict(lds_bytes=-2),
+                dict(lds_bytes=65537)]:
         with pytest.raises(binding.PipeOptimError) as e:
             st.plan.set_launch(**bad)
         assert e.value.status == binding.PO_EINVAL, bad
@@ -540,15 +624,67 @@ def test_probe_copy_copies():
 
 
 # --------------------------------------------------------------------------- the five configurations
-def _full_config(cfg, s, layout="packed"):
+# bf16 What: the kernel rounds ITS fp32 prediction, so a code can differ from the oracle's by more than one unit only
+# where W and s*lr*dW cancel to a result so small that the fp32 tolerance band spans several bf16 steps (`compare`
+# asserts that).  How many elements of a configuration do is counted and capped: the ceilings are the counts this
+# kernel produces on the seeded inputs (fp32 arithmetic in a fixed order: the same on every run), so a change that
+# multiplies them fails here.  Key: (config, s, "fused" | "predict"); configurations not listed must have none.
+OVER_1ULP_CEILING = {
+    (3, 2, "fused"): 14,                                                     # of 75,577,344
+    (4, 1, "fused"): 13, (4, 2, "fused"): 38, (4, 3, "fused"): 40, (4, 4, "fused"): 64,
+    (4, 5, "fused"): 58, (4, 6, "fused"): 71, (4, 7, "fused"): 72,           # of 151,074,816; grows with s as more
+    (4, 7, "predict"): 42,                                                   # elements have s*lr*dW as large as W
+    (5, 7, "fused"): 548,                                                    # of 738,222,080
+    (5, 7, "predict"): 392,
+}
+
+
+def _check_over_1ulp(cfg, s, mode, report, what_dtype):
+    if what_dtype != "bf16":
+        return
+    n = report.get("What_bf16_over_1ulp", 0)
+    cap = OVER_1ULP_CEILING.get((cfg, s, mode), 0)
+    _say("config %d s=%d %s: %d bf16 What codes more than 1 ulp from the oracle's (ceiling %d), worst distance %d ulp"
+         % (cfg, s, mode, n, cap, report.get("What_bf16_ulp", 0)))
+    assert n <= cap, "config %d s=%d %s: %d bf16 codes beyond 1 ulp, ceiling %d" % (cfg, s, mode, n, cap)
+
+
+def _full_config(cfg, s, layout="packed", what_dtype=None, predict=False):
+    """The whole stage at its real shape in the default (benchmarked) launch shape; EVERY element of every output
+    is compared with the oracle, tensor by tensor."""
+    import dataclasses
+    from parity_util import compare_stage_streamed
     wl = workload(cfg)
-    _say("config %d (%s) s=%d full compare, N=%d, layout %s" % (cfg, wl.name, s, wl.n_params, layout))
+    if what_dtype and what_dtype != wl.what_dtype:
+        wl = dataclasses.replace(wl, what_dtype=what_dtype)
+    mode = "predict" if predict else "fused"
+    _say("config %d (%s) s=%d %s, full compare, N=%d, layout %s, %s What" % (cfg, wl.name, s, mode, wl.n_params, layout, wl.what_dtype))
     tensors = make_inputs(wl, DEV, layout=layout)
-    reps = run_and_compare_full(wl.optimizer, wl.hyper, wl.t, s, tensors, wl.what_dtype, label="config %d" % cfg)
-    if layout == "local":
-        tensors["stage_arena"].close()
-    worst = {k: max(r[k] for r in reps if k in r) for k in reps[0]}
-    _say("config %d s=%d worst error ratios (1.0 = 1e-0 of scale): %s" % (cfg, s, worst))
+    keys = [k for k in ("W", "g", "m", "v") if tensors.get(k) is not None]
+    before = {k: [x.clone() for x in tensors[k]] for k in keys}
+    stage = Stage(tensors["W"], tensors["g"], tensors["m"], tensors.get("v"), wl.what_dtype,
+                  What=tensors.get("What"), arena=tensors.get("arena"))
+    try:
+        if layout == "local":
+            assert stage.n_local_params == wl.n_params
+        hyper = make_hyper(wl.optimizer, wl.hyper)
+        (stage.predict if predict else stage.step_predict)(hyper, wl.t, s)
+        torch.cuda.synchronize()
+        untouched = keys if predict else ["g"]          # g is only ever read; the prediction-only call writes What alone
+        for k in untouched:
+            for x, y in zip(before[k], getattr(stage, k)):
+                assert torch.equal(x, y), k + " was modified"
+        rep = compare_stage_streamed(wl.optimizer, wl.hyper, wl.t, s, before, stage, wl.what_dtype, predict=predict,
+                                     label="config %d %s" % (cfg, mode))
+    finally:
+        stage.close()
+        if layout == "local":
+            tensors["stage_arena"].close()
+    assert rep["elements_compared"] == wl.n_params
+    _say("config %d s=%d %s layout %s: %d elements compared; worst error ratios (1.0 = the 1e-6 bound): %s"
+         % (cfg, s, mode, layout, rep["elements_compared"], {k: v for k, v in rep.items() if isinstance(v, float)}))
+    _check_over_1ulp(cfg, s, mode, rep, wl.what_dtype)
+    return rep
 
 
 def test_config1_flat_adam_full():
@@ -564,65 +700,14 @@ def test_config3_bert_adam_bf16_full():
     _full_config(3, 2)
 
 
-def _sampled_config(cfg, s, blocks_per_tensor=6, block=8192, seed=0, layout="packed"):
-    """Full-size run in the default (benchmarked) launch shape; the oracle recomputes sampled
-    index ranges of every tensor: its head, its ragged tail and random interior ranges."""
-    wl = workload(cfg)
-    _say("config %d (%s) s=%d sampled compare, N=%d, layout %s" % (cfg, wl.name, s, wl.n_params, layout))
-    tensors = make_inputs(wl, DEV, layout=layout)
-    rng = np.random.default_rng(1234 + cfg * 10 + s + seed)
-    ranges, saved = [], []
-    for i, n in enumerate(wl.numels):
-        r = [(0, min(block, n)), (max(0, n - block - 3), n)]
-        for _ in range(blocks_per_tensor - 2):
-            a = int(rng.integers(0, max(1, n - block)))
-            r.append((a, min(n, a + block + int(rng.integers(0, 9)))))
-        ranges.append(r)
-        idx = torch.cat([torch.arange(a, b, device=DEV) for a, b in r])
-        saved.append((idx, {k: tensors[k][i][idx].cpu().numpy() for k in ("W", "g", "m", "v") if tensors.get(k) is not None}))
-    W_in = [w.clone() for w in tensors["W"]]
-    stage = Stage(tensors["W"], tensors["g"], tensors["m"], tensors.get("v"), wl.what_dtype,
-                  What=tensors.get("What"), arena=tensors.get("arena"))
-    if layout == "local":
-        assert stage.n_local_params == wl.n_params
-    stage.step_predict(make_hyper(wl.optimizer, wl.hyper), wl.t, s)
-    torch.cuda.synchronize()
-    worst = {}
-    for i, (idx, inp) in enumerate(saved):
-        ref = run_oracle(wl.optimizer, wl.hyper, wl.t, s, inp)
-        got = {"W": stage.W[i][idx].cpu().numpy(), "m": stage.m[i][idx].cpu().numpy(),
-               "v": stage.v[i][idx].cpu().numpy() if stage.v is not None else None,
-               "What": what_bits(stage.What[i][idx]) if wl.what_dtype == "bf16" else stage.What[i][idx].cpu().numpy()}
-        rep = compare(wl.optimizer, wl.hyper, wl.t, s, inp, ref, got, wl.what_dtype, "config %d tensor %d" % (cfg, i))
-        for k, val in rep.items():
-            worst[k] = max(worst.get(k, 0), val)
-    # A property that holds at any size, checked over ALL elements on the device: Eq. 1 and Eq. 5 share the
-    # same dW_t, so the three weight-sized results lie on one line: What = W_in + s*(W' - W_in).
-    for i in range(len(stage.W)):
-        Win, Wnew, What = W_in[i], stage.W[i], stage.What[i].float()
-        assert torch.isfinite(Wnew).all() and torch.isfinite(stage.m[i]).all() and torch.isfinite(What).all()
-        line = torch.addcmul(Win, Wnew - Win, torch.tensor(float(s), device=DEV))
-        unit = 2.0 ** -8 if wl.what_dtype == "bf16" else 2.0 ** -22          # one unit of the stored format
-        tol = unit * line.abs() + (s + 1) * 2.0 ** -21 * (Win.abs() + Wnew.abs()) + 1e-30
-        bad = ((What - line).abs() > tol).sum().item()
-        assert bad == 0, "config %d tensor %d: %d elements off the line through W_in and W'" % (cfg, i, bad)
-    stage.close()
-    if layout == "local":
-        tensors["stage_arena"].close()
-    _say("config %d s=%d worst: %s" % (cfg, s, worst))
-
-
 @pytest.mark.parametrize("s", list(range(8)))
-def test_config4_gpt_adamw_bf16_sweep_sampled(s):
-    _sampled_config(4, s)
+def test_config4_gpt_adamw_bf16_sweep_full(s):
+    _full_config(4, s)
 
 
-def test_config4_gpt_adamw_bf16_full():
-    _full_config(4, 5)
-
-
-def test_config5_llama_adamw_bf16_sampled():
-    _sampled_config(5, 7, blocks_per_tensor=10)
+def test_config5_llama_adamw_bf16_full():
+    # the configuration the headline metric is quoted on, in plain PyTorch allocations
+    _full_config(5, 7)
 
 
 def test_config3_bert_adam_bf16_full_in_near_memory_arena():
@@ -634,13 +719,36 @@ def test_config2_resnet_sgdm_full_in_near_memory_arena():
 
 
 @pytest.mark.parametrize("s", [0, 7])
-def test_config4_gpt_adamw_bf16_sampled_in_near_memory_arena(s):
-    _sampled_config(4, s, layout="local")
+def test_config4_gpt_adamw_bf16_full_in_near_memory_arena(s):
+    _full_config(4, s, layout="local")
 
 
-def test_config5_llama_adamw_bf16_sampled_in_near_memory_arena():
-    # the layout and launch shape bench.py times by default
-    _sampled_config(5, 7, blocks_per_tensor=10, layout="local")
+def test_config5_llama_adamw_bf16_full_in_near_memory_arena():
+    # the layout and launch shape bench.py's `value` is measured in
+    _full_config(5, 7, layout="local")
+
+
+def test_config5_predict_full():
+    _full_config(5, 7, predict=True)
+
+
+def test_config5_predict_full_in_near_memory_arena():
+    _full_config(5, 7, layout="local", predict=True)
+
+
+@pytest.mark.parametrize("s", [0, 7])
+def test_config4_predict_full(s):
+    _full_config(4, s, predict=True)
+
+
+# fp32 predicted weights on the bf16 configurations' shapes (32 instead of 30 bytes per parameter)
+def test_config3_fp32_prediction_full():
+    _full_config(3, 2, what_dtype="f32")
+
+
+@pytest.mark.parametrize("layout", ["packed", "local"])
+def test_config5_fp32_prediction_full(layout):
+    _full_config(5, 7, layout=layout, what_dtype="f32")
 
 
 def test_config5_s0_prediction_is_rounded_W_everywhere():
@@ -747,10 +855,8 @@ def test_random_cases(case):
     dip = bool(rng.integers(0, 2))
     sizes = [int(x) for x in rng.integers(0, 40000, size=int(rng.integers(1, 7)))] + [int(rng.integers(1, 9))]
     block = int(rng.choice([64, 128, 256]))
-    unroll = int(rng.choice([1, 2, 4]))
-    launch = dict(block=block, unroll=unroll, chunk_elems=block * 4 * unroll * int(2 ** rng.integers(0, 6)),
-                  cache_policy=int(rng.integers(0, 5)), lds_bytes=int(rng.choice([0, 4096, 16384, 40000])),
-                  xcd_remap=int(rng.integers(0, 2)))
+    launch = dict(block=block, chunk_elems=block * 4 * int(2 ** rng.integers(0, 6)),
+                  lds_bytes=int(rng.choice([0, 4096, 16384, 40000])))
     sig = dict(sw=float(10 ** rng.uniform(-3, 0)), sg=float(10 ** rng.uniform(-6, -1)),
                sm=float(10 ** rng.uniform(-6, -1)), sv=float(10 ** rng.uniform(-6, -1)))
     _say("random case %d: %s %s g=%s t=%d s=%d dip=%d sizes=%s launch=%s" % (case, kind, what_dtype, grad_dtype, t, s, dip, sizes, launch))
