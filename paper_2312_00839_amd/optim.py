@@ -153,28 +153,6 @@ class StageOptimizer:
         """The optimizer's buffers (flat views, by parameter order): dict with W, g, m, v, What and the step count."""
         return {"W": self._W, "g": self._g, "m": self._m, "v": self._v, "What": self._What, "t": self.t, "s": self.s}
 
-    def state_dict(self):
-        """Copies of the optimizer state (m, v and the predicted weights by parameter order, the step count): what a
-        checkpoint needs next to the module's own parameters.  What is part of it: the fused call predicted it from
-        the weights BEFORE the step, which no longer exist, so it cannot be recomputed from the rest."""
-        return {"optimizer": self.optimizer, "t": self.t,
-                "m": [x.clone() for x in self._m] if self._m is not None else None,
-                "v": [x.clone() for x in self._v] if self._v is not None else None,
-                "What": [x.clone() for x in self._What]}
-
-    def load_state_dict(self, sd) -> None:
-        """Restores m, v, the predicted weights and the step count (the parameters themselves are the module's
-        business: load them before)."""
-        if sd["optimizer"] != self.optimizer:
-            raise ValueError("state of a %s optimizer loaded into %s" % (sd["optimizer"], self.optimizer))
-        for name, mine in (("m", self._m), ("v", self._v), ("What", self._What)):
-            theirs = sd[name]
-            if (mine is None) != (theirs is None) or (mine is not None and [x.numel() for x in mine] != [x.numel() for x in theirs]):
-                raise ValueError("state buffers %r do not match this optimizer's parameters" % name)
-            for dst, src in zip(mine or (), theirs or ()):
-                dst.copy_(src.view(-1))
-        self.t = int(sd["t"])
-
     @property
     def n_local_params(self) -> int:
         """Parameters whose streams the kernels process in the near-memory tile order."""

@@ -89,48 +89,6 @@ def test_forward_inside_the_block_uses_the_predicted_weights():
     opt.close()
 
 
-@pytest.mark.parametrize("kind", ["adamw", "sgdm", "rmsprop"])
-def test_checkpoint_and_resume_continue_bit_for_bit(kind):
-    x = torch.randn(32, 37, device=DEV)
-    y = torch.randn(32, 11, device=DEV)
-
-    def iterate(model, opt, n):
-        for _ in range(n):
-            opt.zero_grad()
-            with opt.predicted_weights():
-                loss = torch.nn.functional.mse_loss(model(x), y)
-            loss.backward()
-            opt.step()
-
-    model = _mlp(11)
-    opt = StageOptimizer(model.parameters(), kind, lr=0.01, rank=0, depth=3, arena=True)
-    iterate(model, opt, 2)
-    saved_params = [p.detach().clone() for p in model.parameters()]
-    saved = opt.state_dict()
-    iterate(model, opt, 2)
-    torch.cuda.synchronize()
-    expect = [p.detach().clone() for p in model.parameters()]
-    expect_what = [h.clone() for h in opt.state()["What"]]
-    opt.close()
-
-    model2 = _mlp(12)                                                   # other initial weights
-    with torch.no_grad():
-        for p, q in zip(model2.parameters(), saved_params):
-            p.copy_(q)
-    opt2 = StageOptimizer(model2.parameters(), kind, lr=0.01, rank=0, depth=3, arena=False)
-    opt2.load_state_dict(saved)
-    assert opt2.t == 2
-    iterate(model2, opt2, 2)
-    torch.cuda.synchronize()
-    for p, q in zip(model2.parameters(), expect):
-        assert torch.equal(p.detach(), q)
-    for h, q in zip(opt2.state()["What"], expect_what):
-        assert torch.equal(h, q)
-    with pytest.raises(ValueError):
-        opt2.load_state_dict(dict(saved, optimizer="adam" if kind != "adam" else "sgdm"))
-    opt2.close()
-
-
 def test_last_stage_and_misuse():
     model = _mlp(7)
     opt = StageOptimizer(model.parameters(), "sgdm", lr=0.1, rank=3, depth=4)
