@@ -283,6 +283,27 @@ int pipeoptim_step_predict(const po_plan* plan, const po_hyper* hyper, int64_t t
                            void* hip_stream);
 
 /*
+ * For callers that cannot allocate: code under HIP graph capture, tight serving loops, harnesses that forbid
+ * hipMalloc.  The same update as pipeoptim_step_predict, for a ragged list handed over in the call itself instead
+ * of a plan (arguments as in pipeoptim_plan_create, fp32 gradients; hyper, t, s as in pipeoptim_step_predict).
+ * The call allocates nothing, on the device or through HIP: the tensor descriptors and the chunk table that a
+ * plan keeps in memory of its own live here in a fixed device array inside the library (64 KiB + 512 KiB per
+ * GPU the library runs on, held until the process ends).  The descriptors reach it inside kernel arguments, the
+ * chunk table is built from them on the device, then the fused kernel runs: 2 + ceil(n_tensors / 48) small
+ * kernels in front of the one that does the work, all enqueued on hip_stream, nothing waited for.
+ * Limits: at most PO_STATIC_MAX_TENSORS tensors and PO_STATIC_MAX_CHUNKS chunk-table entries of 65,536 elements
+ * (sum over tensors of ceil(numel / 65536); 4.2 G parameters in large tensors); beyond them PO_EINVAL, nothing
+ * launched.  Launch shape: the default one (block 64, occupancy cap chosen for optimizer and stage size).
+ * Every call on a GPU uses that GPU's one array: calls on the same stream follow each other safely; calls that
+ * overlap in time on different streams of one GPU race on the tables and must be ordered by the caller.
+ */
+#define PO_STATIC_MAX_TENSORS 1024
+#define PO_STATIC_MAX_CHUNKS 65536
+int pipeoptim_step_predict_static(int64_t n_tensors, const int64_t* numel, float* const* W, const float* const* g,
+                                  float* const* m, float* const* v, void* const* What, int32_t what_dtype,
+                                  const po_hyper* hyper, int64_t t, int32_t s, void* hip_stream);
+
+/*
  * Prediction alone, from the cached optimizer state: how paper Algorithm 1 sequences it (cached
  * state -> dW_t by Table 1 -> Eq. 5, ahead of the forward pass), for callers whose optimizer step
  * ran elsewhere or that need What again for another s.  Reads W, m (, v); reads no gradient;

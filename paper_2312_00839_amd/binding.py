@@ -59,8 +59,9 @@ EXPORTS = (
     "pipeoptim_arena_create", "pipeoptim_arena_alloc", "pipeoptim_arena_set_skew", "pipeoptim_arena_near_half",
     "pipeoptim_arena_info", "pipeoptim_arena_check", "pipeoptim_arena_destroy", "pipeoptim_plan_localize", "pipeoptim_plan_effective_launch",
     "pipeoptim_local_tile", "pipeoptim_local_slot", "pipeoptim_plan_local_params", "pipeoptim_plan_launch_phase",
-    "pipeoptim_device_sync_count",
+    "pipeoptim_device_sync_count", "pipeoptim_step_predict_static",
 )
+PO_STATIC_MAX_TENSORS, PO_STATIC_MAX_CHUNKS = 1024, 65536
 
 _lib = None
 
@@ -80,6 +81,7 @@ def lib():
         L.pipeoptim_plan_destroy.argtypes = [vp]
         L.pipeoptim_plan_set_pointers.argtypes = [vp, i32, P(vp), vp]
         L.pipeoptim_device_sync_count.argtypes = [P(i64)]
+        L.pipeoptim_step_predict_static.argtypes = [i64, P(i64), P(vp), P(vp), P(vp), P(vp), P(vp), i32, P(po_hyper), i64, i32, vp]
         L.pipeoptim_plan_get_launch.argtypes = [vp, P(po_launch)]
         L.pipeoptim_plan_set_launch.argtypes = [vp, P(po_launch)]
         L.pipeoptim_plan_info.argtypes = [vp, P(i64), P(i64), P(i64)]
@@ -345,6 +347,20 @@ def pipeoptim_device_sync_count() -> int:
     n = ctypes.c_int64(-1)
     _check(lib().pipeoptim_device_sync_count(ctypes.byref(n)))
     return n.value
+
+
+def pipeoptim_step_predict_static(numel: Sequence[int], W: Sequence[int], g: Sequence[int], m: Optional[Sequence[int]],
+                                  v: Optional[Sequence[int]], What: Sequence[int], what_dtype, hyper: po_hyper,
+                                  t: int, s: int, stream: int = 0) -> None:
+    """The fused call without a plan and without any allocation (tables in the library's fixed device array)."""
+    if isinstance(what_dtype, str):
+        what_dtype = WHAT_DTYPES[what_dtype]
+    n = len(numel)
+    numel_arr = (ctypes.c_int64 * max(n, 1))(*numel)
+    _check(lib().pipeoptim_step_predict_static(
+        n, numel_arr, _ptr_array(W), _ptr_array(g), _ptr_array(m) if m is not None else None,
+        _ptr_array(v) if v is not None else None, _ptr_array(What), int(what_dtype), ctypes.byref(hyper),
+        int(t), int(s), ctypes.c_void_p(stream)))
 
 
 def pipeoptim_probe_copy(dst: int, src: int, nbytes: int, stream: int = 0) -> None:

@@ -11,7 +11,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libpipeoptim.so")
-SOURCES = ["pipeoptim.hip", "step_predict_kernels.hip", "near_arena.hip"]
+SOURCES = ["pipeoptim.hip", "step_predict_kernels.hip", "near_arena.hip", "static_tables.hip"]
 
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wextra",

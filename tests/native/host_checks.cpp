@@ -115,6 +115,32 @@ int main()
     EXPECT(pipeoptim_device_sync_count(&syncs) == PO_OK && syncs == 0);
     EXPECT(pipeoptim_device_sync_count(nullptr) == PO_EINVAL);
 
+    // the allocation-free entry point: every limit and argument check comes before the first device call
+    EXPECT(pipeoptim_step_predict_static(1, one, W, g, m, v, overlapping, PO_WHAT_F32, &h, 1, 1, nullptr) == PO_EINVAL);
+    EXPECT(pipeoptim_step_predict_static(1, one, W, g, m, v, odd, PO_WHAT_BF16, &h, 1, 1, nullptr) == PO_EALIGN);
+    EXPECT(pipeoptim_step_predict_static(1, one, W, g, m, nullptr, Wh, PO_WHAT_F32, &h, 1, 1, nullptr) == PO_EINVAL);   // AdamW needs v
+    EXPECT(pipeoptim_step_predict_static(1, one, W, g, m, v, Wh, PO_WHAT_F32, &h, 0, 1, nullptr) == PO_EINVAL);         // t < 1
+    EXPECT(pipeoptim_step_predict_static(1, one, W, g, m, v, Wh, PO_WHAT_F32, nullptr, 1, 1, nullptr) == PO_EINVAL);
+    EXPECT(pipeoptim_step_predict_static(0, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, PO_WHAT_F32, &h, 1, 1, nullptr) == PO_OK);
+    {
+        const int64_t too_many = PO_STATIC_MAX_TENSORS + 1;
+        std::vector<int64_t> zeros((size_t)too_many, 0);
+        std::vector<float*> nul((size_t)too_many, nullptr);
+        std::vector<void*> nulv((size_t)too_many, nullptr);
+        EXPECT(pipeoptim_step_predict_static(too_many, zeros.data(), nul.data(), const_cast<const float* const*>(nul.data()), nul.data(),
+                                             nul.data(), nulv.data(), PO_WHAT_F32, &h, 1, 1, nullptr) == PO_EINVAL);
+        EXPECT(std::strstr(pipeoptim_last_error(), "at most") != nullptr);
+        // one tensor that needs more chunk-table entries than the static table holds (addresses far apart, never touched)
+        int64_t huge[1] = {(int64_t)PO_STATIC_MAX_CHUNKS * 65536 + 1};
+        float* bW[1] = {reinterpret_cast<float*>(uintptr_t(1) << 40)};
+        const float* bg[1] = {reinterpret_cast<const float*>(uintptr_t(2) << 40)};
+        float* bm[1] = {reinterpret_cast<float*>(uintptr_t(3) << 40)};
+        float* bv[1] = {reinterpret_cast<float*>(uintptr_t(4) << 40)};
+        void* bh[1] = {reinterpret_cast<void*>(uintptr_t(5) << 40)};
+        EXPECT(pipeoptim_step_predict_static(1, huge, bW, bg, bm, bv, bh, PO_WHAT_BF16, &h, 1, 1, nullptr) == PO_EINVAL);
+        EXPECT(std::strstr(pipeoptim_last_error(), "chunk-table entries") != nullptr);
+    }
+
     std::printf("host checks passed\n");
     return 0;
 }

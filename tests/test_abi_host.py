@@ -304,6 +304,27 @@ def test_overlapping_buffers_are_rejected_before_any_device_call():
         L.pipeoptim_plan_destroy(h)
 
 
+def test_static_entry_point_rejects_what_it_cannot_hold_before_any_device_call():
+    L = binding.lib()
+    hyper = binding.make_hyper("adamw", 1e-3, 0.9, 0.999, 1e-8, 0.01)
+    vp = ctypes.c_void_p
+    n = binding.PO_STATIC_MAX_TENSORS + 1
+    zeros = (ctypes.c_int64 * n)()
+    nul = (vp * n)()
+    rc = L.pipeoptim_step_predict_static(n, zeros, nul, nul, nul, nul, nul, 0, ctypes.byref(hyper), 1, 1, None)
+    assert rc == binding.PO_EINVAL and "at most" in binding.pipeoptim_last_error()
+    huge = (ctypes.c_int64 * 1)(binding.PO_STATIC_MAX_CHUNKS * 65536 + 1)
+    col = lambda k: (vp * 1)(vp(k << 40))
+    rc = L.pipeoptim_step_predict_static(1, huge, col(1), col(2), col(3), col(4), col(5), 1, ctypes.byref(hyper), 1, 1, None)
+    assert rc == binding.PO_EINVAL and "chunk-table entries" in binding.pipeoptim_last_error()
+    one = (ctypes.c_int64 * 1)(8)
+    rc = L.pipeoptim_step_predict_static(1, one, col(1), col(2), col(3), None, col(5), 0, ctypes.byref(hyper), 1, 1, None)
+    assert rc == binding.PO_EINVAL                       # AdamW without v
+    rc = L.pipeoptim_step_predict_static(1, one, col(1), col(2), col(3), col(4), col(1), 0, ctypes.byref(hyper), 1, 1, None)
+    assert rc == binding.PO_EINVAL and "overlap" in binding.pipeoptim_last_error()
+    assert L.pipeoptim_step_predict_static(0, None, None, None, None, None, None, 0, ctypes.byref(hyper), 1, 1, None) == binding.PO_OK
+
+
 def test_device_sync_counter_and_set_pointers_argument_checks():
     L = binding.lib()
     assert L.pipeoptim_device_sync_count(None) == binding.PO_EINVAL

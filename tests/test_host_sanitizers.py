@@ -23,7 +23,7 @@ def test_host_entry_points_under_asan_ubsan(tmp_path):
            "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
            "-I", os.path.join(ROOT, "include"), "-I", CSRC,
            os.path.join(CSRC, "pipeoptim.hip"), os.path.join(CSRC, "step_predict_kernels.hip"),
-           os.path.join(CSRC, "near_arena.hip"),
+           os.path.join(CSRC, "near_arena.hip"), os.path.join(CSRC, "static_tables.hip"),
            os.path.join(ROOT, "tests", "native", "host_checks.cpp"), "-o", exe]
     build = subprocess.run(cmd, capture_output=True, text=True)
     assert build.returncode == 0, build.stderr[-3000:]
