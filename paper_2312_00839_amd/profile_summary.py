@@ -62,7 +62,7 @@ def traffic(args):
         factor = (COPY_BYTES / 1024.0) / cval
         nbytes = kval * 1024.0 * factor
         total += nbytes
-        out.append("  %-10s %s: %.1f KiB per dispatch over %d dispatches" % (counter, kname.split("(")[0].replace("void (anonymous namespace)::", ""), kval, kn))
+        out.append("  %-10s %s: %.1f KiB per dispatch over %d dispatches" % (counter, kname.replace("(anonymous namespace)::", "").replace("void ", "").split("(")[0], kval, kn))
         out.append("  %-10s %s (moves 4 GiB each way = 4194304 KiB): %.1f KiB over %d dispatches -> scale factor %.6f"
                    % (counter, COPY_KERNEL, cval, cn, factor))
         out.append("  %-10s scaled: %.0f bytes per launch" % (counter, nbytes))
@@ -82,7 +82,7 @@ def trace(args):
         sys.exit("trace: expected exactly one kernel matching %r, found %d" % (args.kernel, len(rows)))
     r = rows[0]
     avg = float(r["AverageNs"])
-    print("  %s" % r["Name"].split("(")[0].replace("void (anonymous namespace)::", ""))
+    print("  %s" % r["Name"].replace("(anonymous namespace)::", "").replace("void ", "").split("(")[0])
     print("  calls %s  average %.1f us  min %.1f us  max %.1f us  stddev %.1f us"
           % (r["Calls"], avg / 1e3, float(r["MinNs"]) / 1e3, float(r["MaxNs"]) / 1e3, float(r["StdDev"]) / 1e3))
     gbps = args.algorithmic_bytes / avg
