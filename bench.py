@@ -69,11 +69,11 @@ def measured_traffic(variant):
         if not fn.endswith(".txt"):
             continue
         text = open(os.path.join(pdir, fn)).read()
-        sha = re.search(r"^kernel_source_sha256:\s*([0-9a-f]{64})", text, re.M)
-        for m in re.finditer(r"^traffic_bytes_per_launch\s+variant=(\S+)\s+bytes=(\d+)", text, re.M):
+        # each traffic line is followed (within its block) by the fingerprint of the kernel source it was taken from
+        for m in re.finditer(r"^traffic_bytes_per_launch\s+variant=(\S+)\s+bytes=(\d+)\s*\nkernel_source_sha256:\s*([0-9a-f]{64})", text, re.M):
             if m.group(1) != variant:
                 continue
-            if sha and sha.group(1) == want_sha:
+            if m.group(3) == want_sha:
                 return int(m.group(2)), "profiles/%s (rocprofv3 --pmc FETCH_SIZE, WRITE_SIZE; kernel source unchanged since)" % fn
             found_stale = "profiles/%s covers %s but was taken from other kernel source: not quoted" % (fn, variant)
     return None, found_stale or "no rocprofv3 counter summary under profiles/ for %s" % variant
