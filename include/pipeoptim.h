@@ -29,6 +29,7 @@
  *     waits.  No call that a training loop makes per step (pipeoptim_step_predict, pipeoptim_predict,
  *     pipeoptim_plan_set_pointers) waits for the device or for a stream; the set-up calls that do say so.
  *   - On failure nothing is launched and pipeoptim_last_error() describes it.
+ *   - Calls on one plan (or one arena) must not overlap in time: give each host thread its own plan, or serialise.
  */
 #ifndef PIPEOPTIM_H
 #define PIPEOPTIM_H
@@ -136,7 +137,9 @@ typedef struct po_plan po_plan;   /* opaque */
  * path for that tensor.  The tables are uploaded with one asynchronous copy each, enqueued on `hip_stream`
  * from pinned staging memory that the plan owns: the call does not wait for the device or for the stream.
  * A later launch of the plan on another stream is made to wait for the upload by the library (an event), so
- * the plan can be used on any stream of the device right away.
+ * the plan can be used on any stream of the device right away.  (That wait is an ordinary hipStreamWaitEvent: the
+ * first launch on a stream other than the upload's must not be recorded under stream capture; launch once before
+ * capturing, or create the plan on the stream that will be captured.)
  * The caller keeps all buffers alive and at the same addresses while the plan lives.
  */
 int pipeoptim_plan_create(po_plan** out, int64_t n_tensors, const int64_t* numel,

@@ -370,6 +370,35 @@ def test_set_pointers_between_steps_is_stream_ordered_and_waits_for_nothing():
     torch.cuda.synchronize()
 
 
+def test_set_pointers_on_one_stream_is_seen_by_a_launch_on_another():
+    # the upload of new pointers is queued on stream A behind long-running work; a step enqueued right away on stream
+    # B must wait for it (the library orders B behind the upload's event) and so use the NEW gradients
+    _say("set_pointers on stream A, step on stream B")
+    kind, hp = "adam", HP["adam"]
+    t = _rand_list([200000, 513], 62, kind)
+    new_g = [torch.randn_like(x) * 1e-3 for x in t["g"]]
+    host = [{"W": t["W"][i].cpu().numpy().copy(), "g": new_g[i].cpu().numpy().copy(),
+             "m": t["m"][i].cpu().numpy().copy(), "v": t["v"][i].cpu().numpy().copy()} for i in range(2)]
+    A, B = torch.cuda.Stream(), torch.cuda.Stream()
+    with torch.cuda.stream(A):
+        st = Stage(t["W"], t["g"], t["m"], t["v"], "f32")
+    torch.cuda.synchronize()
+    a = torch.randn(4096, 4096, device=DEV)
+    with torch.cuda.stream(A):
+        for _ in range(100):                       # about a hundred milliseconds in front of the upload
+            a = (a @ a).mul_(1e-3)
+        st.plan.set_pointers(1, [x.data_ptr() for x in new_g], A.cuda_stream)
+    with torch.cuda.stream(B):
+        st.step_predict(make_hyper(kind, hp), 3, 2)
+    torch.cuda.synchronize()
+    for i in range(2):
+        ref = run_oracle(kind, hp, 3, 2, host[i])
+        got = {"W": st.W[i].cpu().numpy(), "m": st.m[i].cpu().numpy(), "v": st.v[i].cpu().numpy(),
+               "What": st.What[i].cpu().numpy()}
+        compare(kind, hp, 3, 2, host[i], ref, got, "f32", "cross-stream set_pointers %d" % i)
+    st.close()
+
+
 # --------------------------------------------------------------------------- optimizers beyond Table 1
 @pytest.mark.parametrize("kind", BEYOND)
 @pytest.mark.parametrize("what_dtype", ["f32", "bf16"])

@@ -81,6 +81,45 @@ def test_static_entry_point_equals_plan_call_on_two_calls_in_a_row():
     _run_both("adamw", adamw, big, 73, "f32", 7, 0)
 
 
+def test_static_entry_point_under_graph_capture():
+    # one of the callers it is for: recorded into a graph (nothing it does allocates or waits), every replay equal to
+    # an eager plan-based call from the same state; eager work and synchronisation between the replays
+    kind = "adamw"
+    hp = dict(lr=1e-3, beta1=0.9, beta2=0.999, eps=1e-8, weight_decay=0.01)
+    sizes = [70001, 0, 513, 65536 * 2 + 3]
+    a = _inputs(sizes, 81, True)
+    b = _clone(a)
+    hyper = make_hyper(kind, hp)
+    sa = Stage(a["W"], a["g"], a["m"], a["v"], "bf16")
+    What_b = [torch.zeros(n, dtype=torch.bfloat16, device=DEV) for n in sizes]
+    ptrs = lambda lst: [x.data_ptr() for x in lst]
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    graph = torch.cuda.CUDAGraph()
+
+    def static_call():
+        binding.pipeoptim_step_predict_static(sizes, ptrs(b["W"]), ptrs(b["g"]), ptrs(b["m"]), ptrs(b["v"]), ptrs(What_b),
+                                              "bf16", hyper, 12, 3, torch.cuda.current_stream().cuda_stream)
+
+    with torch.cuda.stream(side):
+        static_call()                                # warm-up outside the capture (counts as replay 0)
+        torch.cuda.synchronize()
+        with torch.cuda.graph(graph, stream=side):
+            static_call()
+    torch.cuda.current_stream().wait_stream(side)
+    sa.step_predict(hyper, 12, 3)
+    for replay in range(4):
+        graph.replay()
+        sa.step_predict(hyper, 12, 3)
+        torch.cuda.synchronize()
+        x = torch.randn(1 << 20, device=DEV).sum().item()      # unrelated eager work between replays
+        assert np.isfinite(x)
+        for i in range(len(sizes)):
+            for u, w in ((sa.W[i], b["W"][i]), (sa.m[i], b["m"][i]), (sa.v[i], b["v"][i]), (sa.What[i], What_b[i])):
+                assert torch.equal(_bits(u), _bits(w)), (replay, i)
+    sa.close()
+
+
 def test_static_entry_point_limits_and_errors_launch_nothing():
     x = torch.zeros(5 * 64, device=DEV)
     p = [[x[k * 64:(k + 1) * 64].data_ptr()] for k in range(5)]
