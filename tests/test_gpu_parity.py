@@ -158,6 +158,35 @@ def test_ragged_list_every_launch_shape(kind, what_dtype, launch):
     run_and_compare_full(kind, HP[kind], 100, 3, tensors, what_dtype, launch=launch, label="ragged")
 
 
+def test_list_of_thousands_of_small_tensors():
+    # 3,000 tensors of 0..3,000 elements carved out of four flat buffers (so most bases are not 16-byte aligned):
+    # a long descriptor table, a chunk table with one ragged entry per tensor, both access paths
+    _say("3000 small tensors")
+    rng = np.random.default_rng(4711)
+    sizes = [int(x) for x in rng.integers(0, 3001, size=3000)]
+    sizes[17] = 0
+    total = sum(sizes)
+    gen = torch.Generator(device=DEV)
+    gen.manual_seed(4712)
+    flat = {"W": torch.randn(total, generator=gen, device=DEV) * 0.02, "g": torch.randn(total, generator=gen, device=DEV) * 1e-3,
+            "m": torch.randn(total, generator=gen, device=DEV) * 1e-4, "v": (torch.randn(total, generator=gen, device=DEV) * 1e-3) ** 2}
+    cuts = np.concatenate([[0], np.cumsum(sizes)])
+    tensors = {k: [x[cuts[i]:cuts[i + 1]] for i in range(len(sizes))] for k, x in flat.items()}
+    host = {k: x.cpu().numpy().copy() for k, x in flat.items()}
+    stage = Stage(tensors["W"], tensors["g"], tensors["m"], tensors["v"], "bf16")
+    info = stage.plan.info()
+    assert info["n_params"] == total and info["n_chunks"] == sum(1 for n in sizes if n) and info["n_unaligned"] > 1000
+    stage.step_predict(make_hyper("adamw", HP["adamw"]), 20, 3)
+    torch.cuda.synchronize()
+    # the tensors are slices of the flat buffers: compare those in one go; What per tensor (each has a buffer of its own)
+    ref = run_oracle("adamw", HP["adamw"], 20, 3, host)
+    What = np.concatenate([what_bits(h) for h in stage.What]) if total else np.zeros(0, np.uint16)
+    got = {"W": flat["W"].cpu().numpy(), "m": flat["m"].cpu().numpy(), "v": flat["v"].cpu().numpy(), "What": What}
+    compare("adamw", HP["adamw"], 20, 3, host, ref, got, "bf16", "3000 tensors")
+    assert np.array_equal(flat["g"].cpu().numpy().view(np.uint32), host["g"].view(np.uint32))
+    stage.close()
+
+
 @pytest.mark.parametrize("kind", ["sgdm", "adamw"])
 @pytest.mark.parametrize("what_dtype", ["f32", "bf16"])
 @pytest.mark.parametrize("offset", [1, 2, 3])
@@ -778,6 +807,28 @@ def test_config3_fp32_prediction_full():
 @pytest.mark.parametrize("layout", ["packed", "local"])
 def test_config5_fp32_prediction_full(layout):
     _full_config(5, 7, layout=layout, what_dtype="f32")
+
+
+@pytest.mark.parametrize("chunk_elems", [4096, 1 << 20])
+def test_config4_full_under_other_chunk_sizes(chunk_elems):
+    # the chunk table's granularity changes which workgroup takes which tile, never a result: config 4 in full with
+    # the finest granularity the near-memory order allows and with a coarse one
+    import dataclasses  # noqa: F401
+    from parity_util import compare_stage_streamed
+    wl = workload(4)
+    _say("config 4 full compare, chunk_elems %d" % chunk_elems)
+    tensors = make_inputs(wl, DEV)
+    before = {k: [x.clone() for x in tensors[k]] for k in ("W", "g", "m", "v")}
+    stage = Stage(tensors["W"], tensors["g"], tensors["m"], tensors["v"], wl.what_dtype)
+    try:
+        stage.plan.set_launch(chunk_elems=chunk_elems)
+        stage.step_predict(make_hyper(wl.optimizer, wl.hyper), wl.t, 5)
+        torch.cuda.synchronize()
+        rep = compare_stage_streamed(wl.optimizer, wl.hyper, wl.t, 5, before, stage, wl.what_dtype, label="config 4 chunk %d" % chunk_elems)
+    finally:
+        stage.close()
+    assert rep["elements_compared"] == wl.n_params
+    _check_over_1ulp(4, 5, "fused", rep, wl.what_dtype)
 
 
 def test_config5_s0_prediction_is_rounded_W_everywhere():

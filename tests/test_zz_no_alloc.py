@@ -81,6 +81,17 @@ def test_static_entry_point_equals_plan_call_on_two_calls_in_a_row():
     _run_both("adamw", adamw, big, 73, "f32", 7, 0)
 
 
+def test_static_entry_point_at_its_tensor_limit():
+    # exactly PO_STATIC_MAX_TENSORS tensors (22 batches of descriptors, every lane of the table-building workgroup
+    # busy), small ragged sizes with empty ones in between and two multi-chunk tensors
+    rng = np.random.default_rng(99)
+    sizes = [int(x) for x in rng.integers(0, 700, size=binding.PO_STATIC_MAX_TENSORS)]
+    sizes[0], sizes[500], sizes[1023] = 0, 5 * 65536 + 9, 65536
+    sgdm = dict(lr=0.1, beta1=0.9, beta2=0.0, eps=0.0, weight_decay=1e-4)
+    print("[no-alloc] %d tensors, %d parameters" % (len(sizes), sum(sizes)), flush=True)
+    _run_both("sgdm", sgdm, sizes, 74, "bf16", 3, 2)
+
+
 def test_static_entry_point_under_graph_capture():
     # one of the callers it is for: recorded into a graph (nothing it does allocates or waits), every replay equal to
     # an eager plan-based call from the same state; eager work and synchronisation between the replays
