@@ -1,6 +1,7 @@
 // Host side of libpipeoptim: the C ABI declared in include/pipeoptim.h.
 //
-// Holds the plan (tensor descriptors + chunk table, mirrored on the device), the
+// Holds the plan (tensor descriptors + chunk table, mirrored on the device and
+// uploaded on the caller's stream from pinned staging memory), the
 // derivation of the fp32 kernel coefficients from the double hyper-parameters
 // (bias corrections of paper Table 1 in fp64), the version-difference rule of
 // paper Eq. 4, and argument validation.  The kernels live in
@@ -130,6 +131,7 @@ struct po_plan {
     hipEvent_t ev_upload = nullptr;            // one of ev_descs, or ev_chunks
     hipEvent_t ev_chunks = nullptr;
     hipStream_t upload_stream = nullptr;
+    bool uploaded = false;                     // an upload was ever enqueued (upload_stream is meaningful)
     mutable hipStream_t ordered_stream = nullptr;
     mutable hipStream_t last_launch_stream = nullptr;
     mutable bool launched = false;
@@ -294,13 +296,21 @@ int wait_for_plan_streams(const po_plan* p)
 {
     hipError_t e = hipSuccess;
     if (p->launched) e = hipStreamSynchronize(p->last_launch_stream);
-    if (e == hipSuccess && p->ev_upload && p->upload_stream != p->last_launch_stream) e = hipStreamSynchronize(p->upload_stream);
+    if (e == hipSuccess && p->uploaded && (!p->launched || p->upload_stream != p->last_launch_stream)) e = hipStreamSynchronize(p->upload_stream);
     if (e != hipSuccess) {
         (void)hipGetLastError();
         e = po_device_sync();
     }
     if (e != hipSuccess) return fail_hip(e, "waiting for the plan's streams");
     return PO_OK;
+}
+
+// Uploads form one chain: an upload on another stream than the previous one first makes its stream wait for the
+// previous upload, so that the copies land in call order and the latest event stands for all of them.
+hipError_t chain_behind_previous_upload(const po_plan* p, hipStream_t stream)
+{
+    if (p->ev_upload && stream != p->upload_stream) return hipStreamWaitEvent(stream, p->ev_upload, 0);
+    return hipSuccess;
 }
 
 // Copies the host descriptors into the staging buffer whose turn it is and enqueues its upload on `stream`.
@@ -311,15 +321,23 @@ int upload_descs(po_plan* p, hipStream_t stream)
     hipError_t e = hipSuccess;
     if (p->ev_recorded[k]) e = hipEventSynchronize(p->ev_descs[k]);      // the copy out of this buffer two uploads ago
     if (e != hipSuccess) return fail_hip(e, "hipEventSynchronize(staging buffer)");
+    e = chain_behind_previous_upload(p, stream);
+    if (e != hipSuccess) return fail_hip(e, "hipStreamWaitEvent(previous upload)");
     const size_t bytes = (size_t)p->n_tensors * sizeof(po_tensor_desc);
     std::memcpy(p->h_descs[k], p->descs.data(), bytes);
     e = hipMemcpyAsync(p->d_descs, p->h_descs[k], bytes, hipMemcpyHostToDevice, stream);
-    if (e != hipSuccess) return fail_hip(e, "hipMemcpyAsync(tensor descriptors)");
+    if (e != hipSuccess) return fail_hip(e, "hipMemcpyAsync(tensor descriptors)");      // nothing was enqueued
+    // From here on the device table WILL change, so the call must not fail any more: if the event cannot be
+    // recorded, wait for the copy instead (then neither the staging buffer nor another stream needs the event).
     e = hipEventRecord(p->ev_descs[k], stream);
-    if (e != hipSuccess) return fail_hip(e, "hipEventRecord(tensor descriptors)");
-    p->ev_recorded[k] = true;
+    p->ev_recorded[k] = (e == hipSuccess);
+    if (e != hipSuccess) {
+        (void)hipGetLastError();
+        (void)hipStreamSynchronize(stream);
+    }
     p->next_staging = k ^ 1;
-    p->ev_upload = p->ev_descs[k];
+    p->ev_upload = p->ev_recorded[k] ? p->ev_descs[k] : nullptr;
+    p->uploaded = true;
     p->upload_stream = stream;
     p->ordered_stream = stream;
     return PO_OK;
@@ -354,11 +372,17 @@ int upload_chunks(po_plan* p, hipStream_t stream)
     }
     if (n > 0) {
         std::memcpy(p->h_chunks, p->chunks.data(), (size_t)n * sizeof(po_chunk));
-        hipError_t e = hipMemcpyAsync(p->d_chunks, p->h_chunks, (size_t)n * sizeof(po_chunk), hipMemcpyHostToDevice, stream);
+        hipError_t e = chain_behind_previous_upload(p, stream);
+        if (e != hipSuccess) return fail_hip(e, "hipStreamWaitEvent(previous upload)");
+        e = hipMemcpyAsync(p->d_chunks, p->h_chunks, (size_t)n * sizeof(po_chunk), hipMemcpyHostToDevice, stream);
         if (e != hipSuccess) return fail_hip(e, "hipMemcpyAsync(chunk table)");
         e = hipEventRecord(p->ev_chunks, stream);
-        if (e != hipSuccess) return fail_hip(e, "hipEventRecord(chunk table)");
-        p->ev_upload = p->ev_chunks;
+        if (e != hipSuccess) {                       // as for the descriptors: wait for the copy instead
+            (void)hipGetLastError();
+            (void)hipStreamSynchronize(stream);
+        }
+        p->ev_upload = (e == hipSuccess) ? p->ev_chunks : nullptr;
+        p->uploaded = true;
         p->upload_stream = stream;
         p->ordered_stream = stream;
     }

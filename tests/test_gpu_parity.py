@@ -428,6 +428,37 @@ def test_set_pointers_on_one_stream_is_seen_by_a_launch_on_another():
     st.close()
 
 
+def test_uploads_on_different_streams_land_in_call_order():
+    # new gradient pointers on stream A (queued behind long-running work), then other ones on stream B right away:
+    # the second upload must land after the first (the library chains B behind A's upload), and a step on a third
+    # stream must see the pointers of the LAST call
+    _say("set_pointers on A then on B, step on C")
+    kind, hp = "sgdm", HP["sgdm"]
+    t = _rand_list([100000, 77], 63, kind)
+    g1 = [torch.randn_like(x) * 1e-2 for x in t["g"]]
+    g2 = [torch.randn_like(x) * 1e-2 for x in t["g"]]
+    host = [{"W": t["W"][i].cpu().numpy().copy(), "g": g2[i].cpu().numpy().copy(), "m": t["m"][i].cpu().numpy().copy()}
+            for i in range(2)]
+    A, B, C = torch.cuda.Stream(), torch.cuda.Stream(), torch.cuda.Stream()
+    with torch.cuda.stream(A):
+        st = Stage(t["W"], t["g"], t["m"], None, "f32")
+    torch.cuda.synchronize()
+    a = torch.randn(4096, 4096, device=DEV)
+    with torch.cuda.stream(A):
+        for _ in range(100):
+            a = (a @ a).mul_(1e-3)
+        st.plan.set_pointers(1, [x.data_ptr() for x in g1], A.cuda_stream)
+    st.plan.set_pointers(1, [x.data_ptr() for x in g2], B.cuda_stream)
+    with torch.cuda.stream(C):
+        st.step_predict(make_hyper(kind, hp), 1, 3)
+    torch.cuda.synchronize()
+    for i in range(2):
+        ref = run_oracle(kind, hp, 1, 3, host[i])
+        got = {"W": st.W[i].cpu().numpy(), "m": st.m[i].cpu().numpy(), "v": None, "What": st.What[i].cpu().numpy()}
+        compare(kind, hp, 1, 3, host[i], ref, got, "f32", "chained uploads %d" % i)
+    st.close()
+
+
 # --------------------------------------------------------------------------- optimizers beyond Table 1
 @pytest.mark.parametrize("kind", BEYOND)
 @pytest.mark.parametrize("what_dtype", ["f32", "bf16"])
