@@ -165,7 +165,8 @@ int pipeoptim_plan_destroy(po_plan* plan);
 /* Replace one pointer column (which: 0 W, 1 g, 2 m, 3 v, 4 What) with n_tensors new device pointers
  * (host array), e.g. when gradient buffers are re-allocated between steps.  May be called every step: the new
  * descriptors go to the device with one asynchronous copy enqueued on `hip_stream`, ordered like any other work
- * there (after the launches already enqueued on it, before the later ones); nothing is waited for.  Launches of
+ * there (after the launches already enqueued on it, before the later ones); nothing is waited for.  Uploads of one
+ * plan land in call order whatever streams they are issued on (each is chained behind the previous one).  Launches of
  * the plan enqueued afterwards on another stream wait for the copy (an event); launches enqueued BEFORE the call
  * on another stream and still running are the caller's to order, as for any write to memory a kernel reads.
  * On failure the plan is left exactly as it was.  Clears the near-memory marks (pipeoptim_plan_localize). */
