@@ -46,6 +46,7 @@ class StageOptimizer:
         self.s = binding.pipeoptim_version_difference(depth, rank)            # paper Eq. 4
         self.rank, self.depth = rank, depth
         self.t = 0                                                            # steps taken; the next step is t + 1
+        self._warned_moved = False
         if optimizer == "sgdm":
             b1, b2 = momentum, dampening
         elif optimizer == "nesterov":
@@ -110,13 +111,31 @@ class StageOptimizer:
         """W_{t+1} = W_t - lr*dW_t (Eq. 1) and What = W_t - lr*s*dW_t (Eq. 5), one kernel."""
         if self._swapped:
             raise RuntimeError("step() inside predicted_weights(): the parameters currently alias What")
+        moved = False
         for p, g, w in zip(self.params, self._g, self._W):
-            if p.grad is None or p.grad.data_ptr() != g.data_ptr():
-                raise RuntimeError("a parameter's .grad no longer is the buffer this optimizer gave it "
-                                   "(use zero_grad() of this class, or zero_grad(set_to_none=False))")
+            if p.grad is None:
+                raise RuntimeError("a parameter has no gradient: run the backward pass before step()")
+            moved = moved or p.grad.data_ptr() != g.data_ptr()
             if p.data_ptr() != w.data_ptr():
                 raise RuntimeError("a parameter's storage was replaced after this optimizer was created "
                                    "(e.g. by module.to() or by assigning .data): create the optimizer afterwards")
+        if moved:
+            # autograd put the gradients into buffers of its own (e.g. after zero_grad(set_to_none=True)): hand the new
+            # addresses to the plan, on the current stream, ahead of the step; nothing is waited for
+            new = []
+            for p in self.params:
+                gr = p.grad
+                if gr.dtype != torch.float32 or not gr.is_contiguous() or gr.device != p.device or gr.numel() != p.numel():
+                    raise RuntimeError("gradients must be contiguous fp32 tensors of the parameter's size on its device")
+                new.append(gr.view(-1))
+            if self._stage.n_local_params and not self._warned_moved:
+                warnings.warn("gradients left the near-memory arena: the step runs in the plain tile order from here on "
+                              "(keep the buffers this optimizer handed out, e.g. zero_grad(set_to_none=False), to avoid that)")
+                self._warned_moved = True
+            self._stage.plan.set_pointers(1, [x.data_ptr() for x in new], torch.cuda.current_stream().cuda_stream)
+            self._stage.n_local_params = 0
+            self._g = new
+            self._stage.g = new
         self.t += 1
         self._stage.step_predict(self.hyper, self.t, self.s)
 

@@ -67,6 +67,42 @@ def test_training_iterations_match_the_oracle(kind, kw, hp, arena):
     opt.close()
 
 
+def test_gradients_reallocated_every_iteration_are_followed():
+    # zero_grad(set_to_none=True) style: autograd allocates fresh gradient tensors in every backward pass; the optimizer
+    # re-points its plan at them each step (stream-ordered, no device-wide wait) and every step still matches the oracle
+    print("[gpu-stage-optimizer] gradients re-allocated every iteration", flush=True)
+    from paper_2312_00839_amd import binding
+    kind, kw, hp = CASES[0]                                          # AdamW
+    model = _mlp(13)
+    opt = StageOptimizer(model.parameters(), kind, rank=0, depth=3, arena=False, **kw)
+    x = torch.randn(64, 37, device=DEV)
+    y = torch.randn(64, 11, device=DEV)
+    torch.cuda.synchronize()
+    syncs = binding.pipeoptim_device_sync_count()
+    seen = set()
+    for it in range(4):
+        for p in model.parameters():
+            p.grad = None
+        with opt.predicted_weights():
+            loss = torch.nn.functional.mse_loss(model(x), y)
+        loss.backward()
+        seen.update(p.grad.data_ptr() for p in model.parameters())
+        st = opt.state()
+        before = [{"W": st["W"][i].cpu().numpy().copy(), "g": p.grad.view(-1).cpu().numpy().copy(),
+                   "m": st["m"][i].cpu().numpy().copy(), "v": st["v"][i].cpu().numpy().copy()}
+                  for i, p in enumerate(model.parameters())]
+        opt.step()
+        torch.cuda.synchronize()
+        st = opt.state()
+        for i, inp in enumerate(before):
+            ref = run_oracle(kind, hp, it + 1, opt.s, inp)
+            got = {"W": st["W"][i].cpu().numpy(), "m": st["m"][i].cpu().numpy(), "v": st["v"][i].cpu().numpy(),
+                   "What": st["What"][i].cpu().numpy()}
+            compare(kind, hp, it + 1, opt.s, inp, ref, got, "f32", "moving gradients iteration %d parameter %d" % (it, i))
+    assert binding.pipeoptim_device_sync_count() == syncs
+    opt.close()
+
+
 def test_forward_inside_the_block_uses_the_predicted_weights():
     model = _mlp(5)
     opt = StageOptimizer(model.parameters(), "adamw", lr=0.05, rank=0, depth=3)
@@ -110,7 +146,7 @@ def test_last_stage_and_misuse():
     for p in model.parameters():
         p.grad = None
     with pytest.raises(RuntimeError):
-        opt3.step()                                                     # gradient buffers were detached
+        opt3.step()                                                     # no gradients: the backward pass has not run
     opt4 = StageOptimizer(_mlp(9).parameters(), "adam", rank=0, depth=2)
     for p in opt4.params:
         p.data = p.data.clone()
