@@ -228,8 +228,8 @@ int pipeoptim_arena_destroy(po_arena* arena);
  * pipeoptim_arena_alloc call of `arena` (same layout class, 16 KiB aligned); both kernels then process such a
  * tensor in the near-memory tile order: of 16 consecutive workgroups (two rounds over the 8 XCCs, which take
  * workgroups round-robin) the eight on XCCs 0-3 take the 8 KiB block of each stream that lies on their die, the
- * other eight the other block.  Only with 256-element tiles (block 64, unroll 1), chunk_elems >= 4096 and
- * xcd_remap 0; any other launch shape, and every tensor not marked, keeps the plain order.  Results do not depend
+ * other eight the other block.  Only with 256-element tiles (block 64) and chunk_elems >= 4096; any other launch
+ * shape, and every tensor not marked, keeps the plain order.  Results do not depend
  * on the order.  arena == NULL clears all marks; pipeoptim_plan_set_pointers clears them too.  *n_local_params
  * (may be NULL) receives the number of parameters marked.
  * On which XCC a launch's round starts depends on the hardware queue behind the stream.  This call finds out for
@@ -238,8 +238,6 @@ int pipeoptim_arena_destroy(po_arena* arena);
  * launch with the old value (slower, never wrong) before it follows.  A set-up call: waits for hip_stream (the
  * tiny kernel's answer), not for the device; the descriptors are then uploaded on hip_stream like in
  * pipeoptim_plan_set_pointers.
- * A stage below 2^25 parameters whose prediction launch shape the caller never set gets 256-element tiles for that
- * kernel too when most of it is marked (its default there is bigger tiles, which the order is not defined for).
  */
 int pipeoptim_plan_localize(po_plan* plan, const po_arena* arena, void* hip_stream, int64_t* n_local_params);
 
@@ -322,7 +320,8 @@ int pipeoptim_step_predict_static(int64_t n_tensors, const int64_t* numel, float
  * With SGDM and the previous step's momentum it is SpecTrain's predictor (paper Eq. 6, first line).
  * Only the Table 1 optimizers have a direction that follows from the state alone; Nesterov, RMSprop and
  * Adagrad need the gradient and are rejected here (PO_EINVAL).
- * Enqueues exactly one kernel; uses the launch shape set with pipeoptim_plan_set_predict_launch.
+ * Enqueues exactly one kernel; uses the launch shape set with pipeoptim_plan_set_predict_launch (default: the
+ * fused kernel's default shape, with the occupancy cap chosen for this kernel).
  */
 int pipeoptim_predict(const po_plan* plan, const po_hyper* hyper, int64_t t, int32_t s, void* hip_stream);
 
