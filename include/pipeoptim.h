@@ -288,7 +288,8 @@ int pipeoptim_step_predict(const po_plan* plan, const po_hyper* hyper, int64_t t
  * For callers that cannot allocate: code under HIP graph capture, tight serving loops, harnesses that forbid
  * hipMalloc.  The same update as pipeoptim_step_predict, for a ragged list handed over in the call itself instead
  * of a plan (arguments as in pipeoptim_plan_create, fp32 gradients; hyper, t, s as in pipeoptim_step_predict).
- * The call allocates nothing, on the device or through HIP: the tensor descriptors and the chunk table that a
+ * The call allocates nothing on the device and calls no allocating HIP routine (its argument checks use a little
+ * ordinary host heap memory, freed before it returns): the tensor descriptors and the chunk table that a
  * plan keeps in memory of its own live here in a fixed device array inside the library (64 KiB + 512 KiB per
  * GPU the library runs on, held until the process ends).  The descriptors reach it inside kernel arguments, the
  * chunk table is built from them on the device, then the fused kernel runs: 2 + ceil(n_tensors / 48) small

@@ -4,7 +4,8 @@
 // allocates.  Here the same two tables live in a fixed device array that is part of the library's image
 // (`scratch` below): the descriptors travel to it inside kernel arguments (no copy from host memory, so no
 // staging buffer either), the chunk table is built from them on the device, and the fused kernel then runs
-// over the tables exactly as it does for a plan.  Nothing is allocated, on the device or through HIP.
+// over the tables exactly as it does for a plan.  Nothing is allocated on the device and no allocating HIP routine is
+// called (the argument checks use ordinary host heap memory).
 #include <cstddef>
 #include <cstring>
 #include <mutex>
