@@ -297,6 +297,79 @@ def test_nonfinite_values_in_the_bf16_prediction():
     st.close()
 
 
+@pytest.mark.parametrize("path", ["vector", "scalar"])
+def test_bf16_conversion_of_every_fp32_value(path):
+    # s = 0 makes What the bf16 rounding of W itself: feed ALL 2^32 fp32 bit patterns through the prediction-only call
+    # (SGDM: reads W, m, writes What), a quarter at a time, and compare every code with the oracle's rounding routine.
+    # "vector": 16-byte aligned bases (packed pair conversion); "scalar": bases off by one element (per-element path).
+    import oracle
+    from concurrent.futures import ThreadPoolExecutor
+    _say("bf16 conversion, all 2^32 fp32 patterns, %s path" % path)
+    n = 1 << 30
+    off = 0 if path == "vector" else 1
+    Wbuf = torch.empty(n + 4, dtype=torch.int32, device=DEV)
+    W = Wbuf[off:off + n].view(torch.float32)
+    m = torch.zeros(n + 4, device=DEV)[off:off + n]
+    g = torch.zeros(n + 4, device=DEV)[off:off + n]               # never read by the prediction-only call
+    st = Stage([W], [g], [m], None, "bf16")
+    assert st.plan.info()["n_unaligned"] == (0 if path == "vector" else 1)
+    hyper = make_hyper("sgdm", HP["sgdm"])
+    piece = 1 << 24
+    bad_total = 0
+
+    def check(args):
+        base, codes = args
+        bits = (np.arange(base, base + codes.size, dtype=np.int64) & 0xFFFFFFFF).astype(np.uint32)
+        x = bits.view(np.float32)
+        want = oracle.bf16_from_f32(x)
+        nan = (bits & 0x7FFFFFFF) > 0x7F800000
+        ok = (codes == want) | nan
+        # NaN: stays NaN, keeps its sign, comes out quiet
+        ok_nan = ((codes & 0x7F80) == 0x7F80) & ((codes & 0x007F) != 0) & ((codes & 0x8000) == (want & 0x8000)) & ((codes & 0x0040) != 0)
+        return int((~ok).sum() + (nan & ~ok_nan).sum())
+
+    with ThreadPoolExecutor(max_workers=min(16, os.cpu_count() or 1)) as pool:
+        for quarter in range(4):
+            Wbuf[off:off + n].copy_(torch.arange(quarter * n, (quarter + 1) * n, dtype=torch.int64, device=DEV).to(torch.int32)
+                                    if quarter < 2 else
+                                    (torch.arange(quarter * n, (quarter + 1) * n, dtype=torch.int64, device=DEV) - (1 << 32)).to(torch.int32))
+            st.predict(hyper, 1, 0)
+            torch.cuda.synchronize()
+            codes = what_bits(st.What[0])
+            bad = sum(pool.map(check, [(quarter * n + k, codes[k:k + piece]) for k in range(0, n, piece)]))
+            _say("  patterns [%d * 2^30, +2^30): %d codes differ from the oracle's" % (quarter, bad))
+            bad_total += bad
+    st.close()
+    assert bad_total == 0
+
+
+def test_every_bf16_gradient_pattern_is_widened_exactly():
+    # SGDM with u = 0, tau = 0, wd = 0 makes m' = g: with bf16 gradients m' must be the exact fp32 widening of every
+    # one of the 65,536 bf16 patterns (NaNs: still NaN, sign kept), on the vector and on the per-element path
+    import oracle
+    _say("bf16 gradient widening, all 65536 patterns")
+    hp = dict(lr=0.0, beta1=0.0, beta2=0.0, eps=0.0, weight_decay=0.0)
+    pats = torch.arange(0, 65536, dtype=torch.int32, device=DEV).to(torch.int16)
+    for off in (0, 1):
+        gbuf = torch.zeros(65536 + 8, dtype=torch.int16, device=DEV)
+        gbuf[off:off + 65536] = pats
+        g = gbuf[off:off + 65536].view(torch.bfloat16)
+        W = torch.zeros(65536 + 8, device=DEV)[off:off + 65536]
+        m = torch.ones(65536 + 8, device=DEV)[off:off + 65536]
+        st = Stage([W], [g], [m], None, "f32")
+        st.step_predict(make_hyper("sgdm", hp), 1, 1)
+        torch.cuda.synchronize()
+        got = st.m[0].cpu().numpy()
+        want = oracle.f32_from_bf16(np.arange(65536, dtype=np.uint32).astype(np.uint16))
+        nan = np.isnan(want)
+        # float equality: bit for bit except that -0 (which 0*m + g turns into +0) equals +0
+        assert np.array_equal(got[~nan], want[~nan]), "offset %d" % off
+        gb, wb = got.view(np.uint32), want.view(np.uint32)
+        assert np.array_equal(gb[(wb & 0x7FFFFFFF) != 0][:10], wb[(wb & 0x7FFFFFFF) != 0][:10])      # and really bit for bit
+        assert (np.isnan(got[nan]) & ((gb[nan] >> 31) == (wb[nan] >> 31))).all()
+        st.close()
+
+
 def test_two_steps_in_place_chain():
     # the state a call leaves in place is the next call's input: check the second of two chained calls
     # against the oracle started from the state the first call left on the device
