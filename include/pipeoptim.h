@@ -169,7 +169,8 @@ int pipeoptim_plan_destroy(po_plan* plan);
  * plan land in call order whatever streams they are issued on (each is chained behind the previous one).  Launches of
  * the plan enqueued afterwards on another stream wait for the copy (an event); launches enqueued BEFORE the call
  * on another stream and still running are the caller's to order, as for any write to memory a kernel reads.
- * On failure the plan is left exactly as it was.  Clears the near-memory marks (pipeoptim_plan_localize). */
+ * On failure the plan is left exactly as it was.  Clears the near-memory marks (pipeoptim_plan_localize).  Not meant
+ * to be recorded under stream capture: the two staging buffers are recycled with host-side waits on their events. */
 int pipeoptim_plan_set_pointers(po_plan* plan, int32_t which, void* const* ptrs, void* hip_stream);
 
 /* Get / set the launch shape of the fused kernel.  A set-up call: if chunk_elems changes, set rebuilds the
