@@ -35,6 +35,9 @@ def parse_args():
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--config", type=int, default=5, help="workload 1..5 (default: the 0.74B-parameter stage)")
+    ap.add_argument("--flat-params", type=int, default=0,
+                    help="instead of the config's tensor list: ONE flat tensor of this many parameters with the config's "
+                         "optimizer, scalars and value distributions (how the time scales with the stage size)")
     ap.add_argument("--mode", choices=("fused", "predict"), default="fused",
                     help="fused: optimizer step + prediction (the headline path); predict: prediction alone from cached state")
     ap.add_argument("--grad-dtype", choices=("f32", "bf16"), default="f32",
@@ -150,6 +153,8 @@ def main():
     torch.cuda.set_device(0)
 
     wl = workload(args.config)
+    if args.flat_params > 0:
+        wl = dataclasses.replace(wl, name="%s-flat-%d" % (wl.name, args.flat_params), shapes=[("flat", (args.flat_params,))])
     s_cfg = args.s if args.s >= 0 else wl.s_values[-1]
     D = args.pipeline_depth or (s_cfg + 1)
     rank = D - 1 - s_cfg
@@ -218,7 +223,8 @@ def main():
         per_launch_ms = sorted(events[i].elapsed_time(events[i + 1]) for i in range(K))
         avg_ms = sum(per_launch_ms) / K
         achieved = bytes_per_launch / (avg_ms * 1e-3) / 1e9
-        variant = "%s-config%d-%s-%s-g%s-h%s" % (args.mode, wl.config, wl.optimizer, layout.split()[0], args.grad_dtype, wl.what_dtype)
+        variant = "%s-config%d%s-%s-%s-g%s-h%s" % (args.mode, wl.config, "flat%d" % args.flat_params if args.flat_params else "",
+                                                   wl.optimizer, layout.split()[0], args.grad_dtype, wl.what_dtype)
         traffic, traffic_source = (None, "launch shape overridden: no summary applies") if launch_kw else measured_traffic(variant)
         res = {
             "layout": layout, "value": N * K / wall, "unit": "params/s", "steps": K, "warmup": args.warmup,
