@@ -8,11 +8,13 @@ updates W, m, v in place and writes the predicted weights What (paper Table 1,
 Eq. 1, Eq. 5).  The chunk table is built once per stage, before the timed region.
 
 Prints ONE JSON line.  `value` is parameters per second over the timed steps in the
-layout named in `config.workload`; `layouts` holds the same measurement (same steps,
+layout named in `config.workload` (by default the caller's own plain PyTorch allocations
+in the learnt tile order); `layouts` holds the same measurement (same steps,
 same warm-up, one event pair per launch, a roofline block of its own) for each
 memory layout that was run: "local" (all streams placed by the library's
-near-memory arena) and "packed" (separate plain PyTorch allocations, the layout a
-caller who owns its parameters has).  `roofline.achieved` is algorithmic HBM bytes
+near-memory arena), "packed" (separate plain PyTorch allocations, the layout a
+caller who owns its parameters has, in the plain tile order) and "learnt" (the same
+plain allocations after pipeoptim_plan_learn_layout has found each piece's die by timing).  `roofline.achieved` is algorithmic HBM bytes
 per launch divided by the kernel's average launch duration, measured with HIP events
 on the stream the kernel runs on; `cpu_baseline` is the CPU oracle timed on a bounded
 sample of the same workload on this machine's host cores (a reported baseline, not a target).
@@ -46,13 +48,14 @@ def parse_args():
                     help="element type of the predicted weights (default: the config's own)")
     ap.add_argument("--optimizer", default="", choices=("", "sgdm", "adam", "adamw", "nesterov", "rmsprop", "adagrad"),
                     help="run the config's tensor list under another optimizer (default: the config's own)")
-    ap.add_argument("--layout", choices=("local", "packed", "skewed"), default="local",
-                    help="the layout `value` is measured in.  local (default): all streams placed by the library's "
-                         "near-memory arena, every XCC working on its own die's HBM; packed: plain PyTorch allocations, "
-                         "back to back; skewed: plain allocations whose W, g, m, v buffers differ in address bits 12-13")
+    ap.add_argument("--layout", choices=("local", "packed", "learnt", "skewed"), default="learnt",
+                    help="the layout `value` is measured in.  learnt (default): separate plain PyTorch allocations, the "
+                         "caller's own memory, in the tile order the plan learns by timing them once "
+                         "(pipeoptim_plan_learn_layout); packed: the same allocations in the plain tile order; local: all "
+                         "streams placed by the library's near-memory arena, every XCC working on its own die's HBM; skewed: plain allocations whose W, g, m, v buffers differ in address bits 12-13")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-plain-compare", action="store_true",
-                    help="with --layout local: skip the peer measurement of the same workload in plain allocations")
+                    help="skip the peer measurements of the same workload in the other layouts")
     ap.add_argument("--no-copy-probe", action="store_true")
     ap.add_argument("--launch", default="", help="comma separated po_launch overrides, e.g. block=64,lds_bytes=16384")
     ap.add_argument("--s", type=int, default=-1, help="version difference to run with (default: the config's last s)")
@@ -185,7 +188,7 @@ def main():
     def measure(layout):
         """W warm-up steps, then exactly K timed steps with one event pair per launch, in `layout`."""
         try:
-            tensors = make_inputs(wl_inputs, dev, layout=layout, optimizer=opt)
+            tensors = make_inputs(wl_inputs, dev, layout="packed" if layout == "learnt" else layout, optimizer=opt)
         except binding.PipeOptimError as e:
             if layout != "local":
                 raise
@@ -196,9 +199,15 @@ def main():
         if args.grad_dtype == "bf16":
             tensors["g"] = [x.to(torch.bfloat16) for x in tensors["g"]]
         stage = Stage(tensors["W"], tensors["g"], tensors["m"], tensors["v"], wl.what_dtype,
-                      What=tensors.get("What"), arena=tensors.get("arena"))
+                      What=tensors.get("What"), arena=tensors.get("arena"), skew_what=layout != "learnt")
         if launch_kw:
             (stage.plan.set_predict_launch if predict_only else stage.plan.set_launch)(**launch_kw)
+        learn_ms = None
+        if layout == "learnt":                                        # a set-up step, outside the timed region like plan creation
+            torch.cuda.synchronize()
+            t_learn = time.perf_counter()
+            stage.n_local_params = stage.plan.learn_layout(stream.cuda_stream)
+            learn_ms = (time.perf_counter() - t_learn) * 1e3
         L = stage.plan.get_predict_launch() if predict_only else stage.plan.get_launch()
 
         def one_step(i):
@@ -236,9 +245,12 @@ def main():
                            lds_bytes_in_effect=stage.plan.effective_launch(
                                binding.PO_KERNEL_KIND_PREDICT if predict_only else binding.PO_KERNEL_KIND_FUSED,
                                wl.optimizer).lds_bytes),
-            "n_local_params": stage.n_local_params, "launch_phase": stage.plan.launch_phase(),
+            "n_local_params": stage.n_local_params, "near_share": stage.plan.near_share(),
+            "launch_phase": stage.plan.launch_phase(),
             "n_chunks": stage.plan.info()["n_chunks"],
         }
+        if learn_ms is not None:
+            res["learn_layout_ms"] = learn_ms
         stage.close()
         if tensors.get("stage_arena") is not None:
             tensors["stage_arena"].close()
@@ -248,11 +260,17 @@ def main():
 
     primary = measure(args.layout)
     layouts = {primary["layout"].split()[0]: primary}
-    if args.layout == "local" and primary["layout"] == "local" and not args.no_plain_compare:
-        layouts["packed"] = measure("packed")        # the same workload where the caller owns plain PyTorch allocations
+    if args.layout in ("learnt", "local") and not args.no_plain_compare:
+        # the same workload, same steps and warm-up, in the other layouts: plain allocations in the plain tile order,
+        # plain allocations in the learnt order, and the library's own placement
+        for peer in ("learnt", "packed", "local"):
+            if peer not in layouts:
+                res = measure(peer)
+                layouts.setdefault(res["layout"].split()[0], res)
 
     owner = {"local": "all five streams placed by the library's near-memory arena",
-             "packed": "separate plain PyTorch allocations (caller-owned memory)",
+             "packed": "separate plain PyTorch allocations (caller-owned memory), plain tile order",
+             "learnt": "separate plain PyTorch allocations (caller-owned memory), tile order learnt by timing them",
              "skewed": "plain PyTorch allocations with staggered address bits 12-13"}[primary["layout"].split()[0]]
     out = {
         "metric": "params/sec, weight prediction from cached state, 1 GPU" if predict_only
@@ -294,10 +312,11 @@ def main():
         copy_gbps = 2.0 * nbytes * reps / (e0.elapsed_time(e1) * 1e-3) / 1e9
         out["copy_kernel_GBps"] = copy_gbps
         out["frac_of_copy_kernel"] = achieved / copy_gbps
-        if "packed" in layouts and layouts["packed"] is not primary:
-            layouts["packed"]["frac_of_copy_kernel"] = layouts["packed"]["roofline"]["achieved"] / copy_gbps
+        for peer in layouts.values():
+            if peer is not primary:
+                peer["frac_of_copy_kernel"] = peer["roofline"]["achieved"] / copy_gbps
         del src, dst
-        if primary["layout"] == "local":
+        if layouts.get("local", {}).get("layout") == "local":
             # the same yardstick with both buffers in an arena and the near-memory tile order (best of three caps)
             half = 2 << 30
             ca = binding.Arena(5 << 30)
@@ -314,7 +333,7 @@ def main():
                 best = max(best, 2.0 * half * reps / (e0.elapsed_time(e1) * 1e-3) / 1e9)
             ca.destroy()
             out["copy_kernel_near_GBps"] = best
-            out["frac_of_copy_kernel_near"] = achieved / best
+            layouts["local"]["frac_of_copy_kernel_near"] = layouts["local"]["roofline"]["achieved"] / best
         torch.cuda.empty_cache()
 
     if not args.no_cpu_baseline:

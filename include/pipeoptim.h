@@ -13,7 +13,8 @@
  * pipeoptim_step_predict(plan, hyper, t, s, stream)  ->  pipeoptim_plan_destroy.  A caller that lets the library
  * place the stage's memory gets the pointers from pipeoptim_arena_create / pipeoptim_arena_alloc (one call per
  * tensor for its W, g, m, v, What buffers) and calls pipeoptim_plan_localize once after pipeoptim_plan_create: the
- * kernels then keep every XCC of the chip on its own I/O die's HBM (about 4 % faster on a large stage).
+ * kernels then keep every XCC of the chip on its own I/O die's HBM (about 4 % faster on a large stage).  A caller
+ * that places the memory itself calls pipeoptim_plan_learn_layout once instead (about 3 % faster).
  *
  * Conventions for every function
  *   - extern "C"; returns PO_OK (0) or a negative po_status; never throws.
@@ -169,7 +170,8 @@ int pipeoptim_plan_destroy(po_plan* plan);
  * plan land in call order whatever streams they are issued on (each is chained behind the previous one).  Launches of
  * the plan enqueued afterwards on another stream wait for the copy (an event); launches enqueued BEFORE the call
  * on another stream and still running are the caller's to order, as for any write to memory a kernel reads.
- * On failure the plan is left exactly as it was.  Clears the near-memory marks (pipeoptim_plan_localize).  Not meant
+ * On failure the plan is left exactly as it was.  Clears the near-memory marks of pipeoptim_plan_localize, and those of
+ * pipeoptim_plan_learn_layout unless only g or What move (see there).  Not meant
  * to be recorded under stream capture: the two staging buffers are recycled with host-side waits on their events. */
 int pipeoptim_plan_set_pointers(po_plan* plan, int32_t which, void* const* ptrs, void* hip_stream);
 
@@ -241,6 +243,36 @@ int pipeoptim_arena_destroy(po_arena* arena);
  * pipeoptim_plan_set_pointers.
  */
 int pipeoptim_plan_localize(po_plan* plan, const po_arena* arena, void* hip_stream, int64_t* n_local_params);
+
+/*
+ * The near-memory tile order for buffers the CALLER placed (e.g. plain PyTorch allocations): the library cannot choose
+ * where they lie, but it can find out.  Times a few loads in every whole 2 MiB piece of the plan's fp32 buffers (loads
+ * only: nothing is written; two independent timings per piece must agree), and then decides chunk by chunk of the
+ * chunk table which XCC half takes which 8 KiB block of each 16 KiB group: the assignment that makes more of the
+ * chunk's bytes near wins (W, m, v weigh 8 bytes per element, g and an fp32 What 4).  Where all streams of a chunk
+ * happen to agree every access is near, where they split two against two nothing is lost against the plain order,
+ * on average about two thirds of the traffic becomes near instead of half (measured on MI355X: 2-3 % faster than the
+ * plain order on large stages).  A stream takes part if its base address is a multiple of chunk_elems * 4 bytes;
+ * needs chunk_elems between 4096 and 524288 and 256-element tiles (block 64), as pipeoptim_plan_localize does.
+ * Results do not depend on the order.  A set-up call: waits for the device (the timing wants the memory system to
+ * itself), about 10 ms per GiB of buffers.  pipeoptim_plan_set_pointers of W, m or v, a chunk_elems change and
+ * pipeoptim_plan_localize drop what was learnt (learn again after them); new g or What pointers do not: the order was
+ * decided mostly by the three heavier streams and stays in force.  *n_local_params (may be NULL) receives the
+ * number of parameters in chunks that got an order of their own.
+ */
+int pipeoptim_plan_learn_layout(po_plan* plan, void* hip_stream, int64_t* n_local_params);
+
+/* Diagnostic: out[k] (k < capacity) = what pipeoptim_plan_learn_layout decided for chunk-table entry k: -1 plain order,
+ * 0 / 1 the XCC half near to the first 8 KiB block of every 16 KiB group of the chunk; *n_chunks = entries in the table. */
+int pipeoptim_plan_chunk_marks(const po_plan* plan, int8_t* out, int64_t capacity, int64_t* n_chunks);
+
+/* Diagnostic: *share = the estimated share of the fused call's HBM bytes that are served by the memory of the die the
+ * workgroup runs on: 0.5 in the plain order (every XCC's traffic is half near, half far), up to (all fp32 streams)
+ * / (all streams) + half of the bf16 streams for a plan localized over an arena (0.98 for AdamW with bf16 What), and
+ * what the votes of pipeoptim_plan_learn_layout added up to for a learnt order (0.71 when the four fp32 streams of each
+ * tensor lie independently; pieces whose layout could not be told count as half near).  As of the last
+ * pipeoptim_plan_localize / pipeoptim_plan_learn_layout call. */
+int pipeoptim_plan_near_share(const po_plan* plan, double* share);
 
 /* The XCC (0-7) on which the last launch of a localized plan that has reported so far started its round, i.e. the
  * value the next call will hand to its kernel; -1 for a plan that was never localized.  Does not wait for anything. */

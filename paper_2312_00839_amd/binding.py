@@ -59,7 +59,8 @@ EXPORTS = (
     "pipeoptim_arena_create", "pipeoptim_arena_alloc", "pipeoptim_arena_set_skew", "pipeoptim_arena_near_half",
     "pipeoptim_arena_info", "pipeoptim_arena_check", "pipeoptim_arena_destroy", "pipeoptim_plan_localize", "pipeoptim_plan_effective_launch",
     "pipeoptim_local_tile", "pipeoptim_local_slot", "pipeoptim_plan_local_params", "pipeoptim_plan_launch_phase",
-    "pipeoptim_device_sync_count", "pipeoptim_step_predict_static",
+    "pipeoptim_device_sync_count", "pipeoptim_step_predict_static", "pipeoptim_plan_learn_layout", "pipeoptim_plan_chunk_marks",
+    "pipeoptim_plan_near_share",
 )
 PO_STATIC_MAX_TENSORS, PO_STATIC_MAX_CHUNKS = 1024, 65536
 
@@ -104,6 +105,9 @@ def lib():
         L.pipeoptim_arena_destroy.argtypes = [vp]
         L.pipeoptim_plan_localize.argtypes = [vp, vp, vp, P(i64)]
         L.pipeoptim_plan_local_params.argtypes = [vp, P(i64)]
+        L.pipeoptim_plan_learn_layout.argtypes = [vp, vp, P(i64)]
+        L.pipeoptim_plan_chunk_marks.argtypes = [vp, P(ctypes.c_int8), i64, P(i64)]
+        L.pipeoptim_plan_near_share.argtypes = [vp, P(ctypes.c_double)]
         L.pipeoptim_plan_launch_phase.argtypes = [vp, P(i32)]
         L.pipeoptim_plan_effective_launch.argtypes = [vp, i32, i32, P(po_launch)]
         L.pipeoptim_local_tile.argtypes = [ctypes.c_uint32, i32, P(ctypes.c_uint32)]
@@ -306,6 +310,27 @@ class Plan:
         _check(lib().pipeoptim_plan_localize(self._h, arena._h if arena is not None else None,
                                              ctypes.c_void_p(stream), ctypes.byref(n)))
         return n.value
+
+    def learn_layout(self, stream: int = 0) -> int:
+        """Finds the die layout of the plan's (caller-placed) buffers by timing loads and gives every chunk the
+        near-memory tile order that suits it; returns the number of parameters in such chunks.  Blocking."""
+        n = ctypes.c_int64(0)
+        _check(lib().pipeoptim_plan_learn_layout(self._h, ctypes.c_void_p(stream), ctypes.byref(n)))
+        return n.value
+
+    def chunk_marks(self):
+        """Per chunk-table entry: -1 plain order, 0 / 1 the XCC half that takes the first block of each group."""
+        n = ctypes.c_int64(0)
+        _check(lib().pipeoptim_plan_chunk_marks(self._h, None, 0, ctypes.byref(n)))
+        buf = (ctypes.c_int8 * max(n.value, 1))()
+        _check(lib().pipeoptim_plan_chunk_marks(self._h, buf, n.value, ctypes.byref(n)))
+        return [buf[k] for k in range(n.value)]
+
+    def near_share(self) -> float:
+        """Estimated share of the fused call's HBM bytes served by the near die (0.5: plain order)."""
+        x = ctypes.c_double(0.0)
+        _check(lib().pipeoptim_plan_near_share(self._h, ctypes.byref(x)))
+        return x.value
 
     def launch_phase(self) -> int:
         """XCC on which the plan's last reported launch started its round (-1: never localized)."""

@@ -17,6 +17,7 @@
 // (W, g, m, v, What) have the same block-to-die layout at every element offset, and the fused kernel's
 // near-memory tile order (po_local_tile) makes all of their fp32 traffic local.
 #include <algorithm>
+#include <atomic>
 #include <cstdarg>
 #include <cstdio>
 #include <cstring>
@@ -35,25 +36,26 @@ constexpr int kRounds = 3;                          // timing rounds before a ha
 constexpr int kLinesPerRound = 4;
 constexpr size_t kBigBuffer = size_t(1) << 20;      // buffers from this size on are followed by the skew gap
 
-// One lane of workgroup 0 times cold loads: for region r (2 MiB, all nregions mapped from `base`) and block p
-// (0, 1) of the region's 16 KiB group number 3, lat[r*2 + p] = fastest of kLinesPerRound cache lines, a different
-// set of lines in every round.  Every address lies inside [base, base + nregions * 2 MiB).
-__global__ __launch_bounds__(64) void po_arena_probe_kernel(const char* base, uint32_t nregions, uint32_t round,
+// One lane of workgroup 0 times cold loads: for region r (2 MiB, all nregions readable from `base`) and block p
+// (0, 1) of the region's 16 KiB group number `group` (0..127), lat[r*2 + p] = fastest of kLinesPerRound cache lines, a
+// different set of lines in every round (round <= 3).  Every address lies inside [base, base + nregions * 2 MiB).
+__global__ __launch_bounds__(64) void po_arena_probe_kernel(const char* base, uint32_t nregions, uint32_t group, uint32_t round,
                                                             uint32_t* lat, uint32_t* xcc_out)
 {
     if (blockIdx.x != 0 || threadIdx.x != 0) return;
     xcc_out[0] = po_xcc_id();
     uint32_t acc = 0;
+    const uint32_t g = group & 127u, warm = (g + 50u) & 127u;
     for (uint32_t r = 0; r < nregions; ++r) {
         const char* reg = base + (size_t)r * kRegion;
         // address translation of the region, through a line that is never timed
-        acc += __builtin_nontemporal_load(reinterpret_cast<const uint32_t*>(reg + 100 * kAlign + 63 * 128));
+        acc += __builtin_nontemporal_load(reinterpret_cast<const uint32_t*>(reg + warm * kAlign + 63 * 128));
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
         for (uint32_t p = 0; p < 2; ++p) {
             uint32_t best = 0xFFFFFFFFu;
             for (uint32_t line = 0; line < (uint32_t)kLinesPerRound; ++line) {
-                const uint32_t l = round * 16u + line * 4u + 1u;                      // round <= 3: below the 64 lines of a block
-                const uint32_t* ptr = reinterpret_cast<const uint32_t*>(reg + 3 * kAlign + p * 8192u + l * 128u);
+                const uint32_t l = (round & 3u) * 16u + line * 4u + 1u;                // below the 64 lines of a block
+                const uint32_t* ptr = reinterpret_cast<const uint32_t*>(reg + g * kAlign + p * 8192u + l * 128u);
                 const uint64_t t0 = clock64();
                 const uint32_t v = __builtin_nontemporal_load(ptr);
                 asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
@@ -66,6 +68,8 @@ __global__ __launch_bounds__(64) void po_arena_probe_kernel(const char* base, ui
     }
     xcc_out[1] = acc;      // keeps the loads alive
 }
+
+constexpr uint32_t kArenaGroup = 3;                 // the 16 KiB group of a piece that the arena times
 
 size_t round_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
@@ -143,7 +147,7 @@ int grow_once(po_arena* a)
     std::vector<uint32_t> best0(n, 0xFFFFFFFFu), best1(n, 0xFFFFFFFFu), lat((size_t)n * 2);
     if (rc == PO_OK) {
         for (int round = 0; round < kRounds && rc == PO_OK; ++round) {
-            hipLaunchKernelGGL(po_arena_probe_kernel, dim3(8), dim3(64), 0, nullptr, a->staging, n, (uint32_t)round,
+            hipLaunchKernelGGL(po_arena_probe_kernel, dim3(8), dim3(64), 0, nullptr, a->staging, n, kArenaGroup, (uint32_t)round,
                                a->d_lat, a->d_lat + (size_t)kBatch * 2);
             hipError_t e = hipGetLastError();
             if (e == hipSuccess) e = po_device_sync();
@@ -212,6 +216,19 @@ int grow_once(po_arena* a)
 
 }  // namespace
 
+// The die layout rule (two dies' memory in alternating 8 KiB blocks, XCCs 0-3 near one, 4-7 near the other) is what
+// was measured on an MI355X running as one partition; nothing here is assumed of any other device.
+static int check_whole_mi355x(int device)
+{
+    hipDeviceProp_t dp;
+    hipError_t e = hipGetDeviceProperties(&dp, device);
+    if (e != hipSuccess) return po_fail(PO_EHIP, "hipGetDeviceProperties: %s", hipGetErrorString(e));
+    if (std::strncmp(dp.gcnArchName, "gfx950", 6) != 0 || dp.multiProcessorCount != 256)
+        return po_fail(PO_EINVAL, "the near-memory layout is defined for an MI355X in one partition (gfx950, 256 CUs); found %s with %d CUs",
+                       dp.gcnArchName, dp.multiProcessorCount);
+    return PO_OK;
+}
+
 int po_arena_class_of(const po_arena* a, const void* p, size_t bytes)
 {
     if (!a || !p) return -1;
@@ -222,6 +239,71 @@ int po_arena_class_of(const po_arena* a, const void* p, size_t bytes)
     }
     return -1;
 }
+
+// The die layout of memory the library did not place: for each of the n 2 MiB-aligned regions starting at `base`
+// (all readable device memory), out[i] = the XCC half (0: XCCs 0-3, 1: XCCs 4-7) near to the region's 8 KiB blocks with
+// address bit 13 clear, or -1 where it cannot be told.  A region's answer needs two timings in different parts of the
+// region (two 16 KiB groups that the arena's own timing never touches, up to kRounds rounds each) that both decide and
+// agree: that also covers a region whose physical memory is not one contiguous 2 MiB piece.  The timing needs loads
+// that miss the L2, and a line stays there after it was timed until other traffic evicts it: every call therefore
+// times another pair of groups (24 pairs in turn), so that learning again right after a change still works.
+// Only loads; waits for the device (the timing wants the memory system to itself).
+int po_probe_layout(const void* base, size_t n, int8_t* out)
+try {
+    if (n == 0) return PO_OK;
+    if (((uintptr_t)base & (kRegion - 1)) != 0) return po_fail(PO_EINVAL, "po_probe_layout: base is not 2 MiB aligned");
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess) return po_fail(PO_EHIP, "hipGetDevice failed");
+    int rc_dev = check_whole_mi355x(dev);
+    if (rc_dev != PO_OK) return rc_dev;
+    uint32_t* d_lat = nullptr;
+    hipError_t e = hipMalloc(reinterpret_cast<void**>(&d_lat), ((size_t)kBatch * 2 + 2) * 4);
+    if (e != hipSuccess) return po_fail(PO_ENOMEM, "hipMalloc(timing buffer): %s", hipGetErrorString(e));
+    int rc = PO_OK;
+    static std::atomic<uint32_t> epoch{0};
+    const uint32_t turn = epoch.fetch_add(1) % 24u;
+    const uint32_t groups[2] = {5u + 2u * turn, 69u + 2u * turn};         // 5..51 and 69..115: never the arena's 3 or 53
+    std::vector<uint32_t> lat((size_t)kBatch * 2);
+    for (size_t first = 0; first < n && rc == PO_OK; first += kBatch) {
+        const uint32_t cnt = (uint32_t)std::min<size_t>(kBatch, n - first);
+        int8_t answer[2][kBatch];
+        for (int gi = 0; gi < 2 && rc == PO_OK; ++gi) {
+            std::vector<uint32_t> best0(cnt, 0xFFFFFFFFu), best1(cnt, 0xFFFFFFFFu);
+            for (uint32_t i = 0; i < cnt; ++i) answer[gi][i] = -1;
+            for (int round = 0; round < kRounds; ++round) {
+                e = po_device_sync();
+                if (e == hipSuccess) {
+                    hipLaunchKernelGGL(po_arena_probe_kernel, dim3(8), dim3(64), 0, nullptr,
+                                       static_cast<const char*>(base) + first * kRegion, cnt, groups[gi], (uint32_t)round, d_lat,
+                                       d_lat + (size_t)kBatch * 2);
+                    e = hipGetLastError();
+                }
+                if (e == hipSuccess) e = po_device_sync();
+                if (e == hipSuccess) e = hipMemcpy(lat.data(), d_lat, (size_t)cnt * 2 * 4, hipMemcpyDeviceToHost);
+                uint32_t xcc = 0;
+                if (e == hipSuccess) e = hipMemcpy(&xcc, d_lat + (size_t)kBatch * 2, 4, hipMemcpyDeviceToHost);
+                if (e != hipSuccess) { rc = po_fail(PO_EHIP, "layout probe: %s", hipGetErrorString(e)); break; }
+                if (xcc > 7) { rc = po_fail(PO_EHIP, "layout probe: the timing wave reports XCC %u of a chip with 8", xcc); break; }
+                const int timing_half = (int)(xcc >> 2);
+                bool open = false;
+                for (uint32_t i = 0; i < cnt; ++i) {
+                    if (answer[gi][i] >= 0) continue;
+                    best0[i] = std::min(best0[i], lat[i * 2]);
+                    best1[i] = std::min(best1[i], lat[i * 2 + 1]);
+                    const uint32_t lo = std::min(best0[i], best1[i]), hi = std::max(best0[i], best1[i]);
+                    if ((hi - lo) * 6u >= lo) answer[gi][i] = (int8_t)(best0[i] < best1[i] ? timing_half : 1 - timing_half);
+                    else open = true;
+                }
+                if (!open) break;
+            }
+        }
+        for (uint32_t i = 0; i < cnt && rc == PO_OK; ++i)
+            out[first + i] = (answer[0][i] >= 0 && answer[0][i] == answer[1][i]) ? answer[0][i] : (int8_t)-1;
+    }
+    (void)hipFree(d_lat);
+    return rc;
+}
+catch (const std::bad_alloc&) { return po_fail(PO_ENOMEM, "po_probe_layout: out of host memory"); }
 
 extern "C" {
 
@@ -235,12 +317,8 @@ try {
     if (!a) return po_fail(PO_ENOMEM, "out of host memory");
     hipError_t e = hipGetDevice(&a->device);
     if (e != hipSuccess) return po_fail(PO_EHIP, "hipGetDevice: %s", hipGetErrorString(e));
-    hipDeviceProp_t dp;
-    e = hipGetDeviceProperties(&dp, a->device);
-    if (e != hipSuccess) return po_fail(PO_EHIP, "hipGetDeviceProperties: %s", hipGetErrorString(e));
-    if (std::strncmp(dp.gcnArchName, "gfx950", 6) != 0 || dp.multiProcessorCount != 256)
-        return po_fail(PO_EINVAL, "the near-memory arena is defined for an MI355X in one partition (gfx950, 256 CUs); found %s with %d CUs",
-                       dp.gcnArchName, dp.multiProcessorCount);
+    int rc_dev = check_whole_mi355x(a->device);
+    if (rc_dev != PO_OK) return rc_dev;
     const hipMemAllocationProp prop = device_prop(a->device);
     size_t gran = 0;
     e = hipMemGetAllocationGranularity(&gran, &prop, hipMemAllocationGranularityMinimum);
@@ -362,7 +440,7 @@ try {
             const uint32_t n = (uint32_t)std::min<size_t>(kBatch, regions - first);
             // cache lines that the sorting pass (rounds 0 .. kRounds-1) never touched, so that they are cold
             hipLaunchKernelGGL(po_arena_probe_kernel, dim3(8), dim3(64), 0, nullptr,
-                               a->va + (size_t)c * a->capacity + first * kRegion, n, (uint32_t)kRounds, a->d_lat,
+                               a->va + (size_t)c * a->capacity + first * kRegion, n, kArenaGroup, (uint32_t)kRounds, a->d_lat,
                                a->d_lat + (size_t)kBatch * 2);
             e = hipGetLastError();
             if (e == hipSuccess) e = po_device_sync();

@@ -9,11 +9,13 @@
 #include <algorithm>
 #include <atomic>
 #include <cmath>
+#include <cstdlib>
 #include <cstdarg>
 #include <cstdio>
 #include <cstring>
 #include <memory>
 #include <new>
+#include <utility>
 #include <vector>
 
 #include "po_internal.h"
@@ -103,6 +105,7 @@ struct po_plan {
     int64_t n_params = 0;
     int64_t n_unaligned = 0;
     int64_t n_local_params = 0;   // parameters of tensors that run in the near-memory tile order
+    double near_bytes = 0.0;      // of the fused call's bytes per launch, those known to be near beyond the plain order's half
     int32_t what_dtype = PO_WHAT_F32;
     int32_t grad_dtype = PO_GRAD_F32;
     bool has_v = false;
@@ -112,7 +115,12 @@ struct po_plan {
     po_launch predict_launch{};   // prediction-only kernel; chunk_elems always equals launch.chunk_elems
     std::vector<int64_t> numel;
     std::vector<po_tensor_desc> descs;    // host mirror
-    std::vector<po_chunk> chunks;         // host mirror
+    std::vector<po_chunk> chunks;         // host mirror (tensor indices without marks)
+    // Near-memory order decided chunk by chunk from the learnt die layout of caller-placed buffers
+    // (pipeoptim_plan_learn_layout): -1 plain order, 0 / 1 the XCC half near to the chunk's first 8 KiB blocks.
+    // Valid (and uploaded in the chunk table's top bits) only while chunk_marks_valid.
+    std::vector<int8_t> chunk_mark;
+    bool chunk_marks_valid = false;
     po_tensor_desc* d_descs = nullptr;
     po_chunk* d_chunks = nullptr;
     int64_t d_chunks_capacity = 0;
@@ -191,7 +199,7 @@ int po_describe_list(int64_t n_tensors, const int64_t* numel, float* const* W, c
                      std::vector<po_tensor_desc>& descs, int64_t* n_params, int64_t* n_unaligned)
 {
     if (n_tensors < 0) return po_fail(PO_EINVAL, "n_tensors < 0");
-    if (n_tensors > (int64_t)UINT32_MAX) return po_fail(PO_EINVAL, "too many tensors");
+    if (n_tensors > (int64_t)PO_CHUNK_TENSOR_MASK) return po_fail(PO_EINVAL, "too many tensors (at most 2^30 - 1)");
     if (n_tensors > 0 && (!numel || !W || !g || !What)) return po_fail(PO_EINVAL, "a required pointer array is NULL");
     if (n_tensors > 0 && !m && !v) return po_fail(PO_EINVAL, "a stage needs at least one of m and v");
     if (what_dtype != PO_WHAT_F32 && what_dtype != PO_WHAT_BF16) return po_fail(PO_EINVAL, "unknown what_dtype %d", what_dtype);
@@ -230,10 +238,14 @@ int po_describe_list(int64_t n_tensors, const int64_t* numel, float* const* W, c
 // streams evict each other.  A fused Adam/AdamW tile moves 7.5 KB (10 workgroups per CU), a one-state
 // optimizer's 5.5-6 KB (13), a prediction tile 3.5 KB (20) or 2.5 KB (26).  Smaller stages, whose launch is
 // dominated by ramp-up and ramp-down, like a few more.
-int32_t po_auto_lds_bytes(int kernel, int opt, int64_t n_params, bool local)
+int32_t po_auto_lds_bytes(int kernel, int opt, int64_t n_params, int layout)
 {
     const bool two_state = opt == PO_ADAM || opt == PO_ADAMW;
     const bool large = n_params >= (int64_t(1) << 27), mid = n_params >= (int64_t(1) << 25);
+    // a learnt layout (caller-placed buffers, about two thirds of the traffic near) likes the arena's cap for the fused
+    // two-state kernel from mid-sized stages up (config 3's shapes: 6.62 -> 6.71 TB/s) and the plain caps otherwise
+    if (layout == PO_LAYOUT_LEARNT) layout = (kernel == PO_KERNEL_KIND_FUSED && two_state && mid) ? PO_LAYOUT_ARENA : PO_LAYOUT_PLAIN;
+    const bool local = layout == PO_LAYOUT_ARENA;
     if (local) {
         // every XCC on its own die's memory: shorter latency, no shared link; the sweeps put the optimum at 10
         // workgroups per CU for the fused two-state kernel at every size from 64 M parameters up, at 12-13 for the
@@ -286,7 +298,14 @@ po_launch resolve_launch(const po_plan* p, const po_launch& L, int kernel, int o
 {
     po_launch R = L;
     const bool local = p->n_local_params * 2 >= p->n_params && p->n_local_params > 0;
-    if (R.lds_bytes == PO_LDS_AUTO) R.lds_bytes = po_auto_lds_bytes(kernel, opt, p->n_params, local);
+    const int layout = !local ? PO_LAYOUT_PLAIN : p->chunk_marks_valid ? PO_LAYOUT_LEARNT : PO_LAYOUT_ARENA;
+    if (R.lds_bytes == PO_LDS_AUTO) {
+        R.lds_bytes = po_auto_lds_bytes(kernel, opt, p->n_params, layout);
+        // an fp32 What makes the fused two-state tile 8 KB instead of 7.5: in the near-memory orders 8 workgroups per
+        // CU are then ahead of 10 (config 5's shapes, arena 6.95 -> 6.98 TB/s, learnt 6.85 -> 6.93; config 4's likewise)
+        if (layout != PO_LAYOUT_PLAIN && kernel == PO_KERNEL_KIND_FUSED && p->what_dtype == PO_WHAT_F32 && R.lds_bytes == 16384)
+            R.lds_bytes = 18432;
+    }
     return R;
 }
 
@@ -370,8 +389,13 @@ int upload_chunks(po_plan* p, hipStream_t stream)
         if (e != hipSuccess) return po_fail(PO_ENOMEM, "hipHostMalloc(chunk table staging): %s", hipGetErrorString(e));
         p->h_chunks_capacity = n;
     }
+    if (p->chunk_marks_valid && (int64_t)p->chunk_mark.size() != n) p->chunk_marks_valid = false;
     if (n > 0) {
         std::memcpy(p->h_chunks, p->chunks.data(), (size_t)n * sizeof(po_chunk));
+        if (p->chunk_marks_valid)
+            for (int64_t k = 0; k < n; ++k)
+                if (p->chunk_mark[(size_t)k] >= 0)
+                    p->h_chunks[k].tensor |= PO_CHUNK_LOCAL | (p->chunk_mark[(size_t)k] ? PO_CHUNK_HALF1 : 0u);
         hipError_t e = chain_behind_previous_upload(p, stream);
         if (e != hipSuccess) return fail_hip(e, "hipStreamWaitEvent(previous upload)");
         e = hipMemcpyAsync(p->d_chunks, p->h_chunks, (size_t)n * sizeof(po_chunk), hipMemcpyHostToDevice, stream);
@@ -492,7 +516,7 @@ int pipeoptim_auto_lds_bytes(int32_t kernel, int32_t opt, int64_t n_params, int3
     if (kernel != PO_KERNEL_KIND_FUSED && kernel != PO_KERNEL_KIND_PREDICT) return po_fail(PO_EINVAL, "kernel must be 0 (fused) or 1 (prediction)");
     if (opt < PO_SGDM || opt > PO_ADAGRAD) return po_fail(PO_EINVAL, "unknown optimizer %d", opt);
     if (n_params < 0) return po_fail(PO_EINVAL, "n_params < 0");
-    *out = po_auto_lds_bytes(kernel, opt, n_params, false);
+    *out = po_auto_lds_bytes(kernel, opt, n_params, PO_LAYOUT_PLAIN);
     return PO_OK;
 }
 
@@ -605,6 +629,8 @@ try {
     // everything the call changes, so that any failure below leaves the plan exactly as it was
     const std::vector<po_tensor_desc> saved = p->descs;
     const int64_t saved_unaligned = p->n_unaligned, saved_local = p->n_local_params;
+    const double saved_near = p->near_bytes;
+    const bool saved_marks = p->chunk_marks_valid;
     for (int64_t i = 0; i < p->n_tensors; ++i) {
         po_tensor_desc& d = p->descs[(size_t)i];
         switch (which) {
@@ -618,13 +644,23 @@ try {
     rc = check_disjoint(p->descs, p->grad_dtype, p->what_dtype);
     if (rc == PO_OK) {
         p->n_unaligned = refresh_flags(p->descs);
-        p->n_local_params = 0;
+        // A learnt order was decided mostly by W, m and v (8 bytes of traffic per element each): it stays in force
+        // when only g or What move (any order is correct; this one is still the better one for three streams of
+        // four).  When W, m or v move, the marks in the device table are ignored from the next launch on.
+        const bool keep_learnt = saved_marks && (which == 1 || which == 4);
+        if (!keep_learnt) {
+            p->n_local_params = 0;
+            p->near_bytes = 0.0;
+            p->chunk_marks_valid = false;
+        }
         rc = upload_descs(p, static_cast<hipStream_t>(hip_stream));
     }
     if (rc != PO_OK) {      // the device table was not touched: upload_descs fails before or at the enqueue of its copy
         p->descs = saved;
         p->n_unaligned = saved_unaligned;
         p->n_local_params = saved_local;
+        p->near_bytes = saved_near;
+        p->chunk_marks_valid = saved_marks;
     }
     return rc;
 }
@@ -660,6 +696,7 @@ try {
         rc = check_device(p);
         if (rc == PO_OK) rc = wait_for_plan_streams(p);   // a launch may still read the old table; the old upload is done
         if (rc != PO_OK) { p->launch = old; p->predict_launch = old_predict; return rc; }
+        if (p->chunk_marks_valid) { p->chunk_marks_valid = false; p->n_local_params = 0; p->near_bytes = 0.0; }   // marks belong to the old table
         rc = upload_chunks(p, p->upload_stream);
         if (rc != PO_OK) { p->launch = old; p->predict_launch = old_predict; (void)upload_chunks(p, p->upload_stream); return rc; }
     }
@@ -704,6 +741,7 @@ try {
     }
     const std::vector<po_tensor_desc> saved = p->descs;
     int64_t n_local = 0;
+    double near_gain = 0.0;
     for (int64_t i = 0; i < p->n_tensors; ++i) {
         po_tensor_desc& d = p->descs[(size_t)i];
         d.flags &= ~(PO_DESC_LOCAL | PO_DESC_HALF1);
@@ -723,6 +761,9 @@ try {
         if (cls < 0) continue;
         d.flags |= PO_DESC_LOCAL | (cls ? PO_DESC_HALF1 : 0u);
         n_local += d.numel;
+        int fp32_bytes = 0;                             // moved per element through the tensor's fp32 streams: all near now
+        for (int k = 0; k < 5; ++k) if (streams[k]) fp32_bytes += (k == 1 || k == 4) ? 4 : 8;
+        near_gain += 0.5 * fp32_bytes * (double)d.numel;
     }
     hipError_t e = hipSuccess;
     if (arena && n_local > 0) {
@@ -734,11 +775,150 @@ try {
     const int rc = upload_descs(p, stream);
     if (rc != PO_OK) { p->descs = saved; return rc; }
     p->n_local_params = n_local;
+    p->near_bytes = near_gain;
+    p->chunk_marks_valid = false;           // the two ways of marking do not mix: the last call wins
     if (n_local_params) *n_local_params = n_local;
     return PO_OK;
 }
 catch (const std::bad_alloc&) { return po_fail(PO_ENOMEM, "pipeoptim_plan_localize: out of host memory"); }
 catch (...) { return po_fail(PO_EINVAL, "pipeoptim_plan_localize: unexpected exception"); }
+
+int pipeoptim_plan_learn_layout(po_plan* p, void* hip_stream, int64_t* n_local_params)
+try {
+    if (!p) return po_fail(PO_EINVAL, "plan is NULL");
+    int rc = check_device(p);
+    if (rc != PO_OK) return rc;
+    constexpr uintptr_t kPiece = uintptr_t(2) << 20;
+    const uintptr_t chunk_bytes = (uintptr_t)p->launch.chunk_elems * 4;
+    if (chunk_bytes < 16384 || chunk_bytes > kPiece)
+        return po_fail(PO_EINVAL, "learning the layout needs chunk_elems between 4096 and 524288 (it is %lld)", (long long)p->launch.chunk_elems);
+    const hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    // nothing of the plan may be in flight while its tables change under a launch's feet (the timing below waits
+    // for the whole device anyway)
+    rc = wait_for_plan_streams(p);
+    if (rc != PO_OK) return rc;
+
+    // the fp32 streams of a tensor and what each weighs in bytes moved per element (read + written)
+    struct Stream { const void* base; int weight; };
+    auto streams_of = [&](const po_tensor_desc& d, Stream out[5]) {
+        int k = 0;
+        out[k++] = {d.W, 8};
+        if (p->grad_dtype == PO_GRAD_F32) out[k++] = {d.g, 4};
+        if (d.m) out[k++] = {d.m, 8};
+        if (d.v) out[k++] = {d.v, 8};
+        if (p->what_dtype == PO_WHAT_F32) out[k++] = {d.What, 4};
+        return k;
+    };
+    // A stream takes part if its base is a multiple of the chunk size in bytes: then no chunk of it straddles two
+    // 2 MiB pieces and every 16 KiB group of tiles is two whole 8 KiB blocks of it.  (A stream that is not, e.g. one
+    // placed at a staggered address, is half near and half far under either order and has no say.)
+    std::vector<std::pair<uintptr_t, uintptr_t>> ranges;          // whole 2 MiB pieces inside the buffers, [lo, hi)
+    for (int64_t i = 0; i < p->n_tensors; ++i) {
+        const po_tensor_desc& d = p->descs[(size_t)i];
+        if (d.numel == 0) continue;
+        Stream st[5];
+        const int ns = streams_of(d, st);
+        for (int k = 0; k < ns; ++k) {
+            if (((uintptr_t)st[k].base % chunk_bytes) != 0) continue;
+            const uintptr_t b = (uintptr_t)st[k].base, e = b + (uintptr_t)d.numel * 4;
+            const uintptr_t lo = (b + kPiece - 1) / kPiece * kPiece, hi = e / kPiece * kPiece;
+            if (lo < hi) ranges.push_back({lo, hi});
+        }
+    }
+    std::sort(ranges.begin(), ranges.end());
+    std::vector<std::pair<uintptr_t, uintptr_t>> merged;
+    for (const auto& r : ranges) {
+        if (!merged.empty() && r.first <= merged.back().second) merged.back().second = std::max(merged.back().second, r.second);
+        else merged.push_back(r);
+    }
+    std::vector<std::vector<int8_t>> layout(merged.size());        // per merged range: one answer per piece
+    for (size_t k = 0; k < merged.size(); ++k) {
+        const size_t n = (size_t)((merged[k].second - merged[k].first) / kPiece);
+        layout[k].assign(n, (int8_t)-1);
+        rc = po_probe_layout(reinterpret_cast<const void*>(merged[k].first), n, layout[k].data());
+        if (rc != PO_OK) return rc;
+    }
+    auto piece_layout = [&](uintptr_t addr) -> int {               // -1: not probed or not decided
+        auto it = std::upper_bound(merged.begin(), merged.end(), std::make_pair(addr, ~uintptr_t(0)));
+        if (it == merged.begin()) return -1;
+        --it;
+        if (addr < it->first || addr >= it->second) return -1;
+        return layout[(size_t)(it - merged.begin())][(size_t)((addr - it->first) / kPiece)];
+    };
+    // chunk by chunk: the half that brings more bytes near wins; a chunk none of whose streams is known stays plain
+    std::vector<int8_t> mark(p->chunks.size(), (int8_t)-1);
+    int64_t n_local = 0;
+    double near_gain = 0.0;
+    for (size_t k = 0; k < p->chunks.size(); ++k) {
+        const po_chunk& ch = p->chunks[k];
+        const po_tensor_desc& d = p->descs[ch.tensor];
+        Stream st[5];
+        const int ns = streams_of(d, st);
+        int near_weight[2] = {0, 0};
+        for (int j = 0; j < ns; ++j) {
+            if (((uintptr_t)st[j].base % chunk_bytes) != 0) continue;
+            const int h = piece_layout((uintptr_t)st[j].base + (uintptr_t)ch.chunk * chunk_bytes);
+            if (h >= 0) near_weight[h] += st[j].weight;
+        }
+        if (near_weight[0] + near_weight[1] == 0) continue;
+        mark[k] = (int8_t)(near_weight[1] > near_weight[0] ? 1 : 0);
+        const int64_t begin = (int64_t)ch.chunk * p->launch.chunk_elems;
+        const int64_t elems = std::min<int64_t>(p->launch.chunk_elems, d.numel - begin);
+        n_local += elems;
+        // of the voting bytes the winner's are near and the loser's far; the plain order had half of each near
+        near_gain += 0.5 * std::abs(near_weight[1] - near_weight[0]) * (double)elems;
+    }
+    if (!p->h_phase && n_local > 0) {
+        hipError_t eh = hipHostMalloc(reinterpret_cast<void**>(&p->h_phase), 64, hipHostMallocDefault);
+        if (eh != hipSuccess) { p->h_phase = nullptr; return po_fail(PO_ENOMEM, "hipHostMalloc(phase word): %s", hipGetErrorString(eh)); }
+        *p->h_phase = 0;
+    }
+    // arena marks and learnt marks do not mix: drop the former (descriptors), install the latter (chunk table)
+    const std::vector<po_tensor_desc> saved = p->descs;
+    bool had_arena_marks = false;
+    for (auto& d : p->descs) { had_arena_marks = had_arena_marks || (d.flags & PO_DESC_LOCAL); d.flags &= ~(PO_DESC_LOCAL | PO_DESC_HALF1); }
+    if (had_arena_marks) {
+        rc = upload_descs(p, stream);
+        if (rc != PO_OK) { p->descs = saved; return rc; }
+    }
+    const std::vector<int8_t> old_mark = p->chunk_mark;
+    const bool old_valid = p->chunk_marks_valid;
+    p->chunk_mark = mark;
+    p->chunk_marks_valid = true;
+    rc = upload_chunks(p, stream);
+    if (rc != PO_OK) { p->chunk_mark = old_mark; p->chunk_marks_valid = old_valid; return rc; }
+    if (n_local > 0) {
+        hipError_t e = po_launch_phase_probe(p->h_phase, stream);      // where this stream's launches start
+        if (e == hipSuccess) e = hipStreamSynchronize(stream);
+        if (e != hipSuccess) return fail_hip(e, "phase probe");
+    }
+    p->n_local_params = n_local;
+    p->near_bytes = near_gain;
+    if (n_local_params) *n_local_params = n_local;
+    return PO_OK;
+}
+catch (const std::bad_alloc&) { return po_fail(PO_ENOMEM, "pipeoptim_plan_learn_layout: out of host memory"); }
+catch (...) { return po_fail(PO_EINVAL, "pipeoptim_plan_learn_layout: unexpected exception"); }
+
+int pipeoptim_plan_chunk_marks(const po_plan* p, int8_t* out, int64_t capacity, int64_t* n_chunks)
+{
+    if (!p || !n_chunks) return po_fail(PO_EINVAL, "plan or n_chunks is NULL");
+    if (capacity < 0 || (capacity > 0 && !out)) return po_fail(PO_EINVAL, "bad output buffer");
+    const int64_t n = (int64_t)p->chunks.size();
+    for (int64_t k = 0; k < n && k < capacity; ++k)
+        out[k] = (p->chunk_marks_valid && (size_t)k < p->chunk_mark.size()) ? p->chunk_mark[(size_t)k] : (int8_t)-1;
+    *n_chunks = n;
+    return PO_OK;
+}
+
+int pipeoptim_plan_near_share(const po_plan* p, double* share)
+{
+    if (!p || !share) return po_fail(PO_EINVAL, "plan or share is NULL");
+    const int per_param = 8 + (p->grad_dtype == PO_GRAD_F32 ? 4 : 2) + (p->has_m ? 8 : 0) + (p->has_v ? 8 : 0) +
+                          (p->what_dtype == PO_WHAT_F32 ? 4 : 2);
+    *share = p->n_params > 0 ? 0.5 + p->near_bytes / ((double)per_param * (double)p->n_params) : 0.5;
+    return PO_OK;
+}
 
 int pipeoptim_plan_local_params(const po_plan* p, int64_t* n_local_params)
 {
@@ -807,7 +987,8 @@ int pipeoptim_step_predict(const po_plan* p, const po_hyper* h, int64_t t, int32
     hipError_t e = order_behind_upload(p, stream);
     if (e == hipSuccess)
         e = po_launch_step_predict(h->opt, p->what_dtype, p->grad_dtype, L, p->d_descs, p->d_chunks,
-                                   (uint32_t)p->chunks.size(), c, stream, phase, local ? p->h_phase : nullptr);
+                                   (uint32_t)p->chunks.size(), c, stream, phase, local ? p->h_phase : nullptr,
+                                   p->chunk_marks_valid);
     if (e != hipSuccess) return fail_hip(e, "launch of the fused step+predict kernel");
     return PO_OK;
 }
@@ -832,7 +1013,7 @@ int pipeoptim_predict(const po_plan* p, const po_hyper* h, int64_t t, int32_t s,
     hipError_t e = order_behind_upload(p, stream);
     if (e == hipSuccess)
         e = po_launch_predict(h->opt, p->what_dtype, L, p->d_descs, p->d_chunks, (uint32_t)p->chunks.size(), c,
-                              stream, phase, local ? p->h_phase : nullptr);
+                              stream, phase, local ? p->h_phase : nullptr, p->chunk_marks_valid);
     if (e != hipSuccess) return fail_hip(e, "launch of the prediction kernel");
     return PO_OK;
 }

@@ -146,7 +146,7 @@ try {
         return po_fail(PO_EINVAL, "pipeoptim_step_predict_static: the list needs %lld chunk-table entries of %lld elements, "
                        "the static table holds %d; use a plan", (long long)n_chunks, (long long)L.chunk_elems, PO_STATIC_MAX_CHUNKS);
     if (n_chunks == 0) return PO_OK;
-    L.lds_bytes = po_auto_lds_bytes(PO_KERNEL_KIND_FUSED, hyper->opt, n_params, false);
+    L.lds_bytes = po_auto_lds_bytes(PO_KERNEL_KIND_FUSED, hyper->opt, n_params, PO_LAYOUT_PLAIN);
 
     unsigned char* base = nullptr;
     rc = scratch_of_current_device(&base);
@@ -171,7 +171,7 @@ try {
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return po_fail(PO_EHIP, "launch of the chunk-table kernel: %s", hipGetErrorString(e));
     e = po_launch_step_predict(hyper->opt, what_dtype, PO_GRAD_F32, L, d_descs, d_chunks, (uint32_t)n_chunks, c, stream,
-                               0u, nullptr);
+                               0u, nullptr, false);
     if (e != hipSuccess) return po_fail(PO_EHIP, "launch of the fused step+predict kernel: %s", hipGetErrorString(e));
     return PO_OK;
 }

@@ -150,8 +150,8 @@ struct alignas(32) KArgs {
     uint32_t reserved;
     uint32_t tile;           // block * 4
     po_coeffs c;             // 52 bytes
-    uint32_t local_ok;       // 1: this launch shape supports the near-memory tile order (1 KiB tiles, whole groups
-                             //    of 16 tiles per chunk)
+    uint32_t local_ok;       // bit 0: this launch shape supports the near-memory tile order (1 KiB tiles, whole groups
+                             //    of 16 tiles per chunk); bit 1: the chunk table's own marks are valid as well
     uint32_t* phase_out;     // host-visible word that workgroup 0 writes its XCC id to (or nullptr)
     uint32_t phase;          // XCC on which this queue's launches start, as last observed: workgroup id b runs
                              // on XCC (b + phase) mod 8
@@ -194,13 +194,17 @@ __device__ __forceinline__ bool locate_tile(const KArgs& a, Tile& t)
     // the tables are not written while a kernel runs: read them through the constant address space so that
     // the (workgroup-uniform) loads go down the scalar path and their results stay in SGPRs
     const u32x2 entry = *(const PO_CONSTANT u32x2*)(uintptr_t)(a.chunks + (slot >> a.tiles_log2));
-    const po_chunk ch{entry[0], entry[1]};
+    const po_chunk ch{entry[0] & PO_CHUNK_TENSOR_MASK, entry[1]};
     union { u32x16 raw; po_tensor_desc d; } u;
     u.raw = *(const PO_CONSTANT u32x16*)(uintptr_t)(a.descs + ch.tensor);
     t.d = u.d;
     uint32_t tile_in_chunk = slot & ((1u << a.tiles_log2) - 1u);
-    // tensors in a near-memory arena: the workgroups on XCCs 0-3 take the tiles whose blocks are near to their die
-    if (a.local_ok && (t.d.flags & PO_DESC_LOCAL)) tile_in_chunk = po_local_tile(tile_in_chunk, (t.d.flags & PO_DESC_HALF1) ? 1u : 0u);
+    // near-memory order: the workgroups on XCCs 0-3 take the tiles whose blocks are near to their die.  Either the
+    // whole tensor sits in an arena (descriptor flags), or the plan learnt the layout of this chunk (chunk marks)
+    if (a.local_ok) {
+        if (t.d.flags & PO_DESC_LOCAL) tile_in_chunk = po_local_tile(tile_in_chunk, (t.d.flags & PO_DESC_HALF1) ? 1u : 0u);
+        else if ((a.local_ok & 2u) && (entry[0] & PO_CHUNK_LOCAL)) tile_in_chunk = po_local_tile(tile_in_chunk, (entry[0] & PO_CHUNK_HALF1) ? 1u : 0u);
+    }
     t.off = (int64_t)ch.chunk * a.chunk_elems + (int64_t)tile_in_chunk * a.tile;
     if (t.off >= t.d.numel) return false;
     t.len = (t.d.numel - t.off < (int64_t)a.tile) ? (uint32_t)(t.d.numel - t.off) : a.tile;
@@ -347,7 +351,7 @@ __global__ __launch_bounds__(256) void predict_kernel(KArgs)
 }
 
 // Where a launch starts its round over the XCCs: last observed value, and where workgroup 0 reports the next.
-struct Phase { uint32_t value; uint32_t* report; };
+struct Phase { uint32_t value; uint32_t* report; bool chunk_marks; };
 
 template <int KIND, int OPT, bool BF16, bool GB16>
 hipError_t launch_one(const po_launch& L, const po_tensor_desc* descs, const po_chunk* chunks, uint32_t n_chunks,
@@ -368,7 +372,7 @@ hipError_t launch_one(const po_launch& L, const po_tensor_desc* descs, const po_
     a.tiles_log2 = tiles_log2;
     a.tile = tile;
     a.c = c;
-    a.local_ok = (tile == PO_LOCAL_TILE_ELEMS && tiles_per_chunk >= PO_LOCAL_GROUP_TILES) ? 1u : 0u;
+    a.local_ok = (tile == PO_LOCAL_TILE_ELEMS && tiles_per_chunk >= PO_LOCAL_GROUP_TILES) ? (ph.chunk_marks ? 3u : 1u) : 0u;
     a.phase = a.local_ok ? (ph.value & 7u) : 0u;
     a.phase_out = a.local_ok ? ph.report : nullptr;
     if constexpr (KIND == PO_KERNEL_PREDICT)
@@ -451,29 +455,29 @@ hipError_t po_launch_phase_probe(uint32_t* host_visible_word, hipStream_t stream
 
 hipError_t po_launch_step_predict(int opt, int what_dtype, int grad_dtype, const po_launch& L,
                                   const po_tensor_desc* d_descs, const po_chunk* d_chunks, uint32_t n_chunks,
-                                  const po_coeffs& c, hipStream_t stream, uint32_t phase, uint32_t* phase_report)
+                                  const po_coeffs& c, hipStream_t stream, uint32_t phase, uint32_t* phase_report, bool chunk_marks)
 {
     if (n_chunks == 0) return hipSuccess;
     switch (opt) {
-    case PO_SGDM: return dispatch_dtype<PO_KERNEL_FUSED, PO_SGDM>(what_dtype, grad_dtype, L, d_descs, d_chunks, n_chunks, c, stream, Phase{phase, phase_report});
-    case PO_ADAM: return dispatch_dtype<PO_KERNEL_FUSED, PO_ADAM>(what_dtype, grad_dtype, L, d_descs, d_chunks, n_chunks, c, stream, Phase{phase, phase_report});
-    case PO_ADAMW: return dispatch_dtype<PO_KERNEL_FUSED, PO_ADAMW>(what_dtype, grad_dtype, L, d_descs, d_chunks, n_chunks, c, stream, Phase{phase, phase_report});
-    case PO_NESTEROV: return dispatch_dtype<PO_KERNEL_FUSED, K_NESTEROV>(what_dtype, grad_dtype, L, d_descs, d_chunks, n_chunks, c, stream, Phase{phase, phase_report});
+    case PO_SGDM: return dispatch_dtype<PO_KERNEL_FUSED, PO_SGDM>(what_dtype, grad_dtype, L, d_descs, d_chunks, n_chunks, c, stream, Phase{phase, phase_report, chunk_marks});
+    case PO_ADAM: return dispatch_dtype<PO_KERNEL_FUSED, PO_ADAM>(what_dtype, grad_dtype, L, d_descs, d_chunks, n_chunks, c, stream, Phase{phase, phase_report, chunk_marks});
+    case PO_ADAMW: return dispatch_dtype<PO_KERNEL_FUSED, PO_ADAMW>(what_dtype, grad_dtype, L, d_descs, d_chunks, n_chunks, c, stream, Phase{phase, phase_report, chunk_marks});
+    case PO_NESTEROV: return dispatch_dtype<PO_KERNEL_FUSED, K_NESTEROV>(what_dtype, grad_dtype, L, d_descs, d_chunks, n_chunks, c, stream, Phase{phase, phase_report, chunk_marks});
     case PO_RMSPROP:
-    case PO_ADAGRAD: return dispatch_dtype<PO_KERNEL_FUSED, K_RMS>(what_dtype, grad_dtype, L, d_descs, d_chunks, n_chunks, c, stream, Phase{phase, phase_report});
+    case PO_ADAGRAD: return dispatch_dtype<PO_KERNEL_FUSED, K_RMS>(what_dtype, grad_dtype, L, d_descs, d_chunks, n_chunks, c, stream, Phase{phase, phase_report, chunk_marks});
     }
     return hipErrorInvalidValue;
 }
 
 hipError_t po_launch_predict(int opt, int what_dtype, const po_launch& L, const po_tensor_desc* d_descs,
                              const po_chunk* d_chunks, uint32_t n_chunks, const po_coeffs& c, hipStream_t stream,
-                             uint32_t phase, uint32_t* phase_report)
+                             uint32_t phase, uint32_t* phase_report, bool chunk_marks)
 {
     if (n_chunks == 0) return hipSuccess;
     switch (opt) {
-    case PO_SGDM: return dispatch_dtype<PO_KERNEL_PREDICT, PO_SGDM>(what_dtype, PO_GRAD_F32, L, d_descs, d_chunks, n_chunks, c, stream, Phase{phase, phase_report});
-    case PO_ADAM: return dispatch_dtype<PO_KERNEL_PREDICT, PO_ADAM>(what_dtype, PO_GRAD_F32, L, d_descs, d_chunks, n_chunks, c, stream, Phase{phase, phase_report});
-    case PO_ADAMW: return dispatch_dtype<PO_KERNEL_PREDICT, PO_ADAMW>(what_dtype, PO_GRAD_F32, L, d_descs, d_chunks, n_chunks, c, stream, Phase{phase, phase_report});
+    case PO_SGDM: return dispatch_dtype<PO_KERNEL_PREDICT, PO_SGDM>(what_dtype, PO_GRAD_F32, L, d_descs, d_chunks, n_chunks, c, stream, Phase{phase, phase_report, chunk_marks});
+    case PO_ADAM: return dispatch_dtype<PO_KERNEL_PREDICT, PO_ADAM>(what_dtype, PO_GRAD_F32, L, d_descs, d_chunks, n_chunks, c, stream, Phase{phase, phase_report, chunk_marks});
+    case PO_ADAMW: return dispatch_dtype<PO_KERNEL_PREDICT, PO_ADAMW>(what_dtype, PO_GRAD_F32, L, d_descs, d_chunks, n_chunks, c, stream, Phase{phase, phase_report, chunk_marks});
     }
     return hipErrorInvalidValue;
 }

@@ -17,7 +17,9 @@ nothing), and passes pointers.  Parameters must be contiguous fp32 tensors on th
 With ``arena=True`` (the default for stages of 4 Mi parameters and more; smaller ones gain nothing from it) the
 optimizer owns the stage's memory the way flat-parameter optimizers do: the parameters are moved once into the
 library's near-memory arena, next to their gradient, state and What buffers, so that both kernels run with every
-XCC on its own die's HBM.  ``close()`` moves them back out.
+XCC on its own die's HBM.  ``close()`` moves them back out.  With ``arena=False, learn_layout=True`` the parameters
+stay where the caller put them, the other buffers are plain PyTorch allocations, and the plan finds out by timing
+which die each 2 MiB piece lies on (``pipeoptim_plan_learn_layout``): about two thirds of the way to the arena's gain.
 """
 import contextlib
 import warnings
@@ -33,7 +35,7 @@ class StageOptimizer:
     def __init__(self, params: Iterable[torch.nn.Parameter], optimizer: str = "adamw", lr: float = 1e-3,
                  betas=(0.9, 0.999), eps: float = 1e-8, weight_decay: float = 0.0, momentum: float = 0.9,
                  dampening: float = 0.0, alpha: float = 0.99, rank: int = 0, depth: int = 1,
-                 decay_in_prediction: bool = True, arena: Optional[bool] = None):
+                 decay_in_prediction: bool = True, arena: Optional[bool] = None, learn_layout: bool = False):
         self.params: List[torch.nn.Parameter] = [p for p in params]
         if not self.params:
             raise ValueError("no parameters")
@@ -89,7 +91,10 @@ class StageOptimizer:
         self._W = [p.data.view(-1) for p in self.params]
 
         def state_like(slot_offset):
-            # gradient and state buffers: zero-filled, placed in address slots (bits 12-13) next to W's
+            # gradient and state buffers: zero-filled, placed in address slots (bits 12-13) next to W's; under a learnt
+            # layout plain allocations instead (a stream has a say there only if it starts on a chunk boundary)
+            if learn_layout:
+                return [torch.zeros(w.numel(), dtype=torch.float32, device=dev) for w in self._W]
             out = []
             for w in self._W:
                 x = alloc_skewed(w.numel(), torch.float32, dev, (address_slot(w.data_ptr()) + slot_offset) % SKEW_SLOTS)
@@ -102,7 +107,7 @@ class StageOptimizer:
         for p, g in zip(self.params, self._g):
             p.grad = g.view_as(p)                                              # autograd accumulates in place
         # the prediction is consumed by an fp32 module, so What is fp32 here (the C ABI also offers bf16)
-        self._stage = Stage(self._W, self._g, self._m, self._v, "f32")
+        self._stage = Stage(self._W, self._g, self._m, self._v, "f32", skew_what=not learn_layout, learn_layout=learn_layout)
         self._What = self._stage.What
         self._swapped = False
 
@@ -128,12 +133,13 @@ class StageOptimizer:
                 if gr.dtype != torch.float32 or not gr.is_contiguous() or gr.device != p.device or gr.numel() != p.numel():
                     raise RuntimeError("gradients must be contiguous fp32 tensors of the parameter's size on its device")
                 new.append(gr.view(-1))
-            if self._stage.n_local_params and not self._warned_moved:
+            self._stage.plan.set_pointers(1, [x.data_ptr() for x in new], torch.cuda.current_stream().cuda_stream)
+            still_local = self._stage.plan.local_params()         # a learnt order survives new gradient buffers, the arena's does not
+            if self._stage.n_local_params and not still_local and not self._warned_moved:
                 warnings.warn("gradients left the near-memory arena: the step runs in the plain tile order from here on "
                               "(keep the buffers this optimizer handed out, e.g. zero_grad(set_to_none=False), to avoid that)")
                 self._warned_moved = True
-            self._stage.plan.set_pointers(1, [x.data_ptr() for x in new], torch.cuda.current_stream().cuda_stream)
-            self._stage.n_local_params = 0
+            self._stage.n_local_params = still_local
             self._g = new
             self._stage.g = new
         self.t += 1

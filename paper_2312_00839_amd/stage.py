@@ -113,9 +113,12 @@ class Stage:
 
     def __init__(self, W: List[torch.Tensor], g: List[torch.Tensor], m: Optional[List[torch.Tensor]],
                  v: Optional[List[torch.Tensor]], what_dtype: str, skew_what: bool = True,
-                 What: Optional[List[torch.Tensor]] = None, arena: Optional[binding.Arena] = None):
+                 What: Optional[List[torch.Tensor]] = None, arena: Optional[binding.Arena] = None,
+                 learn_layout: bool = False):
         """`What`: prediction buffers the caller already holds (else the stage allocates them).  `arena`: the
-        near-memory arena the tensors came from, if any; the plan is then localized over it."""
+        near-memory arena the tensors came from, if any; the plan is then localized over it.  `learn_layout`
+        (without an arena): let the library find the die layout of these buffers by timing and order its tiles
+        accordingly (`pipeoptim_plan_learn_layout`; a blocking set-up step)."""
         for lst in (W,) + ((m,) if m is not None else ()) + ((v,) if v is not None else ()):
             for x in lst:
                 if x.dtype != torch.float32 or not x.is_contiguous() or x.device.type != "cuda":
@@ -134,8 +137,10 @@ class Stage:
                                           for h, x in zip(What, W)):
                 raise ValueError("What must match W in length and sizes and have the prediction's dtype")
             self.What = What
-        elif skew_what:
-            # What takes an address slot (bits 12-13) that no other stream of its tensor uses, else the gradient's
+        elif skew_what and not (learn_layout and arena is None):
+            # What takes an address slot (bits 12-13) that no other stream of its tensor uses, else the gradient's.
+            # (Not under a learnt layout: a stream has a say in the vote only if it starts on a chunk boundary, and an
+            # fp32 What 4 KiB off the others' blocks took the learnt order's gain away on the 0.74B-parameter stage.)
             self.What = []
             for i, x in enumerate(W):
                 used = {address_slot(lst[i].data_ptr()) for lst in (W, g, m, v) if lst is not None}
@@ -152,6 +157,8 @@ class Stage:
                                  grad_dtype=self.grad_dtype)
         self.n_local_params = (self.plan.localize(arena, torch.cuda.current_stream().cuda_stream)
                                if arena is not None else 0)
+        if arena is None and learn_layout:
+            self.n_local_params = self.plan.learn_layout(torch.cuda.current_stream().cuda_stream)
 
     @property
     def n_params(self) -> int:

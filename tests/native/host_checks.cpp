@@ -93,6 +93,10 @@ int main()
     int64_t n_local = -1;
     EXPECT(pipeoptim_plan_localize(nullptr, nullptr, nullptr, &n_local) == PO_EINVAL);
     EXPECT(pipeoptim_plan_local_params(nullptr, &n_local) == PO_EINVAL);
+    EXPECT(pipeoptim_plan_learn_layout(nullptr, nullptr, &n_local) == PO_EINVAL);
+    EXPECT(pipeoptim_plan_chunk_marks(nullptr, nullptr, 0, &n_local) == PO_EINVAL);
+    double share = 0.0;
+    EXPECT(pipeoptim_plan_near_share(nullptr, &share) == PO_EINVAL);
     po_launch eff{};
     EXPECT(pipeoptim_plan_effective_launch(nullptr, PO_KERNEL_KIND_FUSED, PO_ADAM, &eff) == PO_EINVAL);
     for (int32_t first_half = 0; first_half < 2; ++first_half)

@@ -207,6 +207,9 @@ def test_arena_and_localize_argument_validation():
     n = ctypes.c_int64()
     assert L.pipeoptim_plan_localize(None, None, None, ctypes.byref(n)) == binding.PO_EINVAL
     assert L.pipeoptim_plan_local_params(None, ctypes.byref(n)) == binding.PO_EINVAL
+    assert L.pipeoptim_plan_learn_layout(None, None, ctypes.byref(n)) == binding.PO_EINVAL
+    assert L.pipeoptim_plan_chunk_marks(None, None, 0, ctypes.byref(n)) == binding.PO_EINVAL
+    assert L.pipeoptim_plan_near_share(None, ctypes.byref(ctypes.c_double())) == binding.PO_EINVAL
     k = ctypes.c_int32()
     assert L.pipeoptim_plan_launch_phase(None, ctypes.byref(k)) == binding.PO_EINVAL
     launch = binding.po_launch()

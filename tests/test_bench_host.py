@@ -34,5 +34,6 @@ def test_tracked_summaries_cover_the_headline_variants():
     # the summaries under profiles/ name the variants bench.py asks for by default (whether they are still current
     # is decided at run time by the fingerprint)
     text = "".join(open(os.path.join(ROOT, "profiles", f)).read() for f in os.listdir(os.path.join(ROOT, "profiles")))
-    for v in ("fused-config5-adamw-local-gf32-hbf16", "fused-config5-adamw-packed-gf32-hbf16"):
+    for v in ("fused-config5-adamw-local-gf32-hbf16", "fused-config5-adamw-packed-gf32-hbf16",
+              "fused-config5-adamw-learnt-gf32-hbf16"):
         assert "traffic_bytes_per_launch variant=%s " % v in text

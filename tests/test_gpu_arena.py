@@ -255,6 +255,7 @@ def test_localized_plan_follows_the_stream_it_runs_on():
     stage = Stage(tensors["W"], tensors["g"], tensors["m"], tensors["v"], "f32", What=tensors["What"], arena=tensors["arena"])
     try:
         assert stage.n_local_params == stage.n_params
+        assert stage.plan.near_share() == 1.0                # fp32 What: all five streams near
         assert stage.plan.launch_phase() in range(8)
         hyper = make_hyper(kind, hp)
         seen = []

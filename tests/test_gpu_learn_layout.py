@@ -1,0 +1,174 @@
+"""pipeoptim_plan_learn_layout: the near-memory tile order for buffers the caller placed, found by timing loads."""
+import numpy as np
+import pytest
+import torch
+
+pytestmark = pytest.mark.gpu
+
+from parity_util import raw_bits, run_and_compare_full  # noqa: E402
+
+from paper_2312_00839_amd import binding  # noqa: E402
+from paper_2312_00839_amd.stage import Stage, StageArena  # noqa: E402
+
+DEV = "cuda:0"
+CHUNK = 65536
+HP = dict(lr=1e-3, beta1=0.9, beta2=0.999, eps=1e-8, weight_decay=0.01)
+
+
+def _say(msg):
+    print("[gpu-learn] " + msg, flush=True)
+
+
+def _stream():
+    return torch.cuda.current_stream().cuda_stream
+
+
+def test_learnt_marks_agree_with_the_arena_that_placed_the_memory():
+    """Memory whose layout is known: a stage in a near-memory arena, handed to a plan as if the caller had placed
+    it.  What the timing finds chunk by chunk must be the half the arena reports for that address."""
+    numels = [1 << 24, 3 << 22, 1 << 20, 70000, 5]
+    _say("ground truth: arena-placed tensors %s, plan not localized, layout learnt by timing" % numels)
+    sa = StageArena(numels, "bf16")
+    st = Stage(sa.W, sa.g, sa.m, sa.v, "bf16", What=sa.What)
+    try:
+        n_local = st.plan.learn_layout(_stream())
+        marks = st.plan.chunk_marks()
+        assert len(marks) == sum((n + CHUNK - 1) // CHUNK for n in numels)
+        agree = disagree = plain = whole_plain = k = 0
+        for i, n in enumerate(numels):
+            for c in range((n + CHUNK - 1) // CHUNK):
+                want = sa.arena.near_half(sa.W[i].data_ptr() + c * CHUNK * 4)
+                assert want in (0, 1)
+                in_whole_piece = (c * CHUNK * 4) // (2 << 20) < (n * 4) // (2 << 20)   # W[i] starts a 2 MiB piece here
+                if marks[k] < 0:
+                    plain += 1
+                    whole_plain += in_whole_piece
+                elif marks[k] == want:
+                    agree += 1
+                else:
+                    disagree += 1
+                k += 1
+        _say("%d chunks agree with the arena, %d disagree, %d left plain (%d of those inside whole 2 MiB pieces); "
+             "%d of %d parameters" % (agree, disagree, plain, whole_plain, n_local, sum(numels)))
+        assert disagree == 0
+        # two independent timings per piece decide nearly every piece; a few may stay open
+        assert agree >= 0.9 * ((numels[0] + numels[1] + numels[2]) // CHUNK)
+        assert n_local == sum(min(CHUNK, n - c * CHUNK) for i, n in enumerate(numels)
+                              for c in range((n + CHUNK - 1) // CHUNK)
+                              if marks[sum((x + CHUNK - 1) // CHUNK for x in numels[:i]) + c] >= 0)
+        assert st.plan.local_params() == n_local
+        # arena memory: the four fp32 streams of every tensor agree, so every vote is unanimous: of 30 bytes per
+        # parameter 28 are near where a chunk is marked, 1 of the bf16 What's 2 in any case
+        share = st.plan.near_share()
+        _say("estimated near share %.4f" % share)
+        full = 0.5 + 14.0 * n_local / (30.0 * sum(numels))      # if every stream's piece were known in every marked chunk
+        assert full - 0.1 <= share <= full + 1e-9               # a stream whose piece stayed open counts as half near
+    finally:
+        st.close()
+        sa.close()
+
+
+def _ragged(seed, kind="adamw", grad_dtype=torch.float32):
+    """Sizes that give chunks of every kind: whole 2 MiB pieces, tails, tensors under one chunk, an unaligned one."""
+    gen = torch.Generator(device=DEV)
+    gen.manual_seed(seed)
+    sizes = [3 * (1 << 20) + 12345, 1 << 21, 700001, 65536, 4097, 1, 0, (1 << 20) + 3]
+    out = {"W": [], "g": [], "m": [], "v": []}
+    for j, n in enumerate(sizes):
+        off = 1 if j == 7 else 0                        # the last tensor starts 4 bytes into its allocation
+        out["W"].append((torch.randn(n + off, generator=gen, device=DEV) * 0.02)[off:])
+        out["g"].append((torch.randn(n + 2 * off, generator=gen, device=DEV) * 1e-3).to(grad_dtype)[2 * off:])
+        out["m"].append((torch.randn(n + off, generator=gen, device=DEV) * 1e-4)[off:])
+        out["v"].append((torch.randn(n + off, generator=gen, device=DEV) * 1e-3).square()[off:])
+    return out
+
+
+@pytest.mark.parametrize("what_dtype", ["bf16", "f32"])
+def test_results_under_the_learnt_order_are_those_of_the_plain_order(what_dtype):
+    """Same inputs, plain order against learnt order, fused and prediction-only: every output bit equal."""
+    _say("ragged list, %s What: plain order against learnt order, bit for bit" % what_dtype)
+    hyper = binding.make_hyper("adamw", HP["lr"], HP["beta1"], HP["beta2"], HP["eps"], HP["weight_decay"], True)
+    outs = []
+    for learn in (False, True):
+        t = _ragged(11)
+        st = Stage(t["W"], t["g"], t["m"], t["v"], what_dtype, learn_layout=learn)
+        try:
+            if learn:
+                marks = st.plan.chunk_marks()
+                _say("marks: %d for half 0, %d for half 1, %d plain" % (marks.count(0), marks.count(1), marks.count(-1)))
+                assert st.n_local_params > 0
+            st.step_predict(hyper, 10, 3)
+            torch.cuda.synchronize()
+            fused = [[raw_bits(x) for x in col] for col in (st.W, st.m, st.v, st.What)]
+            st.predict(hyper, 11, 5)
+            torch.cuda.synchronize()
+            outs.append(fused + [[raw_bits(x) for x in st.What]])
+        finally:
+            st.close()
+    for name, a, b in zip(("W", "m", "v", "What (fused)", "What (predict)"), outs[0], outs[1]):
+        for i, (x, y) in enumerate(zip(a, b)):
+            assert np.array_equal(x, y), "%s of tensor %d differs between the two orders" % (name, i)
+
+
+@pytest.mark.parametrize("kind,grad_dtype", [("adamw", torch.float32), ("adam", torch.bfloat16), ("sgdm", torch.float32)])
+def test_oracle_parity_under_the_learnt_order(kind, grad_dtype):
+    _say("ragged list, %s, %s gradients, learnt order, against the oracle" % (kind, grad_dtype))
+    hp = dict(HP, weight_decay=HP["weight_decay"] if kind != "adam" else 0.0)
+    t = _ragged(12, kind, grad_dtype)
+    if kind == "sgdm":
+        t["v"] = None
+        hp = dict(lr=0.1, beta1=0.9, beta2=0.0, eps=0.0, weight_decay=1e-4)
+    run_and_compare_full(kind, hp, 7, 4, t, "bf16", label="learnt " + kind, learn=True)
+
+
+def test_what_drops_the_learnt_marks_and_what_keeps_them():
+    t = _ragged(13)
+    st = Stage(t["W"], t["g"], t["m"], t["v"], "bf16", learn_layout=True)
+    try:
+        n_local = st.n_local_params
+        marks = st.plan.chunk_marks()
+        assert n_local > 0 and any(m >= 0 for m in marks)
+        # new gradient buffers (what an autograd engine does every step): the order stays
+        g2 = [torch.empty_like(x) for x in t["g"]]
+        st.plan.set_pointers(1, [x.data_ptr() for x in g2], _stream())
+        assert st.plan.local_params() == n_local and st.plan.chunk_marks() == marks
+        assert 0.5 < st.plan.near_share() <= 29.0 / 30.0
+        # new W: the marks are gone
+        W2 = [x.clone() for x in t["W"]]
+        st.plan.set_pointers(0, [x.data_ptr() for x in W2], _stream())
+        assert st.plan.local_params() == 0 and all(m == -1 for m in st.plan.chunk_marks())
+        assert st.plan.near_share() == 0.5
+        # learnt again, then a chunk size change drops them
+        assert st.plan.learn_layout(_stream()) > 0
+        st.plan.set_launch(chunk_elems=16384)
+        assert st.plan.local_params() == 0 and all(m == -1 for m in st.plan.chunk_marks())
+        # learning works at the new chunk size too; a chunk size the rule does not cover is refused and leaves the plan usable
+        assert st.plan.learn_layout(_stream()) > 0
+        st.plan.set_launch(chunk_elems=1024)
+        with pytest.raises(binding.PipeOptimError) as ei:
+            st.plan.learn_layout(_stream())
+        assert ei.value.status == binding.PO_EINVAL
+        hyper = binding.make_hyper("adamw", HP["lr"], HP["beta1"], HP["beta2"], HP["eps"], HP["weight_decay"], True)
+        st.plan.set_pointers(1, [x.data_ptr() for x in t["g"]], _stream())
+        st.step_predict(hyper, 3, 1)
+        torch.cuda.synchronize()
+    finally:
+        st.close()
+
+
+def test_learning_costs_no_more_than_a_set_up_step():
+    """About 10 ms per GiB of buffers: the call must stay a set-up step, not grow with something else."""
+    import time
+    n = 1 << 26                                            # 1 GiB of fp32 streams (W, g, m, v)
+    W, g, m, v = (torch.zeros(n, device=DEV) for _ in range(4))
+    st = Stage([W], [g], [m], [v], "bf16")
+    try:
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        n_local = st.plan.learn_layout(_stream())
+        dt = time.perf_counter() - t0
+        _say("1 GiB of streams: layout learnt in %.1f ms, %d of %d parameters" % (dt * 1e3, n_local, n))
+        assert n_local >= 0.9 * n
+        assert dt < 1.0
+    finally:
+        st.close()

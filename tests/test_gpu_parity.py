@@ -811,24 +811,34 @@ def _check_over_1ulp(cfg, s, mode, report, what_dtype):
     assert n <= cap, "config %d s=%d %s: %d bf16 codes beyond 1 ulp, ceiling %d" % (cfg, s, mode, n, cap)
 
 
-def _full_config(cfg, s, layout="packed", what_dtype=None, predict=False):
+def _full_config(cfg, s, layout="packed", what_dtype=None, predict=False, learn=False):
     """The whole stage at its real shape in the default (benchmarked) launch shape; EVERY element of every output
-    is compared with the oracle, tensor by tensor."""
+    is compared with the oracle, tensor by tensor.  `learn`: plain allocations whose die layout the plan learns by
+    timing (pipeoptim_plan_learn_layout) before the call."""
     import dataclasses
     from parity_util import compare_stage_streamed
     wl = workload(cfg)
     if what_dtype and what_dtype != wl.what_dtype:
         wl = dataclasses.replace(wl, what_dtype=what_dtype)
     mode = "predict" if predict else "fused"
-    _say("config %d (%s) s=%d %s, full compare, N=%d, layout %s, %s What" % (cfg, wl.name, s, mode, wl.n_params, layout, wl.what_dtype))
+    _say("config %d (%s) s=%d %s, full compare, N=%d, layout %s%s, %s What"
+         % (cfg, wl.name, s, mode, wl.n_params, layout, " + learnt tile order" if learn else "", wl.what_dtype))
     tensors = make_inputs(wl, DEV, layout=layout)
     keys = [k for k in ("W", "g", "m", "v") if tensors.get(k) is not None]
     before = {k: [x.clone() for x in tensors[k]] for k in keys}
     stage = Stage(tensors["W"], tensors["g"], tensors["m"], tensors.get("v"), wl.what_dtype,
-                  What=tensors.get("What"), arena=tensors.get("arena"))
+                  What=tensors.get("What"), arena=tensors.get("arena"), learn_layout=learn)
     try:
         if layout == "local":
             assert stage.n_local_params == wl.n_params
+        if learn:
+            marks = stage.plan.chunk_marks()
+            _say("config %d: learnt order for %d of %d parameters; chunks: %d for half 0, %d for half 1, %d plain; "
+                 "estimated near share of the traffic %.3f" % (cfg, stage.n_local_params, wl.n_params, marks.count(0),
+                                                              marks.count(1), marks.count(-1), stage.plan.near_share()))
+            assert stage.plan.near_share() > 0.5
+            # large plain allocations are 2 MiB-aligned and decided almost everywhere; both assignments occur
+            assert stage.n_local_params >= 0.5 * wl.n_params and marks.count(0) > 0 and marks.count(1) > 0
         hyper = make_hyper(wl.optimizer, wl.hyper)
         (stage.predict if predict else stage.step_predict)(hyper, wl.t, s)
         torch.cuda.synchronize()
@@ -886,7 +896,7 @@ def test_config4_gpt_adamw_bf16_full_in_near_memory_arena(s):
 
 
 def test_config5_llama_adamw_bf16_full_in_near_memory_arena():
-    # the layout and launch shape bench.py's `value` is measured in
+    # the layout and launch shape of bench.py's "local" line
     _full_config(5, 7, layout="local")
 
 
@@ -901,6 +911,29 @@ def test_config5_predict_full_in_near_memory_arena():
 @pytest.mark.parametrize("s", [0, 7])
 def test_config4_predict_full(s):
     _full_config(4, s, predict=True)
+
+
+# plain PyTorch allocations under the tile order learnt from timing them
+def test_config3_full_under_learnt_layout():
+    _full_config(3, 2, learn=True)
+
+
+@pytest.mark.parametrize("s", [0, 7])
+def test_config4_full_under_learnt_layout(s):
+    _full_config(4, s, learn=True)
+
+
+def test_config4_predict_full_under_learnt_layout():
+    _full_config(4, 7, predict=True, learn=True)
+
+
+def test_config5_full_under_learnt_layout():
+    # the layout and launch shape bench.py's `value` is measured in
+    _full_config(5, 7, learn=True)
+
+
+def test_config5_fp32_prediction_full_under_learnt_layout():
+    _full_config(5, 7, what_dtype="f32", learn=True)
 
 
 # fp32 predicted weights on the bf16 configurations' shapes (32 instead of 30 bytes per parameter)

@@ -103,6 +103,43 @@ def test_gradients_reallocated_every_iteration_are_followed():
     opt.close()
 
 
+def test_learnt_layout_mode_matches_the_oracle_and_survives_new_gradient_buffers():
+    # parameters stay where PyTorch put them; the plan learns the die layout of the big ones by timing
+    print("[gpu-stage-optimizer] learn_layout=True", flush=True)
+    kind, kw, hp = CASES[0]                                          # AdamW
+    torch.manual_seed(5)
+    model = torch.nn.Sequential(torch.nn.Linear(1024, 2048), torch.nn.Tanh(), torch.nn.Linear(2048, 512)).to(DEV)
+    opt = StageOptimizer(model.parameters(), kind, rank=0, depth=3, arena=False, learn_layout=True, **kw)
+    n_local = opt.n_local_params
+    print("[gpu-stage-optimizer] learnt order for %d of %d parameters" % (n_local, sum(p.numel() for p in model.parameters())), flush=True)
+    assert n_local >= 1 << 21                                        # at least the first layer's weight matrix
+    x = torch.randn(32, 1024, device=DEV)
+    y = torch.randn(32, 512, device=DEV)
+    for it in range(3):
+        if it == 1:
+            for p in model.parameters():
+                p.grad = None                                        # autograd allocates new gradient buffers
+        else:
+            opt.zero_grad()
+        with opt.predicted_weights():
+            loss = torch.nn.functional.mse_loss(model(x), y)
+        loss.backward()
+        st = opt.state()
+        before = [{"W": st["W"][i].cpu().numpy().copy(), "g": p.grad.view(-1).cpu().numpy().copy(),
+                   "m": st["m"][i].cpu().numpy().copy(), "v": st["v"][i].cpu().numpy().copy()}
+                  for i, p in enumerate(model.parameters())]
+        opt.step()
+        torch.cuda.synchronize()
+        assert opt.n_local_params == n_local                         # new gradient buffers keep the learnt order
+        st = opt.state()
+        for i, inp in enumerate(before):
+            ref = run_oracle(kind, hp, it + 1, opt.s, inp)
+            got = {"W": st["W"][i].cpu().numpy(), "m": st["m"][i].cpu().numpy(), "v": st["v"][i].cpu().numpy(),
+                   "What": st["What"][i].cpu().numpy()}
+            compare(kind, hp, it + 1, opt.s, inp, ref, got, "f32", "learnt layout iteration %d parameter %d" % (it, i))
+    opt.close()
+
+
 def test_forward_inside_the_block_uses_the_predicted_weights():
     model = _mlp(5)
     opt = StageOptimizer(model.parameters(), "adamw", lr=0.05, rank=0, depth=3)

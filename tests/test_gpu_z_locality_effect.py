@@ -63,6 +63,44 @@ def test_localized_plan_is_faster_than_the_plain_order_on_the_same_memory():
         tensors["stage_arena"].close()
 
 
+def test_learnt_order_is_faster_than_the_plain_order_on_plain_allocations():
+    """Plain PyTorch allocations: after pipeoptim_plan_learn_layout the same launches must not be slower than before
+    (measured: 3-4 % faster on this stage).  A vote that picked the wrong half per chunk would send two thirds of
+    the traffic to the far die and show here as a launch some 20 % slower."""
+    print("[gpu-locality] config 4 in plain allocations: learnt order against plain order", flush=True)
+    wl = workload(4)
+    tensors = make_inputs(wl, "cuda:0")
+    stage = Stage(tensors["W"], tensors["g"], tensors["m"], tensors["v"], wl.what_dtype)
+    try:
+        hyper = binding.make_hyper(wl.optimizer, wl.hyper["lr"], wl.hyper["beta1"], wl.hyper["beta2"], wl.hyper["eps"],
+                                   wl.hyper["weight_decay"], True)
+        bytes_per_launch = 30 * wl.n_params
+        step = lambda i: stage.step_predict(hyper, wl.t + i, 3)
+        stage.plan.set_launch(lds_bytes=16384)                 # the same occupancy cap for both orders
+        tbps = lambda ms: bytes_per_launch / ms / 1e9
+        cur = torch.cuda.current_stream().cuda_stream
+
+        def measure():
+            stage.plan.set_pointers(0, [x.data_ptr() for x in stage.W], cur)      # drops whatever was learnt
+            assert stage.plan.local_params() == 0
+            plain_ms = _median_ms(step)
+            n_local = stage.plan.learn_layout(cur)
+            assert n_local >= 0.9 * wl.n_params
+            learnt_ms = _median_ms(step)
+            print("[gpu-locality] medians of 100 launches: learnt order %.1f us (%.2f TB/s, %d of %d parameters), plain "
+                  "order %.1f us (%.2f TB/s)" % (learnt_ms * 1e3, tbps(learnt_ms), n_local, wl.n_params, plain_ms * 1e3,
+                                                 tbps(plain_ms)), flush=True)
+            return learnt_ms, plain_ms
+
+        learnt_ms, plain_ms = measure()
+        if not learnt_ms <= plain_ms:
+            print("[gpu-locality] learnt order not ahead; measuring once more", flush=True)
+            learnt_ms, plain_ms = measure()
+        assert learnt_ms <= plain_ms, "learnt order %.1f us, plain order %.1f us" % (learnt_ms * 1e3, plain_ms * 1e3)
+    finally:
+        stage.close()
+
+
 def test_time_does_not_depend_on_the_version_difference():
     """s enters the kernel as one scalar product and one flag: config 4 at s = 0 and s = 7 must take the same time
     (within 1 %, medians of 100 launches each, taken in alternation; one more measurement on a miss)."""
