@@ -321,7 +321,8 @@ def make_hyper(kind, hp, decay_in_prediction=True):
 def run_and_compare_full(kind, hp, t, s, tensors, what_dtype, launch=None, decay_in_prediction=True, label="",
                          learn=False):
     """tensors: dict of lists of device tensors W, g, m, v (m or v None where the optimizer has no such state).
-    Compares every element.  `learn`: the plan first learns the die layout of the buffers by timing."""
+    Compares every element.  `learn`: the plan first learns the die layout of the buffers by timing (True: and
+    something must come of it; None: and nothing can)."""
     host = [{k: host_f32(tensors[k][i]) for k in ("W", "g", "m", "v") if tensors.get(k) is not None}
             for i in range(len(tensors["W"]))]
     g_before = [raw_bits(x) for x in tensors["g"]]
@@ -330,7 +331,10 @@ def run_and_compare_full(kind, hp, t, s, tensors, what_dtype, launch=None, decay
     try:
         if launch:
             stage.plan.set_launch(**launch)
-        if learn:
+        if learn is None:                                   # call it, expect nothing to be learnt (no whole 2 MiB piece)
+            assert stage.plan.learn_layout(torch.cuda.current_stream().cuda_stream) == 0
+            assert all(mark == -1 for mark in stage.plan.chunk_marks())
+        elif learn:
             assert stage.plan.learn_layout(torch.cuda.current_stream().cuda_stream) > 0
         stage.step_predict(make_hyper(kind, hp, decay_in_prediction), t, s)
         torch.cuda.synchronize()

@@ -172,3 +172,56 @@ def test_learning_costs_no_more_than_a_set_up_step():
         assert dt < 1.0
     finally:
         st.close()
+
+
+def test_a_launch_in_the_learnt_order_can_be_captured_and_replayed():
+    """The learnt order adds nothing to a call but two bits per chunk entry and the launch-phase word: the call
+    still enqueues exactly one kernel, and every replay of a captured call equals an eager call from the same state."""
+    _say("graph capture under the learnt order")
+    hyper = binding.make_hyper("adamw", HP["lr"], HP["beta1"], HP["beta2"], HP["eps"], HP["weight_decay"], True)
+    a, b = _ragged(21), _ragged(21)
+    sa = Stage(a["W"], a["g"], a["m"], a["v"], "bf16", learn_layout=True)
+    sb = Stage(b["W"], b["g"], b["m"], b["v"], "bf16")                 # eager, plain order
+    try:
+        assert sa.n_local_params > 0
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.stream(side):
+            sa.step_predict(hyper, 9, 2)                 # warm-up outside the capture (counts as replay 0)
+            torch.cuda.synchronize()
+            with torch.cuda.graph(graph, stream=side):
+                sa.step_predict(hyper, 9, 2)
+        torch.cuda.current_stream().wait_stream(side)
+        sb.step_predict(hyper, 9, 2)
+        for replay in range(3):
+            graph.replay()
+            sb.step_predict(hyper, 9, 2)
+            torch.cuda.synchronize()
+            assert np.isfinite(torch.randn(1 << 20, device=DEV).sum().item())      # unrelated eager work between replays
+            for name in ("W", "m", "v", "What"):
+                for i, (u, w) in enumerate(zip(getattr(sa, name), getattr(sb, name))):
+                    assert np.array_equal(raw_bits(u), raw_bits(w)), (replay, i, name)
+    finally:
+        sa.close()
+        sb.close()
+
+
+def test_nothing_to_learn_is_not_an_error():
+    """An empty plan, and a plan whose buffers hold no whole 2 MiB piece: nothing is timed, nothing is marked, and the
+    plan works as before."""
+    _say("empty and tiny plans")
+    empty = binding.Plan([], [], [], [], [], [], "bf16")
+    try:
+        assert empty.learn_layout(_stream()) == 0 and empty.chunk_marks() == [] and empty.near_share() == 0.5
+    finally:
+        empty.destroy()
+    t = {"W": [], "g": [], "m": [], "v": []}
+    gen = torch.Generator(device=DEV)
+    gen.manual_seed(31)
+    for n in (70000, 4096, 300001, 17):
+        t["W"].append(torch.randn(n, generator=gen, device=DEV) * 0.02)
+        t["g"].append(torch.randn(n, generator=gen, device=DEV) * 1e-3)
+        t["m"].append(torch.randn(n, generator=gen, device=DEV) * 1e-4)
+        t["v"].append((torch.randn(n, generator=gen, device=DEV) * 1e-3).square())
+    run_and_compare_full("adamw", HP, 5, 2, t, "bf16", label="tiny plan after learn_layout", learn=None)
