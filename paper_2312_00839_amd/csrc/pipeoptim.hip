@@ -792,6 +792,8 @@ try {
     const uintptr_t chunk_bytes = (uintptr_t)p->launch.chunk_elems * 4;
     if (chunk_bytes < 16384 || chunk_bytes > kPiece)
         return po_fail(PO_EINVAL, "learning the layout needs chunk_elems between 4096 and 524288 (it is %lld)", (long long)p->launch.chunk_elems);
+    if ((int64_t)p->launch.block * 4 != PO_LOCAL_TILE_ELEMS)
+        return po_fail(PO_EINVAL, "the near-memory tile order is defined for 256-element tiles (block 64); the plan's block is %d", p->launch.block);
     const hipStream_t stream = static_cast<hipStream_t>(hip_stream);
     // nothing of the plan may be in flight while its tables change under a launch's feet (the timing below waits
     // for the whole device anyway)
@@ -809,29 +811,30 @@ try {
         if (p->what_dtype == PO_WHAT_F32) out[k++] = {d.What, 4};
         return k;
     };
-    // A stream takes part if its base is a multiple of the chunk size in bytes: then no chunk of it straddles two
-    // 2 MiB pieces and every 16 KiB group of tiles is two whole 8 KiB blocks of it.  (A stream that is not, e.g. one
-    // placed at a staggered address, is half near and half far under either order and has no say.)
-    std::vector<std::pair<uintptr_t, uintptr_t>> ranges;          // whole 2 MiB pieces inside the buffers, [lo, hi)
+    // Every byte of every fp32 stream is readable device memory, so every whole 2 MiB piece inside the union of the
+    // streams' ranges may be timed (buffers that a caching allocator placed back to back merge into one range).
+    std::vector<std::pair<uintptr_t, uintptr_t>> ranges;          // exact byte ranges of the streams, [lo, hi)
     for (int64_t i = 0; i < p->n_tensors; ++i) {
         const po_tensor_desc& d = p->descs[(size_t)i];
         if (d.numel == 0) continue;
         Stream st[5];
         const int ns = streams_of(d, st);
-        for (int k = 0; k < ns; ++k) {
-            if (((uintptr_t)st[k].base % chunk_bytes) != 0) continue;
-            const uintptr_t b = (uintptr_t)st[k].base, e = b + (uintptr_t)d.numel * 4;
-            const uintptr_t lo = (b + kPiece - 1) / kPiece * kPiece, hi = e / kPiece * kPiece;
-            if (lo < hi) ranges.push_back({lo, hi});
-        }
+        for (int k = 0; k < ns; ++k) ranges.push_back({(uintptr_t)st[k].base, (uintptr_t)st[k].base + (uintptr_t)d.numel * 4});
     }
     std::sort(ranges.begin(), ranges.end());
-    std::vector<std::pair<uintptr_t, uintptr_t>> merged;
-    for (const auto& r : ranges) {
-        if (!merged.empty() && r.first <= merged.back().second) merged.back().second = std::max(merged.back().second, r.second);
-        else merged.push_back(r);
+    std::vector<std::pair<uintptr_t, uintptr_t>> merged;          // whole pieces inside the union, [lo, hi)
+    {
+        std::vector<std::pair<uintptr_t, uintptr_t>> whole;
+        for (const auto& r : ranges) {
+            if (!whole.empty() && r.first <= whole.back().second) whole.back().second = std::max(whole.back().second, r.second);
+            else whole.push_back(r);
+        }
+        for (const auto& r : whole) {
+            const uintptr_t lo = (r.first + kPiece - 1) / kPiece * kPiece, hi = r.second / kPiece * kPiece;
+            if (lo < hi) merged.push_back({lo, hi});
+        }
     }
-    std::vector<std::vector<int8_t>> layout(merged.size());        // per merged range: one answer per piece
+    std::vector<std::vector<int8_t>> layout(merged.size());        // per range: one answer per piece
     for (size_t k = 0; k < merged.size(); ++k) {
         const size_t n = (size_t)((merged[k].second - merged[k].first) / kPiece);
         layout[k].assign(n, (int8_t)-1);
@@ -845,28 +848,45 @@ try {
         if (addr < it->first || addr >= it->second) return -1;
         return layout[(size_t)(it - merged.begin())][(size_t)((addr - it->first) / kPiece)];
     };
-    // chunk by chunk: the half that brings more bytes near wins; a chunk none of whose streams is known stays plain
+    // Chunk by chunk: the half that brings more bytes near wins; a chunk none of whose streams is known stays plain.
+    // What a stream has to say: under mark h the XCCs of half h take the first 8 KiB of every 16 KiB of the chunk's
+    // elements.  With the stream's chunk starting o bytes into an 8 KiB block whose near half is x, 8192 - o of those
+    // bytes lie in that block and o in the next one (near to the other half), and the second 8 KiB likewise: the
+    // stream's bytes vote (8192 - o) : o for x.  o = 0 for buffers on a block boundary (any large allocation); a
+    // stream 4 KiB off has no say, being half near and half far under either order.  A chunk that straddles two
+    // pieces votes with each part's own layout.
     std::vector<int8_t> mark(p->chunks.size(), (int8_t)-1);
     int64_t n_local = 0;
     double near_gain = 0.0;
     for (size_t k = 0; k < p->chunks.size(); ++k) {
         const po_chunk& ch = p->chunks[k];
         const po_tensor_desc& d = p->descs[ch.tensor];
-        Stream st[5];
-        const int ns = streams_of(d, st);
-        int near_weight[2] = {0, 0};
-        for (int j = 0; j < ns; ++j) {
-            if (((uintptr_t)st[j].base % chunk_bytes) != 0) continue;
-            const int h = piece_layout((uintptr_t)st[j].base + (uintptr_t)ch.chunk * chunk_bytes);
-            if (h >= 0) near_weight[h] += st[j].weight;
-        }
-        if (near_weight[0] + near_weight[1] == 0) continue;
-        mark[k] = (int8_t)(near_weight[1] > near_weight[0] ? 1 : 0);
         const int64_t begin = (int64_t)ch.chunk * p->launch.chunk_elems;
         const int64_t elems = std::min<int64_t>(p->launch.chunk_elems, d.numel - begin);
+        Stream st[5];
+        const int ns = streams_of(d, st);
+        double near_weight[2] = {0.0, 0.0};                        // bytes of the call's traffic
+        for (int j = 0; j < ns; ++j) {
+            const uintptr_t a0 = (uintptr_t)st[j].base + (uintptr_t)begin * 4, a1 = a0 + (uintptr_t)elems * 4;
+            const double o = (double)(a0 % 8192u) / 8192.0;
+            const int first_block_odd = (int)((a0 >> 13) & 1u);
+            for (uintptr_t at = a0; at < a1;) {
+                const uintptr_t stop = std::min(a1, (at / kPiece + 1) * kPiece);
+                const int pol = piece_layout(at);
+                if (pol >= 0) {
+                    const int x = first_block_odd ^ pol;
+                    const double traffic = (double)(stop - at) * (st[j].weight / 4.0);
+                    near_weight[x] += traffic * (1.0 - o);
+                    near_weight[1 - x] += traffic * o;
+                }
+                at = stop;
+            }
+        }
+        if (near_weight[0] + near_weight[1] == 0.0) continue;
+        mark[k] = (int8_t)(near_weight[1] > near_weight[0] ? 1 : 0);
         n_local += elems;
         // of the voting bytes the winner's are near and the loser's far; the plain order had half of each near
-        near_gain += 0.5 * std::abs(near_weight[1] - near_weight[0]) * (double)elems;
+        near_gain += 0.5 * std::fabs(near_weight[1] - near_weight[0]);
     }
     if (!p->h_phase && n_local > 0) {
         hipError_t eh = hipHostMalloc(reinterpret_cast<void**>(&p->h_phase), 64, hipHostMallocDefault);

@@ -148,6 +148,10 @@ def test_what_drops_the_learnt_marks_and_what_keeps_them():
         with pytest.raises(binding.PipeOptimError) as ei:
             st.plan.learn_layout(_stream())
         assert ei.value.status == binding.PO_EINVAL
+        st.plan.set_launch(chunk_elems=65536, block=128)        # 512-element tiles: the order is not defined for them
+        with pytest.raises(binding.PipeOptimError) as ei:
+            st.plan.learn_layout(_stream())
+        assert ei.value.status == binding.PO_EINVAL
         hyper = binding.make_hyper("adamw", HP["lr"], HP["beta1"], HP["beta2"], HP["eps"], HP["weight_decay"], True)
         st.plan.set_pointers(1, [x.data_ptr() for x in t["g"]], _stream())
         st.step_predict(hyper, 3, 1)
@@ -225,3 +229,45 @@ def test_nothing_to_learn_is_not_an_error():
         t["m"].append(torch.randn(n, generator=gen, device=DEV) * 1e-4)
         t["v"].append((torch.randn(n, generator=gen, device=DEV) * 1e-3).square())
     run_and_compare_full("adamw", HP, 5, 2, t, "bf16", label="tiny plan after learn_layout", learn=None)
+
+
+def test_streams_at_odd_offsets_and_back_to_back_buffers():
+    """All streams carved out of one allocation, back to back (so that whole 2 MiB pieces span several buffers) and at
+    offsets that are not chunk multiples: on a block boundary but in an odd block, 4 KiB into a block (no say in the
+    vote), 1 KiB into a block, 16 bytes and (one tensor) 4 bytes off.  The learnt order must still give the plain order's results bit for bit."""
+    _say("one slab, streams at odd offsets")
+    hyper = binding.make_hyper("adamw", HP["lr"], HP["beta1"], HP["beta2"], HP["eps"], HP["weight_decay"], True)
+    sizes = [(3 << 20) + 5, 1 << 20, 70001, (1 << 21)]
+    offsets = {"W": 0, "g": 8192, "m": 4096, "v": 1024, "What": 16}
+    outs = []
+    for learn in (False, True):
+        gen = torch.Generator(device=DEV)
+        gen.manual_seed(41)
+        slab = torch.zeros(sum(5 * (n * 4 + 16384) for n in sizes) + (4 << 20), dtype=torch.uint8, device=DEV)
+        at = (-slab.data_ptr()) % (2 << 20)                       # start on a piece boundary
+        t = {k: [] for k in offsets}
+        for j, n in enumerate(sizes):
+            for k in ("W", "g", "m", "v", "What"):
+                lo = at + (4 if (k == "What" and j == 2) else offsets[k])        # tensor 2: the per-element path
+                x = slab[lo:lo + 4 * n].view(torch.float32)
+                at = (lo + 4 * n + 1023) // 1024 * 1024
+                if k != "What":
+                    x.copy_(torch.randn(n, generator=gen, device=DEV) * (0.02 if k == "W" else 1e-3))
+                    if k == "v":
+                        x.square_()
+                t[k].append(x)
+        st = Stage(t["W"], t["g"], t["m"], t["v"], "f32", What=t["What"], learn_layout=learn)
+        try:
+            if learn:
+                marks = st.plan.chunk_marks()
+                _say("marks: %d for half 0, %d for half 1, %d plain; near share %.3f"
+                     % (marks.count(0), marks.count(1), marks.count(-1), st.plan.near_share()))
+                assert st.n_local_params > 0 and 0.5 <= st.plan.near_share() <= 1.0
+            st.step_predict(hyper, 10, 3)
+            torch.cuda.synchronize()
+            outs.append([[raw_bits(x) for x in col] for col in (st.W, st.m, st.v, st.What)])
+        finally:
+            st.close()
+    for name, a, b in zip(("W", "m", "v", "What"), outs[0], outs[1]):
+        for i, (x, y) in enumerate(zip(a, b)):
+            assert np.array_equal(x, y), "%s of tensor %d differs between the two orders" % (name, i)
