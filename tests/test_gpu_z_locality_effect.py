@@ -63,10 +63,10 @@ def test_localized_plan_is_faster_than_the_plain_order_on_the_same_memory():
         tensors["stage_arena"].close()
 
 
-def test_learnt_order_is_faster_than_the_plain_order_on_plain_allocations():
+def test_learnt_order_is_not_slower_than_the_plain_order_on_plain_allocations():
     """Plain PyTorch allocations: after pipeoptim_plan_learn_layout the same launches must not be slower than before
-    (measured: 3-4 % faster on this stage).  A vote that picked the wrong half per chunk would send two thirds of
-    the traffic to the far die and show here as a launch some 20 % slower."""
+    (measured: 3-5 % faster on this stage).  A vote that picked the wrong half per chunk would send most of the
+    traffic to the far die and show here as a launch some 20 % slower."""
     print("[gpu-locality] config 4 in plain allocations: learnt order against plain order", flush=True)
     wl = workload(4)
     tensors = make_inputs(wl, "cuda:0")
@@ -92,11 +92,14 @@ def test_learnt_order_is_faster_than_the_plain_order_on_plain_allocations():
                                                  tbps(plain_ms)), flush=True)
             return learnt_ms, plain_ms
 
+        # how much the learnt order wins depends on how the allocator placed the streams (3-5 % as a rule, next to
+        # nothing if every tensor's streams split two against two); a vote for the wrong half loses 20 %.  So: not
+        # slower than the plain order beyond 1 % of noise, and one more measurement on a miss
         learnt_ms, plain_ms = measure()
-        if not learnt_ms <= plain_ms:
-            print("[gpu-locality] learnt order not ahead; measuring once more", flush=True)
+        if not learnt_ms <= 1.01 * plain_ms:
+            print("[gpu-locality] learnt order behind; measuring once more", flush=True)
             learnt_ms, plain_ms = measure()
-        assert learnt_ms <= plain_ms, "learnt order %.1f us, plain order %.1f us" % (learnt_ms * 1e3, plain_ms * 1e3)
+        assert learnt_ms <= 1.01 * plain_ms, "learnt order %.1f us, plain order %.1f us" % (learnt_ms * 1e3, plain_ms * 1e3)
     finally:
         stage.close()
 
