@@ -5,7 +5,9 @@ A "step" is one pass of the whole hot path over one stage of synthetic input tha
 is already resident in HBM: the version difference s = D - rank - 1 (paper Eq. 4),
 the host-side coefficient derivation, and the single fused kernel launch that
 updates W, m, v in place and writes the predicted weights What (paper Table 1,
-Eq. 1, Eq. 5).  The chunk table is built once per stage, before the timed region.
+Eq. 1, Eq. 5).  The chunk table is built once per stage, before the timed region, and so is
+the tile order of the "learnt" layout (one pipeoptim_plan_learn_layout call per stage, about
+0.1 s on the 0.74B-parameter stage, reported as `learn_layout_ms`).
 
 Prints ONE JSON line.  `value` is parameters per second over the timed steps in the
 layout named in `config.workload` (by default the caller's own plain PyTorch allocations
