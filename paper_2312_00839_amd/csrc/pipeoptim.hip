@@ -428,6 +428,103 @@ hipError_t order_behind_upload(const po_plan* p, hipStream_t stream)
 
 }  // namespace
 
+namespace {
+
+constexpr uintptr_t kPiece = uintptr_t(2) << 20;       // what the driver backs large allocations with; see near_arena.hip
+
+// The fp32 streams of a tensor and what each weighs in the fused call's traffic, in bytes moved per element.
+struct VotingStream { uintptr_t base; int weight; };
+int voting_streams(const po_plan* p, const po_tensor_desc& d, VotingStream out[5])
+{
+    int k = 0;
+    out[k++] = {(uintptr_t)d.W, 8};
+    if (p->grad_dtype == PO_GRAD_F32) out[k++] = {(uintptr_t)d.g, 4};
+    if (d.m) out[k++] = {(uintptr_t)d.m, 8};
+    if (d.v) out[k++] = {(uintptr_t)d.v, 8};
+    if (p->what_dtype == PO_WHAT_F32) out[k++] = {(uintptr_t)d.What, 4};
+    return k;
+}
+
+// What timing found out about the memory under a plan's buffers: for the 2 MiB pieces of some address ranges, the XCC
+// half that is near to the piece's 8 KiB blocks with address bit 13 clear (-1: could not be told).
+struct PieceLayout {
+    std::vector<std::pair<uintptr_t, uintptr_t>> ranges;      // sorted, disjoint, piece-aligned [lo, hi)
+    std::vector<std::vector<int8_t>> answer;                  // per range, per piece
+    int at(uintptr_t addr) const                              // -1: not timed or not decided
+    {
+        auto it = std::upper_bound(ranges.begin(), ranges.end(), std::make_pair(addr, ~uintptr_t(0)));
+        if (it == ranges.begin()) return -1;
+        --it;
+        if (addr < it->first || addr >= it->second) return -1;
+        return answer[(size_t)(it - ranges.begin())][(size_t)((addr - it->first) / kPiece)];
+    }
+};
+
+// Times every whole 2 MiB piece inside the union of the plan's fp32 streams.  Every byte of every stream is readable
+// device memory, so such a piece may be read wherever it lies (buffers that a caching allocator placed back to
+// back merge into one range).  Waits for the device, several times.
+int time_pieces_under(const po_plan* p, PieceLayout& out)
+{
+    std::vector<std::pair<uintptr_t, uintptr_t>> bytes;       // exact byte ranges of the streams
+    for (const po_tensor_desc& d : p->descs) {
+        if (d.numel == 0) continue;
+        VotingStream st[5];
+        const int ns = voting_streams(p, d, st);
+        for (int k = 0; k < ns; ++k) bytes.push_back({st[k].base, st[k].base + (uintptr_t)d.numel * 4});
+    }
+    std::sort(bytes.begin(), bytes.end());
+    std::vector<std::pair<uintptr_t, uintptr_t>> merged;
+    for (const auto& r : bytes) {
+        if (!merged.empty() && r.first <= merged.back().second) merged.back().second = std::max(merged.back().second, r.second);
+        else merged.push_back(r);
+    }
+    for (const auto& r : merged) {
+        const uintptr_t lo = (r.first + kPiece - 1) / kPiece * kPiece, hi = r.second / kPiece * kPiece;
+        if (lo < hi) out.ranges.push_back({lo, hi});
+    }
+    out.answer.resize(out.ranges.size());
+    for (size_t k = 0; k < out.ranges.size(); ++k) {
+        const size_t n = (size_t)((out.ranges[k].second - out.ranges[k].first) / kPiece);
+        out.answer[k].assign(n, (int8_t)-1);
+        const int rc = po_probe_layout(reinterpret_cast<const void*>(out.ranges[k].first), n, out.answer[k].data());
+        if (rc != PO_OK) return rc;
+    }
+    return PO_OK;
+}
+
+// One chunk-table entry's vote.  Under mark h the XCCs of half h take the first 8 KiB of every 16 KiB of the chunk's
+// elements.  With a stream's part of the chunk starting o bytes into an 8 KiB block whose near half is x, 8192 - o
+// of those bytes lie in that block and o in the next one (near to the other half), and the second 8 KiB likewise:
+// the stream's bytes vote (8192 - o) : o for x.  o = 0 for buffers on a block boundary (any large allocation); a
+// stream 4 KiB off has no say, being half near and half far under either order.  A chunk that straddles two pieces
+// votes with each part's own layout.  near[h] = bytes of the call's traffic that mark h would make near.
+void chunk_vote(const po_plan* p, const PieceLayout& pieces, const po_chunk& ch, int64_t elems, double near[2])
+{
+    const po_tensor_desc& d = p->descs[ch.tensor];
+    const uintptr_t begin = (uintptr_t)ch.chunk * (uintptr_t)p->launch.chunk_elems * 4;
+    VotingStream st[5];
+    const int ns = voting_streams(p, d, st);
+    near[0] = near[1] = 0.0;
+    for (int j = 0; j < ns; ++j) {
+        const uintptr_t a0 = st[j].base + begin, a1 = a0 + (uintptr_t)elems * 4;
+        const double o = (double)(a0 % 8192u) / 8192.0;
+        const int first_block_odd = (int)((a0 >> 13) & 1u);
+        for (uintptr_t at = a0; at < a1;) {
+            const uintptr_t stop = std::min(a1, (at / kPiece + 1) * kPiece);
+            const int even_blocks_near = pieces.at(at);
+            if (even_blocks_near >= 0) {
+                const int x = first_block_odd ^ even_blocks_near;
+                const double traffic = (double)(stop - at) * (st[j].weight / 4.0);
+                near[x] += traffic * (1.0 - o);
+                near[1 - x] += traffic * o;
+            }
+            at = stop;
+        }
+    }
+}
+
+}  // namespace
+
 extern "C" {
 
 const char* pipeoptim_last_error(void) { return g_err; }
@@ -788,110 +885,46 @@ try {
     if (!p) return po_fail(PO_EINVAL, "plan is NULL");
     int rc = check_device(p);
     if (rc != PO_OK) return rc;
-    constexpr uintptr_t kPiece = uintptr_t(2) << 20;
     const uintptr_t chunk_bytes = (uintptr_t)p->launch.chunk_elems * 4;
     if (chunk_bytes < 16384 || chunk_bytes > kPiece)
         return po_fail(PO_EINVAL, "learning the layout needs chunk_elems between 4096 and 524288 (it is %lld)", (long long)p->launch.chunk_elems);
     if ((int64_t)p->launch.block * 4 != PO_LOCAL_TILE_ELEMS)
         return po_fail(PO_EINVAL, "the near-memory tile order is defined for 256-element tiles (block 64); the plan's block is %d", p->launch.block);
     const hipStream_t stream = static_cast<hipStream_t>(hip_stream);
-    // nothing of the plan may be in flight while its tables change under a launch's feet (the timing below waits
-    // for the whole device anyway)
+    // nothing of the plan may be in flight while its tables change under a launch's feet (the timing waits for the
+    // whole device anyway)
     rc = wait_for_plan_streams(p);
     if (rc != PO_OK) return rc;
+    PieceLayout pieces;
+    rc = time_pieces_under(p, pieces);
+    if (rc != PO_OK) return rc;
 
-    // the fp32 streams of a tensor and what each weighs in bytes moved per element (read + written)
-    struct Stream { const void* base; int weight; };
-    auto streams_of = [&](const po_tensor_desc& d, Stream out[5]) {
-        int k = 0;
-        out[k++] = {d.W, 8};
-        if (p->grad_dtype == PO_GRAD_F32) out[k++] = {d.g, 4};
-        if (d.m) out[k++] = {d.m, 8};
-        if (d.v) out[k++] = {d.v, 8};
-        if (p->what_dtype == PO_WHAT_F32) out[k++] = {d.What, 4};
-        return k;
-    };
-    // Every byte of every fp32 stream is readable device memory, so every whole 2 MiB piece inside the union of the
-    // streams' ranges may be timed (buffers that a caching allocator placed back to back merge into one range).
-    std::vector<std::pair<uintptr_t, uintptr_t>> ranges;          // exact byte ranges of the streams, [lo, hi)
-    for (int64_t i = 0; i < p->n_tensors; ++i) {
-        const po_tensor_desc& d = p->descs[(size_t)i];
-        if (d.numel == 0) continue;
-        Stream st[5];
-        const int ns = streams_of(d, st);
-        for (int k = 0; k < ns; ++k) ranges.push_back({(uintptr_t)st[k].base, (uintptr_t)st[k].base + (uintptr_t)d.numel * 4});
-    }
-    std::sort(ranges.begin(), ranges.end());
-    std::vector<std::pair<uintptr_t, uintptr_t>> merged;          // whole pieces inside the union, [lo, hi)
-    {
-        std::vector<std::pair<uintptr_t, uintptr_t>> whole;
-        for (const auto& r : ranges) {
-            if (!whole.empty() && r.first <= whole.back().second) whole.back().second = std::max(whole.back().second, r.second);
-            else whole.push_back(r);
-        }
-        for (const auto& r : whole) {
-            const uintptr_t lo = (r.first + kPiece - 1) / kPiece * kPiece, hi = r.second / kPiece * kPiece;
-            if (lo < hi) merged.push_back({lo, hi});
-        }
-    }
-    std::vector<std::vector<int8_t>> layout(merged.size());        // per range: one answer per piece
-    for (size_t k = 0; k < merged.size(); ++k) {
-        const size_t n = (size_t)((merged[k].second - merged[k].first) / kPiece);
-        layout[k].assign(n, (int8_t)-1);
-        rc = po_probe_layout(reinterpret_cast<const void*>(merged[k].first), n, layout[k].data());
-        if (rc != PO_OK) return rc;
-    }
-    auto piece_layout = [&](uintptr_t addr) -> int {               // -1: not probed or not decided
-        auto it = std::upper_bound(merged.begin(), merged.end(), std::make_pair(addr, ~uintptr_t(0)));
-        if (it == merged.begin()) return -1;
-        --it;
-        if (addr < it->first || addr >= it->second) return -1;
-        return layout[(size_t)(it - merged.begin())][(size_t)((addr - it->first) / kPiece)];
-    };
-    // Chunk by chunk: the half that brings more bytes near wins; a chunk none of whose streams is known stays plain.
-    // What a stream has to say: under mark h the XCCs of half h take the first 8 KiB of every 16 KiB of the chunk's
-    // elements.  With the stream's chunk starting o bytes into an 8 KiB block whose near half is x, 8192 - o of those
-    // bytes lie in that block and o in the next one (near to the other half), and the second 8 KiB likewise: the
-    // stream's bytes vote (8192 - o) : o for x.  o = 0 for buffers on a block boundary (any large allocation); a
-    // stream 4 KiB off has no say, being half near and half far under either order.  A chunk that straddles two
-    // pieces votes with each part's own layout.
+    // chunk by chunk: the half that brings more bytes near wins; a chunk none of whose streams is known stays plain
     std::vector<int8_t> mark(p->chunks.size(), (int8_t)-1);
     int64_t n_local = 0;
     double near_gain = 0.0;
     for (size_t k = 0; k < p->chunks.size(); ++k) {
         const po_chunk& ch = p->chunks[k];
-        const po_tensor_desc& d = p->descs[ch.tensor];
         const int64_t begin = (int64_t)ch.chunk * p->launch.chunk_elems;
-        const int64_t elems = std::min<int64_t>(p->launch.chunk_elems, d.numel - begin);
-        Stream st[5];
-        const int ns = streams_of(d, st);
-        double near_weight[2] = {0.0, 0.0};                        // bytes of the call's traffic
-        for (int j = 0; j < ns; ++j) {
-            const uintptr_t a0 = (uintptr_t)st[j].base + (uintptr_t)begin * 4, a1 = a0 + (uintptr_t)elems * 4;
-            const double o = (double)(a0 % 8192u) / 8192.0;
-            const int first_block_odd = (int)((a0 >> 13) & 1u);
-            for (uintptr_t at = a0; at < a1;) {
-                const uintptr_t stop = std::min(a1, (at / kPiece + 1) * kPiece);
-                const int pol = piece_layout(at);
-                if (pol >= 0) {
-                    const int x = first_block_odd ^ pol;
-                    const double traffic = (double)(stop - at) * (st[j].weight / 4.0);
-                    near_weight[x] += traffic * (1.0 - o);
-                    near_weight[1 - x] += traffic * o;
-                }
-                at = stop;
-            }
-        }
-        if (near_weight[0] + near_weight[1] == 0.0) continue;
-        mark[k] = (int8_t)(near_weight[1] > near_weight[0] ? 1 : 0);
+        const int64_t elems = std::min<int64_t>(p->launch.chunk_elems, p->descs[ch.tensor].numel - begin);
+        double near[2];
+        chunk_vote(p, pieces, ch, elems, near);
+        if (near[0] + near[1] == 0.0) continue;
+        mark[k] = (int8_t)(near[1] > near[0] ? 1 : 0);
         n_local += elems;
         // of the voting bytes the winner's are near and the loser's far; the plain order had half of each near
-        near_gain += 0.5 * std::fabs(near_weight[1] - near_weight[0]);
+        near_gain += 0.5 * std::fabs(near[1] - near[0]);
     }
     if (!p->h_phase && n_local > 0) {
         hipError_t eh = hipHostMalloc(reinterpret_cast<void**>(&p->h_phase), 64, hipHostMallocDefault);
         if (eh != hipSuccess) { p->h_phase = nullptr; return po_fail(PO_ENOMEM, "hipHostMalloc(phase word): %s", hipGetErrorString(eh)); }
         *p->h_phase = 0;
+    }
+    if (n_local > 0) {
+        // where this stream's launches start: a tiny kernel reports it, and the answer is needed before the next launch
+        hipError_t e = po_launch_phase_probe(p->h_phase, stream);
+        if (e == hipSuccess) e = hipStreamSynchronize(stream);
+        if (e != hipSuccess) return fail_hip(e, "phase probe");
     }
     // arena marks and learnt marks do not mix: drop the former (descriptors), install the latter (chunk table)
     const std::vector<po_tensor_desc> saved = p->descs;
@@ -900,6 +933,8 @@ try {
     if (had_arena_marks) {
         rc = upload_descs(p, stream);
         if (rc != PO_OK) { p->descs = saved; return rc; }
+        p->n_local_params = 0;
+        p->near_bytes = 0.0;
     }
     const std::vector<int8_t> old_mark = p->chunk_mark;
     const bool old_valid = p->chunk_marks_valid;
@@ -907,11 +942,6 @@ try {
     p->chunk_marks_valid = true;
     rc = upload_chunks(p, stream);
     if (rc != PO_OK) { p->chunk_mark = old_mark; p->chunk_marks_valid = old_valid; return rc; }
-    if (n_local > 0) {
-        hipError_t e = po_launch_phase_probe(p->h_phase, stream);      // where this stream's launches start
-        if (e == hipSuccess) e = hipStreamSynchronize(stream);
-        if (e != hipSuccess) return fail_hip(e, "phase probe");
-    }
     p->n_local_params = n_local;
     p->near_bytes = near_gain;
     if (n_local_params) *n_local_params = n_local;
