@@ -208,8 +208,13 @@ def main():
         if layout == "learnt":                                        # a set-up step, outside the timed region like plan creation
             torch.cuda.synchronize()
             t_learn = time.perf_counter()
-            stage.n_local_params = stage.plan.learn_layout(stream.cuda_stream)
-            learn_ms = (time.perf_counter() - t_learn) * 1e3
+            try:
+                stage.n_local_params = stage.plan.learn_layout(stream.cuda_stream)
+                learn_ms = (time.perf_counter() - t_learn) * 1e3
+            except binding.PipeOptimError as e:
+                # the layout rule is defined for an MI355X in one partition: say so, measure the plain tile order
+                print("bench.py: the layout could not be learnt (%s); measuring the plain tile order instead" % e, file=sys.stderr)
+                layout = "packed (layout not learnt)"
         L = stage.plan.get_predict_launch() if predict_only else stage.plan.get_launch()
 
         def one_step(i):
