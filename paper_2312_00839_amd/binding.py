@@ -60,7 +60,7 @@ EXPORTS = (
     "pipeoptim_arena_info", "pipeoptim_arena_check", "pipeoptim_arena_destroy", "pipeoptim_plan_localize", "pipeoptim_plan_effective_launch",
     "pipeoptim_local_tile", "pipeoptim_local_slot", "pipeoptim_plan_local_params", "pipeoptim_plan_launch_phase",
     "pipeoptim_device_sync_count", "pipeoptim_step_predict_static", "pipeoptim_plan_learn_layout", "pipeoptim_plan_chunk_marks",
-    "pipeoptim_plan_near_share",
+    "pipeoptim_plan_near_share", "pipeoptim_chunk_vote",
 )
 PO_STATIC_MAX_TENSORS, PO_STATIC_MAX_CHUNKS = 1024, 65536
 
@@ -108,6 +108,8 @@ def lib():
         L.pipeoptim_plan_learn_layout.argtypes = [vp, vp, P(i64)]
         L.pipeoptim_plan_chunk_marks.argtypes = [vp, P(ctypes.c_int8), i64, P(i64)]
         L.pipeoptim_plan_near_share.argtypes = [vp, P(ctypes.c_double)]
+        L.pipeoptim_chunk_vote.argtypes = [i32, P(ctypes.c_uint64), P(i32), i64, i64, P(ctypes.c_uint64), P(ctypes.c_int8),
+                                           P(ctypes.c_double)]
         L.pipeoptim_plan_launch_phase.argtypes = [vp, P(i32)]
         L.pipeoptim_plan_effective_launch.argtypes = [vp, i32, i32, P(po_launch)]
         L.pipeoptim_local_tile.argtypes = [ctypes.c_uint32, i32, P(ctypes.c_uint32)]
@@ -173,6 +175,16 @@ def pipeoptim_local_tile(tile_in_chunk: int, first_block_half: int) -> int:
     out = ctypes.c_uint32(0)
     _check(lib().pipeoptim_local_tile(int(tile_in_chunk), int(first_block_half), ctypes.byref(out)))
     return out.value
+
+
+def pipeoptim_chunk_vote(first_byte, weight, elems: int, piece_addr, even_blocks_near):
+    """Host-only: (near[0], near[1]) = bytes of traffic each tile-order mark would make near for one chunk."""
+    ns, npieces = len(first_byte), len(piece_addr)
+    near = (ctypes.c_double * 2)()
+    _check(lib().pipeoptim_chunk_vote(ns, (ctypes.c_uint64 * max(ns, 1))(*first_byte), (ctypes.c_int32 * max(ns, 1))(*weight),
+                                      int(elems), npieces, (ctypes.c_uint64 * max(npieces, 1))(*piece_addr),
+                                      (ctypes.c_int8 * max(npieces, 1))(*even_blocks_near), near))
+    return near[0], near[1]
 
 
 def pipeoptim_local_slot(workgroup: int, phase: int, n_slots: int) -> int:

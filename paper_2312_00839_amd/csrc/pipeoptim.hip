@@ -497,13 +497,10 @@ int time_pieces_under(const po_plan* p, PieceLayout& out)
 // of those bytes lie in that block and o in the next one (near to the other half), and the second 8 KiB likewise:
 // the stream's bytes vote (8192 - o) : o for x.  o = 0 for buffers on a block boundary (any large allocation); a
 // stream 4 KiB off has no say, being half near and half far under either order.  A chunk that straddles two pieces
-// votes with each part's own layout.  near[h] = bytes of the call's traffic that mark h would make near.
-void chunk_vote(const po_plan* p, const PieceLayout& pieces, const po_chunk& ch, int64_t elems, double near[2])
+// votes with each part's own layout.  near[h] = bytes of the call's traffic that mark h would make near; `begin` =
+// byte offset of the chunk inside each of the `ns` streams.
+void chunk_vote(const VotingStream* st, int ns, uintptr_t begin, int64_t elems, const PieceLayout& pieces, double near[2])
 {
-    const po_tensor_desc& d = p->descs[ch.tensor];
-    const uintptr_t begin = (uintptr_t)ch.chunk * (uintptr_t)p->launch.chunk_elems * 4;
-    VotingStream st[5];
-    const int ns = voting_streams(p, d, st);
     near[0] = near[1] = 0.0;
     for (int j = 0; j < ns; ++j) {
         const uintptr_t a0 = st[j].base + begin, a1 = a0 + (uintptr_t)elems * 4;
@@ -907,8 +904,10 @@ try {
         const po_chunk& ch = p->chunks[k];
         const int64_t begin = (int64_t)ch.chunk * p->launch.chunk_elems;
         const int64_t elems = std::min<int64_t>(p->launch.chunk_elems, p->descs[ch.tensor].numel - begin);
+        VotingStream st[5];
+        const int ns = voting_streams(p, p->descs[ch.tensor], st);
         double near[2];
-        chunk_vote(p, pieces, ch, elems, near);
+        chunk_vote(st, ns, (uintptr_t)begin * 4, elems, pieces, near);
         if (near[0] + near[1] == 0.0) continue;
         mark[k] = (int8_t)(near[1] > near[0] ? 1 : 0);
         n_local += elems;
@@ -949,6 +948,30 @@ try {
 }
 catch (const std::bad_alloc&) { return po_fail(PO_ENOMEM, "pipeoptim_plan_learn_layout: out of host memory"); }
 catch (...) { return po_fail(PO_EINVAL, "pipeoptim_plan_learn_layout: unexpected exception"); }
+
+int pipeoptim_chunk_vote(int32_t n_streams, const uint64_t* first_byte, const int32_t* weight, int64_t elems,
+                         int64_t n_pieces, const uint64_t* piece_addr, const int8_t* even_blocks_near, double* near)
+try {
+    if (n_streams < 0 || n_streams > 5 || elems < 0 || n_pieces < 0 || !near) return po_fail(PO_EINVAL, "bad argument");
+    if ((n_streams > 0 && (!first_byte || !weight)) || (n_pieces > 0 && (!piece_addr || !even_blocks_near)))
+        return po_fail(PO_EINVAL, "a required array is NULL");
+    PieceLayout pieces;
+    for (int64_t k = 0; k < n_pieces; ++k) {
+        if (piece_addr[k] % kPiece != 0 || (k > 0 && piece_addr[k] <= piece_addr[k - 1]))
+            return po_fail(PO_EINVAL, "piece addresses must be 2 MiB aligned and ascending");
+        if (even_blocks_near[k] < -1 || even_blocks_near[k] > 1) return po_fail(PO_EINVAL, "a piece's layout must be -1, 0 or 1");
+        pieces.ranges.push_back({(uintptr_t)piece_addr[k], (uintptr_t)piece_addr[k] + kPiece});
+        pieces.answer.push_back(std::vector<int8_t>(1, even_blocks_near[k]));
+    }
+    VotingStream st[5];
+    for (int32_t j = 0; j < n_streams; ++j) {
+        if ((first_byte[j] & 3u) || weight[j] < 0) return po_fail(PO_EINVAL, "stream %d: address not 4-byte aligned or negative weight", j);
+        st[j] = {(uintptr_t)first_byte[j], weight[j]};
+    }
+    chunk_vote(st, n_streams, 0, elems, pieces, near);
+    return PO_OK;
+}
+catch (const std::bad_alloc&) { return po_fail(PO_ENOMEM, "pipeoptim_chunk_vote: out of host memory"); }
 
 int pipeoptim_plan_chunk_marks(const po_plan* p, int8_t* out, int64_t capacity, int64_t* n_chunks)
 {

@@ -97,6 +97,15 @@ int main()
     EXPECT(pipeoptim_plan_chunk_marks(nullptr, nullptr, 0, &n_local) == PO_EINVAL);
     double share = 0.0;
     EXPECT(pipeoptim_plan_near_share(nullptr, &share) == PO_EINVAL);
+    {   // one stream of 4096 elements on a block boundary of a piece whose even blocks are near to half 1, weight 8
+        const uint64_t stream = uint64_t(64) << 21, piece = uint64_t(64) << 21;
+        const int32_t weight = 8;
+        const int8_t half = 1;
+        double near[2] = {-1.0, -1.0};
+        EXPECT(pipeoptim_chunk_vote(1, &stream, &weight, 4096, 1, &piece, &half, near) == PO_OK && near[0] == 0.0 && near[1] == 8.0 * 4096);
+        EXPECT(pipeoptim_chunk_vote(1, &stream, &weight, 4096, 1, &piece, &half, nullptr) == PO_EINVAL);
+        EXPECT(pipeoptim_chunk_vote(6, &stream, &weight, 4096, 1, &piece, &half, near) == PO_EINVAL);
+    }
     po_launch eff{};
     EXPECT(pipeoptim_plan_effective_launch(nullptr, PO_KERNEL_KIND_FUSED, PO_ADAM, &eff) == PO_EINVAL);
     for (int32_t first_half = 0; first_half < 2; ++first_half)

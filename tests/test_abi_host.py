@@ -186,6 +186,98 @@ def test_every_tile_is_taken_once_and_on_its_own_die_for_any_launch_phase(phase)
     assert L.pipeoptim_local_slot(0, 0, 16, None) == binding.PO_EINVAL
 
 
+PIECE = 2 << 20
+
+
+def _brute_force_near_bytes(first_byte, weight, elems, layout_of_piece, mark):
+    """The definition the vote summarises, tile by tile and block by block: under `mark` the workgroups of XCC half
+    (k mod 8) // 4 at position k of a run of 16 take tile pipeoptim_local_tile(k, mark); a byte is near if the 8 KiB
+    block it lies in is near to the half of the workgroup that moves it.  Bytes in pieces of unknown layout are
+    skipped.  Returns bytes of traffic (stream bytes times weight / 4)."""
+    near = 0.0
+    n_tiles = (elems + 255) // 256
+    for group in range(0, n_tiles, 16):
+        for k in range(16):
+            tile = group + binding.pipeoptim_local_tile(k, mark)
+            if tile >= n_tiles:                          # past the chunk's ragged end: that workgroup has nothing to do
+                continue
+            half = (k % 8) // 4
+            lo, hi = tile * 1024, min(elems * 4, tile * 1024 + 1024)
+            for base, w in zip(first_byte, weight):
+                a = base + lo
+                while a < base + hi:
+                    stop = min(base + hi, (a // 8192 + 1) * 8192)
+                    pol = layout_of_piece.get(a // PIECE * PIECE, -1)
+                    if pol >= 0 and (((a >> 13) & 1) ^ pol) == half:
+                        near += (stop - a) * w / 4.0
+                    a = stop
+    return near
+
+
+def test_chunk_vote_special_cases():
+    """The vote pipeoptim_plan_learn_layout takes per chunk, on cases with an answer that can be written down."""
+    base, CH = 64 * PIECE, 65536                         # a chunk of 65,536 fp32 elements = 256 KiB per stream
+    known = lambda *pols: ([base + k * PIECE for k in range(len(pols))], list(pols))
+    total = lambda weights: sum(weights) * CH            # bytes of traffic of the chunk
+    # all four streams on chunk boundaries in one piece whose even blocks are near to half 1: everything votes for 1
+    addr, pol = known(1)
+    streams, w = [base, base + CH * 4, base + 2 * CH * 4, base + 3 * CH * 4], [8, 4, 8, 8]
+    assert binding.pipeoptim_chunk_vote(streams, w, CH, addr, pol) == (0.0, float(total(w)))
+    # a stream that starts in an odd block votes the other way with all of its bytes
+    assert binding.pipeoptim_chunk_vote([base + 8192], [8], CH, *known(1, 1)) == (8.0 * CH, 0.0)
+    # 4 KiB into a block: half of its bytes are near under either mark
+    assert binding.pipeoptim_chunk_vote([base + 4096], [8], CH, *known(1, 1)) == (4.0 * CH, 4.0 * CH)
+    # 1 KiB into a block: 7 : 1
+    assert binding.pipeoptim_chunk_vote([base + 1024], [8], CH, *known(0, 0)) == (7.0 * CH, 1.0 * CH)
+    # two against two with equal weights: a tie; W, m against g alone: 16 : 4
+    two = [base, base + CH * 4, base + 8192 + 2 * CH * 4, base + 8192 + 3 * CH * 4]
+    assert binding.pipeoptim_chunk_vote(two, [8, 8, 8, 8], CH, addr, pol) == (16.0 * CH, 16.0 * CH)
+    assert binding.pipeoptim_chunk_vote(two[:3], [8, 8, 4], CH, addr, pol) == (4.0 * CH, 16.0 * CH)
+    # a chunk that straddles two pieces of opposite layout, one quarter in the first: votes part by part
+    start = base + PIECE - CH                            # CH bytes = a quarter of the chunk's 4 * CH bytes
+    assert binding.pipeoptim_chunk_vote([start], [8], CH, *known(0, 1)) == (2.0 * CH, 6.0 * CH)
+    # the second piece unknown: only the known quarter votes; nothing known: no vote
+    assert binding.pipeoptim_chunk_vote([start], [8], CH, *known(0, -1)) == (2.0 * CH, 0.0)
+    assert binding.pipeoptim_chunk_vote([start], [8], CH, [], []) == (0.0, 0.0)
+    assert binding.pipeoptim_chunk_vote([], [], CH, addr, pol) == (0.0, 0.0)
+    # errors
+    L = binding.lib()
+    near = (ctypes.c_double * 2)()
+    one64, one32, one8 = (ctypes.c_uint64 * 1)(base), (ctypes.c_int32 * 1)(8), (ctypes.c_int8 * 1)(0)
+    assert L.pipeoptim_chunk_vote(1, one64, one32, CH, 1, one64, one8, None) == binding.PO_EINVAL
+    assert L.pipeoptim_chunk_vote(6, one64, one32, CH, 1, one64, one8, near) == binding.PO_EINVAL
+    assert L.pipeoptim_chunk_vote(1, None, one32, CH, 1, one64, one8, near) == binding.PO_EINVAL
+    assert L.pipeoptim_chunk_vote(1, (ctypes.c_uint64 * 1)(base + 2), one32, CH, 1, one64, one8, near) == binding.PO_EINVAL
+    assert L.pipeoptim_chunk_vote(1, one64, one32, CH, 1, (ctypes.c_uint64 * 1)(base + 4096), one8, near) == binding.PO_EINVAL
+    assert L.pipeoptim_chunk_vote(1, one64, one32, CH, 1, one64, (ctypes.c_int8 * 1)(2), near) == binding.PO_EINVAL
+
+
+def test_chunk_vote_against_the_tile_by_tile_definition():
+    """Random streams (any 4-byte-aligned address, any weights), random piece layouts, whole and ragged chunks: the
+    vote must equal the near bytes counted tile by tile through the tile order itself, up to the groups that
+    straddle a piece boundary or the chunk's ragged end (16 KiB of each stream per such place)."""
+    import random
+    rng = random.Random(20231200839)
+    base = 512 * PIECE
+    for case in range(60):
+        ns = rng.randint(1, 5)
+        elems = rng.choice([4096, 8192, 65536, 65536, 5000, 12345, 300])
+        align = rng.choice([4, 16, 1024, 4096, 8192, 16384, 262144])
+        first = [base + rng.randrange(0, 6 * PIECE // align) * align for _ in range(ns)]
+        weight = [rng.choice([4, 8]) for _ in range(ns)]
+        layout = {base + k * PIECE: rng.choice([-1, 0, 0, 1, 1]) for k in range(8)}
+        addr = sorted(a for a, v in layout.items())
+        got = binding.pipeoptim_chunk_vote(first, weight, elems, addr, [layout[a] for a in addr])
+        slack = sum(w / 4.0 * 16384 * 3 for w in weight)      # tail group + at most one piece boundary, both sides
+        for mark in (0, 1):
+            want = _brute_force_near_bytes(first, weight, elems, layout, mark)
+            assert abs(got[mark] - want) <= slack, (case, mark, got, want, first, weight, elems)
+        if elems % 4096 == 0 and align >= 8192 and all((f % PIECE) + elems * 4 <= PIECE for f in first):
+            # whole groups of whole blocks inside one piece per stream: the vote is exact
+            for mark in (0, 1):
+                assert got[mark] == _brute_force_near_bytes(first, weight, elems, layout, mark), (case, mark)
+
+
 def test_arena_and_localize_argument_validation():
     L = binding.lib()
     h = ctypes.c_void_p()
