@@ -19,7 +19,8 @@ optimizer owns the stage's memory the way flat-parameter optimizers do: the para
 library's near-memory arena, next to their gradient, state and What buffers, so that both kernels run with every
 XCC on its own die's HBM.  ``close()`` moves them back out.  With ``arena=False, learn_layout=True`` the parameters
 stay where the caller put them, the other buffers are plain PyTorch allocations, and the plan finds out by timing
-which die each 2 MiB piece lies on (``pipeoptim_plan_learn_layout``): about two thirds of the way to the arena's gain.
+which die each 2 MiB piece lies on (``pipeoptim_plan_learn_layout``): most of the arena's gain, depending on how
+the allocator happened to place the buffers.
 """
 import contextlib
 import warnings

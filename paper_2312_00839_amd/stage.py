@@ -1,4 +1,5 @@
 """A pipeline stage's tensors bound to a libpipeoptim plan (PyTorch used for device memory only)."""
+import warnings
 from typing import List, Optional
 
 import torch
@@ -158,7 +159,10 @@ class Stage:
         self.n_local_params = (self.plan.localize(arena, torch.cuda.current_stream().cuda_stream)
                                if arena is not None else 0)
         if arena is None and learn_layout:
-            self.n_local_params = self.plan.learn_layout(torch.cuda.current_stream().cuda_stream)
+            try:
+                self.n_local_params = self.plan.learn_layout(torch.cuda.current_stream().cuda_stream)
+            except binding.PipeOptimError as e:         # e.g. not an MI355X in one partition: the plain order still works
+                warnings.warn("the layout of the buffers could not be learnt (%s): using the plain tile order" % e)
 
     @property
     def n_params(self) -> int:
