@@ -274,6 +274,13 @@ int pipeoptim_plan_learn_layout(po_plan* plan, void* hip_stream, int64_t* n_loca
 int pipeoptim_chunk_vote(int32_t n_streams, const uint64_t* first_byte, const int32_t* weight, int64_t elems,
                          int64_t n_pieces, const uint64_t* piece_addr, const int8_t* even_blocks_near, double* near);
 
+/* Host-only: which memory pipeoptim_plan_learn_layout may time.  Given n_ranges byte ranges [lo[k], hi[k]) (the plan's
+ * fp32 buffers; any order, may touch or overlap), the runs of whole 2 MiB-aligned pieces every byte of which lies in
+ * at least one range: run j is [piece_lo[j], piece_hi[j]), ascending; *n_runs = their number (at most `capacity` are
+ * written).  Nothing outside these runs is ever read by the timing. */
+int pipeoptim_whole_pieces(int64_t n_ranges, const uint64_t* lo, const uint64_t* hi, uint64_t* piece_lo, uint64_t* piece_hi,
+                           int64_t capacity, int64_t* n_runs);
+
 /* Diagnostic: out[k] (k < capacity) = what pipeoptim_plan_learn_layout decided for chunk-table entry k: -1 plain order,
  * 0 / 1 the XCC half that takes the first 8 KiB of every 16 KiB of the chunk's elements; *n_chunks = entries in the table. */
 int pipeoptim_plan_chunk_marks(const po_plan* plan, int8_t* out, int64_t capacity, int64_t* n_chunks);

@@ -60,7 +60,7 @@ EXPORTS = (
     "pipeoptim_arena_info", "pipeoptim_arena_check", "pipeoptim_arena_destroy", "pipeoptim_plan_localize", "pipeoptim_plan_effective_launch",
     "pipeoptim_local_tile", "pipeoptim_local_slot", "pipeoptim_plan_local_params", "pipeoptim_plan_launch_phase",
     "pipeoptim_device_sync_count", "pipeoptim_step_predict_static", "pipeoptim_plan_learn_layout", "pipeoptim_plan_chunk_marks",
-    "pipeoptim_plan_near_share", "pipeoptim_chunk_vote",
+    "pipeoptim_plan_near_share", "pipeoptim_chunk_vote", "pipeoptim_whole_pieces",
 )
 PO_STATIC_MAX_TENSORS, PO_STATIC_MAX_CHUNKS = 1024, 65536
 
@@ -108,6 +108,8 @@ def lib():
         L.pipeoptim_plan_learn_layout.argtypes = [vp, vp, P(i64)]
         L.pipeoptim_plan_chunk_marks.argtypes = [vp, P(ctypes.c_int8), i64, P(i64)]
         L.pipeoptim_plan_near_share.argtypes = [vp, P(ctypes.c_double)]
+        L.pipeoptim_whole_pieces.argtypes = [i64, P(ctypes.c_uint64), P(ctypes.c_uint64), P(ctypes.c_uint64), P(ctypes.c_uint64),
+                                             i64, P(i64)]
         L.pipeoptim_chunk_vote.argtypes = [i32, P(ctypes.c_uint64), P(i32), i64, i64, P(ctypes.c_uint64), P(ctypes.c_int8),
                                            P(ctypes.c_double)]
         L.pipeoptim_plan_launch_phase.argtypes = [vp, P(i32)]
@@ -175,6 +177,17 @@ def pipeoptim_local_tile(tile_in_chunk: int, first_block_half: int) -> int:
     out = ctypes.c_uint32(0)
     _check(lib().pipeoptim_local_tile(int(tile_in_chunk), int(first_block_half), ctypes.byref(out)))
     return out.value
+
+
+def pipeoptim_whole_pieces(ranges):
+    """Host-only: the runs [lo, hi) of whole 2 MiB pieces inside the union of the byte ranges [(lo, hi), ...]."""
+    n = len(ranges)
+    lo = (ctypes.c_uint64 * max(n, 1))(*[r[0] for r in ranges])
+    hi = (ctypes.c_uint64 * max(n, 1))(*[r[1] for r in ranges])
+    out_lo, out_hi = (ctypes.c_uint64 * max(n, 1))(), (ctypes.c_uint64 * max(n, 1))()
+    k = ctypes.c_int64(0)
+    _check(lib().pipeoptim_whole_pieces(n, lo, hi, out_lo, out_hi, n, ctypes.byref(k)))
+    return [(out_lo[j], out_hi[j]) for j in range(k.value)]
 
 
 def pipeoptim_chunk_vote(first_byte, weight, elems: int, piece_addr, even_blocks_near):

@@ -460,6 +460,24 @@ struct PieceLayout {
     }
 };
 
+// The runs of whole, 2 MiB-aligned pieces every byte of which lies in at least one of the byte ranges [lo, hi)
+// (sorted, disjoint).  Ranges that touch or overlap count as one; a gap of a single byte ends a run.
+std::vector<std::pair<uintptr_t, uintptr_t>> whole_pieces_inside(std::vector<std::pair<uintptr_t, uintptr_t>> bytes)
+{
+    std::sort(bytes.begin(), bytes.end());
+    std::vector<std::pair<uintptr_t, uintptr_t>> merged, pieces;
+    for (const auto& r : bytes) {
+        if (r.first >= r.second) continue;
+        if (!merged.empty() && r.first <= merged.back().second) merged.back().second = std::max(merged.back().second, r.second);
+        else merged.push_back(r);
+    }
+    for (const auto& r : merged) {
+        const uintptr_t lo = (r.first + kPiece - 1) / kPiece * kPiece, hi = r.second / kPiece * kPiece;
+        if (lo < hi) pieces.push_back({lo, hi});
+    }
+    return pieces;
+}
+
 // Times every whole 2 MiB piece inside the union of the plan's fp32 streams.  Every byte of every stream is readable
 // device memory, so such a piece may be read wherever it lies (buffers that a caching allocator placed back to
 // back merge into one range).  Waits for the device, several times.
@@ -472,16 +490,7 @@ int time_pieces_under(const po_plan* p, PieceLayout& out)
         const int ns = voting_streams(p, d, st);
         for (int k = 0; k < ns; ++k) bytes.push_back({st[k].base, st[k].base + (uintptr_t)d.numel * 4});
     }
-    std::sort(bytes.begin(), bytes.end());
-    std::vector<std::pair<uintptr_t, uintptr_t>> merged;
-    for (const auto& r : bytes) {
-        if (!merged.empty() && r.first <= merged.back().second) merged.back().second = std::max(merged.back().second, r.second);
-        else merged.push_back(r);
-    }
-    for (const auto& r : merged) {
-        const uintptr_t lo = (r.first + kPiece - 1) / kPiece * kPiece, hi = r.second / kPiece * kPiece;
-        if (lo < hi) out.ranges.push_back({lo, hi});
-    }
+    out.ranges = whole_pieces_inside(bytes);
     out.answer.resize(out.ranges.size());
     for (size_t k = 0; k < out.ranges.size(); ++k) {
         const size_t n = (size_t)((out.ranges[k].second - out.ranges[k].first) / kPiece);
@@ -948,6 +957,23 @@ try {
 }
 catch (const std::bad_alloc&) { return po_fail(PO_ENOMEM, "pipeoptim_plan_learn_layout: out of host memory"); }
 catch (...) { return po_fail(PO_EINVAL, "pipeoptim_plan_learn_layout: unexpected exception"); }
+
+int pipeoptim_whole_pieces(int64_t n_ranges, const uint64_t* lo, const uint64_t* hi, uint64_t* piece_lo, uint64_t* piece_hi,
+                           int64_t capacity, int64_t* n_runs)
+try {
+    if (n_ranges < 0 || capacity < 0 || !n_runs) return po_fail(PO_EINVAL, "bad argument");
+    if ((n_ranges > 0 && (!lo || !hi)) || (capacity > 0 && (!piece_lo || !piece_hi))) return po_fail(PO_EINVAL, "a required array is NULL");
+    std::vector<std::pair<uintptr_t, uintptr_t>> bytes;
+    for (int64_t k = 0; k < n_ranges; ++k) {
+        if (lo[k] > hi[k]) return po_fail(PO_EINVAL, "range %lld ends before it starts", (long long)k);
+        bytes.push_back({(uintptr_t)lo[k], (uintptr_t)hi[k]});
+    }
+    const auto runs = whole_pieces_inside(bytes);
+    for (size_t k = 0; k < runs.size() && (int64_t)k < capacity; ++k) { piece_lo[k] = runs[k].first; piece_hi[k] = runs[k].second; }
+    *n_runs = (int64_t)runs.size();
+    return PO_OK;
+}
+catch (const std::bad_alloc&) { return po_fail(PO_ENOMEM, "pipeoptim_whole_pieces: out of host memory"); }
 
 int pipeoptim_chunk_vote(int32_t n_streams, const uint64_t* first_byte, const int32_t* weight, int64_t elems,
                          int64_t n_pieces, const uint64_t* piece_addr, const int8_t* even_blocks_near, double* near)

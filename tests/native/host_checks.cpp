@@ -105,6 +105,12 @@ int main()
         EXPECT(pipeoptim_chunk_vote(1, &stream, &weight, 4096, 1, &piece, &half, near) == PO_OK && near[0] == 0.0 && near[1] == 8.0 * 4096);
         EXPECT(pipeoptim_chunk_vote(1, &stream, &weight, 4096, 1, &piece, &half, nullptr) == PO_EINVAL);
         EXPECT(pipeoptim_chunk_vote(6, &stream, &weight, 4096, 1, &piece, &half, near) == PO_EINVAL);
+        const uint64_t lo[2] = {piece + 4, piece - 100}, hi[2] = {piece + (uint64_t(3) << 21) + 8, piece + 4};
+        uint64_t run_lo[2] = {0, 0}, run_hi[2] = {0, 0};
+        int64_t n_runs = -1;
+        EXPECT(pipeoptim_whole_pieces(2, lo, hi, run_lo, run_hi, 2, &n_runs) == PO_OK && n_runs == 1 &&
+               run_lo[0] == piece && run_hi[0] == piece + (uint64_t(3) << 21));
+        EXPECT(pipeoptim_whole_pieces(2, lo, hi, run_lo, run_hi, 2, nullptr) == PO_EINVAL);
     }
     po_launch eff{};
     EXPECT(pipeoptim_plan_effective_launch(nullptr, PO_KERNEL_KIND_FUSED, PO_ADAM, &eff) == PO_EINVAL);

@@ -214,6 +214,59 @@ def _brute_force_near_bytes(first_byte, weight, elems, layout_of_piece, mark):
     return near
 
 
+def test_whole_pieces_are_exactly_the_pieces_covered_byte_for_byte():
+    """What the layout timing may read: a 2 MiB piece counts only if every byte of it lies in some buffer.  Checked
+    against a direct count on random buffer lists (touching, overlapping, nested, with one-byte gaps)."""
+    import random
+    rng = random.Random(839)
+    P2 = PIECE
+    assert binding.pipeoptim_whole_pieces([]) == []
+    assert binding.pipeoptim_whole_pieces([(5 * P2, 6 * P2)]) == [(5 * P2, 6 * P2)]
+    assert binding.pipeoptim_whole_pieces([(5 * P2 + 4, 6 * P2 + 4)]) == []                       # no whole piece inside
+    assert binding.pipeoptim_whole_pieces([(5 * P2, 5 * P2 + 100), (5 * P2 + 100, 6 * P2)]) == [(5 * P2, 6 * P2)]   # touching
+    assert binding.pipeoptim_whole_pieces([(5 * P2, 5 * P2 + 100), (5 * P2 + 101, 6 * P2)]) == []                   # one byte missing
+    assert binding.pipeoptim_whole_pieces([(7 * P2, 9 * P2), (3 * P2 - 1, 5 * P2 + 1)]) == [(3 * P2, 5 * P2), (7 * P2, 9 * P2)]
+    for case in range(200):
+        ranges = []
+        at = rng.randrange(0, 3) * P2 + rng.choice([0, 0, 4, 512, P2 // 2])
+        for _ in range(rng.randint(1, 12)):
+            size = rng.choice([4, 1024, P2 // 2, P2, P2, 3 * P2 + 512, 2 * P2])
+            ranges.append((at, at + size))
+            at += size + rng.choice([0, 0, 0, 1, 508, P2, -rng.randrange(0, size)])
+        rng.shuffle(ranges)
+        got = binding.pipeoptim_whole_pieces(ranges)
+        # direct count: piece k is covered if the sorted ranges that meet it leave no gap from its first to its last byte
+        top = max(hi for _, hi in ranges) // P2 + 1
+        covered = []
+        for k in range(top):
+            need, end = k * P2, (k + 1) * P2
+            for lo, hi in sorted(ranges):
+                if lo <= need < hi:
+                    need = hi
+                if need >= end:
+                    break
+            covered.append(need >= end)
+        want, k = [], 0
+        while k < top:
+            if covered[k]:
+                j = k
+                while j < top and covered[j]:
+                    j += 1
+                want.append((k * P2, j * P2))
+                k = j
+            else:
+                k += 1
+        # the library reports maximal runs of the merged ranges; adjacent runs from ranges with a gap between them that
+        # lies outside any whole piece cannot occur (a gap inside a piece uncovers it), so the two lists must be equal
+        assert got == want, (case, sorted(ranges), got, want)
+    L = binding.lib()
+    n = ctypes.c_int64()
+    assert L.pipeoptim_whole_pieces(1, None, None, None, None, 0, ctypes.byref(n)) == binding.PO_EINVAL
+    assert L.pipeoptim_whole_pieces(0, None, None, None, None, 0, None) == binding.PO_EINVAL
+    bad_lo, bad_hi = (ctypes.c_uint64 * 1)(10), (ctypes.c_uint64 * 1)(5)
+    assert L.pipeoptim_whole_pieces(1, bad_lo, bad_hi, None, None, 0, ctypes.byref(n)) == binding.PO_EINVAL
+
+
 def test_chunk_vote_special_cases():
     """The vote pipeoptim_plan_learn_layout takes per chunk, on cases with an answer that can be written down."""
     base, CH = 64 * PIECE, 65536                         # a chunk of 65,536 fp32 elements = 256 KiB per stream
